@@ -1,0 +1,193 @@
+/*
+ * gcn.h -- C ABI of the single-GPU hot path of full-batch GCN training on MI355X (gfx950).
+ *
+ * The operations are those of "Reducing Communication in Graph Neural Network Training"
+ * (arXiv 2005.03300): per layer Z^l = A^T H^{l-1} W^l, H^l = sigma(Z^l) ("Forward Propagation"),
+ * and the three backward equations of "Backpropagation Derivations".  This library is what one
+ * process of the paper's 1D algorithm runs between its collectives, on the whole graph.
+ *
+ * Conventions for every call
+ *   - Every pointer named "device" is HIP device memory on the current device; "host" is host
+ *     memory.  Dense matrices are fp32, row-major, with a leading dimension in elements.
+ *   - Dense buffers are owned by the caller; the library neither frees nor keeps them after the
+ *     work queued on `stream` has finished.  Only gcn_csr objects own device memory.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Compute calls only
+ *     queue work on it and return; gcn_csr_create*, gcn_csr_info and gcn_csr_destroy synchronise.
+ *   - Every function returns GCN_OK (0) or a negative GCN_ERR_* code and never throws or aborts.
+ *     gcn_last_error() returns a thread-local message for the last failure on this thread.
+ *   - No call is safe to run concurrently with another call that uses the same gcn_csr.
+ */
+#ifndef GCN_H
+#define GCN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define GCN_OK 0
+#define GCN_ERR_BADARG (-1)      /* NULL pointer, non-positive size, ld < width, aliasing */
+#define GCN_ERR_RANGE (-2)       /* vertex id outside [0,n), n >= 2^31, counts that overflow */
+#define GCN_ERR_NOTRANSPOSE (-3) /* trans=1 asked of a matrix built without GCN_BUILD_TRANSPOSE */
+#define GCN_ERR_OOM (-4)         /* device allocation failed */
+#define GCN_ERR_WORKSPACE (-5)   /* caller workspace too small */
+#define GCN_ERR_HIP (-6)         /* a HIP runtime call failed; see gcn_last_error() */
+#define GCN_ERR_UNSORTED (-7)    /* caller-supplied CSR has unsorted/duplicate/out-of-range columns */
+
+/* gcn_csr_create flags */
+#define GCN_SYMMETRISE 1u      /* store (v,u) for every input (u,v) */
+#define GCN_ADD_SELF_LOOPS 2u  /* insert exactly one diagonal entry per row */
+#define GCN_NORM_SYM 4u        /* values 1/sqrt(d_i d_j); without it every value is 1.0f */
+#define GCN_BUILD_TRANSPOSE 8u /* also store A^T in compressed rows (needed for trans=1) */
+
+/* gcn_spmm / gcn_gemm epilogues */
+#define GCN_EPI_NONE 0
+#define GCN_EPI_RELU 1 /* out = max(out, 0) */
+#define GCN_EPI_MASK 2 /* out = Zprev > 0 ? out : 0   (Hadamard product with sigma'(Zprev)) */
+
+/* association order of A^T H W */
+#define GCN_ORDER_AUTO 0       /* GEMM first if f_out <= f_in, else SpMM first */
+#define GCN_ORDER_GEMM_FIRST 1 /* A^T (H W) */
+#define GCN_ORDER_SPMM_FIRST 2 /* (A^T H) W  -- the order of the paper's Algorithm 1 */
+
+#define GCN_ACT_NONE 0
+#define GCN_ACT_RELU 1
+
+/* gcn_config keys */
+#define GCN_CFG_SPMM_ALGO 1 /* 0 = automatic, 1 = one wavefront per row, 2 = nonzero-split */
+#define GCN_CFG_TIMING 2    /* 1 = bracket the dominant kernels with HIP events (see gcn_timing_read) */
+
+typedef struct gcn_csr gcn_csr; /* opaque: A (and A^T) in compressed rows, degrees, schedules */
+
+/* -------------------------------------------------------------------------------------------
+ * Graph construction -- section "Graph Neural Networks": the adjacency matrix with added
+ * self-connections, scaled to D^-1/2 (A+I) D^-1/2 with D the modified degrees; section
+ * "Communication Schemes and their Analyses": both A and A^T are stored.
+ *
+ * src, dst: DEVICE int32[n_edges], borrowed for the call.  Pairs with src == dst are dropped,
+ * duplicates collapse to one entry.  The result has columns ascending in every row; rowptr is
+ * int64, colidx int32, val fp32, deg int32 = entries per row of A.  With GCN_NORM_SYM,
+ * val(i,j) = (float)(1.0 / sqrt((double)deg_i * (double)deg_j)).
+ * Errors: BADARG (NULL out, n <= 0, n_edges < 0, NULL arrays with n_edges > 0), RANGE (n >= 2^31
+ * or an id outside [0,n)), OOM, HIP.  On error *out is NULL.
+ * ----------------------------------------------------------------------------------------- */
+int gcn_csr_create(gcn_csr** out, int64_t n, int64_t n_edges, const int32_t* src, const int32_t* dst,
+                   uint32_t flags, void* stream);
+
+/* Adopt a caller-built compressed-row matrix (DEVICE arrays, copied).  val == NULL means 1.0f.
+ * Columns must be strictly ascending per row and inside [0,n): otherwise UNSORTED.  Rows may be
+ * empty.  flags: only GCN_BUILD_TRANSPOSE is honoured. */
+int gcn_csr_create_from_csr(gcn_csr** out, int64_t n, const int64_t* rowptr, const int32_t* colidx,
+                            const float* val, uint32_t flags, void* stream);
+
+int gcn_csr_destroy(gcn_csr* a);
+
+/* Sizes; any output pointer may be NULL. */
+int gcn_csr_info(const gcn_csr* a, int64_t* n, int64_t* nnz, int32_t* max_degree);
+
+/* DEVICE pointers to the stored arrays (valid until destroy) for bit-exact checks.
+ * transposed=1 selects A^T (NOTRANSPOSE if absent); deg is always that of A. */
+int gcn_csr_arrays(const gcn_csr* a, int transposed, const int64_t** rowptr, const int32_t** colidx,
+                   const float** val, const int32_t** deg);
+
+/* Copy the stored arrays into caller-owned DEVICE buffers (rowptr int64[n+1], colidx int32[nnz],
+ * val float[nnz], deg int32[n]); any destination may be NULL.  Queued on `stream`. */
+int gcn_csr_export(const gcn_csr* a, int transposed, int64_t* rowptr, int32_t* colidx, float* val, int32_t* deg,
+                   void* stream);
+
+/* -------------------------------------------------------------------------------------------
+ * SpMM -- the local sparse-dense product of sections "Graph Neural Networks" and "A
+ * One-Dimensional (1D) Algorithm":  Z[i,:] = sum over stored entries k of row i of op(A) of
+ * val[k] * X[col[k],:], op(A) = A (trans=0) or A^T (trans=1).
+ * X: device n x f, ld ldx >= f.  Z: device n x f, ld ldz >= f, must not overlap X.
+ * epilogue GCN_EPI_MASK reads Zprev (device n x f, ld ldzprev); otherwise Zprev is ignored.
+ * Sums are fp32 and run-to-run reproducible (no floating-point atomics).
+ * ----------------------------------------------------------------------------------------- */
+int gcn_spmm(gcn_csr* a, int trans, int32_t f, const float* X, int64_t ldx, float* Z, int64_t ldz,
+             int epilogue, const float* Zprev, int64_t ldzprev, void* stream);
+
+/* -------------------------------------------------------------------------------------------
+ * Dense products of "Forward Propagation" (H W) and of Equations 2 and 3 (S W^T, H^T S):
+ * C = op(A) op(B) [+ 1 bias^T], then the epilogue.  op(A) is M x K, op(B) is K x N; ta/tb != 0
+ * mean the stored matrix is the transpose (stored A is K x M, stored B is N x K).  All device,
+ * row-major.  bias (N floats) may be NULL.  ta=1 sums over the long dimension K in a fixed
+ * order (reproducible); it uses a library-owned scratch buffer.  ta=1 with tb=1 is BADARG.
+ * ----------------------------------------------------------------------------------------- */
+int gcn_gemm(int ta, int tb, int64_t M, int64_t N, int64_t K, const float* A, int64_t lda,
+             const float* B, int64_t ldb, float* C, int64_t ldc, const float* bias, int epilogue,
+             const float* Zprev, int64_t ldzprev, void* stream);
+
+/* sigma and sigma' of "Forward Propagation" / Equations 1-2 as stand-alone element-wise calls
+ * over rows x cols matrices with leading dimensions. out may equal the first input. */
+int gcn_relu(int64_t rows, int32_t cols, const float* Z, int64_t ldz, float* H, int64_t ldh, void* stream);
+int gcn_relu_mask(int64_t rows, int32_t cols, const float* G, int64_t ldg, const float* Zprev,
+                  int64_t ldzprev, float* out, int64_t ldo, void* stream);
+
+/* -------------------------------------------------------------------------------------------
+ * Last-layer activation and loss -- the row-wise log_softmax of "Block Two-Dimensional (2D)
+ * Algorithms" with the mean negative log-likelihood over all n vertices, and Equation 1 for it:
+ *   loss = -(1/n) sum_i log_softmax(Z[i,:])[y_i],  G[i,j] = (softmax(Z[i,:])[j] - [j == y_i]) / n.
+ * Z: device n x C (ld ldz); labels: device int32[n] in [0,C); loss: device float (written);
+ * G: device n x C (ld ldg) or NULL.  Row sums are reduced in double in a fixed order.
+ * ----------------------------------------------------------------------------------------- */
+int gcn_softmax_nll(int64_t n, int32_t C, const float* Z, int64_t ldz, const int32_t* labels, float* loss,
+                    float* G, int64_t ldg, void* stream);
+
+/* -------------------------------------------------------------------------------------------
+ * One layer forward -- "Forward Propagation": Z = A^T Hin W (+ bias), Hout = sigma(Z).
+ * Needs GCN_BUILD_TRANSPOSE.  Hin: n x f_in (ld ldh).  W: f_in x f_out dense.  Z, Hout: n x f_out
+ * dense (Hout may be NULL with GCN_ACT_NONE, and may equal Z).  T: scratch, n x f_out dense for
+ * GEMM_FIRST (holds Hin W), n x f_in dense for SPMM_FIRST (holds A^T Hin; keep it for backward).
+ * ----------------------------------------------------------------------------------------- */
+int gcn_layer_forward(gcn_csr* a, int32_t f_in, int32_t f_out, const float* Hin, int64_t ldh,
+                      const float* W, const float* bias, float* Z, float* Hout, float* T, int order,
+                      int act, void* stream);
+
+/* -------------------------------------------------------------------------------------------
+ * One layer backward -- Equations 2 and 3 with A G computed once and used for both:
+ *   Y = Hin^T A G            (f_in x f_out, gradient of W)
+ *   Gprev = (A G W^T) (Hadamard) sigma'(Zprev)     (n x f_in; pass Gprev = NULL at the first layer)
+ * G: n x f_out dense = dL/dZ of this layer.  dbias (f_out, column sums of G) may be NULL.
+ * S: scratch, n x f_out for GEMM_FIRST (returns A G), n x f_in for SPMM_FIRST (returns G W^T).
+ * T: the forward call's T; read only in SPMM_FIRST order (Y = T^T G).  `order` must be the order
+ * the forward call resolved to (AUTO resolves identically in both).
+ * ----------------------------------------------------------------------------------------- */
+int gcn_layer_backward(gcn_csr* a, int32_t f_in, int32_t f_out, const float* Hin, int64_t ldh,
+                       const float* Zprev, const float* W, const float* G, const float* T, float* S,
+                       float* Y, float* dbias, float* Gprev, int order, void* stream);
+
+/* -------------------------------------------------------------------------------------------
+ * One full-batch epoch: forward through L_w layers (ReLU between, none after the last), loss,
+ * backward, and W <- W - lr Y when lr != 0 (the gradient step of Equation 3).
+ * dims: HOST int32[L_w+1] = f^0..f^{L_w}.  H0: device n x dims[0] dense.  labels: device int32[n].
+ * W, Y: HOST arrays of L_w device pointers (W[l] is dims[l] x dims[l+1]; Y[l] receives dL/dW[l]).
+ * loss: device float.  workspace: device, at least gcn_epoch_workspace_bytes(); holds every
+ * Z^l, H^l, G^l and the scratch matrices, O(n * sum f).  `order` applies to every layer.
+ * ----------------------------------------------------------------------------------------- */
+int gcn_epoch(gcn_csr* a, int32_t L_w, const int32_t* dims, const float* H0, const int32_t* labels,
+              float* const* W, float* const* Y, float lr, float* loss, void* workspace,
+              size_t workspace_bytes, int order, void* stream);
+size_t gcn_epoch_workspace_bytes(int64_t n, int32_t L_w, const int32_t* dims, int order);
+
+/* After gcn_epoch: device pointers into the workspace for layer l in [1, L_w] (Z^l and G^l,
+ * both n x dims[l] dense), for parity checks.  BADARG if the workspace/dims do not match. */
+int gcn_epoch_view(int64_t n, int32_t L_w, const int32_t* dims, int order, void* workspace, int32_t l,
+                   float** Z, float** G);
+
+/* Library-wide settings (GCN_CFG_*).  Returns BADARG for an unknown key or value. */
+int gcn_config(int key, int value);
+
+/* With GCN_CFG_TIMING = 1 the SpMM main kernel is bracketed by HIP events on its own stream.
+ * gcn_timing_read synchronises with the recorded events, returns the number of bracketed
+ * launches and their total milliseconds since the last read, and resets the record. */
+int gcn_timing_read(int64_t* launches, double* total_ms);
+
+const char* gcn_last_error(void);
+const char* gcn_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GCN_H */

@@ -1,0 +1,16 @@
+"""Python binding of libgcn_hip.so: same names as the C ABI in include/gcn.h, argument
+marshalling only.  Tensors are torch CUDA(HIP) tensors used as device memory; every step of the
+path runs inside the library's kernels on torch's current stream.
+
+Importing this package does not load the library; the first call does, and raises if the
+library has not been built (there is no CPU fallback).
+"""
+from .binding import (  # noqa: F401
+    GcnError, Csr, lib, library_path, exported_symbols,
+    gcn_csr_create, gcn_csr_create_from_csr, gcn_spmm, gcn_gemm, gcn_relu, gcn_relu_mask,
+    gcn_softmax_nll, gcn_layer_forward, gcn_layer_backward, gcn_epoch, gcn_epoch_workspace_bytes,
+    gcn_epoch_view, gcn_config, gcn_timing_read, gcn_version,
+    SYMMETRISE, ADD_SELF_LOOPS, NORM_SYM, BUILD_TRANSPOSE,
+    EPI_NONE, EPI_RELU, EPI_MASK, ORDER_AUTO, ORDER_GEMM_FIRST, ORDER_SPMM_FIRST, ACT_NONE, ACT_RELU,
+    CFG_SPMM_ALGO, CFG_TIMING,
+)

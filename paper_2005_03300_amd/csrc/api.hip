@@ -1,0 +1,204 @@
+// Error reporting, settings, event timing, allocation helpers and gcn_csr accessors.
+#include <stdarg.h>
+#include <string.h>
+
+#include <mutex>
+#include <vector>
+
+#include "common.h"
+
+namespace gcn {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+}
+
+int fail(int code, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+int device_alloc(void** p, size_t bytes) {
+    *p = nullptr;
+    if (bytes == 0) bytes = 16;
+    hipError_t e = hipMalloc(p, bytes);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        *p = nullptr;
+        return fail(e == hipErrorOutOfMemory ? GCN_ERR_OOM : GCN_ERR_HIP, "hipMalloc(%zu) failed: %s", bytes,
+                    hipGetErrorString(e));
+    }
+    return GCN_OK;
+}
+
+void device_free(void* p) {
+    if (p) (void)hipFree(p);
+}
+
+static std::mutex g_scratch_mu;
+static void* g_scratch = nullptr;
+static size_t g_scratch_bytes = 0;
+
+int scratch_get(void** p, size_t bytes) {
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    if (bytes > g_scratch_bytes) {
+        // Work queued earlier may still read the old buffer: wait before freeing it.
+        if (g_scratch) {
+            GCN_HIP_TRY(hipDeviceSynchronize());
+            device_free(g_scratch);
+            g_scratch = nullptr;
+            g_scratch_bytes = 0;
+        }
+        size_t want = bytes + bytes / 4;
+        GCN_TRY(device_alloc(&g_scratch, want));
+        g_scratch_bytes = want;
+    }
+    *p = g_scratch;
+    return GCN_OK;
+}
+
+Config& config() {
+    static Config c;
+    return c;
+}
+
+// ---- event timing ---------------------------------------------------------------------------
+static std::mutex g_time_mu;
+static std::vector<std::pair<hipEvent_t, hipEvent_t>> g_events;
+static thread_local hipEvent_t g_open = nullptr;
+
+void timing_begin(hipStream_t s) {
+    if (!config().timing) return;
+    hipEvent_t a;
+    if (hipEventCreate(&a) != hipSuccess) return;
+    (void)hipEventRecord(a, s);
+    g_open = a;
+}
+
+void timing_end(hipStream_t s) {
+    if (!config().timing || !g_open) return;
+    hipEvent_t b;
+    if (hipEventCreate(&b) != hipSuccess) {
+        (void)hipEventDestroy(g_open);
+        g_open = nullptr;
+        return;
+    }
+    (void)hipEventRecord(b, s);
+    std::lock_guard<std::mutex> lk(g_time_mu);
+    g_events.emplace_back(g_open, b);
+    g_open = nullptr;
+}
+
+void free_matrix(Matrix& m) {
+    device_free(m.rowptr);
+    device_free(m.colidx);
+    device_free(m.val);
+    device_free(m.flags);
+    device_free(m.sub_row);
+    device_free(m.ne_rows);
+    device_free(m.ne_rowptr);
+    m = Matrix();
+}
+
+}  // namespace gcn
+
+using namespace gcn;
+
+extern "C" {
+
+const char* gcn_last_error(void) { return g_err; }
+const char* gcn_version(void) { return "gcn-hip 0.1 (gfx950)"; }
+
+int gcn_config(int key, int value) {
+    switch (key) {
+        case GCN_CFG_SPMM_ALGO:
+            if (value < 0 || value > 2) return fail(GCN_ERR_BADARG, "GCN_CFG_SPMM_ALGO must be 0, 1 or 2");
+            config().spmm_algo = value;
+            return GCN_OK;
+        case GCN_CFG_TIMING:
+            if (value != 0 && value != 1) return fail(GCN_ERR_BADARG, "GCN_CFG_TIMING must be 0 or 1");
+            config().timing = value;
+            return GCN_OK;
+        default:
+            return fail(GCN_ERR_BADARG, "unknown config key %d", key);
+    }
+}
+
+int gcn_timing_read(int64_t* launches, double* total_ms) {
+    if (!launches || !total_ms) return fail(GCN_ERR_BADARG, "gcn_timing_read: NULL output");
+    std::lock_guard<std::mutex> lk(g_time_mu);
+    double ms = 0.0;
+    int64_t cnt = 0;
+    int rc = GCN_OK;
+    for (auto& ev : g_events) {
+        float t = 0.f;
+        hipError_t e = hipEventSynchronize(ev.second);
+        if (e == hipSuccess) e = hipEventElapsedTime(&t, ev.first, ev.second);
+        if (e == hipSuccess) {
+            ms += t;
+            cnt += 1;
+        } else {
+            rc = fail(GCN_ERR_HIP, "event timing failed: %s", hipGetErrorString(e));
+        }
+        (void)hipEventDestroy(ev.first);
+        (void)hipEventDestroy(ev.second);
+    }
+    g_events.clear();
+    *launches = cnt;
+    *total_ms = ms;
+    return rc;
+}
+
+int gcn_csr_destroy(gcn_csr* a) {
+    if (!a) return GCN_OK;
+    (void)hipDeviceSynchronize();
+    free_matrix(a->A);
+    free_matrix(a->At);
+    device_free(a->deg);
+    device_free(a->carry);
+    delete a;
+    return GCN_OK;
+}
+
+int gcn_csr_info(const gcn_csr* a, int64_t* n, int64_t* nnz, int32_t* max_degree) {
+    if (!a) return fail(GCN_ERR_BADARG, "gcn_csr_info: NULL matrix");
+    if (n) *n = a->n;
+    if (nnz) *nnz = a->nnz;
+    if (max_degree) *max_degree = a->A.max_degree;
+    return GCN_OK;
+}
+
+int gcn_csr_arrays(const gcn_csr* a, int transposed, const int64_t** rowptr, const int32_t** colidx,
+                   const float** val, const int32_t** deg) {
+    if (!a) return fail(GCN_ERR_BADARG, "gcn_csr_arrays: NULL matrix");
+    if (transposed && !a->has_t) return fail(GCN_ERR_NOTRANSPOSE, "matrix was built without GCN_BUILD_TRANSPOSE");
+    const Matrix& m = transposed ? a->At : a->A;
+    if (rowptr) *rowptr = m.rowptr;
+    if (colidx) *colidx = m.colidx;
+    if (val) *val = m.val;
+    if (deg) *deg = a->deg;
+    return GCN_OK;
+}
+
+int gcn_csr_export(const gcn_csr* a, int transposed, int64_t* rowptr, int32_t* colidx, float* val, int32_t* deg,
+                   void* stream) {
+    if (!a) return fail(GCN_ERR_BADARG, "gcn_csr_export: NULL matrix");
+    if (transposed && !a->has_t) return fail(GCN_ERR_NOTRANSPOSE, "matrix was built without GCN_BUILD_TRANSPOSE");
+    const Matrix& m = transposed ? a->At : a->A;
+    hipStream_t s = (hipStream_t)stream;
+    if (rowptr) GCN_HIP_TRY(hipMemcpyAsync(rowptr, m.rowptr, ((size_t)a->n + 1) * sizeof(int64_t), hipMemcpyDeviceToDevice, s));
+    if (colidx && a->nnz) GCN_HIP_TRY(hipMemcpyAsync(colidx, m.colidx, (size_t)a->nnz * sizeof(int32_t), hipMemcpyDeviceToDevice, s));
+    if (val && a->nnz) GCN_HIP_TRY(hipMemcpyAsync(val, m.val, (size_t)a->nnz * sizeof(float), hipMemcpyDeviceToDevice, s));
+    if (deg) GCN_HIP_TRY(hipMemcpyAsync(deg, a->deg, (size_t)a->n * sizeof(int32_t), hipMemcpyDeviceToDevice, s));
+    return GCN_OK;
+}
+
+}  // extern "C"

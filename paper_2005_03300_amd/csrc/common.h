@@ -1,0 +1,108 @@
+// Internal declarations shared by the translation units of libgcn_hip.so (not installed).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+
+#include "gcn.h"
+
+namespace gcn {
+
+// Thread-local error text returned by gcn_last_error().
+void set_error(const char* fmt, ...);
+int fail(int code, const char* fmt, ...);
+
+#define GCN_HIP_TRY(expr)                                                                       \
+    do {                                                                                        \
+        hipError_t e_ = (expr);                                                                 \
+        if (e_ != hipSuccess)                                                                   \
+            return gcn::fail(e_ == hipErrorOutOfMemory ? GCN_ERR_OOM : GCN_ERR_HIP,             \
+                             "%s failed: %s (%s:%d)", #expr, hipGetErrorString(e_), __FILE__,   \
+                             __LINE__);                                                         \
+    } while (0)
+
+#define GCN_TRY(expr)          \
+    do {                       \
+        int rc_ = (expr);      \
+        if (rc_ != GCN_OK) return rc_; \
+    } while (0)
+
+// Launch check: a bad configuration is reported by hipGetLastError right after the launch.
+#define GCN_LAUNCH_CHECK()                                                                      \
+    do {                                                                                        \
+        hipError_t e_ = hipGetLastError();                                                      \
+        if (e_ != hipSuccess)                                                                   \
+            return gcn::fail(GCN_ERR_HIP, "kernel launch failed: %s (%s:%d)",                   \
+                             hipGetErrorString(e_), __FILE__, __LINE__);                        \
+    } while (0)
+
+// Nonzero-split schedule constants: a wavefront owns CHUNK consecutive stored entries, cut into
+// SUB-entry pieces that each carry one 32-bit word of row-start flags.
+constexpr int SUB = 32;
+constexpr int CHUNK = 512;
+constexpr int SUBS_PER_CHUNK = CHUNK / SUB;
+
+// One stored matrix in compressed rows plus its nonzero-split schedule.
+struct Matrix {
+    int64_t* rowptr = nullptr;   // [n+1]
+    int32_t* colidx = nullptr;   // [nnz]
+    float* val = nullptr;        // [nnz]
+    // schedule (built once at creation)
+    uint32_t* flags = nullptr;   // [nsub]  bit b of word j: entry 32j+b is the first of its row
+    int32_t* sub_row = nullptr;  // [nsub]  index (among non-empty rows) of the row holding entry 32j
+    int32_t* ne_rows = nullptr;  // [n_ne]  non-empty row index -> row, or NULL when no row is empty
+    int64_t* ne_rowptr = nullptr;// [n_ne+1] rowptr restricted to non-empty rows, or NULL (= rowptr)
+    int64_t n_ne = 0;
+    int64_t nsub = 0, nchunks = 0;
+    int32_t max_degree = 0;
+};
+
+}  // namespace gcn
+
+struct gcn_csr {
+    int64_t n = 0, nnz = 0;
+    int device = 0;
+    bool has_t = false;
+    gcn::Matrix A, At;
+    int32_t* deg = nullptr;      // [n] entries per row of A
+    float* carry = nullptr;      // per-chunk partial rows for the nonzero-split SpMM
+    size_t carry_bytes = 0;
+};
+
+namespace gcn {
+
+int device_alloc(void** p, size_t bytes);
+template <typename T>
+int device_alloc_t(T** p, size_t count) { return device_alloc((void**)p, count * sizeof(T)); }
+void device_free(void* p);
+
+// library-owned scratch that grows on demand (used by the split-K weight-gradient product and
+// the loss reduction); one per process, calls on different streams must not overlap.
+int scratch_get(void** p, size_t bytes);
+
+struct Config {
+    int spmm_algo = 0;
+    int timing = 0;
+};
+Config& config();
+
+// event bracketing of the dominant kernel (GCN_CFG_TIMING)
+void timing_begin(hipStream_t s);
+void timing_end(hipStream_t s);
+
+int build_schedule(Matrix& m, int64_t n, int64_t nnz, hipStream_t s);
+void free_matrix(Matrix& m);
+
+int spmm_launch(gcn_csr* a, const Matrix& m, int32_t f, const float* X, int64_t ldx, float* Z, int64_t ldz,
+                int epilogue, const float* Zprev, int64_t ldzprev, hipStream_t s);
+
+int gemm_launch(int ta, int tb, int64_t M, int64_t N, int64_t K, const float* A, int64_t lda, const float* B,
+                int64_t ldb, float* C, int64_t ldc, const float* bias, int epilogue, const float* Zprev,
+                int64_t ldzprev, hipStream_t s);
+int colsum_launch(int64_t rows, int32_t cols, const float* G, int64_t ldg, float* out, hipStream_t s);
+int axpy_launch(int64_t count, float* W, const float* Y, float lr, hipStream_t s);
+int relu_launch(int64_t rows, int32_t cols, const float* Z, int64_t ldz, float* H, int64_t ldh, hipStream_t s);
+int bias_add_launch(int64_t rows, int32_t cols, float* Z, int64_t ldz, const float* bias, int relu, hipStream_t s);
+
+}  // namespace gcn

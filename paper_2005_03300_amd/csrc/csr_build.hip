@@ -1,0 +1,441 @@
+// Graph construction on the GPU: cleaned entry set -> compressed rows, degrees, normalised
+// values, the transposed matrix, and the nonzero-split schedule used by the SpMM kernel.
+//
+// Section "Graph Neural Networks" of the paper defines the matrix (self-connections added,
+// D^-1/2 (A+I) D^-1/2); section "Communication Schemes and their Analyses" keeps both A and A^T
+// so that neither product needs a transposition (or, here, floating-point atomics) at run time.
+//
+// Entries are encoded as 64-bit keys row<<32|col; a radix sort of the keys followed by the
+// removal of equal neighbours yields the canonical row-major order with ascending columns.  The
+// device-wide sort, select and scan primitives come from rocPRIM; everything else is below.
+#include <cstring>
+#include <new>
+
+#include <rocprim/device/device_radix_sort.hpp>
+#include <rocprim/device/device_select.hpp>
+#include <rocprim/iterator/counting_iterator.hpp>
+
+#include "common.h"
+
+namespace gcn {
+
+static constexpr uint64_t INVALID_KEY = ~0ull;
+static constexpr int TPB = 256;
+
+static inline unsigned blocks_for(int64_t work, int per_block = TPB) {
+    int64_t b = (work + per_block - 1) / per_block;
+    return (unsigned)(b < 1 ? 1 : b);
+}
+
+struct TempBuf {   // frees on scope exit
+    void* p = nullptr;
+    ~TempBuf() { device_free(p); }
+    int alloc(size_t bytes) { device_free(p); return device_alloc(&p, bytes); }
+    template <typename T> T* as() const { return (T*)p; }
+};
+
+// ---- kernels ---------------------------------------------------------------------------------
+
+__global__ void k_check_ids(int64_t m, int64_t n, const int32_t* __restrict__ src,
+                            const int32_t* __restrict__ dst, int* __restrict__ bad) {
+    int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= m) return;
+    int32_t u = src[e], v = dst[e];
+    if (u < 0 || v < 0 || u >= n || v >= n) *bad = 1;
+}
+
+// One key per stored direction of each input pair; pairs with u == v become INVALID_KEY, which
+// sorts behind every real key.  Self loops are appended after the 'mult*m' edge keys.
+__global__ void k_make_keys(int64_t m, int64_t n, const int32_t* __restrict__ src,
+                            const int32_t* __restrict__ dst, int symmetrise, int self_loops,
+                            uint64_t* __restrict__ keys) {
+    int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int mult = symmetrise ? 2 : 1;
+    if (t < m) {
+        uint64_t u = (uint32_t)src[t], v = (uint32_t)dst[t];
+        bool loop = (u == v);
+        keys[t * mult] = loop ? INVALID_KEY : (u << 32 | v);
+        if (symmetrise) keys[t * mult + 1] = loop ? INVALID_KEY : (v << 32 | u);
+    } else if (self_loops && t < m + n) {
+        uint64_t i = (uint64_t)(t - m);
+        keys[m * mult + (t - m)] = i << 32 | i;
+    }
+}
+
+// Sorted distinct keys -> colidx and rowptr.  Entry k is the first of every row in
+// (row(k-1), row(k)], so its thread writes rowptr for those rows; the last entry's thread also
+// closes all rows behind it.
+__global__ void k_compress(int64_t nnz, int64_t n, const uint64_t* __restrict__ keys,
+                           int64_t* __restrict__ rowptr, int32_t* __restrict__ colidx) {
+    int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (nnz == 0) {
+        for (int64_t r = k; r <= n; r += (int64_t)gridDim.x * blockDim.x) rowptr[r] = 0;
+        return;
+    }
+    if (k >= nnz) return;
+    uint64_t key = keys[k];
+    int64_t r = (int64_t)(key >> 32);
+    int64_t rp = k > 0 ? (int64_t)(keys[k - 1] >> 32) : -1;
+    colidx[k] = (int32_t)(key & 0xffffffffu);
+    for (int64_t q = rp + 1; q <= r; ++q) rowptr[q] = k;
+    if (k == nnz - 1)
+        for (int64_t q = r + 1; q <= n; ++q) rowptr[q] = nnz;
+}
+
+__global__ void k_degrees(int64_t n, const int64_t* __restrict__ rowptr, int32_t* __restrict__ deg,
+                          int32_t* __restrict__ max_deg, unsigned long long* __restrict__ n_nonempty) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    int32_t d = (int32_t)(rowptr[i + 1] - rowptr[i]);
+    if (deg) deg[i] = d;
+    if (max_deg) atomicMax(max_deg, d);
+    if (n_nonempty && d > 0) atomicAdd(n_nonempty, 1ull);
+}
+
+// val(i,j) = (float)(1 / sqrt(d_i d_j)): exact integer product in double, correctly rounded
+// square root and division, one rounding to float -- the same value on any IEEE machine.
+__global__ void k_values(int64_t nnz, const uint64_t* __restrict__ keys, const int32_t* __restrict__ deg,
+                         int norm_sym, float* __restrict__ val) {
+    int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (k >= nnz) return;
+    if (!norm_sym) {
+        val[k] = 1.0f;
+        return;
+    }
+    uint64_t key = keys[k];
+    double di = (double)deg[key >> 32], dj = (double)deg[key & 0xffffffffu];
+    val[k] = (float)__ddiv_rn(1.0, __dsqrt_rn(__dmul_rn(di, dj)));
+}
+
+__global__ void k_swap_halves(int64_t nnz, const uint64_t* __restrict__ keys, uint64_t* __restrict__ out) {
+    int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (k < nnz) out[k] = (keys[k] << 32) | (keys[k] >> 32);
+}
+
+// keys row<<32|col from compressed rows: thread k finds its row by bisection on rowptr.
+__global__ void k_keys_from_csr(int64_t nnz, int64_t n, const int64_t* __restrict__ rowptr,
+                                const int32_t* __restrict__ colidx, uint64_t* __restrict__ keys) {
+    int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (k >= nnz) return;
+    int64_t lo = 0, hi = n;   // largest r with rowptr[r] <= k
+    while (hi - lo > 1) {
+        int64_t mid = (lo + hi) >> 1;
+        if (rowptr[mid] <= k) lo = mid; else hi = mid;
+    }
+    keys[k] = ((uint64_t)lo << 32) | (uint32_t)colidx[k];
+}
+
+__global__ void k_validate_rowptr(int64_t n, const int64_t* __restrict__ rowptr, int* __restrict__ bad) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    if (i == 0 && rowptr[0] != 0) *bad = 1;
+    if (rowptr[i + 1] < rowptr[i]) *bad = 1;
+}
+
+// after k_keys_from_csr: keys must be strictly increasing and columns inside [0,n)
+__global__ void k_validate_keys(int64_t nnz, int64_t n, const uint64_t* __restrict__ keys, int* __restrict__ bad) {
+    int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (k >= nnz) return;
+    if ((keys[k] & 0xffffffffu) >= (uint64_t)n) *bad = 1;
+    if (k > 0 && keys[k] <= keys[k - 1]) *bad = 1;
+}
+
+__global__ void k_fill_f32(int64_t count, float v, float* __restrict__ out) {
+    int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (k < count) out[k] = v;
+}
+
+// ---- schedule kernels ---------------------------------------------------------------------------
+
+struct NonEmpty {
+    const int64_t* rowptr;
+    __device__ bool operator()(const int32_t& r) const { return rowptr[r + 1] > rowptr[r]; }
+};
+
+__global__ void k_ne_rowptr(int64_t n_ne, int64_t nnz, const int32_t* __restrict__ ne_rows,
+                            const int64_t* __restrict__ rowptr, int64_t* __restrict__ out) {
+    int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (q < n_ne) out[q] = rowptr[ne_rows[q]];
+    if (q == n_ne) out[q] = nnz;
+}
+
+__global__ void k_row_flags(int64_t n_ne, const int64_t* __restrict__ rp, uint32_t* __restrict__ flags) {
+    int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (q >= n_ne) return;
+    int64_t k = rp[q];
+    atomicOr(&flags[k >> 5], 1u << (k & 31));
+}
+
+__global__ void k_sub_rows(int64_t nsub, int64_t n_ne, const int64_t* __restrict__ rp, int32_t* __restrict__ sub_row) {
+    int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= nsub) return;
+    int64_t k = j * SUB, lo = 0, hi = n_ne;   // largest q with rp[q] <= k  (rp[0] == 0)
+    while (hi - lo > 1) {
+        int64_t mid = (lo + hi) >> 1;
+        if (rp[mid] <= k) lo = mid; else hi = mid;
+    }
+    sub_row[j] = (int32_t)lo;
+}
+
+// ---- host helpers ---------------------------------------------------------------------------------
+
+static int sort_keys(uint64_t* in, uint64_t* out, int64_t count, int64_t n, hipStream_t s) {
+    unsigned end_bit = 64;   // INVALID_KEY uses every bit
+    (void)n;
+    size_t tmp_bytes = 0;
+    GCN_HIP_TRY(rocprim::radix_sort_keys(nullptr, tmp_bytes, in, out, (size_t)count, 0u, end_bit, s));
+    TempBuf tmp;
+    GCN_TRY(tmp.alloc(tmp_bytes));
+    GCN_HIP_TRY(rocprim::radix_sort_keys(tmp.p, tmp_bytes, in, out, (size_t)count, 0u, end_bit, s));
+    GCN_HIP_TRY(hipStreamSynchronize(s));
+    return GCN_OK;
+}
+
+static unsigned bits_for(int64_t n) {
+    unsigned b = 1;
+    while (b < 32 && (1ll << b) < n) ++b;
+    return b;
+}
+
+// From sorted distinct keys (row<<32|col) fill rowptr/colidx of `m` (allocates them).
+static int compress_keys(Matrix& m, int64_t n, int64_t nnz, const uint64_t* keys, hipStream_t s) {
+    GCN_TRY(device_alloc_t(&m.rowptr, (size_t)n + 1));
+    GCN_TRY(device_alloc_t(&m.colidx, (size_t)nnz));
+    hipLaunchKernelGGL(k_compress, dim3(blocks_for(nnz)), dim3(TPB), 0, s, nnz, n, keys, m.rowptr, m.colidx);
+    GCN_LAUNCH_CHECK();
+    return GCN_OK;
+}
+
+int build_schedule(Matrix& m, int64_t n, int64_t nnz, hipStream_t s) {
+    m.nsub = (nnz + SUB - 1) / SUB;
+    m.nchunks = (nnz + CHUNK - 1) / CHUNK;
+    TempBuf counters;
+    GCN_TRY(counters.alloc(16));
+    GCN_HIP_TRY(hipMemsetAsync(counters.p, 0, 16, s));
+    hipLaunchKernelGGL(k_degrees, dim3(blocks_for(n)), dim3(TPB), 0, s, n, m.rowptr, (int32_t*)nullptr,
+                       (int32_t*)counters.p, (unsigned long long*)((char*)counters.p + 8));
+    GCN_LAUNCH_CHECK();
+    struct { int32_t maxd; int32_t pad; unsigned long long nne; } h;
+    GCN_HIP_TRY(hipMemcpyAsync(&h, counters.p, 16, hipMemcpyDeviceToHost, s));
+    GCN_HIP_TRY(hipStreamSynchronize(s));
+    m.max_degree = h.maxd;
+    m.n_ne = (int64_t)h.nne;
+    const int64_t* rp = m.rowptr;
+    if (m.n_ne < n) {
+        GCN_TRY(device_alloc_t(&m.ne_rows, (size_t)m.n_ne));
+        GCN_TRY(device_alloc_t(&m.ne_rowptr, (size_t)m.n_ne + 1));
+        TempBuf cnt, tmp;
+        GCN_TRY(cnt.alloc(sizeof(size_t)));
+        size_t tmp_bytes = 0;
+        rocprim::counting_iterator<int32_t> rows(0);
+        NonEmpty pred{m.rowptr};
+        GCN_HIP_TRY(rocprim::select(nullptr, tmp_bytes, rows, m.ne_rows, cnt.as<size_t>(), (size_t)n, pred, s));
+        GCN_TRY(tmp.alloc(tmp_bytes));
+        GCN_HIP_TRY(rocprim::select(tmp.p, tmp_bytes, rows, m.ne_rows, cnt.as<size_t>(), (size_t)n, pred, s));
+        hipLaunchKernelGGL(k_ne_rowptr, dim3(blocks_for(m.n_ne + 1)), dim3(TPB), 0, s, m.n_ne, nnz, m.ne_rows,
+                           m.rowptr, m.ne_rowptr);
+        GCN_LAUNCH_CHECK();
+        GCN_HIP_TRY(hipStreamSynchronize(s));
+        rp = m.ne_rowptr;
+    }
+    GCN_TRY(device_alloc_t(&m.flags, (size_t)m.nsub + SUBS_PER_CHUNK));   // padded: one chunk of zero words
+    GCN_TRY(device_alloc_t(&m.sub_row, (size_t)m.nsub + SUBS_PER_CHUNK));
+    GCN_HIP_TRY(hipMemsetAsync(m.flags, 0, ((size_t)m.nsub + SUBS_PER_CHUNK) * sizeof(uint32_t), s));
+    GCN_HIP_TRY(hipMemsetAsync(m.sub_row, 0, ((size_t)m.nsub + SUBS_PER_CHUNK) * sizeof(int32_t), s));
+    if (nnz > 0) {
+        hipLaunchKernelGGL(k_row_flags, dim3(blocks_for(m.n_ne)), dim3(TPB), 0, s, m.n_ne, rp, m.flags);
+        GCN_LAUNCH_CHECK();
+        hipLaunchKernelGGL(k_sub_rows, dim3(blocks_for(m.nsub)), dim3(TPB), 0, s, m.nsub, m.n_ne, rp, m.sub_row);
+        GCN_LAUNCH_CHECK();
+    }
+    GCN_HIP_TRY(hipStreamSynchronize(s));
+    return GCN_OK;
+}
+
+// A^T of `a` from A's sorted keys and values: swap key halves, stable radix sort with the values
+// as payload.  Within a column the rows keep their ascending order.
+static int build_transpose(gcn_csr* a, const uint64_t* keys, uint64_t* scratch_keys, hipStream_t s) {
+    int64_t nnz = a->nnz, n = a->n;
+    TempBuf kin, vtmp;
+    GCN_TRY(kin.alloc((size_t)nnz * 8));
+    GCN_TRY(device_alloc_t(&a->At.val, (size_t)nnz));
+    hipLaunchKernelGGL(k_swap_halves, dim3(blocks_for(nnz)), dim3(TPB), 0, s, nnz, keys, kin.as<uint64_t>());
+    GCN_LAUNCH_CHECK();
+    size_t tmp_bytes = 0;
+    unsigned end_bit = 32 + bits_for(n);
+    GCN_HIP_TRY(rocprim::radix_sort_pairs(nullptr, tmp_bytes, kin.as<uint64_t>(), scratch_keys, a->A.val, a->At.val,
+                                          (size_t)nnz, 0u, end_bit, s));
+    TempBuf tmp;
+    GCN_TRY(tmp.alloc(tmp_bytes));
+    GCN_HIP_TRY(rocprim::radix_sort_pairs(tmp.p, tmp_bytes, kin.as<uint64_t>(), scratch_keys, a->A.val, a->At.val,
+                                          (size_t)nnz, 0u, end_bit, s));
+    GCN_TRY(compress_keys(a->At, n, nnz, scratch_keys, s));
+    GCN_HIP_TRY(hipStreamSynchronize(s));
+    GCN_TRY(build_schedule(a->At, n, nnz, s));
+    a->has_t = true;
+    return GCN_OK;
+}
+
+static int create_impl(gcn_csr* a, int64_t n, int64_t m, const int32_t* src, const int32_t* dst, uint32_t flags,
+                       hipStream_t s) {
+    const bool sym = flags & GCN_SYMMETRISE, loops = flags & GCN_ADD_SELF_LOOPS;
+    const int mult = sym ? 2 : 1;
+    const int64_t cap = m * mult + (loops ? n : 0);
+
+    TempBuf bad;
+    GCN_TRY(bad.alloc(sizeof(int)));
+    GCN_HIP_TRY(hipMemsetAsync(bad.p, 0, sizeof(int), s));
+    if (m > 0) {
+        hipLaunchKernelGGL(k_check_ids, dim3(blocks_for(m)), dim3(TPB), 0, s, m, n, src, dst, bad.as<int>());
+        GCN_LAUNCH_CHECK();
+    }
+    int hbad = 0;
+    GCN_HIP_TRY(hipMemcpyAsync(&hbad, bad.p, sizeof(int), hipMemcpyDeviceToHost, s));
+    GCN_HIP_TRY(hipStreamSynchronize(s));
+    if (hbad) return fail(GCN_ERR_RANGE, "gcn_csr_create: a vertex id is outside [0, %lld)", (long long)n);
+
+    TempBuf k0, k1, cnt;
+    GCN_TRY(k0.alloc((size_t)cap * 8));
+    GCN_TRY(k1.alloc((size_t)cap * 8));
+    GCN_TRY(cnt.alloc(sizeof(size_t)));
+    int64_t nnz = 0;
+    if (cap > 0) {
+        hipLaunchKernelGGL(k_make_keys, dim3(blocks_for(m + (loops ? n : 0))), dim3(TPB), 0, s, m, n, src, dst,
+                           (int)sym, (int)loops, k0.as<uint64_t>());
+        GCN_LAUNCH_CHECK();
+        GCN_TRY(sort_keys(k0.as<uint64_t>(), k1.as<uint64_t>(), cap, n, s));
+        size_t tmp_bytes = 0;
+        GCN_HIP_TRY(rocprim::unique(nullptr, tmp_bytes, k1.as<uint64_t>(), k0.as<uint64_t>(), cnt.as<size_t>(),
+                                    (size_t)cap, rocprim::equal_to<uint64_t>(), s));
+        TempBuf tmp;
+        GCN_TRY(tmp.alloc(tmp_bytes));
+        GCN_HIP_TRY(rocprim::unique(tmp.p, tmp_bytes, k1.as<uint64_t>(), k0.as<uint64_t>(), cnt.as<size_t>(),
+                                    (size_t)cap, rocprim::equal_to<uint64_t>(), s));
+        size_t hcnt = 0;
+        uint64_t last = 0;
+        GCN_HIP_TRY(hipMemcpyAsync(&hcnt, cnt.p, sizeof(size_t), hipMemcpyDeviceToHost, s));
+        GCN_HIP_TRY(hipStreamSynchronize(s));
+        if (hcnt > 0) {
+            GCN_HIP_TRY(hipMemcpyAsync(&last, k0.as<uint64_t>() + (hcnt - 1), 8, hipMemcpyDeviceToHost, s));
+            GCN_HIP_TRY(hipStreamSynchronize(s));
+            if (last == INVALID_KEY) hcnt -= 1;
+        }
+        nnz = (int64_t)hcnt;
+    }
+    const uint64_t* keys = k0.as<uint64_t>();   // sorted, distinct, nnz of them
+    a->n = n;
+    a->nnz = nnz;
+    GCN_TRY(compress_keys(a->A, n, nnz, keys, s));
+    GCN_TRY(device_alloc_t(&a->deg, (size_t)n));
+    GCN_TRY(device_alloc_t(&a->A.val, (size_t)nnz));
+    hipLaunchKernelGGL(k_degrees, dim3(blocks_for(n)), dim3(TPB), 0, s, n, a->A.rowptr, a->deg, (int32_t*)nullptr,
+                       (unsigned long long*)nullptr);
+    GCN_LAUNCH_CHECK();
+    if (nnz > 0) {
+        hipLaunchKernelGGL(k_values, dim3(blocks_for(nnz)), dim3(TPB), 0, s, nnz, keys, a->deg,
+                           (int)((flags & GCN_NORM_SYM) != 0), a->A.val);
+        GCN_LAUNCH_CHECK();
+    }
+    GCN_HIP_TRY(hipStreamSynchronize(s));
+    GCN_TRY(build_schedule(a->A, n, nnz, s));
+    if (flags & GCN_BUILD_TRANSPOSE) GCN_TRY(build_transpose(a, keys, k1.as<uint64_t>(), s));
+    return GCN_OK;
+}
+
+static int from_csr_impl(gcn_csr* a, int64_t n, const int64_t* rowptr, const int32_t* colidx, const float* val,
+                         uint32_t flags, hipStream_t s) {
+    TempBuf bad;
+    GCN_TRY(bad.alloc(sizeof(int)));
+    GCN_HIP_TRY(hipMemsetAsync(bad.p, 0, sizeof(int), s));
+    hipLaunchKernelGGL(k_validate_rowptr, dim3(blocks_for(n)), dim3(TPB), 0, s, n, rowptr, bad.as<int>());
+    GCN_LAUNCH_CHECK();
+    int hbad = 0;
+    int64_t nnz = 0;
+    GCN_HIP_TRY(hipMemcpyAsync(&hbad, bad.p, sizeof(int), hipMemcpyDeviceToHost, s));
+    GCN_HIP_TRY(hipMemcpyAsync(&nnz, rowptr + n, 8, hipMemcpyDeviceToHost, s));
+    GCN_HIP_TRY(hipStreamSynchronize(s));
+    if (hbad || nnz < 0) return fail(GCN_ERR_UNSORTED, "gcn_csr_create_from_csr: rowptr must start at 0 and not decrease");
+    if (nnz > 0 && !colidx) return fail(GCN_ERR_BADARG, "gcn_csr_create_from_csr: NULL colidx");
+    a->n = n;
+    a->nnz = nnz;
+    GCN_TRY(device_alloc_t(&a->A.rowptr, (size_t)n + 1));
+    GCN_TRY(device_alloc_t(&a->A.colidx, (size_t)nnz));
+    GCN_TRY(device_alloc_t(&a->A.val, (size_t)nnz));
+    GCN_TRY(device_alloc_t(&a->deg, (size_t)n));
+    GCN_HIP_TRY(hipMemcpyAsync(a->A.rowptr, rowptr, ((size_t)n + 1) * 8, hipMemcpyDeviceToDevice, s));
+    TempBuf keys, k1;
+    GCN_TRY(keys.alloc((size_t)nnz * 8));
+    if (nnz > 0) {
+        GCN_HIP_TRY(hipMemcpyAsync(a->A.colidx, colidx, (size_t)nnz * 4, hipMemcpyDeviceToDevice, s));
+        if (val) GCN_HIP_TRY(hipMemcpyAsync(a->A.val, val, (size_t)nnz * 4, hipMemcpyDeviceToDevice, s));
+        else {
+            hipLaunchKernelGGL(k_fill_f32, dim3(blocks_for(nnz)), dim3(TPB), 0, s, nnz, 1.0f, a->A.val);
+            GCN_LAUNCH_CHECK();
+        }
+        hipLaunchKernelGGL(k_keys_from_csr, dim3(blocks_for(nnz)), dim3(TPB), 0, s, nnz, n, a->A.rowptr, a->A.colidx,
+                           keys.as<uint64_t>());
+        GCN_LAUNCH_CHECK();
+        hipLaunchKernelGGL(k_validate_keys, dim3(blocks_for(nnz)), dim3(TPB), 0, s, nnz, n, keys.as<uint64_t>(),
+                           bad.as<int>());
+        GCN_LAUNCH_CHECK();
+        GCN_HIP_TRY(hipMemcpyAsync(&hbad, bad.p, sizeof(int), hipMemcpyDeviceToHost, s));
+        GCN_HIP_TRY(hipStreamSynchronize(s));
+        if (hbad) return fail(GCN_ERR_UNSORTED, "gcn_csr_create_from_csr: columns must be strictly ascending per row and inside [0,n)");
+    }
+    hipLaunchKernelGGL(k_degrees, dim3(blocks_for(n)), dim3(TPB), 0, s, n, a->A.rowptr, a->deg, (int32_t*)nullptr,
+                       (unsigned long long*)nullptr);
+    GCN_LAUNCH_CHECK();
+    GCN_HIP_TRY(hipStreamSynchronize(s));
+    GCN_TRY(build_schedule(a->A, n, nnz, s));
+    if (flags & GCN_BUILD_TRANSPOSE) {
+        GCN_TRY(k1.alloc((size_t)nnz * 8));
+        GCN_TRY(build_transpose(a, keys.as<uint64_t>(), k1.as<uint64_t>(), s));
+    }
+    return GCN_OK;
+}
+
+}  // namespace gcn
+
+using namespace gcn;
+
+extern "C" {
+
+int gcn_csr_create(gcn_csr** out, int64_t n, int64_t n_edges, const int32_t* src, const int32_t* dst,
+                   uint32_t flags, void* stream) {
+    if (!out) return fail(GCN_ERR_BADARG, "gcn_csr_create: NULL out");
+    *out = nullptr;
+    if (n <= 0 || n_edges < 0) return fail(GCN_ERR_BADARG, "gcn_csr_create: n must be positive and n_edges non-negative");
+    if (n >= (1ll << 31)) return fail(GCN_ERR_RANGE, "gcn_csr_create: n must be below 2^31");
+    if (n_edges > 0 && (!src || !dst)) return fail(GCN_ERR_BADARG, "gcn_csr_create: NULL edge arrays");
+    if (n_edges > (1ll << 40)) return fail(GCN_ERR_RANGE, "gcn_csr_create: too many edges");
+    gcn_csr* a = new (std::nothrow) gcn_csr();
+    if (!a) return fail(GCN_ERR_OOM, "host allocation failed");
+    (void)hipGetDevice(&a->device);
+    int rc = create_impl(a, n, n_edges, src, dst, flags, (hipStream_t)stream);
+    if (rc != GCN_OK) {
+        gcn_csr_destroy(a);
+        return rc;
+    }
+    *out = a;
+    return GCN_OK;
+}
+
+int gcn_csr_create_from_csr(gcn_csr** out, int64_t n, const int64_t* rowptr, const int32_t* colidx,
+                            const float* val, uint32_t flags, void* stream) {
+    if (!out) return fail(GCN_ERR_BADARG, "gcn_csr_create_from_csr: NULL out");
+    *out = nullptr;
+    if (n <= 0 || !rowptr) return fail(GCN_ERR_BADARG, "gcn_csr_create_from_csr: n must be positive, rowptr non-NULL");
+    if (n >= (1ll << 31)) return fail(GCN_ERR_RANGE, "gcn_csr_create_from_csr: n must be below 2^31");
+    gcn_csr* a = new (std::nothrow) gcn_csr();
+    if (!a) return fail(GCN_ERR_OOM, "host allocation failed");
+    (void)hipGetDevice(&a->device);
+    int rc = from_csr_impl(a, n, rowptr, colidx, val, flags, (hipStream_t)stream);
+    if (rc != GCN_OK) {
+        gcn_csr_destroy(a);
+        return rc;
+    }
+    *out = a;
+    return GCN_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,182 @@
+// One GCN layer forward / backward and the full-batch epoch, composed from the SpMM, the dense
+// products and the loss kernel in the order of the paper's "Forward Propagation" and
+// "Backpropagation Derivations" (Equations 1-3).  A G is computed once per layer and used for both
+// the weight gradient and the propagated gradient, as the paper's 1D analysis notes.
+#include <vector>
+
+#include "common.h"
+
+namespace gcn {
+
+static int resolve_order(int order, int32_t f_in, int32_t f_out) {
+    if (order == GCN_ORDER_GEMM_FIRST || order == GCN_ORDER_SPMM_FIRST) return order;
+    // The SpMM costs in proportion to its width: run it at min(f_in, f_out).
+    return f_out <= f_in ? GCN_ORDER_GEMM_FIRST : GCN_ORDER_SPMM_FIRST;
+}
+
+static int layer_forward_impl(gcn_csr* a, int32_t f_in, int32_t f_out, const float* Hin, int64_t ldh, const float* W,
+                              const float* bias, float* Z, float* Hout, float* T, int order, int act, hipStream_t s) {
+    const int64_t n = a->n;
+    order = resolve_order(order, f_in, f_out);
+    // When the caller passes Hout == Z only the activated matrix is wanted and ReLU is fused into
+    // the kernel that produces Z; otherwise Z is kept (backward needs it) and H is a second pass.
+    const bool in_place = (act == GCN_ACT_RELU) && Hout == Z;
+    if (order == GCN_ORDER_GEMM_FIRST) {
+        GCN_TRY(gemm_launch(0, 0, n, f_out, f_in, Hin, ldh, W, f_out, T, f_out, nullptr, GCN_EPI_NONE, nullptr, 0, s));
+        GCN_TRY(spmm_launch(a, a->At, f_out, T, f_out, Z, f_out, (in_place && !bias) ? GCN_EPI_RELU : GCN_EPI_NONE,
+                            nullptr, 0, s));
+        if (bias) GCN_TRY(bias_add_launch(n, f_out, Z, f_out, bias, in_place ? 1 : 0, s));
+    } else {
+        GCN_TRY(spmm_launch(a, a->At, f_in, Hin, ldh, T, f_in, GCN_EPI_NONE, nullptr, 0, s));
+        GCN_TRY(gemm_launch(0, 0, n, f_out, f_in, T, f_in, W, f_out, Z, f_out, bias,
+                            in_place ? GCN_EPI_RELU : GCN_EPI_NONE, nullptr, 0, s));
+    }
+    if (act == GCN_ACT_RELU && !in_place) GCN_TRY(relu_launch(n, f_out, Z, f_out, Hout, f_out, s));
+    if (act == GCN_ACT_NONE && Hout && Hout != Z)
+        GCN_HIP_TRY(hipMemcpyAsync(Hout, Z, (size_t)n * f_out * sizeof(float), hipMemcpyDeviceToDevice, s));
+    return GCN_OK;
+}
+
+static int layer_backward_impl(gcn_csr* a, int32_t f_in, int32_t f_out, const float* Hin, int64_t ldh,
+                               const float* Zprev, const float* W, const float* G, const float* T, float* S, float* Y,
+                               float* dbias, float* Gprev, int order, hipStream_t s) {
+    const int64_t n = a->n;
+    order = resolve_order(order, f_in, f_out);
+    if (dbias) GCN_TRY(colsum_launch(n, f_out, G, f_out, dbias, s));
+    if (order == GCN_ORDER_GEMM_FIRST) {
+        // S = A G;  Y = Hin^T S;  Gprev = (S W^T) (.) sigma'(Zprev)
+        GCN_TRY(spmm_launch(a, a->A, f_out, G, f_out, S, f_out, GCN_EPI_NONE, nullptr, 0, s));
+        GCN_TRY(gemm_launch(1, 0, f_in, f_out, n, Hin, ldh, S, f_out, Y, f_out, nullptr, GCN_EPI_NONE, nullptr, 0, s));
+        if (Gprev)
+            GCN_TRY(gemm_launch(0, 1, n, f_in, f_out, S, f_out, W, f_out, Gprev, f_in, nullptr, GCN_EPI_MASK, Zprev, f_in, s));
+    } else {
+        // Y = (A^T Hin)^T G = T^T G;  Gprev = (A (G W^T)) (.) sigma'(Zprev): the same matrices, with the
+        // SpMM at width f_in.
+        GCN_TRY(gemm_launch(1, 0, f_in, f_out, n, T, f_in, G, f_out, Y, f_out, nullptr, GCN_EPI_NONE, nullptr, 0, s));
+        if (Gprev) {
+            GCN_TRY(gemm_launch(0, 1, n, f_in, f_out, G, f_out, W, f_out, S, f_in, nullptr, GCN_EPI_NONE, nullptr, 0, s));
+            GCN_TRY(spmm_launch(a, a->A, f_in, S, f_in, Gprev, f_in, GCN_EPI_MASK, Zprev, f_in, s));
+        }
+    }
+    return GCN_OK;
+}
+
+// ---- epoch workspace layout -------------------------------------------------------------------
+struct EpochLayout {
+    std::vector<size_t> Z, H, T, G;   // byte offsets per layer index 0..L_w-1 (layer l = index + 1)
+    size_t S = 0, total = 0;
+    std::vector<int> order;
+};
+
+static size_t round256(size_t b) { return (b + 255) & ~(size_t)255; }
+
+static EpochLayout epoch_layout(int64_t n, int32_t L, const int32_t* dims, int order) {
+    EpochLayout lay;
+    size_t off = 0, smax = 0;
+    auto take = [&](size_t elems) { size_t o = off; off += round256(elems * sizeof(float)); return o; };
+    for (int l = 0; l < L; ++l) {
+        const int32_t fi = dims[l], fo = dims[l + 1];
+        const int ord = resolve_order(order, fi, fo);
+        lay.order.push_back(ord);
+        lay.Z.push_back(take((size_t)n * fo));
+        lay.H.push_back(l + 1 < L ? take((size_t)n * fo) : lay.Z.back());
+        lay.T.push_back(take((size_t)n * (ord == GCN_ORDER_GEMM_FIRST ? fo : fi)));
+        lay.G.push_back(take((size_t)n * fo));
+        const size_t sneed = (size_t)n * (ord == GCN_ORDER_GEMM_FIRST ? fo : fi);
+        if (sneed > smax) smax = sneed;
+    }
+    lay.S = take(smax);
+    lay.total = off;
+    return lay;
+}
+
+static int check_dims(int64_t n, int32_t L, const int32_t* dims) {
+    if (n <= 0 || L <= 0 || L > 64 || !dims) return fail(GCN_ERR_BADARG, "epoch: need n > 0, 1 <= L_w <= 64, dims non-NULL");
+    for (int l = 0; l <= L; ++l)
+        if (dims[l] <= 0 || dims[l] > 65536) return fail(GCN_ERR_BADARG, "epoch: dims[%d] = %d out of range", l, dims[l]);
+    return GCN_OK;
+}
+
+}  // namespace gcn
+
+using namespace gcn;
+
+extern "C" {
+
+int gcn_layer_forward(gcn_csr* a, int32_t f_in, int32_t f_out, const float* Hin, int64_t ldh, const float* W,
+                      const float* bias, float* Z, float* Hout, float* T, int order, int act, void* stream) {
+    if (!a || !Hin || !W || !Z || !T) return fail(GCN_ERR_BADARG, "gcn_layer_forward: NULL argument");
+    if (f_in <= 0 || f_out <= 0 || ldh < f_in) return fail(GCN_ERR_BADARG, "gcn_layer_forward: bad sizes");
+    if (order < GCN_ORDER_AUTO || order > GCN_ORDER_SPMM_FIRST) return fail(GCN_ERR_BADARG, "gcn_layer_forward: unknown order");
+    if (act != GCN_ACT_NONE && act != GCN_ACT_RELU) return fail(GCN_ERR_BADARG, "gcn_layer_forward: unknown activation");
+    if (act == GCN_ACT_RELU && !Hout) return fail(GCN_ERR_BADARG, "gcn_layer_forward: ReLU needs Hout");
+    if (!a->has_t) return fail(GCN_ERR_NOTRANSPOSE, "gcn_layer_forward needs GCN_BUILD_TRANSPOSE");
+    return layer_forward_impl(a, f_in, f_out, Hin, ldh, W, bias, Z, Hout, T, order, act, (hipStream_t)stream);
+}
+
+int gcn_layer_backward(gcn_csr* a, int32_t f_in, int32_t f_out, const float* Hin, int64_t ldh, const float* Zprev,
+                       const float* W, const float* G, const float* T, float* S, float* Y, float* dbias,
+                       float* Gprev, int order, void* stream) {
+    if (!a || !W || !G || !S || !Y) return fail(GCN_ERR_BADARG, "gcn_layer_backward: NULL argument");
+    if (f_in <= 0 || f_out <= 0) return fail(GCN_ERR_BADARG, "gcn_layer_backward: bad sizes");
+    if (order < GCN_ORDER_AUTO || order > GCN_ORDER_SPMM_FIRST) return fail(GCN_ERR_BADARG, "gcn_layer_backward: unknown order");
+    const int ord = resolve_order(order, f_in, f_out);
+    if (ord == GCN_ORDER_GEMM_FIRST && (!Hin || ldh < f_in)) return fail(GCN_ERR_BADARG, "gcn_layer_backward: Hin needed");
+    if (ord == GCN_ORDER_SPMM_FIRST && !T) return fail(GCN_ERR_BADARG, "gcn_layer_backward: SpMM-first order needs the forward T");
+    if (Gprev && !Zprev) return fail(GCN_ERR_BADARG, "gcn_layer_backward: Gprev needs Zprev");
+    return layer_backward_impl(a, f_in, f_out, Hin, ldh, Zprev, W, G, T, S, Y, dbias, Gprev, order, (hipStream_t)stream);
+}
+
+size_t gcn_epoch_workspace_bytes(int64_t n, int32_t L_w, const int32_t* dims, int order) {
+    if (check_dims(n, L_w, dims) != GCN_OK) return 0;
+    return epoch_layout(n, L_w, dims, order).total;
+}
+
+int gcn_epoch_view(int64_t n, int32_t L_w, const int32_t* dims, int order, void* workspace, int32_t l, float** Z,
+                   float** G) {
+    GCN_TRY(check_dims(n, L_w, dims));
+    if (!workspace || l < 1 || l > L_w) return fail(GCN_ERR_BADARG, "gcn_epoch_view: bad layer or workspace");
+    EpochLayout lay = epoch_layout(n, L_w, dims, order);
+    if (Z) *Z = (float*)((char*)workspace + lay.Z[l - 1]);
+    if (G) *G = (float*)((char*)workspace + lay.G[l - 1]);
+    return GCN_OK;
+}
+
+int gcn_epoch(gcn_csr* a, int32_t L_w, const int32_t* dims, const float* H0, const int32_t* labels, float* const* W,
+              float* const* Y, float lr, float* loss, void* workspace, size_t workspace_bytes, int order, void* stream) {
+    if (!a || !H0 || !labels || !W || !Y || !loss || !workspace) return fail(GCN_ERR_BADARG, "gcn_epoch: NULL argument");
+    GCN_TRY(check_dims(a->n, L_w, dims));
+    if (order < GCN_ORDER_AUTO || order > GCN_ORDER_SPMM_FIRST) return fail(GCN_ERR_BADARG, "gcn_epoch: unknown order");
+    if (!a->has_t) return fail(GCN_ERR_NOTRANSPOSE, "gcn_epoch needs GCN_BUILD_TRANSPOSE");
+    for (int l = 0; l < L_w; ++l)
+        if (!W[l] || !Y[l]) return fail(GCN_ERR_BADARG, "gcn_epoch: NULL weight or gradient pointer at layer %d", l + 1);
+    if (((uintptr_t)workspace & 255u) != 0) return fail(GCN_ERR_BADARG, "gcn_epoch: workspace must be 256-byte aligned");
+    const int64_t n = a->n;
+    EpochLayout lay = epoch_layout(n, L_w, dims, order);
+    if (workspace_bytes < lay.total)
+        return fail(GCN_ERR_WORKSPACE, "gcn_epoch: workspace has %zu bytes, %zu needed", workspace_bytes, lay.total);
+    hipStream_t s = (hipStream_t)stream;
+    char* ws = (char*)workspace;
+    auto at = [&](size_t off) { return (float*)(ws + off); };
+
+    const float* Hin = H0;
+    for (int l = 0; l < L_w; ++l) {
+        const bool last = (l + 1 == L_w);
+        GCN_TRY(layer_forward_impl(a, dims[l], dims[l + 1], Hin, dims[l], W[l], nullptr, at(lay.Z[l]),
+                                   last ? nullptr : at(lay.H[l]), at(lay.T[l]), lay.order[l],
+                                   last ? GCN_ACT_NONE : GCN_ACT_RELU, s));
+        Hin = at(lay.H[l]);
+    }
+    GCN_TRY(gcn_softmax_nll(n, dims[L_w], at(lay.Z[L_w - 1]), dims[L_w], labels, loss, at(lay.G[L_w - 1]), dims[L_w], stream));
+    for (int l = L_w - 1; l >= 0; --l) {
+        const float* Hl = l > 0 ? at(lay.H[l - 1]) : H0;
+        GCN_TRY(layer_backward_impl(a, dims[l], dims[l + 1], Hl, dims[l], l > 0 ? at(lay.Z[l - 1]) : nullptr, W[l],
+                                    at(lay.G[l]), at(lay.T[l]), at(lay.S), Y[l], nullptr, l > 0 ? at(lay.G[l - 1]) : nullptr,
+                                    lay.order[l], s));
+    }
+    if (lr != 0.f)
+        for (int l = 0; l < L_w; ++l) GCN_TRY(axpy_launch((int64_t)dims[l] * dims[l + 1], W[l], Y[l], lr, s));
+    return GCN_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,399 @@
+// SpMM: Z = op(A) X for a compressed-row matrix and a tall-skinny dense fp32 operand -- the
+// "SpMM" of the paper's sections "Graph Neural Networks" and "A One-Dimensional (1D) Algorithm",
+// the operation the paper calls the most time consuming.
+//
+// Main kernel: nonzero-split.  Every wavefront owns CHUNK = 512 consecutive stored entries no
+// matter how they fall into rows, so a 20,000-entry row and 20,000 one-entry rows cost the same.
+// The wavefront is cut into G = 64/LPR lane groups; a group of LPR lanes covers one gathered row
+// of X (VEC floats per lane) and walks its own contiguous slice of the chunk.  Row boundaries come
+// from one precomputed 32-bit flag word per 32 entries, so the walk never touches rowptr.
+//   * a row that starts and ends inside one group's slice is written directly;
+//   * pieces of a row spread over several groups are joined by a segmented suffix scan across the
+//     groups (lane shuffles), in a fixed order;
+//   * pieces spread over several wavefronts go through a per-chunk carry buffer and a small
+//     second kernel that adds them in ascending chunk order.
+// No floating-point atomics are used anywhere: results are bit-reproducible run to run.
+// Column indices and values are read with coalesced 16-byte loads into LDS first and consumed
+// from there; the gathered rows of X are read with one 16-byte load per lane.
+#include "common.h"
+
+namespace gcn {
+
+static constexpr int WAVES_PER_BLOCK = 4;
+static constexpr int SUB_STRIDE = SUB + 4;                         // LDS padding: groups hit different banks
+static constexpr int LDS_PER_WAVE = SUBS_PER_CHUNK * SUB_STRIDE;   // ints
+
+struct SplitArgs {
+    const int32_t* colidx;
+    const float* val;
+    const uint32_t* flags;
+    const int32_t* sub_row;
+    const int32_t* ne_rows;   // NULL: row index == non-empty-row index
+    const int64_t* rp;        // rowptr over non-empty rows
+    int64_t nnz, nsub, nchunks;
+    int32_t f;
+    const float* X;
+    int64_t ldx;
+    float* Z;
+    int64_t ldz;
+    const float* Zprev;
+    int64_t ldzprev;
+    float* carry;             // [nchunks][f]
+};
+
+template <int VEC> struct Vec;
+template <> struct Vec<4> { using T = float4; };
+template <> struct Vec<1> { using T = float; };
+
+template <int VEC>
+__device__ __forceinline__ void load_vec(float (&d)[VEC], const float* p) {
+    if constexpr (VEC == 4) {
+        float4 v = *reinterpret_cast<const float4*>(p);
+        d[0] = v.x; d[1] = v.y; d[2] = v.z; d[3] = v.w;
+    } else {
+        d[0] = *p;
+    }
+}
+
+template <int VEC>
+__device__ __forceinline__ void store_vec(float* p, const float (&d)[VEC]) {
+    if constexpr (VEC == 4) {
+        *reinterpret_cast<float4*>(p) = make_float4(d[0], d[1], d[2], d[3]);
+    } else {
+        *p = d[0];
+    }
+}
+
+template <int VEC, int EPI>
+__device__ __forceinline__ void epilogue_store(float* z, const float* zprev, float (&v)[VEC]) {
+    if constexpr (EPI == GCN_EPI_RELU) {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) v[e] = v[e] > 0.f ? v[e] : 0.f;
+    } else if constexpr (EPI == GCN_EPI_MASK) {
+        float m[VEC];
+        load_vec<VEC>(m, zprev);
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) v[e] = m[e] > 0.f ? v[e] : 0.f;
+    }
+    store_vec<VEC>(z, v);
+}
+
+template <int LPR, int VEC, int EPI>
+__global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void k_spmm_split(SplitArgs a) {
+    constexpr int G = 64 / LPR;                 // lane groups per wavefront
+    constexpr int NW = SUBS_PER_CHUNK / G;      // flag words per group
+    static_assert(NW >= 1, "a group needs at least one flag word");
+    __shared__ int32_t s_col[WAVES_PER_BLOCK][LDS_PER_WAVE];
+    __shared__ float s_val[WAVES_PER_BLOCK][LDS_PER_WAVE];
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t c = (int64_t)blockIdx.x * WAVES_PER_BLOCK + wave;
+    if (c >= a.nchunks) return;                 // whole wavefront leaves; no block-wide barrier below
+    const int g = lane / LPR, li = lane % LPR;
+    const int col0 = blockIdx.y * (LPR * VEC) + li * VEC;
+    const bool col_ok = col0 < a.f;
+    const int64_t k0 = c * CHUNK;
+
+    // ---- stage the chunk's column indices and values in LDS (coalesced 16-byte loads) ----
+    int32_t* lc = s_col[wave];
+    float* lv = s_val[wave];
+#pragma unroll
+    for (int t = 0; t < CHUNK / 256; ++t) {
+        const int i = t * 256 + lane * 4;
+        const int64_t k = k0 + i;
+        int4 cc = make_int4(0, 0, 0, 0);
+        float4 vv = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (k + 4 <= a.nnz) {
+            cc = *reinterpret_cast<const int4*>(a.colidx + k);
+            vv = *reinterpret_cast<const float4*>(a.val + k);
+        } else {
+            if (k + 0 < a.nnz) { cc.x = a.colidx[k + 0]; vv.x = a.val[k + 0]; }
+            if (k + 1 < a.nnz) { cc.y = a.colidx[k + 1]; vv.y = a.val[k + 1]; }
+            if (k + 2 < a.nnz) { cc.z = a.colidx[k + 2]; vv.z = a.val[k + 2]; }
+        }
+        const int p = i + (i >> 5) * (SUB_STRIDE - SUB);
+        *reinterpret_cast<int4*>(lc + p) = cc;
+        *reinterpret_cast<float4*>(lv + p) = vv;
+    }
+    // each wavefront reads only what it wrote; LDS operations of one wavefront complete in order
+    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+
+    // ---- walk this group's slice ----
+    const int64_t j0 = c * SUBS_PER_CHUNK + (int64_t)g * NW;
+    int32_t q = a.sub_row[j0];
+    uint32_t first = a.flags[j0];
+    q -= (int32_t)(first & 1u);                 // a start bit at the very first entry re-increments q
+    float acc[VEC], head[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) { acc[e] = 0.f; head[e] = 0.f; }
+    bool owned = false;                         // has this group seen a row start yet?
+    const float* xbase = a.X + col0;
+
+    for (int w = 0; w < NW; ++w) {
+        const int64_t j = j0 + w;
+        uint32_t mask = (w == 0) ? first : a.flags[j];
+        const int64_t left = a.nnz - j * SUB;
+        const int cnt = left >= SUB ? SUB : (left > 0 ? (int)left : 0);
+        const int base = (g * NW + w) * SUB_STRIDE;
+        for (int b = 0; b < cnt; b += 4) {
+            const int4 cc = *reinterpret_cast<const int4*>(lc + base + b);
+            const float4 vv = *reinterpret_cast<const float4*>(lv + base + b);
+            const int32_t cs[4] = {cc.x, cc.y, cc.z, cc.w};
+            const float vs[4] = {vv.x, vv.y, vv.z, vv.w};
+            float x[4][VEC];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                if (b + e < cnt && col_ok) load_vec<VEC>(x[e], xbase + (int64_t)cs[e] * a.ldx);
+                else {
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) x[e][v] = 0.f;
+                }
+            }
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                if (b + e < cnt) {
+                    if (mask & 1u) {            // entry starts a row: close the fragment before it
+                        if (owned) {
+                            if (col_ok) {
+                                const int64_t row = a.ne_rows ? a.ne_rows[q] : q;
+                                epilogue_store<VEC, EPI>(a.Z + row * a.ldz + col0,
+                                                         EPI == GCN_EPI_MASK ? a.Zprev + row * a.ldzprev + col0 : nullptr,
+                                                         acc);
+                            }
+                        } else {
+#pragma unroll
+                            for (int v = 0; v < VEC; ++v) head[v] = acc[v];
+                            owned = true;
+                        }
+                        q += 1;
+#pragma unroll
+                        for (int v = 0; v < VEC; ++v) acc[v] = 0.f;
+                    }
+                    mask >>= 1;
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) acc[v] = fmaf(vs[e], x[e][v], acc[v]);
+                }
+            }
+        }
+    }
+    if (!owned) {                               // the whole slice lies inside one row
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) { head[v] = acc[v]; acc[v] = 0.f; }
+    }
+
+    // ---- join fragments across groups: R_g = head_g + (owned_g ? 0 : R_{g+1}) ----
+    float R[VEC];
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) R[v] = head[v];
+    int stop = owned ? 1 : 0;
+#pragma unroll
+    for (int d = 1; d < G; d <<= 1) {
+        float Rp[VEC];
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) Rp[v] = __shfl_down(R[v], d * LPR, 64);
+        const int sp = __shfl_down(stop, d * LPR, 64);
+        if (g + d < G && !stop) {
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) R[v] += Rp[v];
+            stop = sp;
+        }
+    }
+    float T[VEC];
+    int stop_next = 0;
+    if constexpr (G > 1) {
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) T[v] = __shfl_down(R[v], LPR, 64);
+        stop_next = __shfl_down(stop, LPR, 64);
+    }
+    if (G == 1 || g == G - 1) {
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) T[v] = 0.f;
+        stop_next = 0;
+    }
+    if (g == 0 && col_ok) store_vec<VEC>(a.carry + c * a.f + col0, R);
+
+    if (owned && col_ok) {
+        // the row opened last in this slice: add what later groups of this wavefront hold for it
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) acc[v] += T[v];
+        const int64_t knext = k0 + CHUNK;
+        const bool runs_on = !stop_next && knext < a.nnz && !(a.flags[(c + 1) * SUBS_PER_CHUNK] & 1u);
+        const int64_t row = a.ne_rows ? a.ne_rows[q] : q;
+        if (runs_on) store_vec<VEC>(a.Z + row * a.ldz + col0, acc);     // finished by k_spmm_fixup
+        else epilogue_store<VEC, EPI>(a.Z + row * a.ldz + col0,
+                                      EPI == GCN_EPI_MASK ? a.Zprev + row * a.ldzprev + col0 : nullptr, acc);
+    }
+}
+
+// Adds, in ascending chunk order, the carries of the chunks a row runs on into, then applies the
+// epilogue.  One LPR-lane group per chunk; only the first continuation chunk of a row acts.
+template <int LPR, int VEC, int EPI>
+__global__ __launch_bounds__(256) void k_spmm_fixup(SplitArgs a) {
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t c = t / LPR + 1;              // chunk 0 starts a row by definition
+    const int li = (int)(t % LPR);
+    if (c >= a.nchunks) return;
+    const int col0 = blockIdx.y * (LPR * VEC) + li * VEC;
+    if (col0 >= a.f) return;
+    const int64_t j0 = c * SUBS_PER_CHUNK;
+    if (a.flags[j0] & 1u) return;               // the chunk starts on a row start: no carry-in
+    const int32_t q = a.sub_row[j0];
+    const int64_t rs = a.rp[q], re = a.rp[q + 1];
+    if (c != rs / CHUNK + 1) return;            // an earlier chunk leads this row
+    const int64_t c_last = (re - 1) / CHUNK;
+    float sum[VEC];
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) sum[v] = 0.f;
+    for (int64_t cc = c; cc <= c_last; ++cc) {
+        float part[VEC];
+        load_vec<VEC>(part, a.carry + cc * a.f + col0);
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) sum[v] += part[v];
+    }
+    const int64_t row = a.ne_rows ? a.ne_rows[q] : q;
+    float* z = a.Z + row * a.ldz + col0;
+    float cur[VEC];
+    load_vec<VEC>(cur, z);
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) cur[v] += sum[v];
+    epilogue_store<VEC, EPI>(z, EPI == GCN_EPI_MASK ? a.Zprev + row * a.ldzprev + col0 : nullptr, cur);
+}
+
+// Rows without stored entries produce zeros (any epilogue maps 0 to 0).
+__global__ void k_zero_empty_rows(int64_t n, const int64_t* __restrict__ rowptr, int32_t f, float* __restrict__ Z,
+                                  int64_t ldz) {
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t i = t / f;
+    const int j = (int)(t % f);
+    if (i >= n) return;
+    if (rowptr[i + 1] == rowptr[i]) Z[i * ldz + j] = 0.f;
+}
+
+// Reference-shaped kernel: one thread per output element walks its row.  Kept as a selectable
+// second implementation (GCN_CFG_SPMM_ALGO = 1) for cross-checks; never chosen automatically.
+template <int EPI>
+__global__ void k_spmm_rowwise(int64_t n, const int64_t* __restrict__ rowptr, const int32_t* __restrict__ colidx,
+                               const float* __restrict__ val, int32_t f, const float* __restrict__ X, int64_t ldx,
+                               float* __restrict__ Z, int64_t ldz, const float* __restrict__ Zprev, int64_t ldzprev) {
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t i = t / f;
+    const int j = (int)(t % f);
+    if (i >= n) return;
+    float acc = 0.f;
+    for (int64_t k = rowptr[i]; k < rowptr[i + 1]; ++k) acc = fmaf(val[k], X[(int64_t)colidx[k] * ldx + j], acc);
+    if (EPI == GCN_EPI_RELU) acc = acc > 0.f ? acc : 0.f;
+    if (EPI == GCN_EPI_MASK) acc = Zprev[i * ldzprev + j] > 0.f ? acc : 0.f;
+    Z[i * ldz + j] = acc;
+}
+
+template <int LPR, int VEC>
+static int launch_split(const SplitArgs& args, int epilogue, hipStream_t s) {
+    const int tile = LPR * VEC;
+    const unsigned ytiles = (unsigned)((args.f + tile - 1) / tile);
+    const dim3 grid((unsigned)((args.nchunks + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK), ytiles);
+    const int64_t fix_threads = (args.nchunks - 1) * LPR;
+    const dim3 fgrid((unsigned)((fix_threads + 255) / 256), ytiles);
+    timing_begin(s);
+    switch (epilogue) {
+        case GCN_EPI_NONE: hipLaunchKernelGGL((k_spmm_split<LPR, VEC, GCN_EPI_NONE>), grid, dim3(64 * WAVES_PER_BLOCK), 0, s, args); break;
+        case GCN_EPI_RELU: hipLaunchKernelGGL((k_spmm_split<LPR, VEC, GCN_EPI_RELU>), grid, dim3(64 * WAVES_PER_BLOCK), 0, s, args); break;
+        default: hipLaunchKernelGGL((k_spmm_split<LPR, VEC, GCN_EPI_MASK>), grid, dim3(64 * WAVES_PER_BLOCK), 0, s, args); break;
+    }
+    timing_end(s);
+    GCN_LAUNCH_CHECK();
+    if (fix_threads > 0) {
+        switch (epilogue) {
+            case GCN_EPI_NONE: hipLaunchKernelGGL((k_spmm_fixup<LPR, VEC, GCN_EPI_NONE>), fgrid, dim3(256), 0, s, args); break;
+            case GCN_EPI_RELU: hipLaunchKernelGGL((k_spmm_fixup<LPR, VEC, GCN_EPI_RELU>), fgrid, dim3(256), 0, s, args); break;
+            default: hipLaunchKernelGGL((k_spmm_fixup<LPR, VEC, GCN_EPI_MASK>), fgrid, dim3(256), 0, s, args); break;
+        }
+        GCN_LAUNCH_CHECK();
+    }
+    return GCN_OK;
+}
+
+static inline bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
+
+int spmm_launch(gcn_csr* a, const Matrix& m, int32_t f, const float* X, int64_t ldx, float* Z, int64_t ldz,
+                int epilogue, const float* Zprev, int64_t ldzprev, hipStream_t s) {
+    const int64_t n = a->n, nnz = a->nnz;
+    if (m.n_ne < n) {
+        const int64_t work = n * f;
+        hipLaunchKernelGGL(k_zero_empty_rows, dim3((unsigned)((work + 255) / 256)), dim3(256), 0, s, n, m.rowptr, f, Z, ldz);
+        GCN_LAUNCH_CHECK();
+    }
+    if (nnz == 0) return GCN_OK;
+    int algo = config().spmm_algo;
+    if (algo == 0) algo = 2;
+    if (algo == 1) {
+        const int64_t work = n * f;
+        const dim3 grid((unsigned)((work + 255) / 256));
+        if (work / 256 >= (1ll << 31)) return fail(GCN_ERR_RANGE, "gcn_spmm: n*f too large for the row-wise kernel");
+        timing_begin(s);
+        switch (epilogue) {
+            case GCN_EPI_NONE: hipLaunchKernelGGL(k_spmm_rowwise<GCN_EPI_NONE>, grid, dim3(256), 0, s, n, m.rowptr, m.colidx, m.val, f, X, ldx, Z, ldz, Zprev, ldzprev); break;
+            case GCN_EPI_RELU: hipLaunchKernelGGL(k_spmm_rowwise<GCN_EPI_RELU>, grid, dim3(256), 0, s, n, m.rowptr, m.colidx, m.val, f, X, ldx, Z, ldz, Zprev, ldzprev); break;
+            default: hipLaunchKernelGGL(k_spmm_rowwise<GCN_EPI_MASK>, grid, dim3(256), 0, s, n, m.rowptr, m.colidx, m.val, f, X, ldx, Z, ldz, Zprev, ldzprev); break;
+        }
+        timing_end(s);
+        GCN_LAUNCH_CHECK();
+        return GCN_OK;
+    }
+
+    // carry buffer: one f-wide partial row per chunk
+    const size_t need = (size_t)m.nchunks * (size_t)f * sizeof(float);
+    if (need > a->carry_bytes) {
+        if (a->carry) {
+            GCN_HIP_TRY(hipDeviceSynchronize());
+            device_free(a->carry);
+            a->carry = nullptr;
+            a->carry_bytes = 0;
+        }
+        GCN_TRY(device_alloc((void**)&a->carry, need));
+        a->carry_bytes = need;
+    }
+    SplitArgs args;
+    args.colidx = m.colidx; args.val = m.val; args.flags = m.flags; args.sub_row = m.sub_row;
+    args.ne_rows = m.ne_rows; args.rp = m.ne_rowptr ? m.ne_rowptr : m.rowptr;
+    args.nnz = nnz; args.nsub = m.nsub; args.nchunks = m.nchunks; args.f = f;
+    args.X = X; args.ldx = ldx; args.Z = Z; args.ldz = ldz; args.Zprev = Zprev; args.ldzprev = ldzprev;
+    args.carry = a->carry;
+    if ((m.nchunks + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK >= (1ll << 31))
+        return fail(GCN_ERR_RANGE, "gcn_spmm: too many chunks for one launch");
+
+    const bool vec4 = (f % 4 == 0) && (ldx % 4 == 0) && (ldz % 4 == 0) && aligned16(X) && aligned16(Z) &&
+                      (epilogue != GCN_EPI_MASK || ((ldzprev % 4 == 0) && aligned16(Zprev)));
+    if (vec4) {
+        const int lanes = f / 4;
+        if (lanes <= 4) return launch_split<4, 4>(args, epilogue, s);
+        if (lanes <= 8) return launch_split<8, 4>(args, epilogue, s);
+        if (lanes <= 16) return launch_split<16, 4>(args, epilogue, s);
+        if (lanes <= 32) return launch_split<32, 4>(args, epilogue, s);
+        return launch_split<64, 4>(args, epilogue, s);
+    }
+    if (f <= 4) return launch_split<4, 1>(args, epilogue, s);
+    if (f <= 8) return launch_split<8, 1>(args, epilogue, s);
+    if (f <= 16) return launch_split<16, 1>(args, epilogue, s);
+    if (f <= 32) return launch_split<32, 1>(args, epilogue, s);
+    return launch_split<64, 1>(args, epilogue, s);
+}
+
+}  // namespace gcn
+
+using namespace gcn;
+
+extern "C" int gcn_spmm(gcn_csr* a, int trans, int32_t f, const float* X, int64_t ldx, float* Z, int64_t ldz,
+                        int epilogue, const float* Zprev, int64_t ldzprev, void* stream) {
+    if (!a || !X || !Z) return fail(GCN_ERR_BADARG, "gcn_spmm: NULL argument");
+    if (f <= 0 || ldx < f || ldz < f) return fail(GCN_ERR_BADARG, "gcn_spmm: need f > 0, ldx >= f, ldz >= f");
+    if (epilogue < GCN_EPI_NONE || epilogue > GCN_EPI_MASK) return fail(GCN_ERR_BADARG, "gcn_spmm: unknown epilogue");
+    if (epilogue == GCN_EPI_MASK && (!Zprev || ldzprev < f)) return fail(GCN_ERR_BADARG, "gcn_spmm: mask epilogue needs Zprev with ld >= f");
+    if (trans && !a->has_t) return fail(GCN_ERR_NOTRANSPOSE, "gcn_spmm: trans=1 needs GCN_BUILD_TRANSPOSE");
+    {   // X and Z must not overlap: the product gathers rows of X while rows of Z are written
+        const char* xb = (const char*)X; const char* xe = xb + ((size_t)(a->n - 1) * ldx + f) * sizeof(float);
+        const char* zb = (const char*)Z; const char* ze = zb + ((size_t)(a->n - 1) * ldz + f) * sizeof(float);
+        if (xb < ze && zb < xe) return fail(GCN_ERR_BADARG, "gcn_spmm: X and Z overlap");
+    }
+    return spmm_launch(a, trans ? a->At : a->A, f, X, ldx, Z, ldz, epilogue, Zprev, ldzprev, (hipStream_t)stream);
+}

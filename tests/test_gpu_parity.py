@@ -1,0 +1,521 @@
+"""GPU parity: every C-ABI call of the HIP library against the CPU oracle on the same seeded
+inputs.  Integer outputs (rowptr, colidx, degrees, the transposed arrays) and the normalised
+values must match bit for bit; floating-point outputs must satisfy tests/util.assert_close
+(1e-4 relative, with an rms floor for cancelling sums)."""
+import functools
+
+import numpy as np
+import pytest
+
+import oracle
+import synth
+from util import assert_close, dev, host, rel_fro
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@functools.lru_cache(maxsize=None)
+def G():
+    import paper_2005_03300_amd as g
+    g.lib()
+    return g
+
+
+def flags_all():
+    g = G()
+    return g.SYMMETRISE | g.ADD_SELF_LOOPS | g.NORM_SYM | g.BUILD_TRANSPOSE
+
+
+@functools.lru_cache(maxsize=None)
+def graph(name):
+    if name == "c1":
+        return synth.make_graph(synth.CONFIGS[1])
+    if name == "c2s":      # R-MAT, skewed, mean degree ~ 30
+        return synth.make_graph(synth.scaled(2, 64))
+    if name == "c3s":      # dense power law, heavy rows far longer than one chunk
+        return synth.make_graph(synth.scaled(3, 32))
+    if name == "c4s":      # sparse R-MAT with many one-entry rows
+        return synth.make_graph(synth.scaled(4, 256))
+    if name == "c5s":
+        return synth.make_graph(synth.scaled(5, 512))
+    if name == "star":     # one row with n entries: spans ~100 chunks
+        n = 50_001
+        return (n,) + synth.star(n)
+    if name == "ring":
+        return (1000,) + synth.ring(1000)
+    if name == "one":
+        return 1, np.zeros(0, np.int32), np.zeros(0, np.int32)
+    if name == "tiny":
+        return 3, np.array([0, 1], np.int32), np.array([1, 2], np.int32)
+    raise KeyError(name)
+
+
+@functools.lru_cache(maxsize=None)
+def oracle_csr(name, symmetrise=True, self_loops=True, norm="sym", transpose=False):
+    n, src, dst = graph(name)
+    return oracle.build_csr(n, src, dst, symmetrise, self_loops, norm, transpose)
+
+
+def gpu_csr(name, symmetrise=True, self_loops=True, norm="sym"):
+    g = G()
+    n, src, dst = graph(name)
+    fl = g.BUILD_TRANSPOSE | (g.SYMMETRISE if symmetrise else 0) | (g.ADD_SELF_LOOPS if self_loops else 0) | \
+        (g.NORM_SYM if norm == "sym" else 0)
+    return g.gcn_csr_create(n, dev(src), dev(dst), fl)
+
+
+ALL_GRAPHS = ["c1", "c2s", "c3s", "c4s", "c5s", "star", "ring", "one", "tiny"]
+
+
+# ------------------------------------------------------------------------------------------------
+# a1 / a2: construction and transpose, bit-exact
+# ------------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("name", ALL_GRAPHS)
+def test_csr_build_bit_exact(name):
+    a = gpu_csr(name)
+    ref = oracle_csr(name)
+    assert (a.n, a.nnz, a.max_degree) == (ref.n, ref.nnz, int(ref.deg.max()))
+    rowptr, colidx, val, deg = [host(t) for t in a.arrays(False)]
+    np.testing.assert_array_equal(rowptr, ref.rowptr)
+    np.testing.assert_array_equal(colidx, ref.colidx)
+    np.testing.assert_array_equal(deg, ref.deg)
+    np.testing.assert_array_equal(val.view(np.uint32), ref.val.view(np.uint32))
+    # symmetrised + symmetric values: the stored transpose is the same arrays again
+    rt, ct, vt, _ = [host(t) for t in a.arrays(True)]
+    np.testing.assert_array_equal(rt, ref.rowptr)
+    np.testing.assert_array_equal(ct, ref.colidx)
+    np.testing.assert_array_equal(vt.view(np.uint32), ref.val.view(np.uint32))
+    a.close()
+
+
+@pytest.mark.parametrize("name", ["c2s", "c4s", "tiny"])
+@pytest.mark.parametrize("self_loops", [True, False])
+@pytest.mark.parametrize("norm", ["sym", "none"])
+def test_directed_build_and_transpose_bit_exact(name, self_loops, norm):
+    if norm == "sym" and not self_loops:
+        pytest.skip("rows can be empty without self loops; 1/sqrt(0) is not a use case")
+    a = gpu_csr(name, symmetrise=False, self_loops=self_loops, norm=norm)
+    ref = oracle_csr(name, False, self_loops, norm, False)
+    ref_t = oracle_csr(name, False, self_loops, norm, True)
+    for tr, r in ((False, ref), (True, ref_t)):
+        rowptr, colidx, val, deg = [host(t) for t in a.arrays(tr)]
+        np.testing.assert_array_equal(rowptr, r.rowptr)
+        np.testing.assert_array_equal(colidx, r.colidx)
+        np.testing.assert_array_equal(val.view(np.uint32), r.val.view(np.uint32))
+        np.testing.assert_array_equal(deg, ref.deg)
+    assert not np.array_equal(ref.colidx, ref_t.colidx) or name == "tiny"
+    a.close()
+
+
+def test_create_from_csr_roundtrip_and_transpose_twice():
+    g = G()
+    ref = oracle_csr("c2s", False, False, "none", False)        # directed, has empty rows
+    assert np.any(np.diff(ref.rowptr) == 0)
+    vals = synth.uniform_features(ref.nnz, 1, 7)[:, 0].copy()
+    a = g.gcn_csr_create_from_csr(ref.n, dev(ref.rowptr), dev(ref.colidx), dev(vals), g.BUILD_TRANSPOSE)
+    rowptr, colidx, val, deg = [host(t) for t in a.arrays(False)]
+    np.testing.assert_array_equal(rowptr, ref.rowptr)
+    np.testing.assert_array_equal(colidx, ref.colidx)
+    np.testing.assert_array_equal(val, vals)
+    np.testing.assert_array_equal(deg, np.diff(ref.rowptr).astype(np.int32))
+    rt, ct, vt, _ = a.arrays(True)
+    ref_t = oracle_csr("c2s", False, False, "none", True)
+    np.testing.assert_array_equal(host(rt), ref_t.rowptr)
+    np.testing.assert_array_equal(host(ct), ref_t.colidx)
+    # (A^T)^T == A, values included
+    b = g.gcn_csr_create_from_csr(ref.n, rt, ct, vt, g.BUILD_TRANSPOSE)
+    r2, c2, v2, _ = [host(t) for t in b.arrays(True)]
+    np.testing.assert_array_equal(r2, ref.rowptr)
+    np.testing.assert_array_equal(c2, ref.colidx)
+    np.testing.assert_array_equal(v2, vals)
+    a.close()
+    b.close()
+
+
+def test_error_paths_return_codes():
+    g = G()
+    src = dev(np.array([0, 5], np.int32))
+    dst = dev(np.array([1, 2], np.int32))
+    with pytest.raises(g.GcnError) as e:
+        g.gcn_csr_create(4, src, dst, flags_all())
+    assert e.value.code == -2
+    with pytest.raises(g.GcnError) as e:
+        g.gcn_csr_create(0, src, dst, flags_all())
+    assert e.value.code == -1
+    rowptr = dev(np.array([0, 2, 3], np.int64))
+    with pytest.raises(g.GcnError) as e:        # columns not ascending
+        g.gcn_csr_create_from_csr(2, rowptr, dev(np.array([1, 0, 1], np.int32)), None, 0)
+    assert e.value.code == -7
+    with pytest.raises(g.GcnError) as e:        # column out of range
+        g.gcn_csr_create_from_csr(2, rowptr, dev(np.array([0, 1, 2], np.int32)), None, 0)
+    assert e.value.code == -7
+    a = g.gcn_csr_create(3, dev(np.array([0], np.int32)), dev(np.array([1], np.int32)), g.ADD_SELF_LOOPS)
+    X = torch.zeros(3, 4, device="cuda")
+    Z = torch.zeros(3, 4, device="cuda")
+    with pytest.raises(g.GcnError) as e:        # no transpose stored
+        g.gcn_spmm(a, 1, X, Z)
+    assert e.value.code == -3
+    with pytest.raises(g.GcnError) as e:        # aliasing
+        g.gcn_spmm(a, 0, X, X)
+    assert e.value.code == -1
+    with pytest.raises(g.GcnError) as e:        # mask epilogue without Zprev
+        g.gcn_spmm(a, 0, X, Z, g.EPI_MASK, None)
+    assert e.value.code == -1
+    with pytest.raises(g.GcnError) as e:
+        g.gcn_config(99, 0)
+    assert e.value.code == -1
+    a.close()
+
+
+# ------------------------------------------------------------------------------------------------
+# a3: SpMM
+# ------------------------------------------------------------------------------------------------
+
+def run_spmm(a, X, trans=0, epilogue=0, Zprev=None, algo=0, ld_pad=0):
+    g = G()
+    g.gcn_config(g.CFG_SPMM_ALGO, algo)
+    try:
+        n, f = X.shape
+        Xd = torch.zeros(n, f + ld_pad, device="cuda")
+        Xd[:, :f] = dev(X)
+        Zd = torch.full((n, f + ld_pad), float("nan"), device="cuda")
+        Zp = None
+        if Zprev is not None:
+            Zp = torch.zeros(n, f + ld_pad, device="cuda")
+            Zp[:, :f] = dev(Zprev)
+            Zp = Zp[:, :f]
+        g.gcn_spmm(a, trans, Xd[:, :f], Zd[:, :f], epilogue, Zp)
+        torch.cuda.synchronize()
+        out = host(Zd)
+        if ld_pad:
+            assert np.all(np.isnan(out[:, f:])), "wrote outside the f columns"
+        return out[:, :f]
+    finally:
+        g.gcn_config(g.CFG_SPMM_ALGO, 0)
+
+
+@pytest.mark.parametrize("name", ["c1", "c2s", "c3s", "c4s", "c5s", "star", "one", "tiny"])
+@pytest.mark.parametrize("f", [16, 128])
+def test_spmm_parity_graphs(name, f):
+    a = gpu_csr(name)
+    ref = oracle_csr(name)
+    X = synth.uniform_features(ref.n, f, 11)
+    want = oracle.spmm(ref, X)
+    for algo in (2, 1):
+        assert_close(run_spmm(a, X, algo=algo), want, f"{name} f={f} algo={algo}")
+    a.close()
+
+
+@pytest.mark.parametrize("f", [1, 3, 8, 24, 41, 64, 100, 256, 300, 602])
+def test_spmm_parity_widths(f):
+    a = gpu_csr("c3s")
+    ref = oracle_csr("c3s")
+    X = synth.normal_features(ref.n, f, 12)
+    want = oracle.spmm(ref, X)
+    assert_close(run_spmm(a, X), want, f"f={f}")
+    assert_close(run_spmm(a, X, ld_pad=3), want, f"f={f} unaligned ld")     # scalar-lane path
+    if f % 4 == 0:
+        assert_close(run_spmm(a, X, ld_pad=4), want, f"f={f} padded ld")
+    a.close()
+
+
+@pytest.mark.parametrize("name", ["c2s", "c4s"])
+def test_spmm_directed_transpose_and_empty_rows(name):
+    a = gpu_csr(name, symmetrise=False, self_loops=False, norm="none")
+    ref = oracle_csr(name, False, False, "none", False)
+    ref_t = oracle_csr(name, False, False, "none", True)
+    assert np.any(np.diff(ref.rowptr) == 0)
+    X = synth.uniform_features(ref.n, 16, 13)
+    for algo in (2, 1):
+        assert_close(run_spmm(a, X, trans=0, algo=algo), oracle.spmm(ref, X), f"{name} A algo={algo}")
+        assert_close(run_spmm(a, X, trans=1, algo=algo), oracle.spmm(ref_t, X), f"{name} A^T algo={algo}")
+    a.close()
+
+
+@pytest.mark.parametrize("f", [16, 41])
+def test_spmm_epilogues(f):
+    g = G()
+    a = gpu_csr("c2s")
+    ref = oracle_csr("c2s")
+    X = synth.normal_features(ref.n, f, 14)
+    Zp = synth.normal_features(ref.n, f, 15)
+    plain = oracle.spmm(ref, X)
+    # both sides take the sign decision on the same fp32 Zprev; the ReLU decision is taken on each
+    # side's own sum, so compare max(.,0) of the oracle's sum with a tolerance
+    assert_close(run_spmm(a, X, epilogue=g.EPI_RELU), np.maximum(plain, 0), "relu")
+    assert_close(run_spmm(a, X, epilogue=g.EPI_MASK, Zprev=Zp), oracle.relu_mask(plain, Zp), "mask")
+    a.close()
+
+
+def test_spmm_exact_cases_and_reproducibility():
+    g = G()
+    # A = I returns X bit for bit
+    n = 5000
+    a = g.gcn_csr_create(n, dev(np.zeros(0, np.int32)), dev(np.zeros(0, np.int32)), g.ADD_SELF_LOOPS | g.NORM_SYM)
+    X = synth.normal_features(n, 16, 16)
+    np.testing.assert_array_equal(run_spmm(a, X), X)
+    a.close()
+    # unnormalised adjacency times ones = integer degrees, exactly
+    a = gpu_csr("c3s", norm="none")
+    ref = oracle_csr("c3s", True, True, "none")
+    ones = np.ones((ref.n, 16), np.float32)
+    np.testing.assert_array_equal(run_spmm(a, ones), np.repeat(ref.deg.astype(np.float32)[:, None], 16, 1))
+    a.close()
+    # same call twice: identical bits (no atomics, fixed summation order)
+    a = gpu_csr("c3s")
+    X = synth.normal_features(ref.n, 16, 17)
+    np.testing.assert_array_equal(run_spmm(a, X).view(np.uint32), run_spmm(a, X).view(np.uint32))
+    a.close()
+
+
+# ------------------------------------------------------------------------------------------------
+# a4 / a5 / a6: dense products and element-wise
+# ------------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("M,K,N", [(5000, 602, 16), (4097, 300, 16), (3000, 16, 41), (2049, 16, 256),
+                                   (1000, 64, 16), (777, 128, 16), (33, 7, 5), (1, 1, 1), (4096, 16, 16)])
+def test_gemm_nn_parity(M, K, N):
+    g = G()
+    A = synth.normal_features(M, K, 21)
+    B = synth.normal_features(K, N, 22)
+    Cd = torch.empty(M, N, device="cuda")
+    g.gcn_gemm(0, 0, dev(A), dev(B), Cd)
+    assert_close(host(Cd), oracle.gemm(A, B), f"NN {M}x{K}x{N}")
+    bias = synth.normal_features(1, N, 23)[0]
+    g.gcn_gemm(0, 0, dev(A), dev(B), Cd, bias=dev(bias), epilogue=g.EPI_RELU)
+    want = np.maximum(oracle.gemm(A.astype(np.float64), B.astype(np.float64)) + bias[None, :], 0)
+    assert_close(host(Cd), want, f"NN+bias+relu {M}x{K}x{N}")
+
+
+@pytest.mark.parametrize("M,K,N", [(5000, 16, 602), (3000, 41, 16), (2049, 16, 16), (1500, 256, 16), (33, 7, 5)])
+def test_gemm_nt_mask_parity(M, K, N):
+    """R = S W^T (Hadamard) sigma'(Zprev): op(B) = W^T with W stored N x K."""
+    g = G()
+    S = synth.normal_features(M, K, 24)
+    W = synth.normal_features(N, K, 25)
+    Zp = synth.normal_features(M, N, 26)
+    Cd = torch.empty(M, N, device="cuda")
+    g.gcn_gemm(0, 1, dev(S), dev(W), Cd)
+    plain = oracle.gemm(S, W, tb=True)
+    assert_close(host(Cd), plain, f"NT {M}x{K}x{N}")
+    g.gcn_gemm(0, 1, dev(S), dev(W), Cd, epilogue=g.EPI_MASK, Zprev=dev(Zp))
+    assert_close(host(Cd), oracle.relu_mask(plain, Zp), f"NT+mask {M}x{K}x{N}")
+
+
+@pytest.mark.parametrize("K,M,N", [(20000, 602, 16), (30001, 300, 16), (9999, 16, 41), (5000, 16, 256),
+                                   (100000, 16, 16), (50, 7, 5), (1, 3, 2)])
+def test_gemm_tn_parity(K, M, N):
+    """Y = H^T S with the long dimension summed (Equation 3)."""
+    g = G()
+    H = synth.normal_features(K, M, 27)
+    S = synth.normal_features(K, N, 28)
+    Yd = torch.empty(M, N, device="cuda")
+    g.gcn_gemm(1, 0, dev(H), dev(S), Yd)
+    first = host(Yd)
+    assert_close(first, oracle.gemm(H, S, ta=True), f"TN {K}: {M}x{N}")
+    g.gcn_gemm(1, 0, dev(H), dev(S), Yd)
+    np.testing.assert_array_equal(first.view(np.uint32), host(Yd).view(np.uint32))
+
+
+def test_gemm_leading_dimensions():
+    g = G()
+    A = synth.normal_features(1000, 40, 29)
+    B = synth.normal_features(40, 24, 30)
+    Ad = dev(np.concatenate([A, np.full((1000, 5), np.nan, np.float32)], 1))[:, :40]
+    Cd = torch.full((1000, 30), float("nan"), device="cuda")
+    g.gcn_gemm(0, 0, Ad, dev(B), Cd[:, :24])
+    out = host(Cd)
+    assert np.all(np.isnan(out[:, 24:]))
+    assert_close(out[:, :24], oracle.gemm(A, B), "ld")
+
+
+def test_relu_and_mask_exact():
+    g = G()
+    Z = synth.normal_features(3001, 41, 31)
+    Z[0, :5] = [-0.0, 0.0, 1e-38, -1e-38, 3.0]
+    Gm = synth.normal_features(3001, 41, 32)
+    Hd = torch.empty(3001, 41, device="cuda")
+    g.gcn_relu(dev(Z), Hd)
+    np.testing.assert_array_equal(host(Hd), oracle.relu(Z))
+    g.gcn_relu_mask(dev(Gm), dev(Z), Hd)
+    np.testing.assert_array_equal(host(Hd), oracle.relu_mask(Gm, Z))
+
+
+# ------------------------------------------------------------------------------------------------
+# a7: loss
+# ------------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("n,C", [(4096, 8), (10007, 41), (5000, 24), (3000, 256), (17, 3), (1, 1), (2000, 100)])
+def test_softmax_nll_parity(n, C):
+    g = G()
+    Z = synth.normal_features(n, C, 33) * np.float32(4.0)
+    y = synth.labels(n, C, 34)
+    loss = torch.zeros(1, device="cuda")
+    Gd = torch.empty(n, C, device="cuda")
+    g.gcn_softmax_nll(dev(Z), dev(y), loss, Gd)
+    want_loss, want_G = oracle.softmax_nll(Z, y)
+    assert abs(float(loss.item()) - want_loss) <= 1e-4 * abs(want_loss) + 1e-7
+    assert_close(host(Gd), want_G, f"G n={n} C={C}")
+    g.gcn_softmax_nll(dev(Z), dev(y), loss, None)            # loss only
+    assert abs(float(loss.item()) - want_loss) <= 1e-4 * abs(want_loss) + 1e-7
+    big = Z + np.float32(80.0)                                  # no overflow for large logits
+    g.gcn_softmax_nll(dev(big), dev(y), loss, Gd)
+    assert np.isfinite(loss.item()) and np.all(np.isfinite(host(Gd)))
+
+
+# ------------------------------------------------------------------------------------------------
+# layers: per-call parity on identical fp32 inputs, both association orders
+# ------------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("name,f_in,f_out", [("c1", 64, 16), ("c1", 16, 8), ("c3s", 602, 16), ("c3s", 16, 41),
+                                             ("c4s", 300, 16), ("c5s", 16, 256), ("c2s", 16, 16)])
+@pytest.mark.parametrize("order", [0, 1, 2])
+def test_layer_forward_backward_parity(name, f_in, f_out, order):
+    g = G()
+    a = gpu_csr(name)
+    A = oracle_csr(name)
+    n = A.n
+    Hin = synth.normal_features(n, f_in, 41)
+    W = synth.glorot_weights((f_in, f_out), 42)[0]
+    Zprev = synth.normal_features(n, f_in, 43)
+    Gl = synth.normal_features(n, f_out, 44) * np.float32(1.0 / n)
+    resolved = order if order else (1 if f_out <= f_in else 2)
+    tw = f_out if resolved == 1 else f_in
+    Z = torch.empty(n, f_out, device="cuda")
+    Ho = torch.empty(n, f_out, device="cuda")
+    T = torch.empty(n, tw, device="cuda")
+    Hd, Wd = dev(Hin), dev(W)
+    g.gcn_layer_forward(a, Hd, Wd, Z, Ho, T, order, g.ACT_RELU)
+    Zref, Href = oracle.layer_forward(A, Hin, W, "relu")      # A == A^T here
+    assert_close(host(Z), Zref, "Z")
+    np.testing.assert_array_equal(host(Ho), np.maximum(host(Z), 0))     # ReLU of the GPU's own Z, exactly
+    S = torch.empty(n, tw, device="cuda")
+    Y = torch.empty(f_in, f_out, device="cuda")
+    Gp = torch.empty(n, f_in, device="cuda")
+    db = torch.empty(f_out, device="cuda")
+    g.gcn_layer_backward(a, Hd, dev(Zprev), Wd, dev(Gl), T, S, Y, Gp, order, dbias=db)
+    Sref, Yref, Gpref, dbref = oracle.layer_backward(A, Hin, Zprev, W, Gl)
+    assert_close(host(Y), Yref, "Y")
+    assert_close(host(Gp), Gpref, "Gprev")
+    assert_close(host(db), dbref, "dbias")
+    if resolved == 1:
+        assert_close(host(S), Sref, "S = A G")
+    # first layer: no Gprev
+    g.gcn_layer_backward(a, Hd, None, Wd, dev(Gl), T, S, Y, None, order)
+    assert_close(host(Y), Yref, "Y (first layer)")
+    a.close()
+
+
+def test_layer_forward_bias_and_in_place_relu():
+    g = G()
+    a = gpu_csr("c1")
+    A = oracle_csr("c1")
+    Hin = synth.normal_features(A.n, 64, 45)
+    W = synth.glorot_weights((64, 16), 46)[0]
+    b = synth.normal_features(1, 16, 47)[0]
+    for order in (1, 2):
+        Z = torch.empty(A.n, 16, device="cuda")
+        T = torch.empty(A.n, 16 if order == 1 else 64, device="cuda")
+        g.gcn_layer_forward(a, dev(Hin), dev(W), Z, Z, T, order, g.ACT_RELU, bias=dev(b))
+        _, Href = oracle.layer_forward(A, Hin, W, "relu", bias=b)
+        assert_close(host(Z), Href, f"in-place relu + bias order={order}")
+    a.close()
+
+
+# ------------------------------------------------------------------------------------------------
+# whole epoch
+# ------------------------------------------------------------------------------------------------
+
+def run_epoch(name, w, order, lr=0.0):
+    g = G()
+    a = gpu_csr(name)
+    A = oracle_csr(name)
+    H0, y, Ws = synth.make_model_inputs(dataclass_with_n(w, A.n))
+    dims = list(w.dims)
+    Wd = [dev(x) for x in Ws]
+    Yd = [torch.empty_like(x) for x in Wd]
+    ws = torch.empty(g.gcn_epoch_workspace_bytes(A.n, dims, order), dtype=torch.uint8, device="cuda")
+    loss = torch.zeros(1, device="cuda")
+    g.gcn_epoch(a, dims, dev(H0), dev(y), Wd, Yd, lr, loss, ws, order)
+    torch.cuda.synchronize()
+    ref = oracle.epoch(A, A, H0, y, Ws, lr)
+    return g, a, A, dims, Wd, Yd, ws, loss, ref, (H0, y, Ws)
+
+
+def dataclass_with_n(w, n):
+    import dataclasses
+    return dataclasses.replace(w, n=n)
+
+
+@pytest.mark.parametrize("order", [0, 1, 2])
+def test_epoch_config1_parity(order):
+    w = synth.CONFIGS[1]
+    g, a, A, dims, Wd, Yd, ws, loss, ref, _ = run_epoch("c1", w, order)
+    assert abs(loss.item() - ref["loss"]) <= 1e-4 * abs(ref["loss"])
+    for l in range(len(dims) - 1):
+        assert rel_fro(host(Yd[l]), ref["Y"][l]) <= 1e-4, l
+        Zl, Gl = g.gcn_epoch_view(A.n, dims, order, ws, l + 1)
+        assert rel_fro(host(Zl), ref["Z"][l]) <= 1e-4
+        assert rel_fro(host(Gl), ref["G"][l]) <= 1e-3       # isolated mask flips near Z = 0 are possible
+    a.close()
+
+
+@pytest.mark.parametrize("name,cfg,shrink", [("c3s", 3, 32), ("c4s", 4, 256), ("c5s", 5, 512)])
+def test_epoch_scaled_configs_parity(name, cfg, shrink):
+    w = synth.scaled(cfg, shrink)
+    g, a, A, dims, Wd, Yd, ws, loss, ref, _ = run_epoch(name, w, 0)
+    assert abs(loss.item() - ref["loss"]) <= 1e-4 * abs(ref["loss"])
+    for l in range(len(dims) - 1):
+        assert rel_fro(host(Yd[l]), ref["Y"][l]) <= 2e-4, (l, rel_fro(host(Yd[l]), ref["Y"][l]))
+    a.close()
+
+
+def test_epoch_sgd_step_and_workspace_check():
+    w = synth.CONFIGS[1]
+    g, a, A, dims, Wd, Yd, ws, loss, ref, (H0, y, Ws) = run_epoch("c1", w, 0, lr=0.5)
+    for l in range(len(dims) - 1):
+        assert_close(host(Wd[l]), ref["W"][l], f"W{l} after the step")
+    with pytest.raises(g.GcnError) as e:
+        g.gcn_epoch(a, dims, dev(H0), dev(y), Wd, Yd, 0.0, loss, ws[:1024], 0)
+    assert e.value.code == -5
+    a.close()
+
+
+# ------------------------------------------------------------------------------------------------
+# full size, in the benchmark's launch configuration: sampled rows against the oracle
+# ------------------------------------------------------------------------------------------------
+
+def test_spmm_full_size_config2_sampled_rows():
+    g = G()
+    w = synth.CONFIGS[2]
+    n, src, dst = synth.make_graph(w)
+    A = oracle.build_csr(n, src, dst)
+    a = g.gcn_csr_create(n, dev(src), dev(dst), flags_all())
+    assert a.nnz == A.nnz
+    rowptr, colidx, val, deg = a.arrays(False)
+    assert torch.equal(rowptr.cpu(), torch.from_numpy(A.rowptr))
+    assert torch.equal(colidx.cpu(), torch.from_numpy(A.colidx))
+    assert torch.equal(val.cpu().view(torch.int32), torch.from_numpy(A.val.view(np.int32)))
+    del rowptr, colidx, val, deg
+    X = synth.uniform_features(n, 128, 0)
+    Xd = dev(X)
+    Z = torch.empty(n, 128, device="cuda")
+    heavy = np.argsort(A.deg)[-200:]
+    rng = np.random.default_rng(0)
+    rows = np.unique(np.concatenate([heavy, rng.integers(0, n, 3000), [0, n - 1]]))
+    want = oracle.spmm_rows(A, X, rows)
+    for trans in (0, 1):
+        Z.fill_(float("nan"))
+        g.gcn_spmm(a, trans, Xd, Z)
+        torch.cuda.synchronize()
+        assert_close(host(Z[torch.from_numpy(rows).cuda()]), want, f"config 2 sampled rows trans={trans}")
+        assert bool(torch.isfinite(Z).all())
+    # a property that holds at any size: A (sqrt(d) 1^T) = sqrt(d) 1^T for the normalised matrix
+    sq = torch.sqrt(torch.from_numpy(A.deg.astype(np.float32))).cuda()[:, None].repeat(1, 16).contiguous()
+    Z16 = torch.empty(n, 16, device="cuda")
+    g.gcn_spmm(a, 0, sq, Z16)
+    assert float(((Z16 - sq).abs() / sq).max()) < 1e-4
+    a.close()
