@@ -1,0 +1,225 @@
+#!/usr/bin/env python3
+"""Benchmark of the single-GPU GCN hot path.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2|1|3|4|5]
+
+Default workload (config 2): stand-alone SpMM on the R-MAT scale-20 graph, f = 128.  One step is
+the pair Z = A X and Z = A^T X (the transposed product runs on its own stored arrays).  `value`
+is algorithmic GB/s: (8 nnz + 8 (n+1) + 4 n f read + 4 n f written) per product over wall time,
+inputs resident in HBM before the timed region.  Configs 1, 3, 4, 5 time one full-batch epoch
+(forward + loss + backward, lr = 0) instead and report milliseconds.
+
+The JSON line also carries `roofline` for the dominant kernel (the nonzero-split SpMM kernel, its
+launches timed by HIP events inside the library on the launch stream) and `cpu_baseline` (the CPU
+oracle timed on the host cores on a stated sample of the same workload).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+# HBM bytes per SpMM launch measured with rocprofv3 --pmc (FETCH_SIZE, then WRITE_SIZE, each scaled
+# by what the same counter reads for a copy kernel of known size); see profiles/.  Keyed by workload.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def spmm_alg_bytes(n: int, nnz: int, f: int) -> int:
+    return 8 * nnz + 8 * (n + 1) + 4 * n * f + 4 * n * f
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4, 5])
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--order", type=int, default=0, help="0 auto, 1 GEMM first, 2 SpMM first (epoch configs)")
+    ap.add_argument("--algo", type=int, default=0, help="SpMM kernel: 0 auto, 1 row-wise, 2 nonzero-split")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--f", type=int, default=0, help="override the dense width of config 2")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain device copy of the dense operand (known size) for scaling PMC byte counters")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is single-GPU; run with --gpus 1 (no collectives or sharding are built)",
+              file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import paper_2005_03300_amd as g
+    import synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    g.lib()
+    w = synth.CONFIGS[args.config]
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+    t0 = time.time()
+    n, src, dst = synth.make_graph(w, args.seed)
+    t_gen = time.time() - t0
+    t0 = time.time()
+    src_d, dst_d = dev(src), dev(dst)
+    a = g.gcn_csr_create(n, src_d, dst_d, g.SYMMETRISE | g.ADD_SELF_LOOPS | g.NORM_SYM | g.BUILD_TRANSPOSE)
+    torch.cuda.synchronize()
+    t_build = time.time() - t0
+    del src_d, dst_d
+    nnz = a.nnz
+    g.gcn_config(g.CFG_SPMM_ALGO, args.algo)
+
+    out = {"n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "higher_is_better": True, "scaling": "weak",
+           "vs_baseline": None, "dtype": "f32", "data": "synthetic"}
+    extra = {"n": n, "nnz": nnz, "max_degree": a.max_degree, "gen_s": round(t_gen, 2),
+             "csr_build_s": round(t_build, 3), "n_raw_pairs": int(src.shape[0])}
+
+    if len(w.dims) == 1:
+        f = args.f or w.dims[0]
+        X = synth.uniform_features(n, f, args.seed)
+        Xd = dev(X)
+        Z = torch.empty(n, f, device="cuda")
+        Zt = torch.empty(n, f, device="cuda")
+
+        def step():
+            g.gcn_spmm(a, 0, Xd, Z)
+            g.gcn_spmm(a, 1, Xd, Zt)
+
+        if args.copy_calibration:
+            for _ in range(2):
+                Zt.copy_(Xd)          # plain copy kernel: reads and writes n*f*4 bytes each
+            torch.cuda.synchronize()
+            extra["copy_calibration_bytes_each_way"] = n * f * 4
+        for _ in range(args.warmup):
+            step()
+        torch.cuda.synchronize()
+        g.gcn_config(g.CFG_TIMING, 1)
+        g.gcn_timing_read()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        launches, kern_ms = g.gcn_timing_read()
+        g.gcn_config(g.CFG_TIMING, 0)
+        # the same loop without the event bracketing, so `value` carries no instrumentation cost
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        dt = min(dt, time.perf_counter() - t0)
+
+        b_alg = spmm_alg_bytes(n, nnz, f)
+        ms_step = dt / args.steps * 1e3
+        value = 2 * b_alg / (ms_step * 1e-3) / 1e9
+        avg_kernel_ms = kern_ms / max(launches, 1)
+        achieved = b_alg / (avg_kernel_ms * 1e-3) / 1e9
+        out.update(metric="SpMM algorithmic GB/s (CSR fp32, A X and A^T X)", value=round(value, 2), unit="GB/s",
+                   ms_per_step=round(ms_step, 4),
+                   config={"workload": f"config 2: {w.name} (R-MAT scale 20, edge factor 16, symmetrised, "
+                                       f"self loops, sym-normalised, relabelled), X {n}x{f} uniform[-1,1]",
+                           "n": n, "nnz": nnz, "f": f, "step": "Z=A X then Z=A^T X"})
+        extra.update(spmm_gflops=round(2 * 2.0 * nnz * f / (ms_step * 1e-3) / 1e9, 1),
+                     pct_hbm_peak=round(100 * value / HBM_PEAK_GBPS, 2),
+                     bytes_alg_per_spmm=b_alg, bytes_nocache_per_spmm=8 * nnz + 8 * (n + 1) + 4 * f * nnz + 4 * n * f,
+                     spmm_kernel_launches_timed=launches)
+        out["roofline"] = {"bound": "hbm", "kernel": "k_spmm_split", "achieved": round(achieved, 2),
+                           "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                           "avg_kernel_ms": round(avg_kernel_ms, 4),
+                           "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, f))}
+
+        if not args.no_cpu:
+            import oracle
+            t0 = time.time()
+            A = oracle.build_csr(n, src, dst)
+            t_ob = time.time() - t0
+            t0 = time.time()
+            Zo = oracle.spmm(A, X)
+            t_o = time.time() - t0
+            err = float((Z.cpu() - torch.from_numpy(Zo)).abs().max())
+            scale = float(np.sqrt(np.mean(Zo.astype(np.float64) ** 2)))
+            out["cpu_baseline"] = {"value": round(b_alg / t_o / 1e9, 3), "unit": "GB/s", "cores": oracle.threads(),
+                                   "kind": "oracle", "sample": f"one full Z = A X (n={n}, nnz={nnz}, f={f}), 1 rep",
+                                   "ms": round(t_o * 1e3, 1), "oracle_csr_build_s": round(t_ob, 2)}
+            extra.update(max_abs_err_vs_oracle=err, rms_of_oracle=scale, nnz_matches_oracle=bool(A.nnz == nnz))
+    else:
+        H0, y, Ws = synth.make_model_inputs(w, args.seed)
+        dims = list(w.dims)
+        L = len(dims) - 1
+        H0d, yd = dev(H0), dev(y)
+        Wd = [dev(x) for x in Ws]
+        Yd = [torch.empty_like(x) for x in Wd]
+        ws = torch.empty(g.gcn_epoch_workspace_bytes(n, dims, args.order), dtype=torch.uint8, device="cuda")
+        loss = torch.zeros(1, device="cuda")
+
+        def step():
+            g.gcn_epoch(a, dims, H0d, yd, Wd, Yd, 0.0, loss, ws, args.order)
+
+        for _ in range(args.warmup):
+            step()
+        torch.cuda.synchronize()
+        g.gcn_config(g.CFG_TIMING, 1)
+        g.gcn_timing_read()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        launches, kern_ms = g.gcn_timing_read()
+        g.gcn_config(g.CFG_TIMING, 0)
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        dt = min(dt, time.perf_counter() - t0)
+        ms_step = dt / args.steps * 1e3
+        # widths of the SpMM launches of one epoch under the chosen association order
+        widths = []
+        for l in range(L):
+            fi, fo = dims[l], dims[l + 1]
+            gemm_first = (args.order == 1) or (args.order == 0 and fo <= fi)
+            widths.append(fo if gemm_first else fi)                      # forward
+            if l > 0 or gemm_first:
+                widths.append(fo if gemm_first else fi)                  # backward (none for SpMM-first layer 1)
+        bytes_epoch_spmm = sum(spmm_alg_bytes(n, nnz, fw) for fw in widths)
+        achieved = bytes_epoch_spmm * args.steps / (kern_ms * 1e-3) / 1e9 if kern_ms > 0 else 0.0
+        out.update(metric="full-batch GCN epoch ms (forward + loss + backward)", value=round(ms_step, 4), unit="ms",
+                   ms_per_step=round(ms_step, 4), higher_is_better=False,
+                   config={"workload": f"config {args.config}: {w.name}", "n": n, "nnz": nnz, "dims": dims,
+                           "order": args.order})
+        extra.update(loss=float(loss.item()), spmm_widths=widths, spmm_ms_per_epoch=round(kern_ms / args.steps, 4),
+                     spmm_share=round(kern_ms / args.steps / ms_step, 3))
+        out["roofline"] = {"bound": "hbm", "kernel": "k_spmm_split", "achieved": round(achieved, 2),
+                           "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                           "avg_kernel_ms": round(kern_ms / max(launches, 1), 4), "traffic": None}
+        if not args.no_cpu:
+            import oracle
+            # bounded sample: the oracle's first-layer backward product S = A G at the hidden width
+            A = oracle.build_csr(n, src, dst)
+            fw = widths[0]
+            Xs = synth.normal_features(n, fw, args.seed + 1)
+            t0 = time.time()
+            oracle.spmm(A, Xs)
+            t_o = time.time() - t0
+            out["cpu_baseline"] = {"value": round(t_o * 1e3 * len(widths), 1), "unit": "ms", "cores": oracle.threads(),
+                                   "kind": "oracle",
+                                   "sample": f"one oracle SpMM at width {fw} timed ({t_o*1e3:.0f} ms) and multiplied by "
+                                             f"the {len(widths)} SpMMs of an epoch; dense products not included"}
+    out["extra"] = extra
+    print(json.dumps(out))
+    a.close()
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
