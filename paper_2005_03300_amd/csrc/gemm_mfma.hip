@@ -1,11 +1,311 @@
-// MFMA paths of the dense products (placeholder: nothing handled yet).
+// fp32 MFMA kernels for the dense products around the SpMM (v_mfma_f32_16x16x4_f32; full fp32
+// multiply-add, so the 1e-4 bound against the double oracle holds):
+//   k_gemm_tall   C[M x N] = A[M x K] op(B)            M = n (millions), K and N small: H W of
+//                 "Forward Propagation", S W^T of Equation 2.  Streams A once from HBM; op(B) sits
+//                 in LDS; one wavefront owns a 16-row strip and up to four 16-column tiles.
+//   k_gemm_tn     C[M x N] = A[K x M]^T B[K x N]        K = n: the weight gradient of Equation 3.
+//                 Split over K across workgroups; partial results are reduced in a fixed order.
+// At hidden width 16 both are bandwidth-bound (8 flops per byte of A): the matrix cores keep the
+// arithmetic off the critical path.
+//
+// Operand layout of the 16x16x4 instruction (64 lanes): lane l supplies A[i = l%16][k = l/16] and
+// B[k = l/16][j = l%16], and holds D[i = 4*(l/16) + v][j = l%16] in element v of its accumulator.
 #include "common.h"
 
 namespace gcn {
 
-int gemm_mfma_launch(int, int, int64_t, int64_t, int64_t, const float*, int64_t, const float*, int64_t, float*,
-                     int64_t, const float*, int, const float*, int64_t, hipStream_t, bool* handled) {
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+struct __attribute__((packed, aligned(4))) f4u { float x, y, z, w; };   // 16 bytes at 4-byte alignment
+
+__device__ __forceinline__ float4 load4(const float* p, bool aligned) {
+    if (aligned) return *reinterpret_cast<const float4*>(p);
+    f4u v = *reinterpret_cast<const f4u*>(p);
+    return make_float4(v.x, v.y, v.z, v.w);
+}
+
+template <int EPI>
+__device__ __forceinline__ float epi(float v, const float* zprev_elem) {
+    if (EPI == GCN_EPI_RELU) return v > 0.f ? v : 0.f;
+    if (EPI == GCN_EPI_MASK) return *zprev_elem > 0.f ? v : 0.f;
+    return v;
+}
+
+struct TallArgs {
+    int64_t M;
+    int32_t N, K;
+    const float* A; int64_t lda;
+    const float* B; int64_t ldb; int tb;
+    float* C; int64_t ldc;
+    const float* bias;
+    const float* Zprev; int64_t ldzprev;
+    int32_t Kpad;      // K rounded up to 16
+    int32_t S;         // LDS row stride in floats: 16*NT + 4 (bank-conflict-free B reads)
+    int a_aligned;     // A rows are 16-byte aligned
+};
+
+template <int NT, int EPI>
+__global__ __launch_bounds__(256) void k_gemm_tall(TallArgs a) {
+    extern __shared__ float Bs[];                       // [Kpad][S]
+    const int n0 = blockIdx.y * (NT * 16);
+    const int ncols = NT * 16;
+    for (int idx = threadIdx.x; idx < a.Kpad * ncols; idx += 256) {
+        const int k = idx / ncols, j = idx % ncols;
+        float v = 0.f;
+        if (k < a.K && n0 + j < a.N) v = a.tb ? a.B[(int64_t)(n0 + j) * a.ldb + k] : a.B[(int64_t)k * a.ldb + n0 + j];
+        Bs[k * a.S + j] = v;
+    }
+    __syncthreads();
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int r = lane & 15, kq = lane >> 4;
+    const int64_t ntiles = (a.M + 15) / 16;
+    for (int64_t tile = (int64_t)blockIdx.x * 4 + wave; tile < ntiles; tile += (int64_t)gridDim.x * 4) {
+        const int64_t row0 = tile * 16;
+        int64_t arow = row0 + r;
+        if (arow >= a.M) arow = a.M - 1;                // clamp: loads stay in bounds, stores are masked
+        const float* ap = a.A + arow * a.lda + 4 * kq;
+        floatx4 acc[NT];
+#pragma unroll
+        for (int t = 0; t < NT; ++t) acc[t] = (floatx4){0.f, 0.f, 0.f, 0.f};
+        const int kfull = a.K & ~15;
+        int k0 = 0;
+        for (; k0 + 64 <= kfull; k0 += 64) {            // four 16-deep steps per trip: 4 loads in flight
+            float4 av[4];
+#pragma unroll
+            for (int s = 0; s < 4; ++s) av[s] = load4(ap + k0 + 16 * s, a.a_aligned);
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                const float ae[4] = {av[s].x, av[s].y, av[s].z, av[s].w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float* bp = Bs + (k0 + 16 * s + 4 * kq + e) * a.S + r;
+#pragma unroll
+                    for (int t = 0; t < NT; ++t)
+                        acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(ae[e], bp[16 * t], acc[t], 0, 0, 0);
+                }
+            }
+        }
+        for (; k0 < kfull; k0 += 16) {
+            const float4 av = load4(ap + k0, a.a_aligned);
+            const float ae[4] = {av.x, av.y, av.z, av.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float* bp = Bs + (k0 + 4 * kq + e) * a.S + r;
+#pragma unroll
+                for (int t = 0; t < NT; ++t)
+                    acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(ae[e], bp[16 * t], acc[t], 0, 0, 0);
+            }
+        }
+        if (k0 < a.K) {                                 // ragged tail: element-wise guarded loads
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int k = k0 + 4 * kq + e;
+                const float ae = k < a.K ? ap[k0 + e] : 0.f;
+                const float* bp = Bs + k * a.S + r;     // rows K..Kpad-1 of Bs are zero
+#pragma unroll
+                for (int t = 0; t < NT; ++t)
+                    acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(ae, bp[16 * t], acc[t], 0, 0, 0);
+            }
+        }
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            const int col = n0 + 16 * t + r;
+            if (col >= a.N) continue;
+            const float b = a.bias ? a.bias[col] : 0.f;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int64_t row = row0 + 4 * kq + v;
+                if (row < a.M)
+                    a.C[row * a.ldc + col] =
+                        epi<EPI>(acc[t][v] + b, EPI == GCN_EPI_MASK ? a.Zprev + row * a.ldzprev + col : nullptr);
+            }
+        }
+    }
+}
+
+// ---- C = A^T B over a long K ---------------------------------------------------------------------
+// A workgroup takes the rows [kb, ke) of A and B.  Wavefront w owns the 64-wide column groups
+// w, w+4, w+8, ... of A (at most MG of them); inside a group lane i covers columns 4i..4i+3 with one
+// 16-byte load, which makes four M-tiles {4i+t : i} for t = 0..3.  Each step consumes four rows
+// (one per lane quarter).  The partial M x N results go to part[block][M][N].
+struct TnArgs {
+    int64_t K;
+    int32_t M, N;
+    const float* A; int64_t lda;
+    const float* B; int64_t ldb;
+    float* part;
+    int64_t k_per_block;
+    int a_aligned;
+};
+
+template <int MG, int NT>
+__global__ __launch_bounds__(256) void k_gemm_tn(TnArgs a) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int i = lane & 15, kq = lane >> 4;
+    const int64_t kb = (int64_t)blockIdx.x * a.k_per_block;
+    const int64_t ke = kb + a.k_per_block < a.K ? kb + a.k_per_block : a.K;
+    floatx4 acc[MG][4][NT];
+#pragma unroll
+    for (int g = 0; g < MG; ++g)
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
+            for (int u = 0; u < NT; ++u) acc[g][t][u] = (floatx4){0.f, 0.f, 0.f, 0.f};
+
+    int mcol[MG];
+    bool mfull[MG];
+#pragma unroll
+    for (int g = 0; g < MG; ++g) {
+        mcol[g] = (wave + 4 * g) * 64 + 4 * i;
+        mfull[g] = mcol[g] + 4 <= a.M;
+    }
+    for (int64_t k0 = kb; k0 < ke; k0 += 4) {
+        const int64_t k = k0 + kq;
+        const bool kok = k < ke;
+        const float* arow = a.A + (kok ? k : kb) * a.lda;
+        const float* brow = a.B + (kok ? k : kb) * a.ldb;
+        float bv[NT];
+#pragma unroll
+        for (int u = 0; u < NT; ++u) bv[u] = (kok && 16 * u + i < a.N) ? brow[16 * u + i] : 0.f;
+#pragma unroll
+        for (int g = 0; g < MG; ++g) {
+            float av[4] = {0.f, 0.f, 0.f, 0.f};
+            if (kok) {
+                if (mfull[g]) {
+                    const float4 v = load4(arow + mcol[g], a.a_aligned);
+                    av[0] = v.x; av[1] = v.y; av[2] = v.z; av[3] = v.w;
+                } else {
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) av[t] = mcol[g] + t < a.M ? arow[mcol[g] + t] : 0.f;
+                }
+            }
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+#pragma unroll
+                for (int u = 0; u < NT; ++u)
+                    acc[g][t][u] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[t], bv[u], acc[g][t][u], 0, 0, 0);
+        }
+    }
+    // D[ii = 4*kq + v][j = i] of tile (g, t) is C[m = (wave+4g)*64 + 4*ii + t][n = 16u + j]
+    float* out = a.part + (int64_t)blockIdx.x * a.M * a.N;
+#pragma unroll
+    for (int g = 0; g < MG; ++g)
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
+            for (int u = 0; u < NT; ++u)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int m = (wave + 4 * g) * 64 + 4 * (4 * kq + v) + t;
+                    const int n = 16 * u + i;
+                    if (m < a.M && n < a.N) out[(int64_t)m * a.N + n] = acc[g][t][u][v];
+                }
+}
+
+// Sum the partials in ascending block order; `transposed` means part holds C^T (N x M row-major).
+template <int EPI>
+__global__ void k_tn_reduce(int32_t M, int32_t N, int parts, int transposed, const float* __restrict__ part,
+                            float* __restrict__ C, int64_t ldc, const float* __restrict__ bias,
+                            const float* __restrict__ Zprev, int64_t ldzprev) {
+    const int64_t o = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t count = (int64_t)M * N;
+    if (o >= count) return;
+    const int m = (int)(o / N), n = (int)(o % N);
+    const int64_t src = transposed ? (int64_t)n * M + m : o;
+    float s = 0.f;
+    for (int p = 0; p < parts; ++p) s += part[(int64_t)p * count + src];
+    if (bias) s += bias[n];
+    C[(int64_t)m * ldc + n] = epi<EPI>(s, EPI == GCN_EPI_MASK ? Zprev + (int64_t)m * ldzprev + n : nullptr);
+}
+
+static inline bool al16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
+
+template <int NT>
+static void launch_tall(const TallArgs& args, int epilogue, dim3 grid, size_t lds, hipStream_t s) {
+    switch (epilogue) {
+        case GCN_EPI_NONE: hipLaunchKernelGGL((k_gemm_tall<NT, GCN_EPI_NONE>), grid, dim3(256), lds, s, args); break;
+        case GCN_EPI_RELU: hipLaunchKernelGGL((k_gemm_tall<NT, GCN_EPI_RELU>), grid, dim3(256), lds, s, args); break;
+        default: hipLaunchKernelGGL((k_gemm_tall<NT, GCN_EPI_MASK>), grid, dim3(256), lds, s, args); break;
+    }
+}
+
+template <int MG, int NT>
+static void launch_tn(const TnArgs& args, int blocks, hipStream_t s) {
+    hipLaunchKernelGGL((k_gemm_tn<MG, NT>), dim3(blocks), dim3(256), 0, s, args);
+}
+
+int gemm_mfma_launch(int ta, int tb, int64_t M, int64_t N, int64_t K, const float* A, int64_t lda, const float* B,
+                     int64_t ldb, float* C, int64_t ldc, const float* bias, int epilogue, const float* Zprev,
+                     int64_t ldzprev, hipStream_t s, bool* handled) {
     *handled = false;
+    if (!ta) {
+        if (K > 4096 || N > 4096 || M < 64) return GCN_OK;
+        const int nt_total = (int)((N + 15) / 16);
+        const int NT = nt_total >= 4 ? 4 : nt_total;
+        TallArgs args;
+        args.M = M; args.N = (int32_t)N; args.K = (int32_t)K;
+        args.A = A; args.lda = lda; args.B = B; args.ldb = ldb; args.tb = tb;
+        args.C = C; args.ldc = ldc; args.bias = bias; args.Zprev = Zprev; args.ldzprev = ldzprev;
+        args.Kpad = (int32_t)((K + 15) & ~15ll);
+        args.S = 16 * NT + 4;
+        args.a_aligned = (lda % 4 == 0) && al16(A);
+        const size_t lds = (size_t)args.Kpad * args.S * sizeof(float);
+        if (lds > 64 * 1024) return GCN_OK;
+        const int64_t ntiles = (M + 15) / 16;
+        int64_t bx = (ntiles + 3) / 4;
+        const int64_t cap = 256 * (lds > 40 * 1024 ? 3 : (lds > 20 * 1024 ? 6 : 8));
+        if (bx > cap) bx = cap;
+        const dim3 grid((unsigned)bx, (unsigned)((nt_total + NT - 1) / NT));
+        switch (NT) {
+            case 1: launch_tall<1>(args, epilogue, grid, lds, s); break;
+            case 2: launch_tall<2>(args, epilogue, grid, lds, s); break;
+            case 3: launch_tall<3>(args, epilogue, grid, lds, s); break;
+            default: launch_tall<4>(args, epilogue, grid, lds, s); break;
+        }
+        GCN_LAUNCH_CHECK();
+        *handled = true;
+        return GCN_OK;
+    }
+    // ta: C = A^T B with K long.  Put the wider of (M, N) on the 64-column groups: if N > M compute
+    // C^T = B^T A and let the reduction write it back transposed.
+    if (tb || K < 1024) return GCN_OK;
+    const bool swap = N > M;
+    const float* Aw = swap ? B : A;
+    const float* Bw = swap ? A : B;
+    const int64_t ldaw = swap ? ldb : lda, ldbw = swap ? lda : ldb;
+    const int64_t Mw = swap ? N : M, Nw = swap ? M : N;
+    if (Nw > 32 || Mw > 1024) return GCN_OK;             // narrow side up to 32, wide side up to 1024
+    const int NTn = (int)((Nw + 15) / 16);
+    const int groups = (int)((Mw + 63) / 64);
+    const int MG = (groups + 3) / 4;                      // column groups per wavefront (1..4)
+    int64_t blocks = 512;
+    if (K / blocks < 64) blocks = (K + 63) / 64;
+    if (blocks < 1) blocks = 1;
+    int64_t kpb = (K + blocks - 1) / blocks;
+    kpb = (kpb + 3) & ~3ll;
+    blocks = (K + kpb - 1) / kpb;
+    void* scratch = nullptr;
+    GCN_TRY(scratch_get(&scratch, (size_t)blocks * Mw * Nw * sizeof(float)));
+    TnArgs args;
+    args.K = K; args.M = (int32_t)Mw; args.N = (int32_t)Nw;
+    args.A = Aw; args.lda = ldaw; args.B = Bw; args.ldb = ldbw;
+    args.part = (float*)scratch; args.k_per_block = kpb;
+    args.a_aligned = (ldaw % 4 == 0) && al16(Aw);
+#define GCN_TN_CASE(mg, nt) if (MG == mg && NTn == nt) launch_tn<mg, nt>(args, (int)blocks, s)
+    GCN_TN_CASE(1, 1); GCN_TN_CASE(2, 1); GCN_TN_CASE(3, 1); GCN_TN_CASE(4, 1);
+    GCN_TN_CASE(1, 2); GCN_TN_CASE(2, 2); GCN_TN_CASE(3, 2); GCN_TN_CASE(4, 2);
+#undef GCN_TN_CASE
+    GCN_LAUNCH_CHECK();
+    const int64_t count = M * N;
+    const dim3 rgrid((unsigned)((count + 255) / 256));
+    switch (epilogue) {
+        case GCN_EPI_NONE: hipLaunchKernelGGL(k_tn_reduce<GCN_EPI_NONE>, rgrid, dim3(256), 0, s, (int32_t)M, (int32_t)N, (int)blocks, (int)swap, (const float*)scratch, C, ldc, bias, Zprev, ldzprev); break;
+        case GCN_EPI_RELU: hipLaunchKernelGGL(k_tn_reduce<GCN_EPI_RELU>, rgrid, dim3(256), 0, s, (int32_t)M, (int32_t)N, (int)blocks, (int)swap, (const float*)scratch, C, ldc, bias, Zprev, ldzprev); break;
+        default: hipLaunchKernelGGL(k_tn_reduce<GCN_EPI_MASK>, rgrid, dim3(256), 0, s, (int32_t)M, (int32_t)N, (int)blocks, (int)swap, (const float*)scratch, C, ldc, bias, Zprev, ldzprev); break;
+    }
+    GCN_LAUNCH_CHECK();
+    *handled = true;
     return GCN_OK;
 }
 

@@ -365,6 +365,10 @@ int spmm_launch(gcn_csr* a, const Matrix& m, int32_t f, const float* X, int64_t 
     const bool vec4 = (f % 4 == 0) && (ldx % 4 == 0) && (ldz % 4 == 0) && aligned16(X) && aligned16(Z) &&
                       (epilogue != GCN_EPI_MASK || ((ldzprev % 4 == 0) && aligned16(Zprev)));
     if (vec4) {
+        // Wider operands are processed in panels of 32 columns (one 128-byte line per gathered row):
+        // the panel of X that the gathers touch is 4x smaller than at f = 128, so far more of it stays
+        // in L2, at the price of re-reading the index/value stream once per panel.
+        if (f > 32) return launch_split<8, 4>(args, epilogue, s);
         const int lanes = f / 4;
         if (lanes <= 4) return launch_split<4, 4>(args, epilogue, s);
         if (lanes <= 8) return launch_split<8, 4>(args, epilogue, s);

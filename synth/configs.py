@@ -35,7 +35,7 @@ CONFIGS = {
     2: Workload("rmat20_spmm_f128", "rmat", 1 << 20, 16 << 20, (128,), 0, "uniform", rmat_scale=20),
     # m_raw of 3-5 is chosen so that, after duplicate removal, the number of distinct
     # unordered pairs lands near the dataset's edge count / 2.
-    3: Workload("chunglu_reddit_gcn_602_16_16_41", "chunglu", 232_965, 70_000_000,
+    3: Workload("chunglu_reddit_gcn_602_16_16_41", "chunglu", 232_965, 59_100_000,
                 (602, 16, 16, 41), 41, "normal", gamma=2.1, max_degree=20_000.0),
     4: Workload("rmat_amazon_gcn_300_16_16_24", "rmat", 14_249_639, 190_000_000,
                 (300, 16, 16, 24), 24, "normal", rmat_scale=24),
