@@ -58,6 +58,7 @@ extern "C" {
 /* gcn_config keys */
 #define GCN_CFG_SPMM_ALGO 1 /* 0 = automatic, 1 = one wavefront per row, 2 = nonzero-split */
 #define GCN_CFG_TIMING 2    /* 1 = bracket the dominant kernels with HIP events (see gcn_timing_read) */
+#define GCN_CFG_SPMM_BLOCKS 3 /* column blocks of the SpMM: 0 = automatic, 1 = never block, k >= 2 = k blocks */
 
 typedef struct gcn_csr gcn_csr; /* opaque: A (and A^T) in compressed rows, degrees, schedules */
 
@@ -103,7 +104,9 @@ int gcn_csr_export(const gcn_csr* a, int transposed, int64_t* rowptr, int32_t* c
  * val[k] * X[col[k],:], op(A) = A (trans=0) or A^T (trans=1).
  * X: device n x f, ld ldx >= f.  Z: device n x f, ld ldz >= f, must not overlap X.
  * epilogue GCN_EPI_MASK reads Zprev (device n x f, ld ldzprev); otherwise Zprev is ignored.
- * Sums are fp32 and run-to-run reproducible (no floating-point atomics).
+ * Sums are fp32 and run-to-run reproducible (no floating-point atomics).  The first call at a
+ * given width may build and cache a column-blocked copy of the matrix inside `a` (it allocates
+ * and synchronises once); later calls only queue kernels.
  * ----------------------------------------------------------------------------------------- */
 int gcn_spmm(gcn_csr* a, int trans, int32_t f, const float* X, int64_t ldx, float* Z, int64_t ldz,
              int epilogue, const float* Zprev, int64_t ldzprev, void* stream);
@@ -163,16 +166,17 @@ int gcn_layer_backward(gcn_csr* a, int32_t f_in, int32_t f_out, const float* Hin
  * backward, and W <- W - lr Y when lr != 0 (the gradient step of Equation 3).
  * dims: HOST int32[L_w+1] = f^0..f^{L_w}.  H0: device n x dims[0] dense.  labels: device int32[n].
  * W, Y: HOST arrays of L_w device pointers (W[l] is dims[l] x dims[l+1]; Y[l] receives dL/dW[l]).
- * loss: device float.  workspace: device, at least gcn_epoch_workspace_bytes(); holds every
- * Z^l, H^l, G^l and the scratch matrices, O(n * sum f).  `order` applies to every layer.
+ * loss: device float.  workspace: device, 256-byte aligned, at least gcn_epoch_workspace_bytes();
+ * holds every H^l, Z^{L_w}, G^l and the scratch matrices, O(n * sum f).  `order` applies to every layer.
  * ----------------------------------------------------------------------------------------- */
 int gcn_epoch(gcn_csr* a, int32_t L_w, const int32_t* dims, const float* H0, const int32_t* labels,
               float* const* W, float* const* Y, float lr, float* loss, void* workspace,
               size_t workspace_bytes, int order, void* stream);
 size_t gcn_epoch_workspace_bytes(int64_t n, int32_t L_w, const int32_t* dims, int order);
 
-/* After gcn_epoch: device pointers into the workspace for layer l in [1, L_w] (Z^l and G^l,
- * both n x dims[l] dense), for parity checks.  BADARG if the workspace/dims do not match. */
+/* After gcn_epoch: device pointers into the workspace for layer l in [1, L_w], both n x dims[l]
+ * dense, for parity checks: G = G^l; Z = Z^l for the last layer and H^l = ReLU(Z^l) for the hidden
+ * layers (their Z is never stored: sigma'(Z) = [H > 0]).  BADARG if l or the workspace is bad. */
 int gcn_epoch_view(int64_t n, int32_t L_w, const int32_t* dims, int order, void* workspace, int32_t l,
                    float** Z, float** G);
 

@@ -97,6 +97,17 @@ void timing_end(hipStream_t s) {
     g_open = nullptr;
 }
 
+void free_blocked(Blocked& b) {
+    device_free(b.colidx);
+    device_free(b.val);
+    device_free(b.flags);
+    device_free(b.sub_row);
+    device_free(b.rp);
+    device_free(b.rq_ptr);
+    device_free(b.rq_idx);
+    b = Blocked();
+}
+
 void free_matrix(Matrix& m) {
     device_free(m.rowptr);
     device_free(m.colidx);
@@ -105,6 +116,7 @@ void free_matrix(Matrix& m) {
     device_free(m.sub_row);
     device_free(m.ne_rows);
     device_free(m.ne_rowptr);
+    free_blocked(m.blk);
     m = Matrix();
 }
 
@@ -122,6 +134,10 @@ int gcn_config(int key, int value) {
         case GCN_CFG_SPMM_ALGO:
             if (value < 0 || value > 2) return fail(GCN_ERR_BADARG, "GCN_CFG_SPMM_ALGO must be 0, 1 or 2");
             config().spmm_algo = value;
+            return GCN_OK;
+        case GCN_CFG_SPMM_BLOCKS:
+            if (value < 0 || value > 4096) return fail(GCN_ERR_BADARG, "GCN_CFG_SPMM_BLOCKS must be in [0, 4096]");
+            config().spmm_blocks = value;
             return GCN_OK;
         case GCN_CFG_TIMING:
             if (value != 0 && value != 1) return fail(GCN_ERR_BADARG, "GCN_CFG_TIMING must be 0 or 1");
@@ -164,6 +180,7 @@ int gcn_csr_destroy(gcn_csr* a) {
     free_matrix(a->At);
     device_free(a->deg);
     device_free(a->carry);
+    device_free(a->partial);
     delete a;
     return GCN_OK;
 }

@@ -43,6 +43,23 @@ constexpr int SUB = 32;
 constexpr int CHUNK = 512;
 constexpr int SUBS_PER_CHUNK = CHUNK / SUB;
 
+// Column-blocked copy of a matrix: the entries re-sorted by (column block, row, column).  Each
+// non-empty (block, row) pair is a row of a partial-result matrix P; the SpMM kernel runs over this
+// order unchanged, so all wavefronts gather from one block of X at a time and that block stays in
+// L2.  A second kernel adds each row's partials in ascending block order.
+struct Blocked {
+    int64_t cols_per_block = 0;
+    int32_t nblocks = 0;
+    int64_t nrows = 0;           // R: non-empty (block, row) pairs
+    int32_t* colidx = nullptr;   // [nnz]
+    float* val = nullptr;        // [nnz]
+    uint32_t* flags = nullptr;   // [nsub + pad]
+    int32_t* sub_row = nullptr;  // [nsub + pad]
+    int64_t* rp = nullptr;       // [R+1] first entry of each partial row
+    int64_t* rq_ptr = nullptr;   // [n+1]  row i owns partial rows rq_idx[rq_ptr[i] .. rq_ptr[i+1])
+    int32_t* rq_idx = nullptr;   // [R]    ascending block order inside a row
+};
+
 // One stored matrix in compressed rows plus its nonzero-split schedule.
 struct Matrix {
     int64_t* rowptr = nullptr;   // [n+1]
@@ -56,6 +73,7 @@ struct Matrix {
     int64_t n_ne = 0;
     int64_t nsub = 0, nchunks = 0;
     int32_t max_degree = 0;
+    Blocked blk;                 // built on first use for one block width
 };
 
 }  // namespace gcn
@@ -68,6 +86,8 @@ struct gcn_csr {
     int32_t* deg = nullptr;      // [n] entries per row of A
     float* carry = nullptr;      // per-chunk partial rows for the nonzero-split SpMM
     size_t carry_bytes = 0;
+    float* partial = nullptr;    // P of the column-blocked SpMM
+    size_t partial_bytes = 0;
 };
 
 namespace gcn {
@@ -83,6 +103,7 @@ int scratch_get(void** p, size_t bytes);
 
 struct Config {
     int spmm_algo = 0;
+    int spmm_blocks = 0;
     int timing = 0;
 };
 Config& config();
@@ -92,9 +113,11 @@ void timing_begin(hipStream_t s);
 void timing_end(hipStream_t s);
 
 int build_schedule(Matrix& m, int64_t n, int64_t nnz, hipStream_t s);
+int build_blocked(Matrix& m, int64_t n, int64_t nnz, int64_t cols_per_block, hipStream_t s);
+void free_blocked(Blocked& b);
 void free_matrix(Matrix& m);
 
-int spmm_launch(gcn_csr* a, const Matrix& m, int32_t f, const float* X, int64_t ldx, float* Z, int64_t ldz,
+int spmm_launch(gcn_csr* a, Matrix& m, int32_t f, const float* X, int64_t ldx, float* Z, int64_t ldz,
                 int epilogue, const float* Zprev, int64_t ldzprev, hipStream_t s);
 
 int gemm_launch(int ta, int tb, int64_t M, int64_t N, int64_t K, const float* A, int64_t lda, const float* B,

@@ -12,6 +12,7 @@
 #include <new>
 
 #include <rocprim/device/device_radix_sort.hpp>
+#include <rocprim/device/device_scan.hpp>
 #include <rocprim/device/device_select.hpp>
 #include <rocprim/iterator/counting_iterator.hpp>
 
@@ -249,6 +250,153 @@ int build_schedule(Matrix& m, int64_t n, int64_t nnz, hipStream_t s) {
         GCN_LAUNCH_CHECK();
     }
     GCN_HIP_TRY(hipStreamSynchronize(s));
+    return GCN_OK;
+}
+
+// ---- column-blocked copy -----------------------------------------------------------------------------
+
+// key = block<<32 | row, payload = col<<32 | value bits; thread k finds its row by bisection.
+__global__ void k_block_keys(int64_t nnz, int64_t n, const int64_t* __restrict__ rowptr,
+                             const int32_t* __restrict__ colidx, const float* __restrict__ val, int64_t cpb,
+                             uint64_t* __restrict__ keys, uint64_t* __restrict__ payload) {
+    int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (k >= nnz) return;
+    int64_t lo = 0, hi = n;
+    while (hi - lo > 1) {
+        int64_t mid = (lo + hi) >> 1;
+        if (rowptr[mid] <= k) lo = mid; else hi = mid;
+    }
+    const uint32_t col = (uint32_t)colidx[k];
+    keys[k] = ((uint64_t)(col / cpb) << 32) | (uint64_t)lo;
+    payload[k] = ((uint64_t)col << 32) | (uint64_t)__float_as_uint(val[k]);
+}
+
+// Flag word j: bit b set iff sorted entry 32j+b opens a new (block,row) run; cnt[j] = set bits.
+__global__ void k_block_flags(int64_t nnz, int64_t nsub, const uint64_t* __restrict__ keys,
+                              uint32_t* __restrict__ flags, int32_t* __restrict__ cnt) {
+    int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= nsub) return;
+    uint32_t w = 0;
+    const int64_t k0 = j * SUB;
+    uint64_t prev = k0 > 0 ? keys[k0 - 1] : ~0ull;
+    for (int b = 0; b < SUB && k0 + b < nnz; ++b) {
+        const uint64_t cur = keys[k0 + b];
+        if (k0 + b == 0 || cur != prev) w |= 1u << b;
+        prev = cur;
+    }
+    flags[j] = w;
+    cnt[j] = __popc(w);
+}
+
+// From the flags and their exclusive prefix counts: sub_row, the first entry rp[q] of every partial
+// row q, and the sort key (row<<32 | q) that groups partial rows by the row they belong to.
+__global__ void k_block_rows(int64_t nnz, int64_t nsub, const uint32_t* __restrict__ flags,
+                             const int32_t* __restrict__ pre, const uint64_t* __restrict__ keys,
+                             int32_t* __restrict__ sub_row, int64_t* __restrict__ rp, uint64_t* __restrict__ rowq) {
+    int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= nsub) return;
+    uint32_t w = flags[j];
+    int32_t q = pre[j];
+    sub_row[j] = q + (int32_t)(w & 1u) - 1;
+    while (w) {
+        const int b = __ffs(w) - 1;
+        w &= w - 1;
+        const int64_t k = j * SUB + b;
+        rp[q] = k;
+        rowq[q] = ((keys[k] & 0xffffffffull) << 32) | (uint64_t)(uint32_t)q;
+        ++q;
+    }
+}
+
+__global__ void k_block_unpack(int64_t nnz, const uint64_t* __restrict__ payload, int32_t* __restrict__ colidx,
+                               float* __restrict__ val) {
+    int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (k >= nnz) return;
+    colidx[k] = (int32_t)(payload[k] >> 32);
+    val[k] = __uint_as_float((uint32_t)(payload[k] & 0xffffffffu));
+}
+
+__global__ void k_set_i64(int64_t* p, int64_t v) { *p = v; }
+
+void free_blocked(Blocked& b);
+
+int build_blocked(Matrix& m, int64_t n, int64_t nnz, int64_t cpb, hipStream_t s) {
+    free_blocked(m.blk);
+    Blocked& b = m.blk;
+    if (nnz <= 0 || cpb <= 0) return fail(GCN_ERR_BADARG, "build_blocked: empty matrix or bad block width");
+    const int64_t nblocks = (n + cpb - 1) / cpb;
+    const int64_t nsub = m.nsub;
+    TempBuf k0, k1, p0, p1, cnt, pre, tmp;
+    GCN_TRY(k0.alloc((size_t)nnz * 8));
+    GCN_TRY(k1.alloc((size_t)nnz * 8));
+    GCN_TRY(p0.alloc((size_t)nnz * 8));
+    GCN_TRY(p1.alloc((size_t)nnz * 8));
+    hipLaunchKernelGGL(k_block_keys, dim3(blocks_for(nnz)), dim3(TPB), 0, s, nnz, n, m.rowptr, m.colidx, m.val, cpb,
+                       k0.as<uint64_t>(), p0.as<uint64_t>());
+    GCN_LAUNCH_CHECK();
+    size_t tmp_bytes = 0;
+    const unsigned end_bit = 32 + bits_for(nblocks + 1);
+    GCN_HIP_TRY(rocprim::radix_sort_pairs(nullptr, tmp_bytes, k0.as<uint64_t>(), k1.as<uint64_t>(), p0.as<uint64_t>(),
+                                          p1.as<uint64_t>(), (size_t)nnz, 0u, end_bit, s));
+    GCN_TRY(tmp.alloc(tmp_bytes));
+    GCN_HIP_TRY(rocprim::radix_sort_pairs(tmp.p, tmp_bytes, k0.as<uint64_t>(), k1.as<uint64_t>(), p0.as<uint64_t>(),
+                                          p1.as<uint64_t>(), (size_t)nnz, 0u, end_bit, s));
+    GCN_HIP_TRY(hipStreamSynchronize(s));
+    k0.alloc(16);                                        // release the unsorted copies early
+    p0.alloc(16);
+
+    const size_t padded = (size_t)nsub + SUBS_PER_CHUNK;
+    GCN_TRY(device_alloc_t(&b.flags, padded));
+    GCN_TRY(device_alloc_t(&b.sub_row, padded));
+    GCN_HIP_TRY(hipMemsetAsync(b.flags, 0, padded * sizeof(uint32_t), s));
+    GCN_HIP_TRY(hipMemsetAsync(b.sub_row, 0, padded * sizeof(int32_t), s));
+    GCN_TRY(cnt.alloc((size_t)nsub * 4));
+    GCN_TRY(pre.alloc((size_t)nsub * 4));
+    hipLaunchKernelGGL(k_block_flags, dim3(blocks_for(nsub)), dim3(TPB), 0, s, nnz, nsub, k1.as<uint64_t>(), b.flags,
+                       cnt.as<int32_t>());
+    GCN_LAUNCH_CHECK();
+    tmp_bytes = 0;
+    GCN_HIP_TRY(rocprim::exclusive_scan(nullptr, tmp_bytes, cnt.as<int32_t>(), pre.as<int32_t>(), (int32_t)0,
+                                        (size_t)nsub, rocprim::plus<int32_t>(), s));
+    GCN_TRY(tmp.alloc(tmp_bytes));
+    GCN_HIP_TRY(rocprim::exclusive_scan(tmp.p, tmp_bytes, cnt.as<int32_t>(), pre.as<int32_t>(), (int32_t)0,
+                                        (size_t)nsub, rocprim::plus<int32_t>(), s));
+    int32_t last_pre = 0, last_cnt = 0;
+    GCN_HIP_TRY(hipMemcpyAsync(&last_pre, pre.as<int32_t>() + (nsub - 1), 4, hipMemcpyDeviceToHost, s));
+    GCN_HIP_TRY(hipMemcpyAsync(&last_cnt, cnt.as<int32_t>() + (nsub - 1), 4, hipMemcpyDeviceToHost, s));
+    GCN_HIP_TRY(hipStreamSynchronize(s));
+    const int64_t R = (int64_t)last_pre + last_cnt;
+    if (R <= 0) return fail(GCN_ERR_RANGE, "build_blocked: too many partial rows");   // int32 prefix overflowed
+
+    GCN_TRY(device_alloc_t(&b.rp, (size_t)R + 1));
+    TempBuf rq0, rq1;
+    GCN_TRY(rq0.alloc((size_t)R * 8));
+    GCN_TRY(rq1.alloc((size_t)R * 8));
+    hipLaunchKernelGGL(k_block_rows, dim3(blocks_for(nsub)), dim3(TPB), 0, s, nnz, nsub, b.flags, pre.as<int32_t>(),
+                       k1.as<uint64_t>(), b.sub_row, b.rp, rq0.as<uint64_t>());
+    GCN_LAUNCH_CHECK();
+    hipLaunchKernelGGL(k_set_i64, dim3(1), dim3(1), 0, s, b.rp + R, nnz);
+    GCN_LAUNCH_CHECK();
+    GCN_TRY(device_alloc_t(&b.colidx, (size_t)nnz));
+    GCN_TRY(device_alloc_t(&b.val, (size_t)nnz));
+    hipLaunchKernelGGL(k_block_unpack, dim3(blocks_for(nnz)), dim3(TPB), 0, s, nnz, p1.as<uint64_t>(), b.colidx, b.val);
+    GCN_LAUNCH_CHECK();
+    // group the partial rows by the row they belong to; inside a row q ascends, i.e. block order
+    tmp_bytes = 0;
+    const unsigned end_bit2 = 32 + bits_for(n);
+    GCN_HIP_TRY(rocprim::radix_sort_keys(nullptr, tmp_bytes, rq0.as<uint64_t>(), rq1.as<uint64_t>(), (size_t)R, 0u,
+                                         end_bit2, s));
+    GCN_TRY(tmp.alloc(tmp_bytes));
+    GCN_HIP_TRY(rocprim::radix_sort_keys(tmp.p, tmp_bytes, rq0.as<uint64_t>(), rq1.as<uint64_t>(), (size_t)R, 0u,
+                                         end_bit2, s));
+    GCN_TRY(device_alloc_t(&b.rq_ptr, (size_t)n + 1));
+    GCN_TRY(device_alloc_t(&b.rq_idx, (size_t)R));
+    hipLaunchKernelGGL(k_compress, dim3(blocks_for(R)), dim3(TPB), 0, s, R, n, rq1.as<uint64_t>(), b.rq_ptr, b.rq_idx);
+    GCN_LAUNCH_CHECK();
+    GCN_HIP_TRY(hipStreamSynchronize(s));
+    b.cols_per_block = cpb;
+    b.nblocks = (int32_t)nblocks;
+    b.nrows = R;
     return GCN_OK;
 }
 

@@ -139,71 +139,126 @@ struct TnArgs {
     int a_aligned;
 };
 
-template <int MG, int NT>
+template <int MG, int NT, bool NARROW>   // NARROW: MG counts 16-column tiles of A (M <= 16*MG)
 __global__ __launch_bounds__(256) void k_gemm_tn(TnArgs a) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int i = lane & 15, kq = lane >> 4;
     const int64_t kb = (int64_t)blockIdx.x * a.k_per_block;
     const int64_t ke = kb + a.k_per_block < a.K ? kb + a.k_per_block : a.K;
-    floatx4 acc[MG][4][NT];
+    constexpr int TT = NARROW ? 1 : 4;                  // M-tiles per column group
+    floatx4 acc[MG][TT][NT];
 #pragma unroll
     for (int g = 0; g < MG; ++g)
 #pragma unroll
-        for (int t = 0; t < 4; ++t)
+        for (int t = 0; t < TT; ++t)
 #pragma unroll
             for (int u = 0; u < NT; ++u) acc[g][t][u] = (floatx4){0.f, 0.f, 0.f, 0.f};
 
+    // NARROW (M <= 32): lane i covers columns i, i+16 of A with 4-byte loads (one M-tile each), and
+    // the four wavefronts split the rows instead of the columns.
     int mcol[MG];
-    bool mfull[MG];
+    int mvalid[MG];                                     // how many of the lane's 4 columns exist
 #pragma unroll
     for (int g = 0; g < MG; ++g) {
-        mcol[g] = (wave + 4 * g) * 64 + 4 * i;
-        mfull[g] = mcol[g] + 4 <= a.M;
+        mcol[g] = NARROW ? i + 16 * g : (wave + 4 * g) * 64 + 4 * i;
+        const int left = a.M - mcol[g];
+        mvalid[g] = left >= (NARROW ? 1 : 4) ? (NARROW ? 1 : 4) : (left > 0 ? left : 0);
     }
-    for (int64_t k0 = kb; k0 < ke; k0 += 4) {
-        const int64_t k = k0 + kq;
-        const bool kok = k < ke;
-        const float* arow = a.A + (kok ? k : kb) * a.lda;
-        const float* brow = a.B + (kok ? k : kb) * a.ldb;
-        float bv[NT];
+    bool nok[NT];
 #pragma unroll
-        for (int u = 0; u < NT; ++u) bv[u] = (kok && 16 * u + i < a.N) ? brow[16 * u + i] : 0.f;
+    for (int u = 0; u < NT; ++u) nok[u] = 16 * u + i < a.N;
+    const int kstep = NARROW ? 64 : 16;                 // rows per trip of the whole workgroup
+    const int koff = NARROW ? 16 * wave : 0;
+    for (int64_t k0 = kb + koff; k0 < ke; k0 += kstep) {
+        float av[4][MG][TT];
+        float bv[4][NT];
 #pragma unroll
-        for (int g = 0; g < MG; ++g) {
-            float av[4] = {0.f, 0.f, 0.f, 0.f};
-            if (kok) {
-                if (mfull[g]) {
-                    const float4 v = load4(arow + mcol[g], a.a_aligned);
-                    av[0] = v.x; av[1] = v.y; av[2] = v.z; av[3] = v.w;
+        for (int s = 0; s < 4; ++s) {                   // issue every load of the trip first
+            const int64_t k = k0 + 4 * s + kq;
+            const bool kok = k < ke;
+            const float* arow = a.A + (kok ? k : kb) * a.lda;
+            const float* brow = a.B + (kok ? k : kb) * a.ldb;
+#pragma unroll
+            for (int u = 0; u < NT; ++u) bv[s][u] = (kok && nok[u]) ? brow[16 * u + i] : 0.f;
+#pragma unroll
+            for (int g = 0; g < MG; ++g) {
+                if constexpr (NARROW) {
+                    av[s][g][0] = (kok && mvalid[g]) ? arow[mcol[g]] : 0.f;
                 } else {
+                    if (kok && mvalid[g] == 4) {
+                        const float4 v = load4(arow + mcol[g], a.a_aligned);
+                        av[s][g][0] = v.x; av[s][g][1] = v.y; av[s][g][2] = v.z; av[s][g][3] = v.w;
+                    } else {
 #pragma unroll
-                    for (int t = 0; t < 4; ++t) av[t] = mcol[g] + t < a.M ? arow[mcol[g] + t] : 0.f;
+                        for (int t = 0; t < 4; ++t) av[s][g][t] = (kok && t < mvalid[g]) ? arow[mcol[g] + t] : 0.f;
+                    }
                 }
             }
+        }
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+#pragma unroll
+            for (int g = 0; g < MG; ++g)
+#pragma unroll
+                for (int t = 0; t < TT; ++t)
+#pragma unroll
+                    for (int u = 0; u < NT; ++u)
+                        acc[g][t][u] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[s][g][t], bv[s][u], acc[g][t][u], 0, 0, 0);
+    }
+    float* out = a.part + (int64_t)blockIdx.x * a.M * a.N;
+    if constexpr (NARROW) {
+        // the four wavefronts hold partial sums of the same tiles: add them in LDS, fixed order
+        __shared__ float s_red[4][MG][NT][64][4];
+#pragma unroll
+        for (int g = 0; g < MG; ++g)
+#pragma unroll
+            for (int u = 0; u < NT; ++u)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) s_red[wave][g][u][lane][v] = acc[g][0][u][v];
+        __syncthreads();
+        if (wave == 0) {
+#pragma unroll
+            for (int g = 0; g < MG; ++g)
+#pragma unroll
+                for (int u = 0; u < NT; ++u)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const float sum = ((s_red[0][g][u][lane][v] + s_red[1][g][u][lane][v]) + s_red[2][g][u][lane][v]) +
+                                          s_red[3][g][u][lane][v];
+                        const int m = 16 * g + 4 * kq + v, n = 16 * u + i;
+                        if (m < a.M && n < a.N) out[(int64_t)m * a.N + n] = sum;
+                    }
+        }
+    } else {
+        // D[ii = 4*kq + v][j = i] of tile (g, t) is C[m = (wave+4g)*64 + 4*ii + t][n = 16u + j]
+#pragma unroll
+        for (int g = 0; g < MG; ++g)
 #pragma unroll
             for (int t = 0; t < 4; ++t)
 #pragma unroll
                 for (int u = 0; u < NT; ++u)
-                    acc[g][t][u] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[t], bv[u], acc[g][t][u], 0, 0, 0);
-        }
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const int m = (wave + 4 * g) * 64 + 4 * (4 * kq + v) + t;
+                        const int n = 16 * u + i;
+                        if (m < a.M && n < a.N) out[(int64_t)m * a.N + n] = acc[g][t][u][v];
+                    }
     }
-    // D[ii = 4*kq + v][j = i] of tile (g, t) is C[m = (wave+4g)*64 + 4*ii + t][n = 16u + j]
-    float* out = a.part + (int64_t)blockIdx.x * a.M * a.N;
-#pragma unroll
-    for (int g = 0; g < MG; ++g)
-#pragma unroll
-        for (int t = 0; t < 4; ++t)
-#pragma unroll
-            for (int u = 0; u < NT; ++u)
-#pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    const int m = (wave + 4 * g) * 64 + 4 * (4 * kq + v) + t;
-                    const int n = 16 * u + i;
-                    if (m < a.M && n < a.N) out[(int64_t)m * a.N + n] = acc[g][t][u][v];
-                }
 }
 
-// Sum the partials in ascending block order; `transposed` means part holds C^T (N x M row-major).
+// Stage 1 of the reduction: group g of `groups` sums the partials g, g+groups, g+2*groups, ... in
+// ascending order (coalesced over the output index).
+__global__ void k_tn_fold(int64_t count, int parts, int groups, const float* __restrict__ part, float* __restrict__ out) {
+    const int64_t o = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int g = blockIdx.y;
+    if (o >= count) return;
+    float s = 0.f;
+    for (int p = g; p < parts; p += groups) s += part[(int64_t)p * count + o];
+    out[(int64_t)g * count + o] = s;
+}
+
+// Stage 2: sum the (few) groups in ascending order, add the bias, apply the epilogue and store;
+// `transposed` means part holds C^T (N x M row-major).
 template <int EPI>
 __global__ void k_tn_reduce(int32_t M, int32_t N, int parts, int transposed, const float* __restrict__ part,
                             float* __restrict__ C, int64_t ldc, const float* __restrict__ bias,
@@ -230,9 +285,9 @@ static void launch_tall(const TallArgs& args, int epilogue, dim3 grid, size_t ld
     }
 }
 
-template <int MG, int NT>
+template <int MG, int NT, bool NARROW>
 static void launch_tn(const TnArgs& args, int blocks, hipStream_t s) {
-    hipLaunchKernelGGL((k_gemm_tn<MG, NT>), dim3(blocks), dim3(256), 0, s, args);
+    hipLaunchKernelGGL((k_gemm_tn<MG, NT, NARROW>), dim3(blocks), dim3(256), 0, s, args);
 }
 
 int gemm_mfma_launch(int ta, int tb, int64_t M, int64_t N, int64_t K, const float* A, int64_t lda, const float* B,
@@ -277,32 +332,47 @@ int gemm_mfma_launch(int ta, int tb, int64_t M, int64_t N, int64_t K, const floa
     const int64_t Mw = swap ? N : M, Nw = swap ? M : N;
     if (Nw > 32 || Mw > 1024) return GCN_OK;             // narrow side up to 32, wide side up to 1024
     const int NTn = (int)((Nw + 15) / 16);
+    const bool narrow = Mw <= 32;
     const int groups = (int)((Mw + 63) / 64);
-    const int MG = (groups + 3) / 4;                      // column groups per wavefront (1..4)
-    int64_t blocks = 512;
-    if (K / blocks < 64) blocks = (K + 63) / 64;
+    const int MG = narrow ? (int)((Mw + 15) / 16) : (groups + 3) / 4;   // tiles (narrow) or column groups per wavefront
+    int64_t blocks = K / 256;                             // at least 256 rows per workgroup
+    if (blocks > 2048) blocks = 2048;
     if (blocks < 1) blocks = 1;
     int64_t kpb = (K + blocks - 1) / blocks;
-    kpb = (kpb + 3) & ~3ll;
+    kpb = (kpb + 63) & ~63ll;
     blocks = (K + kpb - 1) / kpb;
+    const int fold = blocks > 64 ? 32 : 0;               // two-stage reduction when there are many partials
     void* scratch = nullptr;
-    GCN_TRY(scratch_get(&scratch, (size_t)blocks * Mw * Nw * sizeof(float)));
+    GCN_TRY(scratch_get(&scratch, (size_t)(blocks + fold) * Mw * Nw * sizeof(float)));
     TnArgs args;
     args.K = K; args.M = (int32_t)Mw; args.N = (int32_t)Nw;
     args.A = Aw; args.lda = ldaw; args.B = Bw; args.ldb = ldbw;
     args.part = (float*)scratch; args.k_per_block = kpb;
     args.a_aligned = (ldaw % 4 == 0) && al16(Aw);
-#define GCN_TN_CASE(mg, nt) if (MG == mg && NTn == nt) launch_tn<mg, nt>(args, (int)blocks, s)
+#define GCN_TN_CASE(mg, nt) if (!narrow && MG == mg && NTn == nt) launch_tn<mg, nt, false>(args, (int)blocks, s)
     GCN_TN_CASE(1, 1); GCN_TN_CASE(2, 1); GCN_TN_CASE(3, 1); GCN_TN_CASE(4, 1);
     GCN_TN_CASE(1, 2); GCN_TN_CASE(2, 2); GCN_TN_CASE(3, 2); GCN_TN_CASE(4, 2);
+    if (narrow && MG == 1 && NTn == 1) launch_tn<1, 1, true>(args, (int)blocks, s);
+    if (narrow && MG == 2 && NTn == 1) launch_tn<2, 1, true>(args, (int)blocks, s);
+    if (narrow && MG == 2 && NTn == 2) launch_tn<2, 2, true>(args, (int)blocks, s);
 #undef GCN_TN_CASE
     GCN_LAUNCH_CHECK();
     const int64_t count = M * N;
+    const float* red_src = (const float*)scratch;
+    int red_parts = (int)blocks;
+    if (fold) {
+        float* folded = (float*)scratch + blocks * count;
+        hipLaunchKernelGGL(k_tn_fold, dim3((unsigned)((count + 255) / 256), (unsigned)fold), dim3(256), 0, s, count,
+                           (int)blocks, fold, (const float*)scratch, folded);
+        GCN_LAUNCH_CHECK();
+        red_src = folded;
+        red_parts = fold;
+    }
     const dim3 rgrid((unsigned)((count + 255) / 256));
     switch (epilogue) {
-        case GCN_EPI_NONE: hipLaunchKernelGGL(k_tn_reduce<GCN_EPI_NONE>, rgrid, dim3(256), 0, s, (int32_t)M, (int32_t)N, (int)blocks, (int)swap, (const float*)scratch, C, ldc, bias, Zprev, ldzprev); break;
-        case GCN_EPI_RELU: hipLaunchKernelGGL(k_tn_reduce<GCN_EPI_RELU>, rgrid, dim3(256), 0, s, (int32_t)M, (int32_t)N, (int)blocks, (int)swap, (const float*)scratch, C, ldc, bias, Zprev, ldzprev); break;
-        default: hipLaunchKernelGGL(k_tn_reduce<GCN_EPI_MASK>, rgrid, dim3(256), 0, s, (int32_t)M, (int32_t)N, (int)blocks, (int)swap, (const float*)scratch, C, ldc, bias, Zprev, ldzprev); break;
+        case GCN_EPI_NONE: hipLaunchKernelGGL(k_tn_reduce<GCN_EPI_NONE>, rgrid, dim3(256), 0, s, (int32_t)M, (int32_t)N, red_parts, (int)swap, red_src, C, ldc, bias, Zprev, ldzprev); break;
+        case GCN_EPI_RELU: hipLaunchKernelGGL(k_tn_reduce<GCN_EPI_RELU>, rgrid, dim3(256), 0, s, (int32_t)M, (int32_t)N, red_parts, (int)swap, red_src, C, ldc, bias, Zprev, ldzprev); break;
+        default: hipLaunchKernelGGL(k_tn_reduce<GCN_EPI_MASK>, rgrid, dim3(256), 0, s, (int32_t)M, (int32_t)N, red_parts, (int)swap, red_src, C, ldc, bias, Zprev, ldzprev); break;
     }
     GCN_LAUNCH_CHECK();
     *handled = true;

@@ -78,8 +78,10 @@ static EpochLayout epoch_layout(int64_t n, int32_t L, const int32_t* dims, int o
         const int32_t fi = dims[l], fo = dims[l + 1];
         const int ord = resolve_order(order, fi, fo);
         lay.order.push_back(ord);
+        // Hidden layers keep only H = ReLU(Z): the ReLU is fused into the kernel that produces Z, and
+        // sigma'(Z) = [Z > 0] = [H > 0], so backward never needs Z itself.  The last layer keeps Z.
         lay.Z.push_back(take((size_t)n * fo));
-        lay.H.push_back(l + 1 < L ? take((size_t)n * fo) : lay.Z.back());
+        lay.H.push_back(lay.Z.back());
         lay.T.push_back(take((size_t)n * (ord == GCN_ORDER_GEMM_FIRST ? fo : fi)));
         lay.G.push_back(take((size_t)n * fo));
         const size_t sneed = (size_t)n * (ord == GCN_ORDER_GEMM_FIRST ? fo : fi);
@@ -163,7 +165,7 @@ int gcn_epoch(gcn_csr* a, int32_t L_w, const int32_t* dims, const float* H0, con
     for (int l = 0; l < L_w; ++l) {
         const bool last = (l + 1 == L_w);
         GCN_TRY(layer_forward_impl(a, dims[l], dims[l + 1], Hin, dims[l], W[l], nullptr, at(lay.Z[l]),
-                                   last ? nullptr : at(lay.H[l]), at(lay.T[l]), lay.order[l],
+                                   last ? nullptr : at(lay.Z[l]), at(lay.T[l]), lay.order[l],
                                    last ? GCN_ACT_NONE : GCN_ACT_RELU, s));
         Hin = at(lay.H[l]);
     }

@@ -2,41 +2,101 @@
 // discusses under "Block Two-Dimensional (2D) Algorithms", Equation H = sigma(Z)) with the mean
 // negative log-likelihood over all vertices, and Equation 1 specialised to it:
 //   G = (softmax(Z) - onehot(y)) / n.
-// L lanes share a row (L = power of two >= min(C, 64)); row maxima and sums are butterfly
-// reductions inside the L lanes; the per-row losses are summed in double in a fixed tree.
+// L lanes share a row and keep its logits in registers (VEC per lane, C <= L*VEC): one read of Z,
+// one write of G.  Row maxima and sums are butterfly reductions inside the L lanes.  Workgroups
+// stride over the rows; every thread adds its rows' losses in double in a fixed order, then a
+// fixed tree joins threads and workgroups, so the loss is reproducible bit for bit.
 #include "common.h"
 
 namespace gcn {
 
-template <int L>
+static constexpr int LOSS_BLOCKS_MAX = 2048;
+
+template <int L, int VEC>
 __global__ __launch_bounds__(256) void k_softmax_nll(int64_t n, int32_t C, const float* __restrict__ Z, int64_t ldz,
                                                      const int32_t* __restrict__ labels, float* __restrict__ G,
                                                      int64_t ldg, float inv_n, double* __restrict__ part) {
     constexpr int ROWS = 256 / L;
     const int li = threadIdx.x % L;
-    const int64_t i = (int64_t)blockIdx.x * ROWS + threadIdx.x / L;
-    const bool row_ok = i < n;
-    const float* z = Z + (row_ok ? i : 0) * ldz;
-    float m = -INFINITY;
-    for (int j = li; j < C; j += L) m = fmaxf(m, z[j]);
+    const int c0 = li * VEC;
+    double mine = 0.0;
+    for (int64_t i = (int64_t)blockIdx.x * ROWS + threadIdx.x / L; i < n; i += (int64_t)gridDim.x * ROWS) {
+        const float* z = Z + i * ldz;
+        float v[VEC];
+        if constexpr (VEC == 4) {
+            if (c0 < C) {
+                const float4 t = *reinterpret_cast<const float4*>(z + c0);
+                v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+            } else {
+                v[0] = v[1] = v[2] = v[3] = -INFINITY;
+            }
+        } else {
+            v[0] = c0 < C ? z[c0] : -INFINITY;
+        }
+        float m = v[0];
 #pragma unroll
-    for (int d = L / 2; d >= 1; d >>= 1) m = fmaxf(m, __shfl_xor(m, d, 64));
-    float ssum = 0.f;
-    for (int j = li; j < C; j += L) ssum += expf(z[j] - m);
+        for (int e = 1; e < VEC; ++e) m = fmaxf(m, v[e]);
 #pragma unroll
-    for (int d = L / 2; d >= 1; d >>= 1) ssum += __shfl_xor(ssum, d, 64);
-    const float lse = m + logf(ssum);
-    int32_t y = row_ok ? labels[i] : 0;
-    y = y < 0 ? 0 : (y >= C ? C - 1 : y);   // out-of-range labels are the caller's error; stay in bounds
-    if (row_ok && G) {
-        float* g = G + i * ldg;
-        for (int j = li; j < C; j += L) g[j] = (expf(z[j] - lse) - (j == y ? 1.f : 0.f)) * inv_n;
+        for (int d = L / 2; d >= 1; d >>= 1) m = fmaxf(m, __shfl_xor(m, d, 64));
+        float ssum = 0.f;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) ssum += expf(v[e] - m);          // exp(-inf) = 0 for padding lanes
+#pragma unroll
+        for (int d = L / 2; d >= 1; d >>= 1) ssum += __shfl_xor(ssum, d, 64);
+        const float lse = m + logf(ssum);
+        int32_t y = labels[i];
+        y = y < 0 ? 0 : (y >= C ? C - 1 : y);   // out-of-range labels are the caller's error; stay in bounds
+        if (G && c0 < C) {
+            float g[VEC];
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) g[e] = (expf(v[e] - lse) - (c0 + e == y ? 1.f : 0.f)) * inv_n;
+            if constexpr (VEC == 4) *reinterpret_cast<float4*>(G + i * ldg + c0) = make_float4(g[0], g[1], g[2], g[3]);
+            else G[i * ldg + c0] = g[0];
+        }
+        // the lane that holds column y contributes lse - z_y
+        float zy = 0.f;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) zy = (c0 + e == y) ? v[e] : zy;
+        if (y >= c0 && y < c0 + VEC) mine += (double)lse - (double)zy;
     }
-    double contrib = (row_ok && li == 0) ? (double)lse - (double)z[y] : 0.0;
 #pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) contrib += __shfl_xor(contrib, d, 64);
+    for (int d = 32; d >= 1; d >>= 1) mine += __shfl_xor(mine, d, 64);
     __shared__ double s_w[4];
-    if ((threadIdx.x & 63) == 0) s_w[threadIdx.x >> 6] = contrib;
+    if ((threadIdx.x & 63) == 0) s_w[threadIdx.x >> 6] = mine;
+    __syncthreads();
+    if (threadIdx.x == 0) part[blockIdx.x] = (s_w[0] + s_w[1]) + (s_w[2] + s_w[3]);
+}
+
+// Any C: lanes loop over the columns and re-read the row (three passes, served by the caches).
+__global__ __launch_bounds__(256) void k_softmax_nll_wide(int64_t n, int32_t C, const float* __restrict__ Z,
+                                                          int64_t ldz, const int32_t* __restrict__ labels,
+                                                          float* __restrict__ G, int64_t ldg, float inv_n,
+                                                          double* __restrict__ part) {
+    const int li = threadIdx.x & 63;
+    double mine = 0.0;
+    for (int64_t i = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6); i < n; i += (int64_t)gridDim.x * 4) {
+        const float* z = Z + i * ldz;
+        float m = -INFINITY;
+        for (int j = li; j < C; j += 64) m = fmaxf(m, z[j]);
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) m = fmaxf(m, __shfl_xor(m, d, 64));
+        float ssum = 0.f;
+        for (int j = li; j < C; j += 64) ssum += expf(z[j] - m);
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) ssum += __shfl_xor(ssum, d, 64);
+        const float lse = m + logf(ssum);
+        int32_t y = labels[i];
+        y = y < 0 ? 0 : (y >= C ? C - 1 : y);
+        if (G) {
+            float* g = G + i * ldg;
+            for (int j = li; j < C; j += 64) g[j] = (expf(z[j] - lse) - (j == y ? 1.f : 0.f)) * inv_n;
+        }
+        if (li == 0) mine += (double)lse - (double)z[y];
+    }
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) mine += __shfl_xor(mine, d, 64);
+    __shared__ double s_w[4];
+    if ((threadIdx.x & 63) == 0) s_w[threadIdx.x >> 6] = mine;
     __syncthreads();
     if (threadIdx.x == 0) part[blockIdx.x] = (s_w[0] + s_w[1]) + (s_w[2] + s_w[3]);
 }
@@ -56,20 +116,30 @@ __global__ __launch_bounds__(256) void k_loss_final(int64_t parts, const double*
     if (threadIdx.x == 0) *loss = (float)(s[0] * inv_n);
 }
 
-template <int L>
-static int launch(int64_t n, int32_t C, const float* Z, int64_t ldz, const int32_t* labels, float* loss, float* G,
-                  int64_t ldg, hipStream_t s) {
-    constexpr int ROWS = 256 / L;
-    const int64_t blocks = (n + ROWS - 1) / ROWS;
-    if (blocks >= (1ll << 31)) return fail(GCN_ERR_RANGE, "gcn_softmax_nll: too many rows");
-    void* scratch = nullptr;
-    GCN_TRY(scratch_get(&scratch, (size_t)blocks * sizeof(double)));
-    hipLaunchKernelGGL(k_softmax_nll<L>, dim3((unsigned)blocks), dim3(256), 0, s, n, C, Z, ldz, labels, G, ldg,
-                       1.0f / (float)n, (double*)scratch);
-    GCN_LAUNCH_CHECK();
-    hipLaunchKernelGGL(k_loss_final, dim3(1), dim3(256), 0, s, blocks, (const double*)scratch, 1.0 / (double)n, loss);
-    GCN_LAUNCH_CHECK();
-    return GCN_OK;
+template <int L, int VEC>
+static void launch_rows(int64_t blocks, int64_t n, int32_t C, const float* Z, int64_t ldz, const int32_t* labels,
+                        float* G, int64_t ldg, double* part, hipStream_t s) {
+    hipLaunchKernelGGL((k_softmax_nll<L, VEC>), dim3((unsigned)blocks), dim3(256), 0, s, n, C, Z, ldz, labels, G, ldg,
+                       1.0f / (float)n, part);
+}
+
+template <int VEC>
+static void dispatch_rows(int lanes, int64_t n, int32_t C, const float* Z, int64_t ldz, const int32_t* labels,
+                          float* G, int64_t ldg, double* part, int64_t* blocks_out, hipStream_t s) {
+    int L = 2;
+    while (L < lanes) L <<= 1;
+    const int64_t rows_per_block = 256 / L;
+    int64_t blocks = (n + rows_per_block - 1) / rows_per_block;
+    if (blocks > LOSS_BLOCKS_MAX) blocks = LOSS_BLOCKS_MAX;
+    *blocks_out = blocks;
+    switch (L) {
+        case 2: launch_rows<2, VEC>(blocks, n, C, Z, ldz, labels, G, ldg, part, s); break;
+        case 4: launch_rows<4, VEC>(blocks, n, C, Z, ldz, labels, G, ldg, part, s); break;
+        case 8: launch_rows<8, VEC>(blocks, n, C, Z, ldz, labels, G, ldg, part, s); break;
+        case 16: launch_rows<16, VEC>(blocks, n, C, Z, ldz, labels, G, ldg, part, s); break;
+        case 32: launch_rows<32, VEC>(blocks, n, C, Z, ldz, labels, G, ldg, part, s); break;
+        default: launch_rows<64, VEC>(blocks, n, C, Z, ldz, labels, G, ldg, part, s); break;
+    }
 }
 
 }  // namespace gcn
@@ -81,9 +151,24 @@ extern "C" int gcn_softmax_nll(int64_t n, int32_t C, const float* Z, int64_t ldz
     if (!Z || !labels || !loss) return fail(GCN_ERR_BADARG, "gcn_softmax_nll: NULL argument");
     if (n <= 0 || C <= 0 || ldz < C || (G && ldg < C)) return fail(GCN_ERR_BADARG, "gcn_softmax_nll: bad size");
     hipStream_t s = (hipStream_t)stream;
-    if (C <= 4) return launch<4>(n, C, Z, ldz, labels, loss, G, ldg, s);
-    if (C <= 8) return launch<8>(n, C, Z, ldz, labels, loss, G, ldg, s);
-    if (C <= 16) return launch<16>(n, C, Z, ldz, labels, loss, G, ldg, s);
-    if (C <= 32) return launch<32>(n, C, Z, ldz, labels, loss, G, ldg, s);
-    return launch<64>(n, C, Z, ldz, labels, loss, G, ldg, s);
+    void* scratch = nullptr;
+    GCN_TRY(scratch_get(&scratch, (size_t)LOSS_BLOCKS_MAX * sizeof(double)));
+    double* part = (double*)scratch;
+    int64_t blocks = 0;
+    const bool vec4 = (C % 4 == 0) && (ldz % 4 == 0) && (((uintptr_t)Z & 15u) == 0) &&
+                      (!G || ((ldg % 4 == 0) && (((uintptr_t)G & 15u) == 0)));
+    if (vec4 && C <= 256) {
+        dispatch_rows<4>(C / 4, n, C, Z, ldz, labels, G, ldg, part, &blocks, s);
+    } else if (C <= 64) {
+        dispatch_rows<1>(C, n, C, Z, ldz, labels, G, ldg, part, &blocks, s);
+    } else {
+        blocks = (n + 3) / 4;
+        if (blocks > LOSS_BLOCKS_MAX) blocks = LOSS_BLOCKS_MAX;
+        hipLaunchKernelGGL(k_softmax_nll_wide, dim3((unsigned)blocks), dim3(256), 0, s, n, C, Z, ldz, labels, G, ldg,
+                           1.0f / (float)n, part);
+    }
+    GCN_LAUNCH_CHECK();
+    hipLaunchKernelGGL(k_loss_final, dim3(1), dim3(256), 0, s, blocks, (const double*)part, 1.0 / (double)n, loss);
+    GCN_LAUNCH_CHECK();
+    return GCN_OK;
 }

@@ -315,15 +315,100 @@ static int launch_split(const SplitArgs& args, int epilogue, hipStream_t s) {
 
 static inline bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
 
-int spmm_launch(gcn_csr* a, const Matrix& m, int32_t f, const float* X, int64_t ldx, float* Z, int64_t ldz,
+// Adds the partial rows of the column-blocked product in ascending block order, then the epilogue.
+template <int VEC, int EPI>
+__global__ __launch_bounds__(256) void k_block_reduce(int64_t n, int32_t f, int32_t lanes, const int64_t* __restrict__ rq_ptr,
+                                                      const int32_t* __restrict__ rq_idx, const float* __restrict__ P,
+                                                      float* __restrict__ Z, int64_t ldz, const float* __restrict__ Zprev,
+                                                      int64_t ldzprev) {
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t i = t / lanes;
+    const int col0 = (int)(t % lanes) * VEC;
+    if (i >= n) return;
+    float acc[VEC];
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) acc[v] = 0.f;
+    for (int64_t k = rq_ptr[i]; k < rq_ptr[i + 1]; ++k) {
+        float part[VEC];
+        load_vec<VEC>(part, P + (int64_t)rq_idx[k] * f + col0);
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) acc[v] += part[v];
+    }
+    epilogue_store<VEC, EPI>(Z + i * ldz + col0, EPI == GCN_EPI_MASK ? Zprev + i * ldzprev + col0 : nullptr, acc);
+}
+
+template <int VEC>
+static int launch_block_reduce(int64_t n, int32_t f, const Blocked& b, const float* P, float* Z, int64_t ldz, int epilogue,
+                               const float* Zprev, int64_t ldzprev, hipStream_t s) {
+    const int lanes = f / VEC;
+    const int64_t threads = n * lanes;
+    const dim3 grid((unsigned)((threads + 255) / 256));
+    switch (epilogue) {
+        case GCN_EPI_NONE: hipLaunchKernelGGL((k_block_reduce<VEC, GCN_EPI_NONE>), grid, dim3(256), 0, s, n, f, lanes, b.rq_ptr, b.rq_idx, P, Z, ldz, Zprev, ldzprev); break;
+        case GCN_EPI_RELU: hipLaunchKernelGGL((k_block_reduce<VEC, GCN_EPI_RELU>), grid, dim3(256), 0, s, n, f, lanes, b.rq_ptr, b.rq_idx, P, Z, ldz, Zprev, ldzprev); break;
+        default: hipLaunchKernelGGL((k_block_reduce<VEC, GCN_EPI_MASK>), grid, dim3(256), 0, s, n, f, lanes, b.rq_ptr, b.rq_idx, P, Z, ldz, Zprev, ldzprev); break;
+    }
+    GCN_LAUNCH_CHECK();
+    return GCN_OK;
+}
+
+// Chooses the lane layout for one nonzero-split product and launches it.
+static int run_split(const SplitArgs& args, int epilogue, hipStream_t s) {
+    const int32_t f = args.f;
+    const bool vec4 = (f % 4 == 0) && (args.ldx % 4 == 0) && (args.ldz % 4 == 0) && aligned16(args.X) && aligned16(args.Z) &&
+                      (epilogue != GCN_EPI_MASK || ((args.ldzprev % 4 == 0) && aligned16(args.Zprev)));
+    if (vec4) {
+        // Wider operands are processed in panels of 32 columns (one 128-byte line per gathered row):
+        // the panel of X that the gathers touch is 4x smaller than at f = 128, so far more of it stays
+        // in L2, at the price of re-reading the index/value stream once per panel.
+        if (f > 32) return launch_split<8, 4>(args, epilogue, s);
+        const int lanes = f / 4;
+        if (lanes <= 4) return launch_split<4, 4>(args, epilogue, s);
+        return launch_split<8, 4>(args, epilogue, s);
+    }
+    if (f <= 4) return launch_split<4, 1>(args, epilogue, s);
+    if (f <= 8) return launch_split<8, 1>(args, epilogue, s);
+    if (f <= 16) return launch_split<16, 1>(args, epilogue, s);
+    if (f <= 32) return launch_split<32, 1>(args, epilogue, s);
+    return launch_split<64, 1>(args, epilogue, s);
+}
+
+static int grow(float** buf, size_t* have, size_t need) {
+    if (need <= *have) return GCN_OK;
+    if (*buf) {
+        GCN_HIP_TRY(hipDeviceSynchronize());             // queued work may still use the old buffer
+        device_free(*buf);
+        *buf = nullptr;
+        *have = 0;
+    }
+    GCN_TRY(device_alloc((void**)buf, need));
+    *have = need;
+    return GCN_OK;
+}
+
+// How many column blocks to cut X into so that one block of the gathered panel stays in one L2
+// (4 MB per XCD).  Blocking costs one partial row per non-empty (block,row) pair, so it only pays
+// when rows are long compared with the number of blocks; otherwise 1 (no blocking).
+static int64_t choose_blocks(int64_t n, int64_t nnz, int32_t f) {
+    const int forced = config().spmm_blocks;
+    if (forced >= 1) return forced;
+    const int64_t panel = f < 32 ? f : 32;
+    const int64_t xbytes = n * panel * 4;
+    if (xbytes <= (7ll << 19)) return 1;                  // 3.5 MB: already L2-resident
+    const int64_t want = (xbytes + (2ll << 20) - 1) / (2ll << 20);
+    const int64_t cap = (nnz / n) / 24;
+    return want <= cap ? want : 1;
+}
+
+int spmm_launch(gcn_csr* a, Matrix& m, int32_t f, const float* X, int64_t ldx, float* Z, int64_t ldz,
                 int epilogue, const float* Zprev, int64_t ldzprev, hipStream_t s) {
     const int64_t n = a->n, nnz = a->nnz;
-    if (m.n_ne < n) {
+    if (nnz == 0) {
         const int64_t work = n * f;
         hipLaunchKernelGGL(k_zero_empty_rows, dim3((unsigned)((work + 255) / 256)), dim3(256), 0, s, n, m.rowptr, f, Z, ldz);
         GCN_LAUNCH_CHECK();
+        return GCN_OK;
     }
-    if (nnz == 0) return GCN_OK;
     int algo = config().spmm_algo;
     if (algo == 0) algo = 2;
     if (algo == 1) {
@@ -340,47 +425,40 @@ int spmm_launch(gcn_csr* a, const Matrix& m, int32_t f, const float* X, int64_t 
         GCN_LAUNCH_CHECK();
         return GCN_OK;
     }
-
-    // carry buffer: one f-wide partial row per chunk
-    const size_t need = (size_t)m.nchunks * (size_t)f * sizeof(float);
-    if (need > a->carry_bytes) {
-        if (a->carry) {
-            GCN_HIP_TRY(hipDeviceSynchronize());
-            device_free(a->carry);
-            a->carry = nullptr;
-            a->carry_bytes = 0;
-        }
-        GCN_TRY(device_alloc((void**)&a->carry, need));
-        a->carry_bytes = need;
-    }
-    SplitArgs args;
-    args.colidx = m.colidx; args.val = m.val; args.flags = m.flags; args.sub_row = m.sub_row;
-    args.ne_rows = m.ne_rows; args.rp = m.ne_rowptr ? m.ne_rowptr : m.rowptr;
-    args.nnz = nnz; args.nsub = m.nsub; args.nchunks = m.nchunks; args.f = f;
-    args.X = X; args.ldx = ldx; args.Z = Z; args.ldz = ldz; args.Zprev = Zprev; args.ldzprev = ldzprev;
-    args.carry = a->carry;
     if ((m.nchunks + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK >= (1ll << 31))
         return fail(GCN_ERR_RANGE, "gcn_spmm: too many chunks for one launch");
+    GCN_TRY(grow(&a->carry, &a->carry_bytes, (size_t)m.nchunks * (size_t)f * sizeof(float)));
 
-    const bool vec4 = (f % 4 == 0) && (ldx % 4 == 0) && (ldz % 4 == 0) && aligned16(X) && aligned16(Z) &&
-                      (epilogue != GCN_EPI_MASK || ((ldzprev % 4 == 0) && aligned16(Zprev)));
-    if (vec4) {
-        // Wider operands are processed in panels of 32 columns (one 128-byte line per gathered row):
-        // the panel of X that the gathers touch is 4x smaller than at f = 128, so far more of it stays
-        // in L2, at the price of re-reading the index/value stream once per panel.
-        if (f > 32) return launch_split<8, 4>(args, epilogue, s);
-        const int lanes = f / 4;
-        if (lanes <= 4) return launch_split<4, 4>(args, epilogue, s);
-        if (lanes <= 8) return launch_split<8, 4>(args, epilogue, s);
-        if (lanes <= 16) return launch_split<16, 4>(args, epilogue, s);
-        if (lanes <= 32) return launch_split<32, 4>(args, epilogue, s);
-        return launch_split<64, 4>(args, epilogue, s);
+    SplitArgs args;
+    args.nnz = nnz; args.nsub = m.nsub; args.nchunks = m.nchunks; args.f = f;
+    args.X = X; args.ldx = ldx; args.carry = a->carry;
+
+    const int64_t nblocks = choose_blocks(n, nnz, f);
+    if (nblocks >= 2) {
+        int64_t cpb = (n + nblocks - 1) / nblocks;
+        cpb = (cpb + 1023) & ~1023ll;
+        if (m.blk.cols_per_block != cpb) GCN_TRY(build_blocked(m, n, nnz, cpb, s));
+        const Blocked& b = m.blk;
+        GCN_TRY(grow(&a->partial, &a->partial_bytes, (size_t)b.nrows * (size_t)f * sizeof(float)));
+        args.colidx = b.colidx; args.val = b.val; args.flags = b.flags; args.sub_row = b.sub_row;
+        args.ne_rows = nullptr; args.rp = b.rp;
+        args.Z = a->partial; args.ldz = f; args.Zprev = nullptr; args.ldzprev = 0;
+        GCN_TRY(run_split(args, GCN_EPI_NONE, s));
+        const bool vec4 = (f % 4 == 0) && (ldz % 4 == 0) && aligned16(Z) &&
+                          (epilogue != GCN_EPI_MASK || ((ldzprev % 4 == 0) && aligned16(Zprev)));
+        if (vec4) return launch_block_reduce<4>(n, f, b, a->partial, Z, ldz, epilogue, Zprev, ldzprev, s);
+        return launch_block_reduce<1>(n, f, b, a->partial, Z, ldz, epilogue, Zprev, ldzprev, s);
     }
-    if (f <= 4) return launch_split<4, 1>(args, epilogue, s);
-    if (f <= 8) return launch_split<8, 1>(args, epilogue, s);
-    if (f <= 16) return launch_split<16, 1>(args, epilogue, s);
-    if (f <= 32) return launch_split<32, 1>(args, epilogue, s);
-    return launch_split<64, 1>(args, epilogue, s);
+
+    if (m.n_ne < n) {
+        const int64_t work = n * f;
+        hipLaunchKernelGGL(k_zero_empty_rows, dim3((unsigned)((work + 255) / 256)), dim3(256), 0, s, n, m.rowptr, f, Z, ldz);
+        GCN_LAUNCH_CHECK();
+    }
+    args.colidx = m.colidx; args.val = m.val; args.flags = m.flags; args.sub_row = m.sub_row;
+    args.ne_rows = m.ne_rows; args.rp = m.ne_rowptr ? m.ne_rowptr : m.rowptr;
+    args.Z = Z; args.ldz = ldz; args.Zprev = Zprev; args.ldzprev = ldzprev;
+    return run_split(args, epilogue, s);
 }
 
 }  // namespace gcn

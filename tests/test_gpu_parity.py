@@ -271,6 +271,65 @@ def test_spmm_exact_cases_and_reproducibility():
     a.close()
 
 
+@pytest.mark.parametrize("name", ["c3s", "c2s", "star", "tiny"])
+@pytest.mark.parametrize("blocks", [2, 5, 16])
+def test_spmm_column_blocked_forced(name, blocks):
+    """The column-blocked schedule (partial rows per column block, then a fixed-order sum) against
+    the oracle, forced on small graphs; 41 exercises the scalar-lane path, 128 the 32-column panels."""
+    g = G()
+    a = gpu_csr(name)
+    ref = oracle_csr(name)
+    g.gcn_config(g.CFG_SPMM_BLOCKS, blocks)
+    try:
+        for f in (16, 41, 128):
+            X = synth.normal_features(ref.n, f, 18)
+            Zp = synth.normal_features(ref.n, f, 19)
+            plain = oracle.spmm(ref, X)
+            assert_close(run_spmm(a, X), plain, f"{name} blocks={blocks} f={f}")
+            assert_close(run_spmm(a, X, epilogue=g.EPI_MASK, Zprev=Zp), oracle.relu_mask(plain, Zp), "mask")
+            assert_close(run_spmm(a, X, epilogue=g.EPI_RELU, ld_pad=4), np.maximum(plain, 0), "relu, padded ld")
+        first = run_spmm(a, X)
+        np.testing.assert_array_equal(first.view(np.uint32), run_spmm(a, X).view(np.uint32))
+    finally:
+        g.gcn_config(g.CFG_SPMM_BLOCKS, 0)
+    a.close()
+
+
+def test_spmm_column_blocked_directed_with_empty_rows():
+    g = G()
+    a = gpu_csr("c2s", symmetrise=False, self_loops=False, norm="none")
+    ref = oracle_csr("c2s", False, False, "none", False)
+    ref_t = oracle_csr("c2s", False, False, "none", True)
+    X = synth.uniform_features(ref.n, 16, 13)
+    g.gcn_config(g.CFG_SPMM_BLOCKS, 3)
+    try:
+        assert_close(run_spmm(a, X, trans=0), oracle.spmm(ref, X), "A")
+        assert_close(run_spmm(a, X, trans=1), oracle.spmm(ref_t, X), "A^T")
+    finally:
+        g.gcn_config(g.CFG_SPMM_BLOCKS, 0)
+    a.close()
+
+
+def test_spmm_column_blocked_automatic_choice():
+    """Large enough that the library blocks on its own (X is 7.7 MB at f = 16, mean degree ~ 500)."""
+    g = G()
+    n = 120_000
+    src, dst = synth.chung_lu(n, 30_000_000, 2.1, 10_000.0, 5)
+    a = g.gcn_csr_create(n, dev(src), dev(dst), flags_all())
+    A = oracle.build_csr(n, src, dst)
+    assert a.nnz == A.nnz and A.nnz / n > 200
+    X = synth.normal_features(n, 16, 20)
+    want = oracle.spmm(A, X)
+    got = run_spmm(a, X)
+    assert_close(got, want, "automatic blocking")
+    g.gcn_config(g.CFG_SPMM_BLOCKS, 1)
+    try:
+        assert_close(run_spmm(a, X), want, "blocking disabled")
+    finally:
+        g.gcn_config(g.CFG_SPMM_BLOCKS, 0)
+    a.close()
+
+
 # ------------------------------------------------------------------------------------------------
 # a4 / a5 / a6: dense products and element-wise
 # ------------------------------------------------------------------------------------------------
@@ -457,8 +516,8 @@ def test_epoch_config1_parity(order):
     assert abs(loss.item() - ref["loss"]) <= 1e-4 * abs(ref["loss"])
     for l in range(len(dims) - 1):
         assert rel_fro(host(Yd[l]), ref["Y"][l]) <= 1e-4, l
-        Zl, Gl = g.gcn_epoch_view(A.n, dims, order, ws, l + 1)
-        assert rel_fro(host(Zl), ref["Z"][l]) <= 1e-4
+        Zl, Gl = g.gcn_epoch_view(A.n, dims, order, ws, l + 1)     # hidden layers store H = ReLU(Z)
+        assert rel_fro(host(Zl), ref["Z"][l] if l + 2 == len(dims) else ref["H"][l + 1]) <= 1e-4
         assert rel_fro(host(Gl), ref["G"][l]) <= 1e-3       # isolated mask flips near Z = 0 are possible
     a.close()
 
