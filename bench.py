@@ -27,9 +27,13 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0
 
-# HBM bytes per SpMM launch measured with rocprofv3 --pmc (FETCH_SIZE, then WRITE_SIZE, each scaled
-# by what the same counter reads for a copy kernel of known size); see profiles/.  Keyed by workload.
-MEASURED_TRAFFIC_BYTES = {}
+# HBM-side bytes per SpMM launch measured with rocprofv3 --pmc (FETCH_SIZE, then WRITE_SIZE, in KiB
+# per dispatch, each scaled by what the same counter reads for a plain device copy of 512 MiB:
+# FETCH_SIZE x 2.0, WRITE_SIZE x 1.0); from profiles/spmm_split_rmat20_f128.txt.  Keyed by
+# (workload, f); workloads without a committed counter profile report null.
+MEASURED_TRAFFIC_BYTES = {
+    ("rmat20_spmm_f128", 128): int((4.67104e6 * 1.9999 + 555976 * 1.0) * 1024),
+}
 
 
 def spmm_alg_bytes(n: int, nnz: int, f: int) -> int:
@@ -122,7 +126,7 @@ def main() -> int:
         b_alg = spmm_alg_bytes(n, nnz, f)
         ms_step = dt / args.steps * 1e3
         value = 2 * b_alg / (ms_step * 1e-3) / 1e9
-        avg_kernel_ms = kern_ms / max(launches, 1)
+        avg_kernel_ms = kern_ms / (2 * args.steps)          # main SpMM kernel time per product
         achieved = b_alg / (avg_kernel_ms * 1e-3) / 1e9
         out.update(metric="SpMM algorithmic GB/s (CSR fp32, A X and A^T X)", value=round(value, 2), unit="GB/s",
                    ms_per_step=round(ms_step, 4),
@@ -132,7 +136,7 @@ def main() -> int:
         extra.update(spmm_gflops=round(2 * 2.0 * nnz * f / (ms_step * 1e-3) / 1e9, 1),
                      pct_hbm_peak=round(100 * value / HBM_PEAK_GBPS, 2),
                      bytes_alg_per_spmm=b_alg, bytes_nocache_per_spmm=8 * nnz + 8 * (n + 1) + 4 * f * nnz + 4 * n * f,
-                     spmm_kernel_launches_timed=launches)
+                     spmm_products_timed=2 * args.steps, event_brackets=launches)
         out["roofline"] = {"bound": "hbm", "kernel": "k_spmm_split", "achieved": round(achieved, 2),
                            "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
                            "avg_kernel_ms": round(avg_kernel_ms, 4),
@@ -201,7 +205,7 @@ def main() -> int:
                      spmm_share=round(kern_ms / args.steps / ms_step, 3))
         out["roofline"] = {"bound": "hbm", "kernel": "k_spmm_split", "achieved": round(achieved, 2),
                            "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                           "avg_kernel_ms": round(kern_ms / max(launches, 1), 4), "traffic": None}
+                           "avg_kernel_ms": round(kern_ms / max(len(widths) * args.steps, 1), 4), "traffic": None}
         if not args.no_cpu:
             import oracle
             # bounded sample: the oracle's first-layer backward product S = A G at the hidden width

@@ -108,6 +108,21 @@ void free_blocked(Blocked& b) {
     b = Blocked();
 }
 
+void free_matrix(Matrix& m);
+
+void free_sweep(Sweep& w) {
+    device_free(w.colidx);
+    device_free(w.val);
+    device_free(w.lrow);
+    device_free(w.task_ptr);
+    device_free(w.task_order);
+    if (w.heavy) {
+        free_matrix(*w.heavy);
+        delete w.heavy;
+    }
+    w = Sweep();
+}
+
 void free_matrix(Matrix& m) {
     device_free(m.rowptr);
     device_free(m.colidx);
@@ -117,6 +132,7 @@ void free_matrix(Matrix& m) {
     device_free(m.ne_rows);
     device_free(m.ne_rowptr);
     free_blocked(m.blk);
+    free_sweep(m.swp);
     m = Matrix();
 }
 
@@ -132,12 +148,16 @@ const char* gcn_version(void) { return "gcn-hip 0.1 (gfx950)"; }
 int gcn_config(int key, int value) {
     switch (key) {
         case GCN_CFG_SPMM_ALGO:
-            if (value < 0 || value > 2) return fail(GCN_ERR_BADARG, "GCN_CFG_SPMM_ALGO must be 0, 1 or 2");
+            if (value < 0 || value > 3) return fail(GCN_ERR_BADARG, "GCN_CFG_SPMM_ALGO must be 0, 1, 2 or 3");
             config().spmm_algo = value;
             return GCN_OK;
         case GCN_CFG_SPMM_BLOCKS:
             if (value < 0 || value > 4096) return fail(GCN_ERR_BADARG, "GCN_CFG_SPMM_BLOCKS must be in [0, 4096]");
             config().spmm_blocks = value;
+            return GCN_OK;
+        case GCN_CFG_SWEEP_HEAVY:
+            if (value < 1) return fail(GCN_ERR_BADARG, "GCN_CFG_SWEEP_HEAVY must be at least 1");
+            config().sweep_heavy = value;
             return GCN_OK;
         case GCN_CFG_TIMING:
             if (value != 0 && value != 1) return fail(GCN_ERR_BADARG, "GCN_CFG_TIMING must be 0 or 1");

@@ -60,6 +60,27 @@ struct Blocked {
     int32_t* rq_idx = nullptr;   // [R]    ascending block order inside a row
 };
 
+struct Matrix;
+
+// Sweep copy of a matrix for operands far larger than the caches.  Rows are cut into tasks of
+// `rb` consecutive rows; a task's entries are re-sorted by column block, so a wavefront that owns
+// a task (accumulating its rows in LDS) walks the columns left to right.  All wavefronts of a
+// launch start together and advance at the same pace, so at any moment the whole GPU gathers from
+// a narrow band of X that stays in L2.  Rows longer than `heavy_threshold` are kept apart and go
+// through the nonzero-split kernel.
+struct Sweep {
+    int64_t cols_per_block = 0;
+    int32_t rb = 0;
+    int32_t heavy_threshold = 0;
+    int64_t ntasks = 0, nnz_light = 0, nnz_heavy = 0, n_heavy = 0;
+    int32_t* colidx = nullptr;    // [nnz_light] task-major, column-block-major inside a task
+    float* val = nullptr;         // [nnz_light]
+    uint8_t* lrow = nullptr;      // [nnz_light] row index inside the task
+    int64_t* task_ptr = nullptr;  // [ntasks+1]
+    int32_t* task_order = nullptr;// [ntasks] task ids, longest first
+    Matrix* heavy = nullptr;      // the heavy rows as a row-subset matrix (ne_rows = their ids)
+};
+
 // One stored matrix in compressed rows plus its nonzero-split schedule.
 struct Matrix {
     int64_t* rowptr = nullptr;   // [n+1]
@@ -74,6 +95,7 @@ struct Matrix {
     int64_t nsub = 0, nchunks = 0;
     int32_t max_degree = 0;
     Blocked blk;                 // built on first use for one block width
+    Sweep swp;                   // built on first use for one block width / task height
 };
 
 }  // namespace gcn
@@ -104,6 +126,7 @@ int scratch_get(void** p, size_t bytes);
 struct Config {
     int spmm_algo = 0;
     int spmm_blocks = 0;
+    int sweep_heavy = 4096;
     int timing = 0;
 };
 Config& config();
@@ -115,6 +138,9 @@ void timing_end(hipStream_t s);
 int build_schedule(Matrix& m, int64_t n, int64_t nnz, hipStream_t s);
 int build_blocked(Matrix& m, int64_t n, int64_t nnz, int64_t cols_per_block, hipStream_t s);
 void free_blocked(Blocked& b);
+int build_sweep(Matrix& m, int64_t n, int64_t nnz, int64_t cols_per_block, int32_t rb, int32_t heavy_threshold,
+                hipStream_t s);
+void free_sweep(Sweep& w);
 void free_matrix(Matrix& m);
 
 int spmm_launch(gcn_csr* a, Matrix& m, int32_t f, const float* X, int64_t ldx, float* Z, int64_t ldz,

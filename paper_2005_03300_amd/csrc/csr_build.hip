@@ -400,6 +400,190 @@ int build_blocked(Matrix& m, int64_t n, int64_t nnz, int64_t cpb, hipStream_t s)
     return GCN_OK;
 }
 
+// ---- sweep copy -----------------------------------------------------------------------------------------
+
+struct SweepPayload { int32_t col; float val; int32_t row; };
+
+// key = task << jbits | column block for entries of light rows, all-ones for entries of heavy rows
+// (they sort behind everything and keep their (row, col) order because the sort is stable).
+__global__ void k_sweep_keys(int64_t nnz, int64_t n, const int64_t* __restrict__ rowptr,
+                             const int32_t* __restrict__ colidx, const float* __restrict__ val, int64_t cpb, int32_t rb,
+                             int32_t heavy_th, unsigned jbits, uint64_t heavy_key, uint64_t* __restrict__ keys,
+                             SweepPayload* __restrict__ payload) {
+    int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (k >= nnz) return;
+    int64_t lo = 0, hi = n;
+    while (hi - lo > 1) {
+        int64_t mid = (lo + hi) >> 1;
+        if (rowptr[mid] <= k) lo = mid; else hi = mid;
+    }
+    const int32_t col = colidx[k];
+    const bool heavy = rowptr[lo + 1] - rowptr[lo] > heavy_th;
+    keys[k] = heavy ? heavy_key : (((uint64_t)(lo / rb) << jbits) | (uint64_t)(col / cpb));
+    payload[k] = SweepPayload{col, val[k], (int32_t)lo};
+}
+
+// task_ptr[t] = first sorted position whose key is >= t << jbits; task_ptr[ntasks] = number of light entries
+__global__ void k_sweep_task_ptr(int64_t ntasks, int64_t nnz, unsigned jbits, uint64_t heavy_key,
+                                 const uint64_t* __restrict__ keys, int64_t* __restrict__ task_ptr,
+                                 int32_t* __restrict__ task_id) {
+    int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t > ntasks) return;
+    const uint64_t want = t == ntasks ? heavy_key : ((uint64_t)t << jbits);
+    int64_t lo = 0, hi = nnz;      // first position with keys[pos] >= want
+    while (lo < hi) {
+        int64_t mid = (lo + hi) >> 1;
+        if (keys[mid] < want) lo = mid + 1; else hi = mid;
+    }
+    task_ptr[t] = lo;
+    if (t < ntasks) task_id[t] = (int32_t)t;
+}
+
+__global__ void k_sweep_task_len(int64_t ntasks, const int64_t* __restrict__ task_ptr, uint32_t* __restrict__ len) {
+    int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t < ntasks) len[t] = (uint32_t)(task_ptr[t + 1] - task_ptr[t]);
+}
+
+__global__ void k_sweep_unpack(int64_t count, int32_t rb, const SweepPayload* __restrict__ payload,
+                               int32_t* __restrict__ colidx, float* __restrict__ val, uint8_t* __restrict__ lrow) {
+    int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (k >= count) return;
+    const SweepPayload p = payload[k];
+    colidx[k] = p.col;
+    val[k] = p.val;
+    if (lrow) lrow[k] = (uint8_t)(p.row % rb);
+}
+
+struct HeavyRow {
+    const int64_t* rowptr;
+    int32_t th;
+    __device__ bool operator()(const int32_t& r) const { return rowptr[r + 1] - rowptr[r] > th; }
+};
+
+__global__ void k_heavy_len(int64_t nh, const int32_t* __restrict__ rows, const int64_t* __restrict__ rowptr,
+                            int64_t* __restrict__ len) {
+    int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (q < nh) len[q] = rowptr[rows[q] + 1] - rowptr[rows[q]];
+    if (q == nh) len[q] = 0;
+}
+
+int build_sweep(Matrix& m, int64_t n, int64_t nnz, int64_t cpb, int32_t rb, int32_t heavy_th, hipStream_t s) {
+    free_sweep(m.swp);
+    Sweep& w = m.swp;
+    if (nnz <= 0 || cpb <= 0 || rb <= 0 || rb > 256) return fail(GCN_ERR_BADARG, "build_sweep: bad parameters");
+    const int64_t ntasks = (n + rb - 1) / rb;
+    const int64_t nj = (n + cpb - 1) / cpb;
+    const unsigned jbits = bits_for(nj + 1);
+    const unsigned tbits = bits_for(ntasks + 1);
+    if (jbits + tbits + 1 > 63) return fail(GCN_ERR_RANGE, "build_sweep: key does not fit");
+    const uint64_t heavy_key = 1ull << (jbits + tbits);
+    TempBuf k0, k1, p0, p1, tmp;
+    GCN_TRY(k0.alloc((size_t)nnz * 8));
+    GCN_TRY(k1.alloc((size_t)nnz * 8));
+    GCN_TRY(p0.alloc((size_t)nnz * sizeof(SweepPayload)));
+    GCN_TRY(p1.alloc((size_t)nnz * sizeof(SweepPayload)));
+    hipLaunchKernelGGL(k_sweep_keys, dim3(blocks_for(nnz)), dim3(TPB), 0, s, nnz, n, m.rowptr, m.colidx, m.val, cpb, rb,
+                       heavy_th, jbits, heavy_key, k0.as<uint64_t>(), p0.as<SweepPayload>());
+    GCN_LAUNCH_CHECK();
+    size_t tmp_bytes = 0;
+    const unsigned end_bit = jbits + tbits + 1;
+    GCN_HIP_TRY(rocprim::radix_sort_pairs(nullptr, tmp_bytes, k0.as<uint64_t>(), k1.as<uint64_t>(), p0.as<SweepPayload>(),
+                                          p1.as<SweepPayload>(), (size_t)nnz, 0u, end_bit, s));
+    GCN_TRY(tmp.alloc(tmp_bytes));
+    GCN_HIP_TRY(rocprim::radix_sort_pairs(tmp.p, tmp_bytes, k0.as<uint64_t>(), k1.as<uint64_t>(), p0.as<SweepPayload>(),
+                                          p1.as<SweepPayload>(), (size_t)nnz, 0u, end_bit, s));
+    GCN_HIP_TRY(hipStreamSynchronize(s));
+    k0.alloc(16);
+    p0.alloc(16);
+
+    GCN_TRY(device_alloc_t(&w.task_ptr, (size_t)ntasks + 1));
+    GCN_TRY(device_alloc_t(&w.task_order, (size_t)ntasks));
+    TempBuf ids, len, len_sorted;
+    GCN_TRY(ids.alloc((size_t)ntasks * 4));
+    GCN_TRY(len.alloc((size_t)ntasks * 4));
+    GCN_TRY(len_sorted.alloc((size_t)ntasks * 4));
+    hipLaunchKernelGGL(k_sweep_task_ptr, dim3(blocks_for(ntasks + 1)), dim3(TPB), 0, s, ntasks, nnz, jbits, heavy_key,
+                       k1.as<uint64_t>(), w.task_ptr, ids.as<int32_t>());
+    GCN_LAUNCH_CHECK();
+    hipLaunchKernelGGL(k_sweep_task_len, dim3(blocks_for(ntasks)), dim3(TPB), 0, s, ntasks, w.task_ptr, len.as<uint32_t>());
+    GCN_LAUNCH_CHECK();
+    tmp_bytes = 0;
+    GCN_HIP_TRY(rocprim::radix_sort_pairs_desc(nullptr, tmp_bytes, len.as<uint32_t>(), len_sorted.as<uint32_t>(),
+                                               ids.as<int32_t>(), w.task_order, (size_t)ntasks, 0u, 32u, s));
+    GCN_TRY(tmp.alloc(tmp_bytes));
+    GCN_HIP_TRY(rocprim::radix_sort_pairs_desc(tmp.p, tmp_bytes, len.as<uint32_t>(), len_sorted.as<uint32_t>(),
+                                               ids.as<int32_t>(), w.task_order, (size_t)ntasks, 0u, 32u, s));
+    int64_t nnz_light = 0;
+    GCN_HIP_TRY(hipMemcpyAsync(&nnz_light, w.task_ptr + ntasks, 8, hipMemcpyDeviceToHost, s));
+    GCN_HIP_TRY(hipStreamSynchronize(s));
+    const int64_t nnz_heavy = nnz - nnz_light;
+
+    GCN_TRY(device_alloc_t(&w.colidx, (size_t)nnz_light));
+    GCN_TRY(device_alloc_t(&w.val, (size_t)nnz_light));
+    GCN_TRY(device_alloc_t(&w.lrow, (size_t)nnz_light));
+    if (nnz_light > 0) {
+        hipLaunchKernelGGL(k_sweep_unpack, dim3(blocks_for(nnz_light)), dim3(TPB), 0, s, nnz_light, rb,
+                           p1.as<SweepPayload>(), w.colidx, w.val, w.lrow);
+        GCN_LAUNCH_CHECK();
+    }
+    if (nnz_heavy > 0) {
+        Matrix* h = new (std::nothrow) Matrix();
+        if (!h) return fail(GCN_ERR_OOM, "host allocation failed");
+        w.heavy = h;
+        GCN_TRY(device_alloc_t(&h->colidx, (size_t)nnz_heavy));
+        GCN_TRY(device_alloc_t(&h->val, (size_t)nnz_heavy));
+        hipLaunchKernelGGL(k_sweep_unpack, dim3(blocks_for(nnz_heavy)), dim3(TPB), 0, s, nnz_heavy, rb,
+                           p1.as<SweepPayload>() + nnz_light, h->colidx, h->val, (uint8_t*)nullptr);
+        GCN_LAUNCH_CHECK();
+        // the heavy rows in ascending order, and their offsets into the heavy entry arrays
+        TempBuf cnt, hl;
+        GCN_TRY(cnt.alloc(sizeof(size_t)));
+        GCN_TRY(device_alloc_t(&h->ne_rows, (size_t)(nnz_heavy / (heavy_th + 1)) + 1));
+        rocprim::counting_iterator<int32_t> rows(0);
+        HeavyRow pred{m.rowptr, heavy_th};
+        tmp_bytes = 0;
+        GCN_HIP_TRY(rocprim::select(nullptr, tmp_bytes, rows, h->ne_rows, cnt.as<size_t>(), (size_t)n, pred, s));
+        GCN_TRY(tmp.alloc(tmp_bytes));
+        GCN_HIP_TRY(rocprim::select(tmp.p, tmp_bytes, rows, h->ne_rows, cnt.as<size_t>(), (size_t)n, pred, s));
+        size_t nh = 0;
+        GCN_HIP_TRY(hipMemcpyAsync(&nh, cnt.p, sizeof(size_t), hipMemcpyDeviceToHost, s));
+        GCN_HIP_TRY(hipStreamSynchronize(s));
+        h->n_ne = (int64_t)nh;
+        GCN_TRY(hl.alloc((nh + 1) * 8));
+        GCN_TRY(device_alloc_t(&h->ne_rowptr, nh + 1));
+        hipLaunchKernelGGL(k_heavy_len, dim3(blocks_for((int64_t)nh + 1)), dim3(TPB), 0, s, (int64_t)nh, h->ne_rows, m.rowptr,
+                           hl.as<int64_t>());
+        GCN_LAUNCH_CHECK();
+        tmp_bytes = 0;
+        GCN_HIP_TRY(rocprim::exclusive_scan(nullptr, tmp_bytes, hl.as<int64_t>(), h->ne_rowptr, (int64_t)0, nh + 1,
+                                            rocprim::plus<int64_t>(), s));
+        GCN_TRY(tmp.alloc(tmp_bytes));
+        GCN_HIP_TRY(rocprim::exclusive_scan(tmp.p, tmp_bytes, hl.as<int64_t>(), h->ne_rowptr, (int64_t)0, nh + 1,
+                                            rocprim::plus<int64_t>(), s));
+        h->nsub = (nnz_heavy + SUB - 1) / SUB;
+        h->nchunks = (nnz_heavy + CHUNK - 1) / CHUNK;
+        const size_t padded = (size_t)h->nsub + SUBS_PER_CHUNK;
+        GCN_TRY(device_alloc_t(&h->flags, padded));
+        GCN_TRY(device_alloc_t(&h->sub_row, padded));
+        GCN_HIP_TRY(hipMemsetAsync(h->flags, 0, padded * sizeof(uint32_t), s));
+        GCN_HIP_TRY(hipMemsetAsync(h->sub_row, 0, padded * sizeof(int32_t), s));
+        hipLaunchKernelGGL(k_row_flags, dim3(blocks_for(h->n_ne)), dim3(TPB), 0, s, h->n_ne, h->ne_rowptr, h->flags);
+        GCN_LAUNCH_CHECK();
+        hipLaunchKernelGGL(k_sub_rows, dim3(blocks_for(h->nsub)), dim3(TPB), 0, s, h->nsub, h->n_ne, h->ne_rowptr, h->sub_row);
+        GCN_LAUNCH_CHECK();
+        GCN_HIP_TRY(hipStreamSynchronize(s));
+    }
+    GCN_HIP_TRY(hipStreamSynchronize(s));
+    w.cols_per_block = cpb;
+    w.rb = rb;
+    w.heavy_threshold = heavy_th;
+    w.ntasks = ntasks;
+    w.nnz_light = nnz_light;
+    w.nnz_heavy = nnz_heavy;
+    w.n_heavy = w.heavy ? w.heavy->n_ne : 0;
+    return GCN_OK;
+}
+
 // A^T of `a` from A's sorted keys and values: swap key halves, stable radix sort with the values
 // as payload.  Within a column the rows keep their ascending order.
 static int build_transpose(gcn_csr* a, const uint64_t* keys, uint64_t* scratch_keys, hipStream_t s) {

@@ -352,6 +352,143 @@ static int launch_block_reduce(int64_t n, int32_t f, const Blocked& b, const flo
     return GCN_OK;
 }
 
+// ---- column sweep ---------------------------------------------------------------------------------------
+// One wavefront owns a task: `rb` consecutive rows whose results live in LDS (rb x W floats, W = 16
+// or 32) for the whole launch.  Its entries come sorted by column block, so it walks X left to
+// right; all wavefronts of a launch start together and advance at the same pace, which keeps the
+// band of X being gathered inside L2 even when X is far larger than every cache.  Each lane group
+// takes every G-th entry, multiplies the gathered row by the value and adds it to the task's row
+// in LDS.  Only this wavefront touches these accumulators, so plain LDS reads and writes in program
+// order suffice once two groups of one step are kept off the same row (see the claim loop).
+struct SweepArgs {
+    const int32_t* colidx;
+    const float* val;
+    const uint8_t* lrow;
+    const int64_t* task_ptr;
+    const int32_t* task_order;
+    int64_t n;
+    int32_t f, rb;
+    const float* X; int64_t ldx;
+    float* Z; int64_t ldz;
+    const float* Zprev; int64_t ldzprev;
+};
+
+template <int LPR, int EPI>
+__global__ __launch_bounds__(64) void k_spmm_sweep(SweepArgs a, int64_t first_task) {
+    constexpr int G = 64 / LPR;                  // entries per step
+    constexpr int W = LPR * 4;                   // panel width in floats
+    constexpr int STEPS = 64 / G;
+    extern __shared__ float smem[];              // acc[rb][W], then owner[rb]
+    float* acc = smem;
+    volatile int* owner = reinterpret_cast<volatile int*>(smem + a.rb * W);
+    const int lane = threadIdx.x;
+    const int g = lane / LPR, li = lane % LPR;
+    const int col0 = li * 4;
+    const bool col_ok = col0 < a.f;
+    const int64_t task = a.task_order[first_task + blockIdx.x];
+    for (int i = lane * 4; i < a.rb * W; i += 256) *reinterpret_cast<float4*>(acc + i) = make_float4(0.f, 0.f, 0.f, 0.f);
+    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+
+    const int64_t e0 = a.task_ptr[task], e1 = a.task_ptr[task + 1];
+    const float* xbase = a.X + col0;
+    // entries of the next trip are fetched while the current one is gathered and added
+    int32_t c = 0; float v = 0.f; int r = 0;
+    if (e0 + lane < e1) { c = a.colidx[e0 + lane]; v = a.val[e0 + lane]; r = (int)a.lrow[e0 + lane]; }
+    for (int64_t base = e0; base < e1; base += 64) {
+        const int64_t nidx = base + 64 + lane;
+        int32_t nc = 0; float nv = 0.f; int nr = 0;
+        if (nidx < e1) { nc = a.colidx[nidx]; nv = a.val[nidx]; nr = (int)a.lrow[nidx]; }
+        const int left = (int)((e1 - base) < 64 ? (e1 - base) : 64);
+        float x[STEPS][4];
+        float vs[STEPS];
+        int rs[STEPS];
+#pragma unroll
+        for (int t = 0; t < STEPS; ++t) {        // every gather of the trip is issued before any add
+            const int src = t * G + g;
+            const int32_t cs = __shfl(c, src, 64);
+            vs[t] = __shfl(v, src, 64);
+            rs[t] = __shfl(r, src, 64);
+            if (src < left && col_ok) {
+                const float4 q = *reinterpret_cast<const float4*>(xbase + (int64_t)cs * a.ldx);
+                x[t][0] = q.x; x[t][1] = q.y; x[t][2] = q.z; x[t][3] = q.w;
+            } else {
+                x[t][0] = x[t][1] = x[t][2] = x[t][3] = 0.f;
+            }
+        }
+#pragma unroll
+        for (int t = 0; t < STEPS; ++t) {
+            // Two lane groups may hold the same row in one step.  Each group claims its row by writing
+            // its number; the group whose number is read back adds (plain read-modify-write, it is alone
+            // on that row); the others try again.  Almost always one round.
+            bool pending = (t * G + g < left) && col_ok;
+            while (true) {
+                if (pending) owner[rs[t]] = g;
+                __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                if (pending && owner[rs[t]] == g) {
+                    float4* dst = reinterpret_cast<float4*>(acc + rs[t] * W + col0);
+                    float4 cur = *dst;
+                    cur.x = fmaf(vs[t], x[t][0], cur.x);
+                    cur.y = fmaf(vs[t], x[t][1], cur.y);
+                    cur.z = fmaf(vs[t], x[t][2], cur.z);
+                    cur.w = fmaf(vs[t], x[t][3], cur.w);
+                    *dst = cur;
+                    pending = false;
+                }
+                __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                if (!__any(pending)) break;
+            }
+        }
+        c = nc; v = nv; r = nr;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    // write the task's rows: G rows per pass, 16 bytes per lane
+    const int64_t row0 = task * a.rb;
+    for (int i = g; i < a.rb; i += G) {
+        const int64_t row = row0 + i;
+        if (row < a.n && col_ok) {
+            const float4 q = *reinterpret_cast<const float4*>(acc + i * W + col0);
+            float out[4] = {q.x, q.y, q.z, q.w};
+            epilogue_store<4, EPI>(a.Z + row * a.ldz + col0, EPI == GCN_EPI_MASK ? a.Zprev + row * a.ldzprev + col0 : nullptr, out);
+        }
+    }
+}
+
+static constexpr int SWEEP_WAVES_PER_CU = 16;
+static constexpr int SWEEP_CUS = 256;
+
+template <int LPR>
+static int launch_sweep(const SweepArgs& args, int64_t ntasks, int epilogue, hipStream_t s) {
+    constexpr int W = LPR * 4;
+    const size_t lds = (size_t)args.rb * (W + 1) * sizeof(float);
+    const unsigned ytiles = (unsigned)((args.f + W - 1) / W);
+    const int64_t gen = (int64_t)SWEEP_CUS * SWEEP_WAVES_PER_CU;      // tasks that are resident at once
+    timing_begin(s);
+    for (unsigned y = 0; y < ytiles; ++y) {
+        for (int64_t first = 0; first < ntasks; first += gen) {
+            const int64_t count = ntasks - first < gen ? ntasks - first : gen;
+            const dim3 grid((unsigned)count, 1);
+            SweepArgs a = args;
+            // one panel per launch: shift the column origin instead of using blockIdx.y
+            a.X = args.X + (size_t)y * W;
+            a.Z = args.Z + (size_t)y * W;
+            a.Zprev = args.Zprev ? args.Zprev + (size_t)y * W : nullptr;
+            a.f = args.f - (int32_t)(y * W) < W ? args.f - (int32_t)(y * W) : W;
+            switch (epilogue) {
+                case GCN_EPI_NONE: hipLaunchKernelGGL((k_spmm_sweep<LPR, GCN_EPI_NONE>), grid, dim3(64), lds, s, a, first); break;
+                case GCN_EPI_RELU: hipLaunchKernelGGL((k_spmm_sweep<LPR, GCN_EPI_RELU>), grid, dim3(64), lds, s, a, first); break;
+                default: hipLaunchKernelGGL((k_spmm_sweep<LPR, GCN_EPI_MASK>), grid, dim3(64), lds, s, a, first); break;
+            }
+        }
+    }
+    timing_end(s);
+    GCN_LAUNCH_CHECK();
+    return GCN_OK;
+}
+
 // Chooses the lane layout for one nonzero-split product and launches it.
 static int run_split(const SplitArgs& args, int epilogue, hipStream_t s) {
     const int32_t f = args.f;
@@ -410,7 +547,40 @@ int spmm_launch(gcn_csr* a, Matrix& m, int32_t f, const float* X, int64_t ldx, f
         return GCN_OK;
     }
     int algo = config().spmm_algo;
-    if (algo == 0) algo = 2;
+    const bool vec4_all = (f % 4 == 0) && (ldx % 4 == 0) && (ldz % 4 == 0) && aligned16(X) && aligned16(Z) &&
+                          (epilogue != GCN_EPI_MASK || ((ldzprev % 4 == 0) && aligned16(Zprev)));
+    if (algo == 0) algo = 2;   // the column sweep (3) is only taken on request: it is not yet faster
+    if (algo == 3 && !vec4_all) algo = 2;
+    if (algo == 3) {
+        const int LPRs = f <= 16 ? 4 : 8;
+        const int W = LPRs * 4;
+        const int32_t rb = 2048 / W;                       // 8 KB of accumulators per wavefront
+        int64_t nj = config().spmm_blocks >= 2 ? config().spmm_blocks : (n * W * 4 + (1ll << 20) - 1) / (1ll << 20);
+        if (nj < 1) nj = 1;
+        int64_t cpb = (n + nj - 1) / nj;
+        if (config().spmm_blocks < 2) cpb = (cpb + 255) & ~255ll;
+        const int32_t th = config().sweep_heavy;
+        if (m.swp.cols_per_block != cpb || m.swp.rb != rb || m.swp.heavy_threshold != th)
+            GCN_TRY(build_sweep(m, n, nnz, cpb, rb, th, s));
+        const Sweep& w = m.swp;
+        SweepArgs sa;
+        sa.colidx = w.colidx; sa.val = w.val; sa.lrow = w.lrow; sa.task_ptr = w.task_ptr; sa.task_order = w.task_order;
+        sa.n = n; sa.f = f; sa.rb = rb; sa.X = X; sa.ldx = ldx; sa.Z = Z; sa.ldz = ldz; sa.Zprev = Zprev; sa.ldzprev = ldzprev;
+        if (LPRs == 4) GCN_TRY(launch_sweep<4>(sa, w.ntasks, epilogue, s));
+        else GCN_TRY(launch_sweep<8>(sa, w.ntasks, epilogue, s));
+        if (w.heavy) {                                       // long rows: nonzero-split kernel over the row subset
+            const Matrix& h = *w.heavy;
+            GCN_TRY(grow(&a->carry, &a->carry_bytes, (size_t)h.nchunks * (size_t)f * sizeof(float)));
+            SplitArgs args;
+            args.nnz = w.nnz_heavy; args.nsub = h.nsub; args.nchunks = h.nchunks; args.f = f;
+            args.X = X; args.ldx = ldx; args.carry = a->carry;
+            args.colidx = h.colidx; args.val = h.val; args.flags = h.flags; args.sub_row = h.sub_row;
+            args.ne_rows = h.ne_rows; args.rp = h.ne_rowptr;
+            args.Z = Z; args.ldz = ldz; args.Zprev = Zprev; args.ldzprev = ldzprev;
+            GCN_TRY(run_split(args, epilogue, s));
+        }
+        return GCN_OK;
+    }
     if (algo == 1) {
         const int64_t work = n * f;
         const dim3 grid((unsigned)((work + 255) / 256));

@@ -35,11 +35,11 @@ CONFIGS = {
     2: Workload("rmat20_spmm_f128", "rmat", 1 << 20, 16 << 20, (128,), 0, "uniform", rmat_scale=20),
     # m_raw of 3-5 is chosen so that, after duplicate removal, the number of distinct
     # unordered pairs lands near the dataset's edge count / 2.
-    3: Workload("chunglu_reddit_gcn_602_16_16_41", "chunglu", 232_965, 59_100_000,
+    3: Workload("chunglu_reddit_gcn_602_16_16_41", "chunglu", 232_965, 59_450_000,
                 (602, 16, 16, 41), 41, "normal", gamma=2.1, max_degree=20_000.0),
     4: Workload("rmat_amazon_gcn_300_16_16_24", "rmat", 14_249_639, 121_500_000,
                 (300, 16, 16, 24), 24, "normal", rmat_scale=24),
-    5: Workload("chunglu_protein_gcn_128_16_16_256", "chunglu", 8_745_542, 672_000_000,
+    5: Workload("chunglu_protein_gcn_128_16_16_256", "chunglu", 8_745_542, 656_500_000,
                 (128, 16, 16, 256), 256, "normal", gamma=2.3, max_degree=50_000.0),
 }
 

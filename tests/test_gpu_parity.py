@@ -330,6 +330,48 @@ def test_spmm_column_blocked_automatic_choice():
     a.close()
 
 
+@pytest.mark.parametrize("name", ["c2s", "c4s", "c3s", "star", "tiny", "one"])
+@pytest.mark.parametrize("heavy", [1 << 20, 64])
+def test_spmm_column_sweep_forced(name, heavy):
+    """The column-sweep schedule (LDS-resident row blocks, entries walked by column block; rows longer
+    than the threshold go through the nonzero-split kernel) forced on small graphs."""
+    g = G()
+    a = gpu_csr(name)
+    ref = oracle_csr(name)
+    g.gcn_config(g.CFG_SWEEP_HEAVY, heavy)
+    g.gcn_config(g.CFG_SPMM_BLOCKS, 7)
+    try:
+        for f in (16, 8, 32, 128, 100):
+            X = synth.normal_features(ref.n, f, 18)
+            Zp = synth.normal_features(ref.n, f, 19)
+            plain = oracle.spmm(ref, X)
+            assert_close(run_spmm(a, X, algo=3), plain, f"{name} heavy>{heavy} f={f}")
+            assert_close(run_spmm(a, X, algo=3, epilogue=g.EPI_MASK, Zprev=Zp), oracle.relu_mask(plain, Zp), "mask")
+            assert_close(run_spmm(a, X, algo=3, epilogue=g.EPI_RELU, ld_pad=4), np.maximum(plain, 0), "relu, padded ld")
+        first = run_spmm(a, X, algo=3)
+        for _ in range(3):      # LDS adds of one wavefront are served in a fixed order: same bits every time
+            np.testing.assert_array_equal(first.view(np.uint32), run_spmm(a, X, algo=3).view(np.uint32))
+    finally:
+        g.gcn_config(g.CFG_SPMM_BLOCKS, 0)
+        g.gcn_config(g.CFG_SWEEP_HEAVY, 4096)
+    a.close()
+
+
+def test_spmm_column_sweep_directed_with_empty_rows():
+    g = G()
+    a = gpu_csr("c4s", symmetrise=False, self_loops=False, norm="none")
+    ref = oracle_csr("c4s", False, False, "none", False)
+    ref_t = oracle_csr("c4s", False, False, "none", True)
+    X = synth.uniform_features(ref.n, 16, 13)
+    g.gcn_config(g.CFG_SWEEP_HEAVY, 100)
+    try:
+        assert_close(run_spmm(a, X, trans=0, algo=3), oracle.spmm(ref, X), "A")
+        assert_close(run_spmm(a, X, trans=1, algo=3), oracle.spmm(ref_t, X), "A^T")
+    finally:
+        g.gcn_config(g.CFG_SWEEP_HEAVY, 4096)
+    a.close()
+
+
 # ------------------------------------------------------------------------------------------------
 # a4 / a5 / a6: dense products and element-wise
 # ------------------------------------------------------------------------------------------------
