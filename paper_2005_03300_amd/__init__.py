@@ -12,5 +12,5 @@ from .binding import (  # noqa: F401
     gcn_epoch_view, gcn_config, gcn_timing_read, gcn_version,
     SYMMETRISE, ADD_SELF_LOOPS, NORM_SYM, BUILD_TRANSPOSE,
     EPI_NONE, EPI_RELU, EPI_MASK, ORDER_AUTO, ORDER_GEMM_FIRST, ORDER_SPMM_FIRST, ACT_NONE, ACT_RELU,
-    CFG_SPMM_ALGO, CFG_TIMING, CFG_SPMM_BLOCKS, CFG_SWEEP_HEAVY,
+    CFG_SPMM_ALGO, CFG_TIMING, CFG_SPMM_BLOCKS, CFG_SWEEP_HEAVY, CFG_SWEEP_WAVES,
 )

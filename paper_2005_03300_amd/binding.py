@@ -13,7 +13,7 @@ SYMMETRISE, ADD_SELF_LOOPS, NORM_SYM, BUILD_TRANSPOSE = 1, 2, 4, 8
 EPI_NONE, EPI_RELU, EPI_MASK = 0, 1, 2
 ORDER_AUTO, ORDER_GEMM_FIRST, ORDER_SPMM_FIRST = 0, 1, 2
 ACT_NONE, ACT_RELU = 0, 1
-CFG_SPMM_ALGO, CFG_TIMING, CFG_SPMM_BLOCKS, CFG_SWEEP_HEAVY = 1, 2, 3, 4
+CFG_SPMM_ALGO, CFG_TIMING, CFG_SPMM_BLOCKS, CFG_SWEEP_HEAVY, CFG_SWEEP_WAVES = 1, 2, 3, 4, 5
 
 _lib = None
 

@@ -114,7 +114,8 @@ void free_sweep(Sweep& w) {
     device_free(w.colidx);
     device_free(w.val);
     device_free(w.lrow);
-    device_free(w.task_ptr);
+    device_free(w.task_base);
+    device_free(w.task_len);
     device_free(w.task_order);
     if (w.heavy) {
         free_matrix(*w.heavy);
@@ -152,8 +153,12 @@ int gcn_config(int key, int value) {
             config().spmm_algo = value;
             return GCN_OK;
         case GCN_CFG_SPMM_BLOCKS:
-            if (value < 0 || value > 4096) return fail(GCN_ERR_BADARG, "GCN_CFG_SPMM_BLOCKS must be in [0, 4096]");
+            if (value < 0 || value > (1 << 24)) return fail(GCN_ERR_BADARG, "GCN_CFG_SPMM_BLOCKS must be in [0, 2^24]");
             config().spmm_blocks = value;
+            return GCN_OK;
+        case GCN_CFG_SWEEP_WAVES:
+            if (value < 1 || value > 18) return fail(GCN_ERR_BADARG, "GCN_CFG_SWEEP_WAVES must be in [1, 18]");
+            config().sweep_waves = value;
             return GCN_OK;
         case GCN_CFG_SWEEP_HEAVY:
             if (value < 1) return fail(GCN_ERR_BADARG, "GCN_CFG_SWEEP_HEAVY must be at least 1");

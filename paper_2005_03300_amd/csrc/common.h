@@ -73,10 +73,13 @@ struct Sweep {
     int32_t rb = 0;
     int32_t heavy_threshold = 0;
     int64_t ntasks = 0, nnz_light = 0, nnz_heavy = 0, n_heavy = 0;
-    int32_t* colidx = nullptr;    // [nnz_light] task-major, column-block-major inside a task
-    float* val = nullptr;         // [nnz_light]
-    uint8_t* lrow = nullptr;      // [nnz_light] row index inside the task
-    int64_t* task_ptr = nullptr;  // [ntasks+1]
+    int64_t padded = 0;           // entries stored: every task starts at a multiple of 16
+    int32_t* colidx = nullptr;    // [padded] task-major, column-block-major inside a task
+    float* val = nullptr;         // [padded]
+    uint8_t* lrow = nullptr;      // [padded] bits 0-6: row inside the task; bit 7 of the first entry of an
+                                  //          aligned group of 16: the group holds some row twice
+    int64_t* task_base = nullptr; // [ntasks] first stored entry of the task
+    int32_t* task_len = nullptr;  // [ntasks] entries of the task
     int32_t* task_order = nullptr;// [ntasks] task ids, longest first
     Matrix* heavy = nullptr;      // the heavy rows as a row-subset matrix (ne_rows = their ids)
 };
@@ -127,6 +130,7 @@ struct Config {
     int spmm_algo = 0;
     int spmm_blocks = 0;
     int sweep_heavy = 4096;
+    int sweep_waves = 16;
     int timing = 0;
 };
 Config& config();

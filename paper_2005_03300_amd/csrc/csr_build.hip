@@ -423,9 +423,9 @@ __global__ void k_sweep_keys(int64_t nnz, int64_t n, const int64_t* __restrict__
     payload[k] = SweepPayload{col, val[k], (int32_t)lo};
 }
 
-// task_ptr[t] = first sorted position whose key is >= t << jbits; task_ptr[ntasks] = number of light entries
+// raw_ptr[t] = first sorted position whose key is >= t << jbits; raw_ptr[ntasks] = number of light entries
 __global__ void k_sweep_task_ptr(int64_t ntasks, int64_t nnz, unsigned jbits, uint64_t heavy_key,
-                                 const uint64_t* __restrict__ keys, int64_t* __restrict__ task_ptr,
+                                 const uint64_t* __restrict__ keys, int64_t* __restrict__ raw_ptr,
                                  int32_t* __restrict__ task_id) {
     int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (t > ntasks) return;
@@ -435,23 +435,50 @@ __global__ void k_sweep_task_ptr(int64_t ntasks, int64_t nnz, unsigned jbits, ui
         int64_t mid = (lo + hi) >> 1;
         if (keys[mid] < want) lo = mid + 1; else hi = mid;
     }
-    task_ptr[t] = lo;
+    raw_ptr[t] = lo;
     if (t < ntasks) task_id[t] = (int32_t)t;
 }
 
-__global__ void k_sweep_task_len(int64_t ntasks, const int64_t* __restrict__ task_ptr, uint32_t* __restrict__ len) {
+// lengths, and lengths rounded up to 16 (every task starts on a multiple of 16 entries)
+__global__ void k_sweep_task_len(int64_t ntasks, const int64_t* __restrict__ raw_ptr, int32_t* __restrict__ len,
+                                 uint32_t* __restrict__ sort_key, int64_t* __restrict__ padded_len) {
     int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (t < ntasks) len[t] = (uint32_t)(task_ptr[t + 1] - task_ptr[t]);
+    if (t >= ntasks) return;
+    const int64_t l = raw_ptr[t + 1] - raw_ptr[t];
+    len[t] = (int32_t)l;
+    sort_key[t] = (uint32_t)l;
+    padded_len[t] = (l + 15) & ~15ll;
 }
 
-__global__ void k_sweep_unpack(int64_t count, int32_t rb, const SweepPayload* __restrict__ payload,
-                               int32_t* __restrict__ colidx, float* __restrict__ val, uint8_t* __restrict__ lrow) {
+// sorted position p of task t goes to task_base[t] + (p - raw_ptr[t]); with task_base == NULL the
+// output is dense (used for the heavy rows, whose local row is not needed)
+__global__ void k_sweep_unpack(int64_t count, int64_t first, int32_t rb, unsigned jbits, const uint64_t* __restrict__ keys,
+                               const SweepPayload* __restrict__ payload, const int64_t* __restrict__ raw_ptr,
+                               const int64_t* __restrict__ task_base, int32_t* __restrict__ colidx,
+                               float* __restrict__ val, uint8_t* __restrict__ lrow) {
     int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (k >= count) return;
-    const SweepPayload p = payload[k];
-    colidx[k] = p.col;
-    val[k] = p.val;
-    if (lrow) lrow[k] = (uint8_t)(p.row % rb);
+    const SweepPayload p = payload[first + k];
+    int64_t dst = k;
+    if (task_base) {
+        const int64_t t = (int64_t)(keys[k] >> jbits);
+        dst = task_base[t] + (k - raw_ptr[t]);
+    }
+    colidx[dst] = p.col;
+    val[dst] = p.val;
+    if (lrow) lrow[dst] = (uint8_t)(p.row % rb);
+}
+
+// bit 7 of the first local-row byte of every aligned group of 16 entries: set when two of the 16 share a row
+__global__ void k_sweep_dirty(int64_t ngroups, uint8_t* __restrict__ lrow) {
+    int64_t b = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= ngroups) return;
+    uint8_t r[16];
+    for (int i = 0; i < 16; ++i) r[i] = lrow[b * 16 + i] & 0x7f;
+    bool dup = false;
+    for (int i = 1; i < 16; ++i)
+        for (int j = 0; j < i; ++j) dup |= (r[i] == r[j]);
+    if (dup) lrow[b * 16] = r[0] | 0x80;
 }
 
 struct HeavyRow {
@@ -470,7 +497,7 @@ __global__ void k_heavy_len(int64_t nh, const int32_t* __restrict__ rows, const 
 int build_sweep(Matrix& m, int64_t n, int64_t nnz, int64_t cpb, int32_t rb, int32_t heavy_th, hipStream_t s) {
     free_sweep(m.swp);
     Sweep& w = m.swp;
-    if (nnz <= 0 || cpb <= 0 || rb <= 0 || rb > 256) return fail(GCN_ERR_BADARG, "build_sweep: bad parameters");
+    if (nnz <= 0 || cpb <= 0 || rb <= 0 || rb > 128) return fail(GCN_ERR_BADARG, "build_sweep: bad parameters");
     const int64_t ntasks = (n + rb - 1) / rb;
     const int64_t nj = (n + cpb - 1) / cpb;
     const unsigned jbits = bits_for(nj + 1);
@@ -496,16 +523,20 @@ int build_sweep(Matrix& m, int64_t n, int64_t nnz, int64_t cpb, int32_t rb, int3
     k0.alloc(16);
     p0.alloc(16);
 
-    GCN_TRY(device_alloc_t(&w.task_ptr, (size_t)ntasks + 1));
+    GCN_TRY(device_alloc_t(&w.task_base, (size_t)ntasks));
+    GCN_TRY(device_alloc_t(&w.task_len, (size_t)ntasks));
     GCN_TRY(device_alloc_t(&w.task_order, (size_t)ntasks));
-    TempBuf ids, len, len_sorted;
+    TempBuf raw, ids, len, len_sorted, plen;
+    GCN_TRY(raw.alloc(((size_t)ntasks + 1) * 8));
     GCN_TRY(ids.alloc((size_t)ntasks * 4));
     GCN_TRY(len.alloc((size_t)ntasks * 4));
     GCN_TRY(len_sorted.alloc((size_t)ntasks * 4));
+    GCN_TRY(plen.alloc((size_t)ntasks * 8));
     hipLaunchKernelGGL(k_sweep_task_ptr, dim3(blocks_for(ntasks + 1)), dim3(TPB), 0, s, ntasks, nnz, jbits, heavy_key,
-                       k1.as<uint64_t>(), w.task_ptr, ids.as<int32_t>());
+                       k1.as<uint64_t>(), raw.as<int64_t>(), ids.as<int32_t>());
     GCN_LAUNCH_CHECK();
-    hipLaunchKernelGGL(k_sweep_task_len, dim3(blocks_for(ntasks)), dim3(TPB), 0, s, ntasks, w.task_ptr, len.as<uint32_t>());
+    hipLaunchKernelGGL(k_sweep_task_len, dim3(blocks_for(ntasks)), dim3(TPB), 0, s, ntasks, raw.as<int64_t>(), w.task_len,
+                       len.as<uint32_t>(), plen.as<int64_t>());
     GCN_LAUNCH_CHECK();
     tmp_bytes = 0;
     GCN_HIP_TRY(rocprim::radix_sort_pairs_desc(nullptr, tmp_bytes, len.as<uint32_t>(), len_sorted.as<uint32_t>(),
@@ -513,17 +544,34 @@ int build_sweep(Matrix& m, int64_t n, int64_t nnz, int64_t cpb, int32_t rb, int3
     GCN_TRY(tmp.alloc(tmp_bytes));
     GCN_HIP_TRY(rocprim::radix_sort_pairs_desc(tmp.p, tmp_bytes, len.as<uint32_t>(), len_sorted.as<uint32_t>(),
                                                ids.as<int32_t>(), w.task_order, (size_t)ntasks, 0u, 32u, s));
-    int64_t nnz_light = 0;
-    GCN_HIP_TRY(hipMemcpyAsync(&nnz_light, w.task_ptr + ntasks, 8, hipMemcpyDeviceToHost, s));
+    tmp_bytes = 0;
+    GCN_HIP_TRY(rocprim::exclusive_scan(nullptr, tmp_bytes, plen.as<int64_t>(), w.task_base, (int64_t)0, (size_t)ntasks,
+                                        rocprim::plus<int64_t>(), s));
+    GCN_TRY(tmp.alloc(tmp_bytes));
+    GCN_HIP_TRY(rocprim::exclusive_scan(tmp.p, tmp_bytes, plen.as<int64_t>(), w.task_base, (int64_t)0, (size_t)ntasks,
+                                        rocprim::plus<int64_t>(), s));
+    int64_t nnz_light = 0, last_base = 0, last_plen = 0;
+    GCN_HIP_TRY(hipMemcpyAsync(&nnz_light, raw.as<int64_t>() + ntasks, 8, hipMemcpyDeviceToHost, s));
+    GCN_HIP_TRY(hipMemcpyAsync(&last_base, w.task_base + (ntasks - 1), 8, hipMemcpyDeviceToHost, s));
+    GCN_HIP_TRY(hipMemcpyAsync(&last_plen, plen.as<int64_t>() + (ntasks - 1), 8, hipMemcpyDeviceToHost, s));
     GCN_HIP_TRY(hipStreamSynchronize(s));
     const int64_t nnz_heavy = nnz - nnz_light;
+    const int64_t padded = last_base + last_plen;
+    w.padded = padded;
 
-    GCN_TRY(device_alloc_t(&w.colidx, (size_t)nnz_light));
-    GCN_TRY(device_alloc_t(&w.val, (size_t)nnz_light));
-    GCN_TRY(device_alloc_t(&w.lrow, (size_t)nnz_light));
+    GCN_TRY(device_alloc_t(&w.colidx, (size_t)padded));
+    GCN_TRY(device_alloc_t(&w.val, (size_t)padded));
+    GCN_TRY(device_alloc_t(&w.lrow, (size_t)padded));
+    if (padded > 0) {
+        GCN_HIP_TRY(hipMemsetAsync(w.colidx, 0, (size_t)padded * 4, s));
+        GCN_HIP_TRY(hipMemsetAsync(w.val, 0, (size_t)padded * 4, s));
+        GCN_HIP_TRY(hipMemsetAsync(w.lrow, 0, (size_t)padded, s));
+    }
     if (nnz_light > 0) {
-        hipLaunchKernelGGL(k_sweep_unpack, dim3(blocks_for(nnz_light)), dim3(TPB), 0, s, nnz_light, rb,
-                           p1.as<SweepPayload>(), w.colidx, w.val, w.lrow);
+        hipLaunchKernelGGL(k_sweep_unpack, dim3(blocks_for(nnz_light)), dim3(TPB), 0, s, nnz_light, (int64_t)0, rb, jbits,
+                           k1.as<uint64_t>(), p1.as<SweepPayload>(), raw.as<int64_t>(), w.task_base, w.colidx, w.val, w.lrow);
+        GCN_LAUNCH_CHECK();
+        hipLaunchKernelGGL(k_sweep_dirty, dim3(blocks_for(padded / 16)), dim3(TPB), 0, s, padded / 16, w.lrow);
         GCN_LAUNCH_CHECK();
     }
     if (nnz_heavy > 0) {
@@ -532,8 +580,9 @@ int build_sweep(Matrix& m, int64_t n, int64_t nnz, int64_t cpb, int32_t rb, int3
         w.heavy = h;
         GCN_TRY(device_alloc_t(&h->colidx, (size_t)nnz_heavy));
         GCN_TRY(device_alloc_t(&h->val, (size_t)nnz_heavy));
-        hipLaunchKernelGGL(k_sweep_unpack, dim3(blocks_for(nnz_heavy)), dim3(TPB), 0, s, nnz_heavy, rb,
-                           p1.as<SweepPayload>() + nnz_light, h->colidx, h->val, (uint8_t*)nullptr);
+        hipLaunchKernelGGL(k_sweep_unpack, dim3(blocks_for(nnz_heavy)), dim3(TPB), 0, s, nnz_heavy, nnz_light, rb, jbits,
+                           k1.as<uint64_t>(), p1.as<SweepPayload>(), (const int64_t*)nullptr, (const int64_t*)nullptr,
+                           h->colidx, h->val, (uint8_t*)nullptr);
         GCN_LAUNCH_CHECK();
         // the heavy rows in ascending order, and their offsets into the heavy entry arrays
         TempBuf cnt, hl;

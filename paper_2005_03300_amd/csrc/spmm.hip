@@ -41,6 +41,19 @@ struct SplitArgs {
     float* carry;             // [nchunks][f]
 };
 
+// The index/value stream is read exactly once per product: load it with the non-temporal hint so
+// it does not push the gathered rows of X out of L2.
+typedef int intx4 __attribute__((ext_vector_type(4)));
+typedef float fltx4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ int4 stream_load_i4(const int32_t* p) {
+    const intx4 v = __builtin_nontemporal_load(reinterpret_cast<const intx4*>(p));
+    return make_int4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ float4 stream_load_f4(const float* p) {
+    const fltx4 v = __builtin_nontemporal_load(reinterpret_cast<const fltx4*>(p));
+    return make_float4(v.x, v.y, v.z, v.w);
+}
+
 template <int VEC> struct Vec;
 template <> struct Vec<4> { using T = float4; };
 template <> struct Vec<1> { using T = float; };
@@ -104,8 +117,8 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void k_spmm_split(SplitArgs a
         int4 cc = make_int4(0, 0, 0, 0);
         float4 vv = make_float4(0.f, 0.f, 0.f, 0.f);
         if (k + 4 <= a.nnz) {
-            cc = *reinterpret_cast<const int4*>(a.colidx + k);
-            vv = *reinterpret_cast<const float4*>(a.val + k);
+            cc = stream_load_i4(a.colidx + k);
+            vv = stream_load_f4(a.val + k);
         } else {
             if (k + 0 < a.nnz) { cc.x = a.colidx[k + 0]; vv.x = a.val[k + 0]; }
             if (k + 1 < a.nnz) { cc.y = a.colidx[k + 1]; vv.y = a.val[k + 1]; }
@@ -364,7 +377,8 @@ struct SweepArgs {
     const int32_t* colidx;
     const float* val;
     const uint8_t* lrow;
-    const int64_t* task_ptr;
+    const int64_t* task_base;
+    const int32_t* task_len;
     const int32_t* task_order;
     int64_t n;
     int32_t f, rb;
@@ -375,9 +389,11 @@ struct SweepArgs {
 
 template <int LPR, int EPI>
 __global__ __launch_bounds__(64) void k_spmm_sweep(SweepArgs a, int64_t first_task) {
-    constexpr int G = 64 / LPR;                  // entries per step
+    constexpr int G = 64 / LPR;                  // entries per step (16 or 8)
     constexpr int W = LPR * 4;                   // panel width in floats
-    constexpr int STEPS = 64 / G;
+    constexpr int SPT = 64 / G;                  // steps per 64 entries
+    constexpr int U = 2;                         // 64-entry loads per trip
+    constexpr int STEPS = SPT * U;
     extern __shared__ float smem[];              // acc[rb][W], then owner[rb]
     float* acc = smem;
     volatile int* owner = reinterpret_cast<volatile int*>(smem + a.rb * W);
@@ -390,58 +406,97 @@ __global__ __launch_bounds__(64) void k_spmm_sweep(SweepArgs a, int64_t first_ta
     __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
     __builtin_amdgcn_wave_barrier();
 
-    const int64_t e0 = a.task_ptr[task], e1 = a.task_ptr[task + 1];
+    const int64_t e0 = a.task_base[task];        // multiple of 16
+    const int len = a.task_len[task];
     const float* xbase = a.X + col0;
-    // entries of the next trip are fetched while the current one is gathered and added
-    int32_t c = 0; float v = 0.f; int r = 0;
-    if (e0 + lane < e1) { c = a.colidx[e0 + lane]; v = a.val[e0 + lane]; r = (int)a.lrow[e0 + lane]; }
-    for (int64_t base = e0; base < e1; base += 64) {
-        const int64_t nidx = base + 64 + lane;
-        int32_t nc = 0; float nv = 0.f; int nr = 0;
-        if (nidx < e1) { nc = a.colidx[nidx]; nv = a.val[nidx]; nr = (int)a.lrow[nidx]; }
-        const int left = (int)((e1 - base) < 64 ? (e1 - base) : 64);
+    // the entries of the next trip are fetched while the current one is gathered and added
+    int32_t c[U]; float v[U]; int r[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int k = 64 * u + lane;
+        c[u] = 0; v[u] = 0.f; r[u] = 0;
+        if (k < len) {
+            c[u] = __builtin_nontemporal_load(a.colidx + e0 + k);
+            v[u] = __builtin_nontemporal_load(a.val + e0 + k);
+            r[u] = (int)__builtin_nontemporal_load(a.lrow + e0 + k);
+        }
+    }
+    for (int base = 0; base < len; base += 64 * U) {
+        int32_t nc[U]; float nv[U]; int nr[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int k = base + 64 * U + 64 * u + lane;
+            nc[u] = 0; nv[u] = 0.f; nr[u] = 0;
+            if (k < len) {
+                nc[u] = __builtin_nontemporal_load(a.colidx + e0 + k);
+                nv[u] = __builtin_nontemporal_load(a.val + e0 + k);
+                nr[u] = (int)__builtin_nontemporal_load(a.lrow + e0 + k);
+            }
+        }
         float x[STEPS][4];
         float vs[STEPS];
         int rs[STEPS];
 #pragma unroll
-        for (int t = 0; t < STEPS; ++t) {        // every gather of the trip is issued before any add
-            const int src = t * G + g;
-            const int32_t cs = __shfl(c, src, 64);
-            vs[t] = __shfl(v, src, 64);
-            rs[t] = __shfl(r, src, 64);
-            if (src < left && col_ok) {
-                const float4 q = *reinterpret_cast<const float4*>(xbase + (int64_t)cs * a.ldx);
-                x[t][0] = q.x; x[t][1] = q.y; x[t][2] = q.z; x[t][3] = q.w;
-            } else {
-                x[t][0] = x[t][1] = x[t][2] = x[t][3] = 0.f;
-            }
-        }
+        for (int u = 0; u < U; ++u)
 #pragma unroll
-        for (int t = 0; t < STEPS; ++t) {
-            // Two lane groups may hold the same row in one step.  Each group claims its row by writing
-            // its number; the group whose number is read back adds (plain read-modify-write, it is alone
-            // on that row); the others try again.  Almost always one round.
-            bool pending = (t * G + g < left) && col_ok;
-            while (true) {
-                if (pending) owner[rs[t]] = g;
-                __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
-                __builtin_amdgcn_wave_barrier();
-                if (pending && owner[rs[t]] == g) {
-                    float4* dst = reinterpret_cast<float4*>(acc + rs[t] * W + col0);
-                    float4 cur = *dst;
-                    cur.x = fmaf(vs[t], x[t][0], cur.x);
-                    cur.y = fmaf(vs[t], x[t][1], cur.y);
-                    cur.z = fmaf(vs[t], x[t][2], cur.z);
-                    cur.w = fmaf(vs[t], x[t][3], cur.w);
-                    *dst = cur;
-                    pending = false;
+            for (int t = 0; t < SPT; ++t) {      // every gather of the trip is issued before any add
+                const int q = u * SPT + t;
+                const int src = t * G + g;
+                const int32_t cs = __shfl(c[u], src, 64);
+                vs[q] = __shfl(v[u], src, 64);
+                rs[q] = __shfl(r[u], src, 64);
+                if (base + 64 * u + src < len && col_ok) {
+                    const float4 w4 = *reinterpret_cast<const float4*>(xbase + (int64_t)cs * a.ldx);
+                    x[q][0] = w4.x; x[q][1] = w4.y; x[q][2] = w4.z; x[q][3] = w4.w;
+                } else {
+                    x[q][0] = x[q][1] = x[q][2] = x[q][3] = 0.f;
+                }
+            }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int t = 0; t < SPT; ++t) {
+                const int q = u * SPT + t;
+                bool pending = (base + 64 * u + t * G + g < len) && col_ok;
+                // bit 7 of the first entry of the aligned 16-entry group says whether two of its entries share
+                // a row; it is the same for the whole step (G = 8 looks at its half-group's leader, which
+                // carries the flag only for the first half, so both halves read the group leader)
+                const int flag = __shfl(r[u], (t * G) & ~15, 64) & 0x80;
+                float4* dst = reinterpret_cast<float4*>(acc + (rs[q] & 0x7f) * W + col0);
+                if (!flag) {                     // all rows of the step differ: plain read-modify-write
+                    if (pending) {
+                        float4 cur = *dst;
+                        cur.x = fmaf(vs[q], x[q][0], cur.x);
+                        cur.y = fmaf(vs[q], x[q][1], cur.y);
+                        cur.z = fmaf(vs[q], x[q][2], cur.z);
+                        cur.w = fmaf(vs[q], x[q][3], cur.w);
+                        *dst = cur;
+                    }
+                } else {
+                    // Some row appears twice.  Each group claims its row by writing its number; the group
+                    // whose number is read back adds (it is alone on that row); the others try again.
+                    while (true) {
+                        if (pending) owner[rs[q] & 0x7f] = g;
+                        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+                        __builtin_amdgcn_wave_barrier();
+                        if (pending && owner[rs[q] & 0x7f] == g) {
+                            float4 cur = *dst;
+                            cur.x = fmaf(vs[q], x[q][0], cur.x);
+                            cur.y = fmaf(vs[q], x[q][1], cur.y);
+                            cur.z = fmaf(vs[q], x[q][2], cur.z);
+                            cur.w = fmaf(vs[q], x[q][3], cur.w);
+                            *dst = cur;
+                            pending = false;
+                        }
+                        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+                        __builtin_amdgcn_wave_barrier();
+                        if (!__any(pending)) break;
+                    }
                 }
                 __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
-                __builtin_amdgcn_wave_barrier();
-                if (!__any(pending)) break;
             }
-        }
-        c = nc; v = nv; r = nr;
+#pragma unroll
+        for (int u = 0; u < U; ++u) { c[u] = nc[u]; v[u] = nv[u]; r[u] = nr[u]; }
     }
     __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
     __builtin_amdgcn_wave_barrier();
@@ -450,14 +505,13 @@ __global__ __launch_bounds__(64) void k_spmm_sweep(SweepArgs a, int64_t first_ta
     for (int i = g; i < a.rb; i += G) {
         const int64_t row = row0 + i;
         if (row < a.n && col_ok) {
-            const float4 q = *reinterpret_cast<const float4*>(acc + i * W + col0);
-            float out[4] = {q.x, q.y, q.z, q.w};
+            const float4 w4 = *reinterpret_cast<const float4*>(acc + i * W + col0);
+            float out[4] = {w4.x, w4.y, w4.z, w4.w};
             epilogue_store<4, EPI>(a.Z + row * a.ldz + col0, EPI == GCN_EPI_MASK ? a.Zprev + row * a.ldzprev + col0 : nullptr, out);
         }
     }
 }
 
-static constexpr int SWEEP_WAVES_PER_CU = 16;
 static constexpr int SWEEP_CUS = 256;
 
 template <int LPR>
@@ -465,7 +519,7 @@ static int launch_sweep(const SweepArgs& args, int64_t ntasks, int epilogue, hip
     constexpr int W = LPR * 4;
     const size_t lds = (size_t)args.rb * (W + 1) * sizeof(float);
     const unsigned ytiles = (unsigned)((args.f + W - 1) / W);
-    const int64_t gen = (int64_t)SWEEP_CUS * SWEEP_WAVES_PER_CU;      // tasks that are resident at once
+    const int64_t gen = (int64_t)SWEEP_CUS * config().sweep_waves;    // tasks that are resident at once
     timing_begin(s);
     for (unsigned y = 0; y < ytiles; ++y) {
         for (int64_t first = 0; first < ntasks; first += gen) {
@@ -555,16 +609,17 @@ int spmm_launch(gcn_csr* a, Matrix& m, int32_t f, const float* X, int64_t ldx, f
         const int LPRs = f <= 16 ? 4 : 8;
         const int W = LPRs * 4;
         const int32_t rb = 2048 / W;                       // 8 KB of accumulators per wavefront
-        int64_t nj = config().spmm_blocks >= 2 ? config().spmm_blocks : (n * W * 4 + (1ll << 20) - 1) / (1ll << 20);
+        // measured: the finer the column blocks the better the wavefronts stay together (the gain
+        // levels off near a thousand blocks), so by default a block is 256 columns
+        int64_t nj = config().spmm_blocks >= 2 ? config().spmm_blocks : (n + 255) / 256;
         if (nj < 1) nj = 1;
-        int64_t cpb = (n + nj - 1) / nj;
-        if (config().spmm_blocks < 2) cpb = (cpb + 255) & ~255ll;
+        const int64_t cpb = (n + nj - 1) / nj;
         const int32_t th = config().sweep_heavy;
         if (m.swp.cols_per_block != cpb || m.swp.rb != rb || m.swp.heavy_threshold != th)
             GCN_TRY(build_sweep(m, n, nnz, cpb, rb, th, s));
         const Sweep& w = m.swp;
         SweepArgs sa;
-        sa.colidx = w.colidx; sa.val = w.val; sa.lrow = w.lrow; sa.task_ptr = w.task_ptr; sa.task_order = w.task_order;
+        sa.colidx = w.colidx; sa.val = w.val; sa.lrow = w.lrow; sa.task_base = w.task_base; sa.task_len = w.task_len; sa.task_order = w.task_order;
         sa.n = n; sa.f = f; sa.rb = rb; sa.X = X; sa.ldx = ldx; sa.Z = Z; sa.ldz = ldz; sa.Zprev = Zprev; sa.ldzprev = ldzprev;
         if (LPRs == 4) GCN_TRY(launch_sweep<4>(sa, w.ntasks, epilogue, s));
         else GCN_TRY(launch_sweep<8>(sa, w.ntasks, epilogue, s));
