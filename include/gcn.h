@@ -41,6 +41,7 @@ extern "C" {
 #define GCN_ADD_SELF_LOOPS 2u  /* insert exactly one diagonal entry per row */
 #define GCN_NORM_SYM 4u        /* values 1/sqrt(d_i d_j); without it every value is 1.0f */
 #define GCN_BUILD_TRANSPOSE 8u /* also store A^T in compressed rows (needed for trans=1) */
+#define GCN_NORM_ROW 16u       /* values 1/d_i (row normalisation D^-1 (A+I), for directed graphs); not with NORM_SYM */
 
 /* gcn_spmm / gcn_gemm epilogues */
 #define GCN_EPI_NONE 0
@@ -72,7 +73,8 @@ typedef struct gcn_csr gcn_csr; /* opaque: A (and A^T) in compressed rows, degre
  * src, dst: DEVICE int32[n_edges], borrowed for the call.  Pairs with src == dst are dropped,
  * duplicates collapse to one entry.  The result has columns ascending in every row; rowptr is
  * int64, colidx int32, val fp32, deg int32 = entries per row of A.  With GCN_NORM_SYM,
- * val(i,j) = (float)(1.0 / sqrt((double)deg_i * (double)deg_j)).
+ * val(i,j) = (float)(1.0 / sqrt((double)deg_i * (double)deg_j)); with GCN_NORM_ROW, (float)(1.0 / (double)deg_i).
+ * The rows of a graph without self loops can be empty; normalising those is the caller's error.
  * Errors: BADARG (NULL out, n <= 0, n_edges < 0, NULL arrays with n_edges > 0), RANGE (n >= 2^31
  * or an id outside [0,n)), OOM, HIP.  On error *out is NULL.
  * ----------------------------------------------------------------------------------------- */
@@ -140,6 +142,13 @@ int gcn_relu_mask(int64_t rows, int32_t cols, const float* G, int64_t ldg, const
 int gcn_softmax_nll(int64_t n, int32_t C, const float* Z, int64_t ldz, const int32_t* labels, float* loss,
                     float* G, int64_t ldg, void* stream);
 
+/* The same with a training split (the paper trains Reddit on a split, "Datasets and Compute
+ * Platform"): vertices with a negative label are outside the split; they add nothing to the loss and
+ * their rows of G are zero.  n_labelled = number of vertices with label >= 0 (host value, the caller
+ * knows its split); the mean and the 1/n factor of G use it.  BADARG unless 1 <= n_labelled <= n. */
+int gcn_softmax_nll_masked(int64_t n, int32_t C, const float* Z, int64_t ldz, const int32_t* labels,
+                           int64_t n_labelled, float* loss, float* G, int64_t ldg, void* stream);
+
 /* -------------------------------------------------------------------------------------------
  * One layer forward -- "Forward Propagation": Z = A^T Hin W (+ bias), Hout = sigma(Z).
  * Needs GCN_BUILD_TRANSPOSE.  Hin: n x f_in (ld ldh).  W: f_in x f_out dense.  Z, Hout: n x f_out
@@ -174,6 +183,12 @@ int gcn_layer_backward(gcn_csr* a, int32_t f_in, int32_t f_out, const float* Hin
 int gcn_epoch(gcn_csr* a, int32_t L_w, const int32_t* dims, const float* H0, const int32_t* labels,
               float* const* W, float* const* Y, float lr, float* loss, void* workspace,
               size_t workspace_bytes, int order, void* stream);
+
+/* gcn_epoch with a training split: labels < 0 mark vertices outside it, n_labelled counts the others
+ * (see gcn_softmax_nll_masked).  Calling it in a loop with lr != 0 is full-batch gradient descent. */
+int gcn_epoch_masked(gcn_csr* a, int32_t L_w, const int32_t* dims, const float* H0, const int32_t* labels,
+                     int64_t n_labelled, float* const* W, float* const* Y, float lr, float* loss, void* workspace,
+                     size_t workspace_bytes, int order, void* stream);
 size_t gcn_epoch_workspace_bytes(int64_t n, int32_t L_w, const int32_t* dims, int order);
 
 /* After gcn_epoch: device pointers into the workspace for layer l in [1, L_w], both n x dims[l]

@@ -97,8 +97,8 @@ def build_csr(n, src, dst, symmetrise=True, self_loops=True, norm="sym", transpo
 
     ``transpose=True`` returns the transposed matrix, built on its own by sorting the same
     entry set by (column, row) rather than by transposing the first result.  ``norm`` is
-    "sym" (entries 1/sqrt(d_i d_j), d = row degrees of the untransposed matrix) or "none"
-    (entries 1)."""
+    "sym" (entries 1/sqrt(d_i d_j), d = row degrees of the untransposed matrix), "row" (entries
+    1/d_i, the row normalisation used for directed graphs) or "none" (entries 1)."""
     lib = _lib("f32")
     src = np.ascontiguousarray(src, np.int32)
     dst = np.ascontiguousarray(dst, np.int32)
@@ -124,6 +124,8 @@ def build_csr(n, src, dst, symmetrise=True, self_loops=True, norm="sym", transpo
     val = np.empty(cnt, np.float32)
     if norm == "sym":
         lib.orc_values_sym(C.c_int64(n), _p(rowptr), _p(colidx), _p(deg), _p(val))
+    elif norm == "row":
+        lib.orc_values_row(C.c_int64(n), _p(rowptr), _p(colidx), _p(deg), int(transpose), _p(val))
     elif norm == "none":
         val[:] = 1.0
     else:
@@ -191,11 +193,12 @@ def relu_mask(G: np.ndarray, Z: np.ndarray) -> np.ndarray:
 
 
 def softmax_nll(Z: np.ndarray, labels: np.ndarray, want_grad: bool = True):
-    """Mean NLL of row-wise log-softmax(Z) and its gradient with respect to Z (Equation 1)."""
+    """Mean NLL of row-wise log-softmax(Z) over the vertices with label >= 0 (negative labels mark
+    vertices outside the training split) and its gradient with respect to Z (Equation 1)."""
     Z = np.ascontiguousarray(Z)
     labels = np.ascontiguousarray(labels, np.int32)
     n, Cn = Z.shape
-    assert labels.shape == (n,) and labels.min() >= 0 and labels.max() < Cn
+    assert labels.shape == (n,) and labels.max() < Cn
     G = np.empty_like(Z) if want_grad else None
     loss = _lib(_kind(Z)).orc_softmax_nll(C.c_int64(n), C.c_int32(Cn), _p(Z), C.c_int64(Cn), _p(labels),
                                           _p(G) if want_grad else None, C.c_int64(Cn))

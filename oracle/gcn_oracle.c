@@ -95,6 +95,16 @@ void orc_values_sym(int64_t n, const int64_t* ptr, const int32_t* minor, const i
             val[k] = (float)(1.0 / sqrt((double)deg[i] * (double)deg[minor[k]]));
 }
 
+/* Row normalisation D^-1 (A+I) for directed graphs: entry (i,j) = 1/d_i with d the degrees of the
+ * untransposed matrix.  `transposed` says that ptr/minor describe the transposed structure, whose
+ * entry in compressed row j with minor index i is the untransposed (i,j). */
+void orc_values_row(int64_t n, const int64_t* ptr, const int32_t* minor, const int32_t* deg, int transposed,
+                    float* val) {
+    for (int64_t r = 0; r < n; ++r)
+        for (int64_t k = ptr[r]; k < ptr[r + 1]; ++k)
+            val[k] = (float)(1.0 / (double)deg[transposed ? minor[k] : r]);
+}
+
 /* ------------------------------------------------------------------------------------------
  * Sparse-dense product, the "SpMM" of sections "Graph Neural Networks" and "A One-Dimensional
  * (1D) Algorithm":  Z[i,:] = sum_k val[k] X[col[k],:]  over the stored entries k of row i.
@@ -159,14 +169,22 @@ void orc_relu_mask(int64_t count, const REAL* g, const REAL* z, REAL* out) {
 
 /* Row-wise log-softmax (the non-elementwise activation of the last layer, section "Block
  * Two-Dimensional (2D) Algorithms", "Equation H = sigma(Z)") followed by the mean negative
- * log-likelihood over all n vertices.  Also Equation 1 for this loss:
- *   G[i,j] = (softmax(Z[i,:])[j] - [j == y_i]) / n.
- * G may be NULL.  Returns the loss in double. */
+ * log-likelihood over the labelled vertices (label >= 0; the paper trains Reddit on a training
+ * split and the other graphs on all vertices).  Also Equation 1 for this loss:
+ *   G[i,j] = (softmax(Z[i,:])[j] - [j == y_i]) / m   for labelled i,   0 for unlabelled i,
+ * with m the number of labelled vertices.  G may be NULL.  Returns the loss in double. */
 double orc_softmax_nll(int64_t n, int32_t C, const REAL* Z, int64_t ldz, const int32_t* labels, REAL* G,
                        int64_t ldg) {
+    int64_t m_lab = 0;
+    for (int64_t i = 0; i < n; ++i) m_lab += labels[i] >= 0;
     double loss = 0.0;
     for (int64_t i = 0; i < n; ++i) {
         const REAL* z = Z + i * ldz;
+        if (labels[i] < 0) {
+            if (G)
+                for (int32_t j = 0; j < C; ++j) G[i * ldg + j] = (REAL)0;
+            continue;
+        }
         double m = (double)z[0];
         for (int32_t j = 1; j < C; ++j)
             if ((double)z[j] > m) m = (double)z[j];
@@ -177,10 +195,10 @@ double orc_softmax_nll(int64_t n, int32_t C, const REAL* Z, int64_t ldz, const i
         if (G)
             for (int32_t j = 0; j < C; ++j) {
                 double p = exp((double)z[j] - lse);
-                G[i * ldg + j] = (REAL)((p - (j == labels[i] ? 1.0 : 0.0)) / (double)n);
+                G[i * ldg + j] = (REAL)((p - (j == labels[i] ? 1.0 : 0.0)) / (double)m_lab);
             }
     }
-    return loss / (double)n;
+    return m_lab ? loss / (double)m_lab : 0.0;
 }
 
 /* Gradient step of Equation 3: W <- W - lr * Y. */

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(HERE, "libgcn_hip.so")
 _HEADER = os.path.join(os.path.dirname(HERE), "include", "gcn.h")
 
-SYMMETRISE, ADD_SELF_LOOPS, NORM_SYM, BUILD_TRANSPOSE = 1, 2, 4, 8
+SYMMETRISE, ADD_SELF_LOOPS, NORM_SYM, BUILD_TRANSPOSE, NORM_ROW = 1, 2, 4, 8, 16
 EPI_NONE, EPI_RELU, EPI_MASK = 0, 1, 2
 ORDER_AUTO, ORDER_GEMM_FIRST, ORDER_SPMM_FIRST = 0, 1, 2
 ACT_NONE, ACT_RELU = 0, 1
@@ -175,6 +175,15 @@ def gcn_softmax_nll(Z, labels, loss, G=None):
     return loss
 
 
+def gcn_softmax_nll_masked(Z, labels, n_labelled: int, loss, G=None):
+    import torch
+    _dev(Z, torch.float32), _dev(labels, torch.int32), _dev(loss, torch.float32)
+    _check(lib().gcn_softmax_nll_masked(C.c_int64(Z.shape[0]), C.c_int32(Z.shape[1]), _ptr(Z), C.c_int64(_ld(Z)),
+                                        _ptr(labels), C.c_int64(n_labelled), _ptr(loss), _ptr(G),
+                                        C.c_int64(_ld(G) if G is not None else 0), _stream()))
+    return loss
+
+
 def gcn_layer_forward(a: Csr, Hin, W, Z, Hout, T, order: int = ORDER_AUTO, act: int = ACT_RELU, bias=None):
     f_in, f_out = W.shape
     assert W.is_contiguous() and Z.is_contiguous() and T.is_contiguous()
@@ -208,6 +217,18 @@ def gcn_epoch(a: Csr, dims, H0, labels, W, Y, lr: float, loss, workspace, order:
     _check(lib().gcn_epoch(a._h, C.c_int32(L), _dims_array(dims), _ptr(H0), _ptr(labels), Wp, Yp, C.c_float(lr),
                            _ptr(loss), _ptr(workspace), C.c_size_t(workspace.numel() * workspace.element_size()),
                            int(order), _stream()))
+    return loss
+
+
+def gcn_epoch_masked(a: Csr, dims, H0, labels, n_labelled: int, W, Y, lr: float, loss, workspace,
+                     order: int = ORDER_AUTO):
+    L = len(dims) - 1
+    assert len(W) == L and len(Y) == L and H0.is_contiguous()
+    Wp = (C.c_void_p * L)(*[w.data_ptr() for w in W])
+    Yp = (C.c_void_p * L)(*[y.data_ptr() for y in Y])
+    _check(lib().gcn_epoch_masked(a._h, C.c_int32(L), _dims_array(dims), _ptr(H0), _ptr(labels),
+                                  C.c_int64(n_labelled), Wp, Yp, C.c_float(lr), _ptr(loss), _ptr(workspace),
+                                  C.c_size_t(workspace.numel() * workspace.element_size()), int(order), _stream()))
     return loss
 
 

@@ -86,26 +86,40 @@ __global__ void k_compress(int64_t nnz, int64_t n, const uint64_t* __restrict__ 
 __global__ void k_degrees(int64_t n, const int64_t* __restrict__ rowptr, int32_t* __restrict__ deg,
                           int32_t* __restrict__ max_deg, unsigned long long* __restrict__ n_nonempty) {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= n) return;
-    int32_t d = (int32_t)(rowptr[i + 1] - rowptr[i]);
-    if (deg) deg[i] = d;
-    if (max_deg) atomicMax(max_deg, d);
-    if (n_nonempty && d > 0) atomicAdd(n_nonempty, 1ull);
+    int32_t d = 0;
+    if (i < n) {
+        d = (int32_t)(rowptr[i + 1] - rowptr[i]);
+        if (deg) deg[i] = d;
+    }
+    // one integer atomic per wavefront instead of one per row
+    int32_t m = d;
+#pragma unroll
+    for (int s = 32; s >= 1; s >>= 1) {
+        const int32_t o = __shfl_xor(m, s, 64);
+        m = o > m ? o : m;
+    }
+    const unsigned long long nz = __popcll(__ballot(d > 0));
+    if ((threadIdx.x & 63) == 0) {
+        if (max_deg) atomicMax(max_deg, m);
+        if (n_nonempty && nz) atomicAdd(n_nonempty, nz);
+    }
 }
 
 // val(i,j) = (float)(1 / sqrt(d_i d_j)): exact integer product in double, correctly rounded
 // square root and division, one rounding to float -- the same value on any IEEE machine.
+// norm 2 is the row normalisation D^-1 (A+I): val(i,j) = (float)(1 / d_i).
 __global__ void k_values(int64_t nnz, const uint64_t* __restrict__ keys, const int32_t* __restrict__ deg,
-                         int norm_sym, float* __restrict__ val) {
+                         int norm, float* __restrict__ val) {
     int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (k >= nnz) return;
-    if (!norm_sym) {
+    if (norm == 0) {
         val[k] = 1.0f;
         return;
     }
     uint64_t key = keys[k];
     double di = (double)deg[key >> 32], dj = (double)deg[key & 0xffffffffu];
-    val[k] = (float)__ddiv_rn(1.0, __dsqrt_rn(__dmul_rn(di, dj)));
+    if (norm == 2) val[k] = (float)__ddiv_rn(1.0, di);
+    else val[k] = (float)__ddiv_rn(1.0, __dsqrt_rn(__dmul_rn(di, dj)));
 }
 
 __global__ void k_swap_halves(int64_t nnz, const uint64_t* __restrict__ keys, uint64_t* __restrict__ out) {
@@ -714,7 +728,7 @@ static int create_impl(gcn_csr* a, int64_t n, int64_t m, const int32_t* src, con
     GCN_LAUNCH_CHECK();
     if (nnz > 0) {
         hipLaunchKernelGGL(k_values, dim3(blocks_for(nnz)), dim3(TPB), 0, s, nnz, keys, a->deg,
-                           (int)((flags & GCN_NORM_SYM) != 0), a->A.val);
+                           (flags & GCN_NORM_ROW) ? 2 : ((flags & GCN_NORM_SYM) ? 1 : 0), a->A.val);
         GCN_LAUNCH_CHECK();
     }
     GCN_HIP_TRY(hipStreamSynchronize(s));
@@ -789,6 +803,7 @@ int gcn_csr_create(gcn_csr** out, int64_t n, int64_t n_edges, const int32_t* src
     if (n >= (1ll << 31)) return fail(GCN_ERR_RANGE, "gcn_csr_create: n must be below 2^31");
     if (n_edges > 0 && (!src || !dst)) return fail(GCN_ERR_BADARG, "gcn_csr_create: NULL edge arrays");
     if (n_edges > (1ll << 40)) return fail(GCN_ERR_RANGE, "gcn_csr_create: too many edges");
+    if ((flags & GCN_NORM_SYM) && (flags & GCN_NORM_ROW)) return fail(GCN_ERR_BADARG, "gcn_csr_create: choose one normalisation");
     gcn_csr* a = new (std::nothrow) gcn_csr();
     if (!a) return fail(GCN_ERR_OOM, "host allocation failed");
     (void)hipGetDevice(&a->device);

@@ -146,7 +146,15 @@ int gcn_epoch_view(int64_t n, int32_t L_w, const int32_t* dims, int order, void*
 
 int gcn_epoch(gcn_csr* a, int32_t L_w, const int32_t* dims, const float* H0, const int32_t* labels, float* const* W,
               float* const* Y, float lr, float* loss, void* workspace, size_t workspace_bytes, int order, void* stream) {
+    if (!a) return fail(GCN_ERR_BADARG, "gcn_epoch: NULL argument");
+    return gcn_epoch_masked(a, L_w, dims, H0, labels, a->n, W, Y, lr, loss, workspace, workspace_bytes, order, stream);
+}
+
+int gcn_epoch_masked(gcn_csr* a, int32_t L_w, const int32_t* dims, const float* H0, const int32_t* labels,
+                     int64_t n_labelled, float* const* W, float* const* Y, float lr, float* loss, void* workspace,
+                     size_t workspace_bytes, int order, void* stream) {
     if (!a || !H0 || !labels || !W || !Y || !loss || !workspace) return fail(GCN_ERR_BADARG, "gcn_epoch: NULL argument");
+    if (n_labelled <= 0 || n_labelled > a->n) return fail(GCN_ERR_BADARG, "gcn_epoch: n_labelled must be in [1, n]");
     GCN_TRY(check_dims(a->n, L_w, dims));
     if (order < GCN_ORDER_AUTO || order > GCN_ORDER_SPMM_FIRST) return fail(GCN_ERR_BADARG, "gcn_epoch: unknown order");
     if (!a->has_t) return fail(GCN_ERR_NOTRANSPOSE, "gcn_epoch needs GCN_BUILD_TRANSPOSE");
@@ -169,7 +177,8 @@ int gcn_epoch(gcn_csr* a, int32_t L_w, const int32_t* dims, const float* H0, con
                                    last ? GCN_ACT_NONE : GCN_ACT_RELU, s));
         Hin = at(lay.H[l]);
     }
-    GCN_TRY(gcn_softmax_nll(n, dims[L_w], at(lay.Z[L_w - 1]), dims[L_w], labels, loss, at(lay.G[L_w - 1]), dims[L_w], stream));
+    GCN_TRY(gcn_softmax_nll_masked(n, dims[L_w], at(lay.Z[L_w - 1]), dims[L_w], labels, n_labelled, loss,
+                                   at(lay.G[L_w - 1]), dims[L_w], stream));
     for (int l = L_w - 1; l >= 0; --l) {
         const float* Hl = l > 0 ? at(lay.H[l - 1]) : H0;
         GCN_TRY(layer_backward_impl(a, dims[l], dims[l + 1], Hl, dims[l], l > 0 ? at(lay.Z[l - 1]) : nullptr, W[l],

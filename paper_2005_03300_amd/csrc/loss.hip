@@ -45,11 +45,13 @@ __global__ __launch_bounds__(256) void k_softmax_nll(int64_t n, int32_t C, const
         for (int d = L / 2; d >= 1; d >>= 1) ssum += __shfl_xor(ssum, d, 64);
         const float lse = m + logf(ssum);
         int32_t y = labels[i];
-        y = y < 0 ? 0 : (y >= C ? C - 1 : y);   // out-of-range labels are the caller's error; stay in bounds
+        const bool labelled = y >= 0;           // negative label: vertex outside the training split
+        y = y < 0 ? 0 : (y >= C ? C - 1 : y);   // labels >= C are the caller's error; stay in bounds
         if (G && c0 < C) {
             float g[VEC];
 #pragma unroll
-            for (int e = 0; e < VEC; ++e) g[e] = (expf(v[e] - lse) - (c0 + e == y ? 1.f : 0.f)) * inv_n;
+            for (int e = 0; e < VEC; ++e)
+                g[e] = labelled ? (expf(v[e] - lse) - (c0 + e == y ? 1.f : 0.f)) * inv_n : 0.f;
             if constexpr (VEC == 4) *reinterpret_cast<float4*>(G + i * ldg + c0) = make_float4(g[0], g[1], g[2], g[3]);
             else G[i * ldg + c0] = g[0];
         }
@@ -57,7 +59,7 @@ __global__ __launch_bounds__(256) void k_softmax_nll(int64_t n, int32_t C, const
         float zy = 0.f;
 #pragma unroll
         for (int e = 0; e < VEC; ++e) zy = (c0 + e == y) ? v[e] : zy;
-        if (y >= c0 && y < c0 + VEC) mine += (double)lse - (double)zy;
+        if (labelled && y >= c0 && y < c0 + VEC) mine += (double)lse - (double)zy;
     }
 #pragma unroll
     for (int d = 32; d >= 1; d >>= 1) mine += __shfl_xor(mine, d, 64);
@@ -86,12 +88,13 @@ __global__ __launch_bounds__(256) void k_softmax_nll_wide(int64_t n, int32_t C, 
         for (int d = 32; d >= 1; d >>= 1) ssum += __shfl_xor(ssum, d, 64);
         const float lse = m + logf(ssum);
         int32_t y = labels[i];
+        const bool labelled = y >= 0;
         y = y < 0 ? 0 : (y >= C ? C - 1 : y);
         if (G) {
             float* g = G + i * ldg;
-            for (int j = li; j < C; j += 64) g[j] = (expf(z[j] - lse) - (j == y ? 1.f : 0.f)) * inv_n;
+            for (int j = li; j < C; j += 64) g[j] = labelled ? (expf(z[j] - lse) - (j == y ? 1.f : 0.f)) * inv_n : 0.f;
         }
-        if (li == 0) mine += (double)lse - (double)z[y];
+        if (li == 0 && labelled) mine += (double)lse - (double)z[y];
     }
 #pragma unroll
     for (int d = 32; d >= 1; d >>= 1) mine += __shfl_xor(mine, d, 64);
@@ -118,14 +121,14 @@ __global__ __launch_bounds__(256) void k_loss_final(int64_t parts, const double*
 
 template <int L, int VEC>
 static void launch_rows(int64_t blocks, int64_t n, int32_t C, const float* Z, int64_t ldz, const int32_t* labels,
-                        float* G, int64_t ldg, double* part, hipStream_t s) {
+                        float* G, int64_t ldg, double* part, float inv_m, hipStream_t s) {
     hipLaunchKernelGGL((k_softmax_nll<L, VEC>), dim3((unsigned)blocks), dim3(256), 0, s, n, C, Z, ldz, labels, G, ldg,
-                       1.0f / (float)n, part);
+                       inv_m, part);
 }
 
 template <int VEC>
 static void dispatch_rows(int lanes, int64_t n, int32_t C, const float* Z, int64_t ldz, const int32_t* labels,
-                          float* G, int64_t ldg, double* part, int64_t* blocks_out, hipStream_t s) {
+                          float* G, int64_t ldg, double* part, int64_t* blocks_out, float inv_m, hipStream_t s) {
     int L = 2;
     while (L < lanes) L <<= 1;
     const int64_t rows_per_block = 256 / L;
@@ -133,12 +136,12 @@ static void dispatch_rows(int lanes, int64_t n, int32_t C, const float* Z, int64
     if (blocks > LOSS_BLOCKS_MAX) blocks = LOSS_BLOCKS_MAX;
     *blocks_out = blocks;
     switch (L) {
-        case 2: launch_rows<2, VEC>(blocks, n, C, Z, ldz, labels, G, ldg, part, s); break;
-        case 4: launch_rows<4, VEC>(blocks, n, C, Z, ldz, labels, G, ldg, part, s); break;
-        case 8: launch_rows<8, VEC>(blocks, n, C, Z, ldz, labels, G, ldg, part, s); break;
-        case 16: launch_rows<16, VEC>(blocks, n, C, Z, ldz, labels, G, ldg, part, s); break;
-        case 32: launch_rows<32, VEC>(blocks, n, C, Z, ldz, labels, G, ldg, part, s); break;
-        default: launch_rows<64, VEC>(blocks, n, C, Z, ldz, labels, G, ldg, part, s); break;
+        case 2: launch_rows<2, VEC>(blocks, n, C, Z, ldz, labels, G, ldg, part, inv_m, s); break;
+        case 4: launch_rows<4, VEC>(blocks, n, C, Z, ldz, labels, G, ldg, part, inv_m, s); break;
+        case 8: launch_rows<8, VEC>(blocks, n, C, Z, ldz, labels, G, ldg, part, inv_m, s); break;
+        case 16: launch_rows<16, VEC>(blocks, n, C, Z, ldz, labels, G, ldg, part, inv_m, s); break;
+        case 32: launch_rows<32, VEC>(blocks, n, C, Z, ldz, labels, G, ldg, part, inv_m, s); break;
+        default: launch_rows<64, VEC>(blocks, n, C, Z, ldz, labels, G, ldg, part, inv_m, s); break;
     }
 }
 
@@ -146,29 +149,42 @@ static void dispatch_rows(int lanes, int64_t n, int32_t C, const float* Z, int64
 
 using namespace gcn;
 
-extern "C" int gcn_softmax_nll(int64_t n, int32_t C, const float* Z, int64_t ldz, const int32_t* labels, float* loss,
-                               float* G, int64_t ldg, void* stream) {
-    if (!Z || !labels || !loss) return fail(GCN_ERR_BADARG, "gcn_softmax_nll: NULL argument");
-    if (n <= 0 || C <= 0 || ldz < C || (G && ldg < C)) return fail(GCN_ERR_BADARG, "gcn_softmax_nll: bad size");
-    hipStream_t s = (hipStream_t)stream;
+static int softmax_nll_impl(int64_t n, int32_t C, const float* Z, int64_t ldz, const int32_t* labels, int64_t n_labelled,
+                            float* loss, float* G, int64_t ldg, hipStream_t s) {
     void* scratch = nullptr;
     GCN_TRY(scratch_get(&scratch, (size_t)LOSS_BLOCKS_MAX * sizeof(double)));
     double* part = (double*)scratch;
     int64_t blocks = 0;
+    const float inv_m = 1.0f / (float)n_labelled;
     const bool vec4 = (C % 4 == 0) && (ldz % 4 == 0) && (((uintptr_t)Z & 15u) == 0) &&
                       (!G || ((ldg % 4 == 0) && (((uintptr_t)G & 15u) == 0)));
     if (vec4 && C <= 256) {
-        dispatch_rows<4>(C / 4, n, C, Z, ldz, labels, G, ldg, part, &blocks, s);
+        dispatch_rows<4>(C / 4, n, C, Z, ldz, labels, G, ldg, part, &blocks, inv_m, s);
     } else if (C <= 64) {
-        dispatch_rows<1>(C, n, C, Z, ldz, labels, G, ldg, part, &blocks, s);
+        dispatch_rows<1>(C, n, C, Z, ldz, labels, G, ldg, part, &blocks, inv_m, s);
     } else {
         blocks = (n + 3) / 4;
         if (blocks > LOSS_BLOCKS_MAX) blocks = LOSS_BLOCKS_MAX;
         hipLaunchKernelGGL(k_softmax_nll_wide, dim3((unsigned)blocks), dim3(256), 0, s, n, C, Z, ldz, labels, G, ldg,
-                           1.0f / (float)n, part);
+                           inv_m, part);
     }
     GCN_LAUNCH_CHECK();
-    hipLaunchKernelGGL(k_loss_final, dim3(1), dim3(256), 0, s, blocks, (const double*)part, 1.0 / (double)n, loss);
+    hipLaunchKernelGGL(k_loss_final, dim3(1), dim3(256), 0, s, blocks, (const double*)part, 1.0 / (double)n_labelled, loss);
     GCN_LAUNCH_CHECK();
     return GCN_OK;
+}
+
+extern "C" int gcn_softmax_nll(int64_t n, int32_t C, const float* Z, int64_t ldz, const int32_t* labels, float* loss,
+                               float* G, int64_t ldg, void* stream) {
+    if (!Z || !labels || !loss) return fail(GCN_ERR_BADARG, "gcn_softmax_nll: NULL argument");
+    if (n <= 0 || C <= 0 || ldz < C || (G && ldg < C)) return fail(GCN_ERR_BADARG, "gcn_softmax_nll: bad size");
+    return softmax_nll_impl(n, C, Z, ldz, labels, n, loss, G, ldg, (hipStream_t)stream);
+}
+
+extern "C" int gcn_softmax_nll_masked(int64_t n, int32_t C, const float* Z, int64_t ldz, const int32_t* labels,
+                                      int64_t n_labelled, float* loss, float* G, int64_t ldg, void* stream) {
+    if (!Z || !labels || !loss) return fail(GCN_ERR_BADARG, "gcn_softmax_nll_masked: NULL argument");
+    if (n <= 0 || C <= 0 || ldz < C || (G && ldg < C)) return fail(GCN_ERR_BADARG, "gcn_softmax_nll_masked: bad size");
+    if (n_labelled <= 0 || n_labelled > n) return fail(GCN_ERR_BADARG, "gcn_softmax_nll_masked: n_labelled must be in [1, n]");
+    return softmax_nll_impl(n, C, Z, ldz, labels, n_labelled, loss, G, ldg, (hipStream_t)stream);
 }

@@ -110,6 +110,26 @@ def test_directed_build_and_transpose_bit_exact(name, self_loops, norm):
     a.close()
 
 
+@pytest.mark.parametrize("name", ["c2s", "tiny"])
+def test_row_normalised_directed_build_bit_exact(name):
+    g = G()
+    n, src, dst = graph(name)
+    a = g.gcn_csr_create(n, dev(src), dev(dst), g.ADD_SELF_LOOPS | g.NORM_ROW | g.BUILD_TRANSPOSE)
+    ref = oracle.build_csr(n, src, dst, symmetrise=False, norm="row")
+    ref_t = oracle.build_csr(n, src, dst, symmetrise=False, norm="row", transpose=True)
+    for tr, r in ((False, ref), (True, ref_t)):
+        rowptr, colidx, val, deg = [host(t) for t in a.arrays(tr)]
+        np.testing.assert_array_equal(rowptr, r.rowptr)
+        np.testing.assert_array_equal(colidx, r.colidx)
+        np.testing.assert_array_equal(val.view(np.uint32), r.val.view(np.uint32))
+    X = synth.normal_features(n, 16, 3)
+    assert_close(run_spmm(a, X, trans=1), oracle.spmm(ref_t, X), "A^T X, row-normalised")
+    with pytest.raises(g.GcnError) as e:
+        g.gcn_csr_create(n, dev(src), dev(dst), g.NORM_ROW | g.NORM_SYM)
+    assert e.value.code == -1
+    a.close()
+
+
 def test_create_from_csr_roundtrip_and_transpose_twice():
     g = G()
     ref = oracle_csr("c2s", False, False, "none", False)        # directed, has empty rows
@@ -467,6 +487,25 @@ def test_softmax_nll_parity(n, C):
     assert np.isfinite(loss.item()) and np.all(np.isfinite(host(Gd)))
 
 
+@pytest.mark.parametrize("n,C", [(5000, 8), (3001, 41), (1500, 256)])
+def test_softmax_nll_training_split_parity(n, C):
+    g = G()
+    Z = synth.normal_features(n, C, 35) * np.float32(3.0)
+    y = synth.labels(n, C, 36)
+    y[synth.labels(n, 3, 37) == 0] = -1                     # about a third outside the split
+    m = int((y >= 0).sum())
+    loss = torch.zeros(1, device="cuda")
+    Gd = torch.full((n, C), float("nan"), device="cuda")
+    g.gcn_softmax_nll_masked(dev(Z), dev(y), m, loss, Gd)
+    want_loss, want_G = oracle.softmax_nll(Z, y)
+    assert abs(float(loss.item()) - want_loss) <= 1e-4 * abs(want_loss)
+    assert_close(host(Gd), want_G, "masked G")
+    assert np.all(host(Gd)[y < 0] == 0.0)
+    with pytest.raises(g.GcnError) as e:
+        g.gcn_softmax_nll_masked(dev(Z), dev(y), 0, loss, Gd)
+    assert e.value.code == -1
+
+
 # ------------------------------------------------------------------------------------------------
 # layers: per-call parity on identical fp32 inputs, both association orders
 # ------------------------------------------------------------------------------------------------
@@ -582,6 +621,39 @@ def test_epoch_sgd_step_and_workspace_check():
     with pytest.raises(g.GcnError) as e:
         g.gcn_epoch(a, dims, dev(H0), dev(y), Wd, Yd, 0.0, loss, ws[:1024], 0)
     assert e.value.code == -5
+    a.close()
+
+
+def test_training_loop_with_split_follows_the_oracle():
+    """Full-batch gradient descent (the gradient step of Equation 3) on config 1 with two thirds of the
+    vertices in the training split: the loss falls, and follows the oracle's trajectory."""
+    g = G()
+    w = synth.CONFIGS[1]
+    a = gpu_csr("c1")
+    A = oracle_csr("c1")
+    H0, y, Ws = synth.make_model_inputs(w)
+    y = y.copy()
+    y[synth.labels(A.n, 3, 38) == 0] = -1
+    m = int((y >= 0).sum())
+    dims = list(w.dims)
+    Wd = [dev(x) for x in Ws]
+    Yd = [torch.empty_like(x) for x in Wd]
+    ws = torch.empty(g.gcn_epoch_workspace_bytes(A.n, dims), dtype=torch.uint8, device="cuda")
+    loss = torch.zeros(1, device="cuda")
+    H0d, yd = dev(H0), dev(y)
+    lr, gpu_losses, ref_losses = 2.0, [], []
+    Wref = [x.copy() for x in Ws]
+    for _ in range(12):
+        g.gcn_epoch_masked(a, dims, H0d, yd, m, Wd, Yd, lr, loss, ws)
+        gpu_losses.append(float(loss.item()))
+        out = oracle.epoch(A, A, H0, y, Wref, lr)
+        ref_losses.append(out["loss"])
+        Wref = out["W"]
+    assert gpu_losses[-1] < gpu_losses[0] - 1e-3      # labels are random: little to learn, but it must fall
+    assert all(b < a for a, b in zip(gpu_losses, gpu_losses[1:]))
+    np.testing.assert_allclose(gpu_losses, ref_losses, rtol=2e-4)
+    for l in range(len(Wd)):
+        assert rel_fro(host(Wd[l]), Wref[l]) <= 1e-3
     a.close()
 
 

@@ -149,6 +149,23 @@ def test_normalised_matrix_has_sqrt_degree_eigenvector():
     np.testing.assert_allclose(y, x, rtol=1e-6)
 
 
+def test_row_normalisation_pins():
+    """D^-1 (A+I) on a directed graph: every row sums to one, the values are 1/d_i by hand, and the
+    transposed structure carries the transposed values."""
+    n, src, dst = small_graph(70, 260, 27)
+    A = oracle.build_csr(n, src, dst, symmetrise=False, norm="row")
+    At = oracle.build_csr(n, src, dst, symmetrise=False, norm="row", transpose=True)
+    D, Dt = np.array(py_dense(A)), np.array(py_dense(At))
+    np.testing.assert_array_equal(Dt, D.T)
+    for i in range(n):
+        row = D[i][D[i] != 0]
+        assert len(row) == A.deg[i]
+        assert np.all(row == np.float32(1.0 / A.deg[i]))
+    ones = np.ones((n, 2), np.float64)
+    np.testing.assert_allclose(oracle.spmm(A, ones), ones, rtol=1e-6)
+    assert not np.allclose(oracle.spmm(At, ones), ones, rtol=1e-3)     # column sums are not one
+
+
 # ------------------------------------------------------------------------------------------------
 # SpMM
 # ------------------------------------------------------------------------------------------------
@@ -293,6 +310,32 @@ def test_softmax_nll_gradient_by_finite_differences():
             Zm[i, j] -= eps
             fd = (oracle.softmax_nll(Zp, y, False)[0] - oracle.softmax_nll(Zm, y, False)[0]) / (2 * eps)
             assert abs(fd - G[i, j]) < 1e-9
+
+
+def test_softmax_nll_training_split():
+    """Negative labels mark vertices outside the training split: the loss is the mean over the others,
+    their gradient rows are zero, and the rest equals the unmasked computation on the subset."""
+    n, Cn = 11, 4
+    Z = synth.normal_features(n, Cn, 21).astype(np.float64) * 2.0
+    y = synth.labels(n, Cn, 5)
+    ym = y.copy()
+    out_of_split = np.array([0, 3, 4, 9])
+    ym[out_of_split] = -1
+    keep = np.setdiff1d(np.arange(n), out_of_split)
+    loss_m, G_m = oracle.softmax_nll(Z, ym)
+    loss_s, G_s = oracle.softmax_nll(Z[keep], y[keep])
+    assert abs(loss_m - loss_s) < 1e-14
+    np.testing.assert_array_equal(G_m[out_of_split], 0.0)
+    np.testing.assert_allclose(G_m[keep], G_s, rtol=1e-14)
+    ref = -sum(Z[i, y[i]] - math.log(math.fsum(math.exp(v) for v in Z[i].tolist())) for i in keep.tolist()) / len(keep)
+    assert abs(loss_m - ref) < 1e-13
+    eps = 1e-6
+    for (i, j) in [(0, 1), (1, 2), (9, 0), (10, 3)]:
+        Zp, Zm = Z.copy(), Z.copy()
+        Zp[i, j] += eps
+        Zm[i, j] -= eps
+        fd = (oracle.softmax_nll(Zp, ym, False)[0] - oracle.softmax_nll(Zm, ym, False)[0]) / (2 * eps)
+        assert abs(fd - G_m[i, j]) < 1e-9
 
 
 def test_sgd_step():
