@@ -51,6 +51,9 @@ def main() -> int:
     ap.add_argument("--algo", type=int, default=0, help="SpMM kernel: 0 auto, 1 row-wise, 2 nonzero-split")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--f", type=int, default=0, help="override the dense width of config 2")
+    ap.add_argument("--slice", type=int, default=0,
+                    help="config 2 only: time one block row of P = SLICE (rows [0, n/P) of A against all of X), "
+                         "one process's share of the paper's 1D algorithm")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain device copy of the dense operand (known size) for scaling PMC byte counters")
     args = ap.parse_args()
@@ -92,12 +95,26 @@ def main() -> int:
         f = args.f or w.dims[0]
         X = synth.uniform_features(n, f, args.seed)
         Xd = dev(X)
-        Z = torch.empty(n, f, device="cuda")
+        zrows = n
+        if args.slice > 1:
+            # block row 0 of P: an (n/P) x n matrix; A X_all forward, A^T X_slice for the transposed product
+            rowptr, colidx, val, _ = a.arrays(False)
+            zrows = n // args.slice
+            hi = int(rowptr[zrows].item())
+            a_full = a
+            a = g.gcn_csr_create_from_csr_rect(zrows, n, rowptr[:zrows + 1].clone(), colidx[:hi].clone(), val[:hi].clone(),
+                                               g.BUILD_TRANSPOSE)
+            a_full.close()
+            del rowptr, colidx, val
+            nnz = a.nnz
+            extra.update(slice_of=args.slice, slice_rows=zrows, slice_nnz=nnz)
+        Z = torch.empty(zrows, f, device="cuda")
         Zt = torch.empty(n, f, device="cuda")
+        Xs = Xd[:zrows]
 
         def step():
             g.gcn_spmm(a, 0, Xd, Z)
-            g.gcn_spmm(a, 1, Xd, Zt)
+            g.gcn_spmm(a, 1, Xs, Zt)
 
         if args.copy_calibration:
             for _ in range(2):
@@ -123,7 +140,7 @@ def main() -> int:
         torch.cuda.synchronize()
         dt = min(dt, time.perf_counter() - t0)
 
-        b_alg = spmm_alg_bytes(n, nnz, f)
+        b_alg = spmm_alg_bytes(n, nnz, f) if args.slice <= 1 else 8 * nnz + 8 * (zrows + 1) + 4 * n * f + 4 * zrows * f
         ms_step = dt / args.steps * 1e3
         value = 2 * b_alg / (ms_step * 1e-3) / 1e9
         avg_kernel_ms = kern_ms / (2 * args.steps)          # main SpMM kernel time per product
@@ -132,7 +149,8 @@ def main() -> int:
                    ms_per_step=round(ms_step, 4),
                    config={"workload": f"config 2: {w.name} (R-MAT scale 20, edge factor 16, symmetrised, "
                                        f"self loops, sym-normalised, relabelled), X {n}x{f} uniform[-1,1]",
-                           "n": n, "nnz": nnz, "f": f, "step": "Z=A X then Z=A^T X"})
+                           "n": n, "nnz": nnz, "f": f, "step": "Z=A X then Z=A^T X",
+                           **({"block_row": f"rows [0, n/{args.slice}) of A ({zrows} x {n})"} if args.slice > 1 else {})})
         extra.update(spmm_gflops=round(2 * 2.0 * nnz * f / (ms_step * 1e-3) / 1e9, 1),
                      pct_hbm_peak=round(100 * value / HBM_PEAK_GBPS, 2),
                      bytes_alg_per_spmm=b_alg, bytes_nocache_per_spmm=8 * nnz + 8 * (n + 1) + 4 * f * nnz + 4 * n * f,
@@ -140,12 +158,14 @@ def main() -> int:
         out["roofline"] = {"bound": "hbm", "kernel": "k_spmm_split", "achieved": round(achieved, 2),
                            "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
                            "avg_kernel_ms": round(avg_kernel_ms, 4),
-                           "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, f))}
+                           "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, f)) if args.slice <= 1 else None}
 
         if not args.no_cpu:
             import oracle
             t0 = time.time()
             A = oracle.build_csr(n, src, dst)
+            if args.slice > 1:
+                A = oracle.slice_rows(A, 0, zrows)
             t_ob = time.time() - t0
             t0 = time.time()
             Zo = oracle.spmm(A, X)
@@ -153,7 +173,7 @@ def main() -> int:
             err = float((Z.cpu() - torch.from_numpy(Zo)).abs().max())
             scale = float(np.sqrt(np.mean(Zo.astype(np.float64) ** 2)))
             out["cpu_baseline"] = {"value": round(b_alg / t_o / 1e9, 3), "unit": "GB/s", "cores": oracle.threads(),
-                                   "kind": "oracle", "sample": f"one full Z = A X (n={n}, nnz={nnz}, f={f}), 1 rep",
+                                   "kind": "oracle", "sample": f"one full Z = A X ({zrows} x {n}, nnz={nnz}, f={f}), 1 rep",
                                    "ms": round(t_o * 1e3, 1), "oracle_csr_build_s": round(t_ob, 2)}
             extra.update(max_abs_err_vs_oracle=err, rms_of_oracle=scale, nnz_matches_oracle=bool(A.nnz == nnz))
     else:

@@ -87,10 +87,20 @@ int gcn_csr_create(gcn_csr** out, int64_t n, int64_t n_edges, const int32_t* src
 int gcn_csr_create_from_csr(gcn_csr** out, int64_t n, const int64_t* rowptr, const int32_t* colidx,
                             const float* val, uint32_t flags, void* stream);
 
+/* The same for a rectangular n_rows x n_cols matrix -- one process's block row of the paper's 1D
+ * algorithm ("A One-Dimensional (1D) Algorithm": rows [i n/P, (i+1) n/P) of A^T against all of H).
+ * gcn_spmm with trans=0 reads X with n_cols rows and writes Z with n_rows rows; trans=1 the other way
+ * round.  The layer and epoch calls need a square matrix. */
+int gcn_csr_create_from_csr_rect(gcn_csr** out, int64_t n_rows, int64_t n_cols, const int64_t* rowptr,
+                                 const int32_t* colidx, const float* val, uint32_t flags, void* stream);
+
 int gcn_csr_destroy(gcn_csr* a);
 
 /* Sizes; any output pointer may be NULL. */
 int gcn_csr_info(const gcn_csr* a, int64_t* n, int64_t* nnz, int32_t* max_degree);
+
+/* Rows and columns of A (equal unless made by gcn_csr_create_from_csr_rect). */
+int gcn_csr_shape(const gcn_csr* a, int64_t* n_rows, int64_t* n_cols);
 
 /* DEVICE pointers to the stored arrays (valid until destroy) for bit-exact checks.
  * transposed=1 selects A^T (NOTRANSPOSE if absent); deg is always that of A. */
@@ -106,7 +116,8 @@ int gcn_csr_export(const gcn_csr* a, int transposed, int64_t* rowptr, int32_t* c
  * SpMM -- the local sparse-dense product of sections "Graph Neural Networks" and "A
  * One-Dimensional (1D) Algorithm":  Z[i,:] = sum over stored entries k of row i of op(A) of
  * val[k] * X[col[k],:], op(A) = A (trans=0) or A^T (trans=1).
- * X: device n x f, ld ldx >= f.  Z: device n x f, ld ldz >= f, must not overlap X.
+ * X: device n x f, ld ldx >= f.  Z: device n x f, ld ldz >= f, must not overlap X (for a rectangular
+ * matrix X has as many rows as op(A) has columns and Z as many as op(A) has rows).
  * epilogue GCN_EPI_MASK reads Zprev (device n x f, ld ldzprev); otherwise Zprev is ignored.
  * Sums are fp32 and run-to-run reproducible (no floating-point atomics).  The first call at a
  * given width may build and cache a column-blocked copy of the matrix inside `a` (it allocates

@@ -86,10 +86,15 @@ class Csr:
     colidx: np.ndarray
     val: np.ndarray
     deg: np.ndarray
+    ncols: int = -1          # -1: square
 
     @property
     def nnz(self) -> int:
         return int(self.rowptr[-1])
+
+    @property
+    def n_cols(self) -> int:
+        return self.n if self.ncols < 0 else self.ncols
 
 
 def build_csr(n, src, dst, symmetrise=True, self_loops=True, norm="sym", transpose=False) -> Csr:
@@ -133,13 +138,31 @@ def build_csr(n, src, dst, symmetrise=True, self_loops=True, norm="sym", transpo
     return Csr(n, rowptr, colidx, val, deg)
 
 
+def slice_rows(A: Csr, r0: int, r1: int) -> Csr:
+    """Rows [r0, r1) of A as an (r1-r0) x n_cols matrix: one process's block row in the paper's 1D
+    algorithm ("A One-Dimensional (1D) Algorithm")."""
+    lo, hi = int(A.rowptr[r0]), int(A.rowptr[r1])
+    return Csr(r1 - r0, (A.rowptr[r0:r1 + 1] - lo).astype(np.int64), A.colidx[lo:hi].copy(), A.val[lo:hi].copy(),
+               A.deg[r0:r1].copy(), A.n_cols)
+
+
+def transpose(A: Csr) -> Csr:
+    """A^T in compressed rows, by the definition: entry (i,j,v) becomes (j,i,v); rows of the result
+    ascend in i because the stable sort keeps the row-major input order."""
+    rows = np.repeat(np.arange(A.n, dtype=np.int64), np.diff(A.rowptr))
+    order = np.argsort(A.colidx, kind="stable")
+    counts = np.bincount(A.colidx, minlength=A.n_cols)
+    rowptr = np.concatenate([[0], np.cumsum(counts)]).astype(np.int64)
+    return Csr(A.n_cols, rowptr, rows[order].astype(np.int32), A.val[order].copy(), A.deg, A.n)
+
+
 # ---------------------------------------------------------------------------------------------
 # primitives
 # ---------------------------------------------------------------------------------------------
 
 def spmm(A: Csr, X: np.ndarray) -> np.ndarray:
     """Z = A X with Z[i,:] = sum over stored entries k of row i of val[k] X[col[k],:]."""
-    assert X.shape[0] == A.n
+    assert X.shape[0] == A.n_cols
     k = _kind(X)
     f = X.shape[1]
     Z = np.empty((A.n, f), X.dtype)
@@ -150,7 +173,7 @@ def spmm(A: Csr, X: np.ndarray) -> np.ndarray:
 
 def spmm_rows(A: Csr, X: np.ndarray, rows) -> np.ndarray:
     """Rows ``rows`` of A X, one at a time (for spot checks at sizes too big for a full product)."""
-    assert X.shape[0] == A.n
+    assert X.shape[0] == A.n_cols
     k = _kind(X)
     rows = np.ascontiguousarray(rows, np.int64)
     f = X.shape[1]

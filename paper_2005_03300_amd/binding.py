@@ -87,11 +87,14 @@ class Csr:
         n, nnz, md = C.c_int64(), C.c_int64(), C.c_int32()
         _check(lib().gcn_csr_info(self._h, C.byref(n), C.byref(nnz), C.byref(md)))
         self.n, self.nnz, self.max_degree = n.value, nnz.value, md.value
+        nr, nc = C.c_int64(), C.c_int64()
+        _check(lib().gcn_csr_shape(self._h, C.byref(nr), C.byref(nc)))
+        self.n_rows, self.n_cols = nr.value, nc.value
 
     def arrays(self, transposed: bool = False):
         """Copies of (rowptr, colidx, val, deg) as torch tensors on the device."""
         import torch
-        rowptr = torch.empty(self.n + 1, dtype=torch.int64, device="cuda")
+        rowptr = torch.empty((self.n_cols if transposed else self.n_rows) + 1, dtype=torch.int64, device="cuda")
         colidx = torch.empty(self.nnz, dtype=torch.int32, device="cuda")
         val = torch.empty(self.nnz, dtype=torch.float32, device="cuda")
         deg = torch.empty(self.n, dtype=torch.int32, device="cuda")
@@ -133,11 +136,24 @@ def gcn_csr_create_from_csr(n: int, rowptr, colidx, val, flags: int) -> Csr:
     return Csr(out.value)
 
 
+def gcn_csr_create_from_csr_rect(n_rows: int, n_cols: int, rowptr, colidx, val, flags: int) -> Csr:
+    import torch
+    rowptr = _dev(rowptr, torch.int64).contiguous()
+    colidx = _dev(colidx, torch.int32).contiguous()
+    if val is not None:
+        val = _dev(val, torch.float32).contiguous()
+    out = C.c_void_p()
+    _check(lib().gcn_csr_create_from_csr_rect(C.byref(out), C.c_int64(n_rows), C.c_int64(n_cols), _ptr(rowptr),
+                                              _ptr(colidx), _ptr(val), C.c_uint32(flags), _stream()))
+    return Csr(out.value)
+
+
 def gcn_spmm(a: Csr, trans: int, X, Z, epilogue: int = EPI_NONE, Zprev=None):
     import torch
     _dev(X, torch.float32), _dev(Z, torch.float32)
     f = X.shape[1]
-    assert X.shape[0] == a.n and tuple(Z.shape) == (a.n, f)
+    xr, zr = (a.n_rows, a.n_cols) if trans else (a.n_cols, a.n_rows)
+    assert X.shape[0] == xr and tuple(Z.shape) == (zr, f)
     _check(lib().gcn_spmm(a._h, int(trans), C.c_int32(f), _ptr(X), C.c_int64(_ld(X)), _ptr(Z), C.c_int64(_ld(Z)),
                           int(epilogue), _ptr(Zprev), C.c_int64(_ld(Zprev) if Zprev is not None else 0), _stream()))
     return Z

@@ -218,6 +218,13 @@ int gcn_csr_info(const gcn_csr* a, int64_t* n, int64_t* nnz, int32_t* max_degree
     return GCN_OK;
 }
 
+int gcn_csr_shape(const gcn_csr* a, int64_t* n_rows, int64_t* n_cols) {
+    if (!a) return fail(GCN_ERR_BADARG, "gcn_csr_shape: NULL matrix");
+    if (n_rows) *n_rows = a->n;
+    if (n_cols) *n_cols = a->ncols;
+    return GCN_OK;
+}
+
 int gcn_csr_arrays(const gcn_csr* a, int transposed, const int64_t** rowptr, const int32_t** colidx,
                    const float** val, const int32_t** deg) {
     if (!a) return fail(GCN_ERR_BADARG, "gcn_csr_arrays: NULL matrix");
@@ -236,7 +243,7 @@ int gcn_csr_export(const gcn_csr* a, int transposed, int64_t* rowptr, int32_t* c
     if (transposed && !a->has_t) return fail(GCN_ERR_NOTRANSPOSE, "matrix was built without GCN_BUILD_TRANSPOSE");
     const Matrix& m = transposed ? a->At : a->A;
     hipStream_t s = (hipStream_t)stream;
-    if (rowptr) GCN_HIP_TRY(hipMemcpyAsync(rowptr, m.rowptr, ((size_t)a->n + 1) * sizeof(int64_t), hipMemcpyDeviceToDevice, s));
+    if (rowptr) GCN_HIP_TRY(hipMemcpyAsync(rowptr, m.rowptr, ((size_t)m.nrows + 1) * sizeof(int64_t), hipMemcpyDeviceToDevice, s));
     if (colidx && a->nnz) GCN_HIP_TRY(hipMemcpyAsync(colidx, m.colidx, (size_t)a->nnz * sizeof(int32_t), hipMemcpyDeviceToDevice, s));
     if (val && a->nnz) GCN_HIP_TRY(hipMemcpyAsync(val, m.val, (size_t)a->nnz * sizeof(float), hipMemcpyDeviceToDevice, s));
     if (deg) GCN_HIP_TRY(hipMemcpyAsync(deg, a->deg, (size_t)a->n * sizeof(int32_t), hipMemcpyDeviceToDevice, s));

@@ -86,7 +86,8 @@ struct Sweep {
 
 // One stored matrix in compressed rows plus its nonzero-split schedule.
 struct Matrix {
-    int64_t* rowptr = nullptr;   // [n+1]
+    int64_t nrows = 0, ncols = 0;
+    int64_t* rowptr = nullptr;   // [nrows+1]
     int32_t* colidx = nullptr;   // [nnz]
     float* val = nullptr;        // [nnz]
     // schedule (built once at creation)
@@ -104,7 +105,7 @@ struct Matrix {
 }  // namespace gcn
 
 struct gcn_csr {
-    int64_t n = 0, nnz = 0;
+    int64_t n = 0, ncols = 0, nnz = 0;   // A is n x ncols (square unless made by gcn_csr_create_from_csr_rect)
     int device = 0;
     bool has_t = false;
     gcn::Matrix A, At;
@@ -140,9 +141,9 @@ void timing_begin(hipStream_t s);
 void timing_end(hipStream_t s);
 
 int build_schedule(Matrix& m, int64_t n, int64_t nnz, hipStream_t s);
-int build_blocked(Matrix& m, int64_t n, int64_t nnz, int64_t cols_per_block, hipStream_t s);
+int build_blocked(Matrix& m, int64_t nnz, int64_t cols_per_block, hipStream_t s);
 void free_blocked(Blocked& b);
-int build_sweep(Matrix& m, int64_t n, int64_t nnz, int64_t cols_per_block, int32_t rb, int32_t heavy_threshold,
+int build_sweep(Matrix& m, int64_t nnz, int64_t cols_per_block, int32_t rb, int32_t heavy_threshold,
                 hipStream_t s);
 void free_sweep(Sweep& w);
 void free_matrix(Matrix& m);

@@ -334,11 +334,12 @@ __global__ void k_set_i64(int64_t* p, int64_t v) { *p = v; }
 
 void free_blocked(Blocked& b);
 
-int build_blocked(Matrix& m, int64_t n, int64_t nnz, int64_t cpb, hipStream_t s) {
+int build_blocked(Matrix& m, int64_t nnz, int64_t cpb, hipStream_t s) {
     free_blocked(m.blk);
     Blocked& b = m.blk;
     if (nnz <= 0 || cpb <= 0) return fail(GCN_ERR_BADARG, "build_blocked: empty matrix or bad block width");
-    const int64_t nblocks = (n + cpb - 1) / cpb;
+    const int64_t n = m.nrows;
+    const int64_t nblocks = (m.ncols + cpb - 1) / cpb;
     const int64_t nsub = m.nsub;
     TempBuf k0, k1, p0, p1, cnt, pre, tmp;
     GCN_TRY(k0.alloc((size_t)nnz * 8));
@@ -508,12 +509,13 @@ __global__ void k_heavy_len(int64_t nh, const int32_t* __restrict__ rows, const 
     if (q == nh) len[q] = 0;
 }
 
-int build_sweep(Matrix& m, int64_t n, int64_t nnz, int64_t cpb, int32_t rb, int32_t heavy_th, hipStream_t s) {
+int build_sweep(Matrix& m, int64_t nnz, int64_t cpb, int32_t rb, int32_t heavy_th, hipStream_t s) {
     free_sweep(m.swp);
     Sweep& w = m.swp;
     if (nnz <= 0 || cpb <= 0 || rb <= 0 || rb > 128) return fail(GCN_ERR_BADARG, "build_sweep: bad parameters");
+    const int64_t n = m.nrows;
     const int64_t ntasks = (n + rb - 1) / rb;
-    const int64_t nj = (n + cpb - 1) / cpb;
+    const int64_t nj = (m.ncols + cpb - 1) / cpb;
     const unsigned jbits = bits_for(nj + 1);
     const unsigned tbits = bits_for(ntasks + 1);
     if (jbits + tbits + 1 > 63) return fail(GCN_ERR_RANGE, "build_sweep: key does not fit");
@@ -650,20 +652,22 @@ int build_sweep(Matrix& m, int64_t n, int64_t nnz, int64_t cpb, int32_t rb, int3
 // A^T of `a` from A's sorted keys and values: swap key halves, stable radix sort with the values
 // as payload.  Within a column the rows keep their ascending order.
 static int build_transpose(gcn_csr* a, const uint64_t* keys, uint64_t* scratch_keys, hipStream_t s) {
-    int64_t nnz = a->nnz, n = a->n;
+    const int64_t nnz = a->nnz, n = a->ncols;            // A^T has ncols rows
     TempBuf kin, vtmp;
     GCN_TRY(kin.alloc((size_t)nnz * 8));
     GCN_TRY(device_alloc_t(&a->At.val, (size_t)nnz));
     hipLaunchKernelGGL(k_swap_halves, dim3(blocks_for(nnz)), dim3(TPB), 0, s, nnz, keys, kin.as<uint64_t>());
     GCN_LAUNCH_CHECK();
     size_t tmp_bytes = 0;
-    unsigned end_bit = 32 + bits_for(n);
+    unsigned end_bit = 32 + bits_for(n);                 // low half: rows of A, high half: its columns
     GCN_HIP_TRY(rocprim::radix_sort_pairs(nullptr, tmp_bytes, kin.as<uint64_t>(), scratch_keys, a->A.val, a->At.val,
                                           (size_t)nnz, 0u, end_bit, s));
     TempBuf tmp;
     GCN_TRY(tmp.alloc(tmp_bytes));
     GCN_HIP_TRY(rocprim::radix_sort_pairs(tmp.p, tmp_bytes, kin.as<uint64_t>(), scratch_keys, a->A.val, a->At.val,
                                           (size_t)nnz, 0u, end_bit, s));
+    a->At.nrows = n;
+    a->At.ncols = a->n;
     GCN_TRY(compress_keys(a->At, n, nnz, scratch_keys, s));
     GCN_HIP_TRY(hipStreamSynchronize(s));
     GCN_TRY(build_schedule(a->At, n, nnz, s));
@@ -719,7 +723,9 @@ static int create_impl(gcn_csr* a, int64_t n, int64_t m, const int32_t* src, con
     }
     const uint64_t* keys = k0.as<uint64_t>();   // sorted, distinct, nnz of them
     a->n = n;
+    a->ncols = n;
     a->nnz = nnz;
+    a->A.nrows = a->A.ncols = n;
     GCN_TRY(compress_keys(a->A, n, nnz, keys, s));
     GCN_TRY(device_alloc_t(&a->deg, (size_t)n));
     GCN_TRY(device_alloc_t(&a->A.val, (size_t)nnz));
@@ -737,8 +743,8 @@ static int create_impl(gcn_csr* a, int64_t n, int64_t m, const int32_t* src, con
     return GCN_OK;
 }
 
-static int from_csr_impl(gcn_csr* a, int64_t n, const int64_t* rowptr, const int32_t* colidx, const float* val,
-                         uint32_t flags, hipStream_t s) {
+static int from_csr_impl(gcn_csr* a, int64_t n, int64_t ncols, const int64_t* rowptr, const int32_t* colidx,
+                         const float* val, uint32_t flags, hipStream_t s) {
     TempBuf bad;
     GCN_TRY(bad.alloc(sizeof(int)));
     GCN_HIP_TRY(hipMemsetAsync(bad.p, 0, sizeof(int), s));
@@ -752,7 +758,10 @@ static int from_csr_impl(gcn_csr* a, int64_t n, const int64_t* rowptr, const int
     if (hbad || nnz < 0) return fail(GCN_ERR_UNSORTED, "gcn_csr_create_from_csr: rowptr must start at 0 and not decrease");
     if (nnz > 0 && !colidx) return fail(GCN_ERR_BADARG, "gcn_csr_create_from_csr: NULL colidx");
     a->n = n;
+    a->ncols = ncols;
     a->nnz = nnz;
+    a->A.nrows = n;
+    a->A.ncols = ncols;
     GCN_TRY(device_alloc_t(&a->A.rowptr, (size_t)n + 1));
     GCN_TRY(device_alloc_t(&a->A.colidx, (size_t)nnz));
     GCN_TRY(device_alloc_t(&a->A.val, (size_t)nnz));
@@ -770,7 +779,7 @@ static int from_csr_impl(gcn_csr* a, int64_t n, const int64_t* rowptr, const int
         hipLaunchKernelGGL(k_keys_from_csr, dim3(blocks_for(nnz)), dim3(TPB), 0, s, nnz, n, a->A.rowptr, a->A.colidx,
                            keys.as<uint64_t>());
         GCN_LAUNCH_CHECK();
-        hipLaunchKernelGGL(k_validate_keys, dim3(blocks_for(nnz)), dim3(TPB), 0, s, nnz, n, keys.as<uint64_t>(),
+        hipLaunchKernelGGL(k_validate_keys, dim3(blocks_for(nnz)), dim3(TPB), 0, s, nnz, ncols, keys.as<uint64_t>(),
                            bad.as<int>());
         GCN_LAUNCH_CHECK();
         GCN_HIP_TRY(hipMemcpyAsync(&hbad, bad.p, sizeof(int), hipMemcpyDeviceToHost, s));
@@ -825,7 +834,25 @@ int gcn_csr_create_from_csr(gcn_csr** out, int64_t n, const int64_t* rowptr, con
     gcn_csr* a = new (std::nothrow) gcn_csr();
     if (!a) return fail(GCN_ERR_OOM, "host allocation failed");
     (void)hipGetDevice(&a->device);
-    int rc = from_csr_impl(a, n, rowptr, colidx, val, flags, (hipStream_t)stream);
+    int rc = from_csr_impl(a, n, n, rowptr, colidx, val, flags, (hipStream_t)stream);
+    if (rc != GCN_OK) {
+        gcn_csr_destroy(a);
+        return rc;
+    }
+    *out = a;
+    return GCN_OK;
+}
+
+int gcn_csr_create_from_csr_rect(gcn_csr** out, int64_t n_rows, int64_t n_cols, const int64_t* rowptr,
+                                 const int32_t* colidx, const float* val, uint32_t flags, void* stream) {
+    if (!out) return fail(GCN_ERR_BADARG, "gcn_csr_create_from_csr_rect: NULL out");
+    *out = nullptr;
+    if (n_rows <= 0 || n_cols <= 0 || !rowptr) return fail(GCN_ERR_BADARG, "gcn_csr_create_from_csr_rect: sizes must be positive, rowptr non-NULL");
+    if (n_rows >= (1ll << 31) || n_cols >= (1ll << 31)) return fail(GCN_ERR_RANGE, "gcn_csr_create_from_csr_rect: sizes must be below 2^31");
+    gcn_csr* a = new (std::nothrow) gcn_csr();
+    if (!a) return fail(GCN_ERR_OOM, "host allocation failed");
+    (void)hipGetDevice(&a->device);
+    int rc = from_csr_impl(a, n_rows, n_cols, rowptr, colidx, val, flags, (hipStream_t)stream);
     if (rc != GCN_OK) {
         gcn_csr_destroy(a);
         return rc;

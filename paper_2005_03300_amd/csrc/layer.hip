@@ -113,6 +113,7 @@ int gcn_layer_forward(gcn_csr* a, int32_t f_in, int32_t f_out, const float* Hin,
     if (act != GCN_ACT_NONE && act != GCN_ACT_RELU) return fail(GCN_ERR_BADARG, "gcn_layer_forward: unknown activation");
     if (act == GCN_ACT_RELU && !Hout) return fail(GCN_ERR_BADARG, "gcn_layer_forward: ReLU needs Hout");
     if (!a->has_t) return fail(GCN_ERR_NOTRANSPOSE, "gcn_layer_forward needs GCN_BUILD_TRANSPOSE");
+    if (a->n != a->ncols) return fail(GCN_ERR_BADARG, "gcn_layer_forward needs a square matrix");
     return layer_forward_impl(a, f_in, f_out, Hin, ldh, W, bias, Z, Hout, T, order, act, (hipStream_t)stream);
 }
 
@@ -122,6 +123,7 @@ int gcn_layer_backward(gcn_csr* a, int32_t f_in, int32_t f_out, const float* Hin
     if (!a || !W || !G || !S || !Y) return fail(GCN_ERR_BADARG, "gcn_layer_backward: NULL argument");
     if (f_in <= 0 || f_out <= 0) return fail(GCN_ERR_BADARG, "gcn_layer_backward: bad sizes");
     if (order < GCN_ORDER_AUTO || order > GCN_ORDER_SPMM_FIRST) return fail(GCN_ERR_BADARG, "gcn_layer_backward: unknown order");
+    if (a->n != a->ncols) return fail(GCN_ERR_BADARG, "gcn_layer_backward needs a square matrix");
     const int ord = resolve_order(order, f_in, f_out);
     if (ord == GCN_ORDER_GEMM_FIRST && (!Hin || ldh < f_in)) return fail(GCN_ERR_BADARG, "gcn_layer_backward: Hin needed");
     if (ord == GCN_ORDER_SPMM_FIRST && !T) return fail(GCN_ERR_BADARG, "gcn_layer_backward: SpMM-first order needs the forward T");
@@ -158,6 +160,7 @@ int gcn_epoch_masked(gcn_csr* a, int32_t L_w, const int32_t* dims, const float* 
     GCN_TRY(check_dims(a->n, L_w, dims));
     if (order < GCN_ORDER_AUTO || order > GCN_ORDER_SPMM_FIRST) return fail(GCN_ERR_BADARG, "gcn_epoch: unknown order");
     if (!a->has_t) return fail(GCN_ERR_NOTRANSPOSE, "gcn_epoch needs GCN_BUILD_TRANSPOSE");
+    if (a->n != a->ncols) return fail(GCN_ERR_BADARG, "gcn_epoch needs a square matrix");
     for (int l = 0; l < L_w; ++l)
         if (!W[l] || !Y[l]) return fail(GCN_ERR_BADARG, "gcn_epoch: NULL weight or gradient pointer at layer %d", l + 1);
     if (((uintptr_t)workspace & 255u) != 0) return fail(GCN_ERR_BADARG, "gcn_epoch: workspace must be 256-byte aligned");

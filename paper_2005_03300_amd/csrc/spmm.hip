@@ -580,11 +580,11 @@ static int grow(float** buf, size_t* have, size_t need) {
 // How many column blocks to cut X into so that one block of the gathered panel stays in one L2
 // (4 MB per XCD).  Blocking costs one partial row per non-empty (block,row) pair, so it only pays
 // when rows are long compared with the number of blocks; otherwise 1 (no blocking).
-static int64_t choose_blocks(int64_t n, int64_t nnz, int32_t f) {
+static int64_t choose_blocks(int64_t n, int64_t ncols, int64_t nnz, int32_t f) {
     const int forced = config().spmm_blocks;
     if (forced >= 1) return forced;
     const int64_t panel = f < 32 ? f : 32;
-    const int64_t xbytes = n * panel * 4;
+    const int64_t xbytes = ncols * panel * 4;
     if (xbytes <= (7ll << 19)) return 1;                  // 3.5 MB: already L2-resident
     const int64_t want = (xbytes + (2ll << 20) - 1) / (2ll << 20);
     const int64_t cap = (nnz / n) / 24;
@@ -593,7 +593,7 @@ static int64_t choose_blocks(int64_t n, int64_t nnz, int32_t f) {
 
 int spmm_launch(gcn_csr* a, Matrix& m, int32_t f, const float* X, int64_t ldx, float* Z, int64_t ldz,
                 int epilogue, const float* Zprev, int64_t ldzprev, hipStream_t s) {
-    const int64_t n = a->n, nnz = a->nnz;
+    const int64_t n = m.nrows, ncols = m.ncols, nnz = a->nnz;
     if (nnz == 0) {
         const int64_t work = n * f;
         hipLaunchKernelGGL(k_zero_empty_rows, dim3((unsigned)((work + 255) / 256)), dim3(256), 0, s, n, m.rowptr, f, Z, ldz);
@@ -611,12 +611,12 @@ int spmm_launch(gcn_csr* a, Matrix& m, int32_t f, const float* X, int64_t ldx, f
         const int32_t rb = 2048 / W;                       // 8 KB of accumulators per wavefront
         // measured: the finer the column blocks the better the wavefronts stay together (the gain
         // levels off near a thousand blocks), so by default a block is 256 columns
-        int64_t nj = config().spmm_blocks >= 2 ? config().spmm_blocks : (n + 255) / 256;
+        int64_t nj = config().spmm_blocks >= 2 ? config().spmm_blocks : (ncols + 255) / 256;
         if (nj < 1) nj = 1;
-        const int64_t cpb = (n + nj - 1) / nj;
+        const int64_t cpb = (ncols + nj - 1) / nj;
         const int32_t th = config().sweep_heavy;
         if (m.swp.cols_per_block != cpb || m.swp.rb != rb || m.swp.heavy_threshold != th)
-            GCN_TRY(build_sweep(m, n, nnz, cpb, rb, th, s));
+            GCN_TRY(build_sweep(m, nnz, cpb, rb, th, s));
         const Sweep& w = m.swp;
         SweepArgs sa;
         sa.colidx = w.colidx; sa.val = w.val; sa.lrow = w.lrow; sa.task_base = w.task_base; sa.task_len = w.task_len; sa.task_order = w.task_order;
@@ -658,11 +658,11 @@ int spmm_launch(gcn_csr* a, Matrix& m, int32_t f, const float* X, int64_t ldx, f
     args.nnz = nnz; args.nsub = m.nsub; args.nchunks = m.nchunks; args.f = f;
     args.X = X; args.ldx = ldx; args.carry = a->carry;
 
-    const int64_t nblocks = choose_blocks(n, nnz, f);
+    const int64_t nblocks = choose_blocks(n, ncols, nnz, f);
     if (nblocks >= 2) {
-        int64_t cpb = (n + nblocks - 1) / nblocks;
+        int64_t cpb = (ncols + nblocks - 1) / nblocks;
         cpb = (cpb + 1023) & ~1023ll;
-        if (m.blk.cols_per_block != cpb) GCN_TRY(build_blocked(m, n, nnz, cpb, s));
+        if (m.blk.cols_per_block != cpb) GCN_TRY(build_blocked(m, nnz, cpb, s));
         const Blocked& b = m.blk;
         GCN_TRY(grow(&a->partial, &a->partial_bytes, (size_t)b.nrows * (size_t)f * sizeof(float)));
         args.colidx = b.colidx; args.val = b.val; args.flags = b.flags; args.sub_row = b.sub_row;
@@ -698,8 +698,9 @@ extern "C" int gcn_spmm(gcn_csr* a, int trans, int32_t f, const float* X, int64_
     if (epilogue == GCN_EPI_MASK && (!Zprev || ldzprev < f)) return fail(GCN_ERR_BADARG, "gcn_spmm: mask epilogue needs Zprev with ld >= f");
     if (trans && !a->has_t) return fail(GCN_ERR_NOTRANSPOSE, "gcn_spmm: trans=1 needs GCN_BUILD_TRANSPOSE");
     {   // X and Z must not overlap: the product gathers rows of X while rows of Z are written
-        const char* xb = (const char*)X; const char* xe = xb + ((size_t)(a->n - 1) * ldx + f) * sizeof(float);
-        const char* zb = (const char*)Z; const char* ze = zb + ((size_t)(a->n - 1) * ldz + f) * sizeof(float);
+        const int64_t xrows = trans ? a->n : a->ncols, zrows = trans ? a->ncols : a->n;
+        const char* xb = (const char*)X; const char* xe = xb + ((size_t)(xrows - 1) * ldx + f) * sizeof(float);
+        const char* zb = (const char*)Z; const char* ze = zb + ((size_t)(zrows - 1) * ldz + f) * sizeof(float);
         if (xb < ze && zb < xe) return fail(GCN_ERR_BADARG, "gcn_spmm: X and Z overlap");
     }
     return spmm_launch(a, trans ? a->At : a->A, f, X, ldx, Z, ldz, epilogue, Zprev, ldzprev, (hipStream_t)stream);

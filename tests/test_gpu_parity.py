@@ -255,6 +255,50 @@ def test_spmm_directed_transpose_and_empty_rows(name):
     a.close()
 
 
+@pytest.mark.parametrize("name,parts", [("c2s", 8), ("c3s", 8), ("c4s", 3)])
+def test_spmm_rectangular_block_row(name, parts):
+    """One process's share of the paper's 1D algorithm at P = parts: rows [p n/P, (p+1) n/P) of the matrix
+    against the whole dense operand, and the transposed product of the slice."""
+    g = G()
+    A = oracle_csr(name)
+    n = A.n
+    for p in (0, parts - 1):
+        r0, r1 = p * n // parts, (p + 1) * n // parts
+        S = oracle.slice_rows(A, r0, r1)
+        St = oracle.transpose(S)
+        a = g.gcn_csr_create_from_csr_rect(S.n, n, dev(S.rowptr), dev(S.colidx), dev(S.val), g.BUILD_TRANSPOSE)
+        assert (a.n_rows, a.n_cols, a.nnz) == (S.n, n, S.nnz)
+        rt, ct, vt, _ = [host(t) for t in a.arrays(True)]
+        np.testing.assert_array_equal(rt, St.rowptr)
+        np.testing.assert_array_equal(ct, St.colidx)
+        np.testing.assert_array_equal(vt, St.val)
+        for f in (16, 128):
+            X = synth.normal_features(n, f, 50)
+            Xs = synth.normal_features(S.n, f, 51)
+            for forced in (0, 4):
+                g.gcn_config(g.CFG_SPMM_BLOCKS, forced)
+                try:
+                    Z = torch.full((S.n, f), float("nan"), device="cuda")
+                    g.gcn_spmm(a, 0, dev(X), Z)
+                    assert_close(host(Z), oracle.spmm(S, X), f"{name} slice {p} f={f} blocks={forced}")
+                    Zt = torch.full((n, f), float("nan"), device="cuda")
+                    g.gcn_spmm(a, 1, dev(Xs), Zt)
+                    assert_close(host(Zt), oracle.spmm(St, Xs), f"{name} slice^T {p} f={f} blocks={forced}")
+                finally:
+                    g.gcn_config(g.CFG_SPMM_BLOCKS, 0)
+        a.close()
+    with pytest.raises(g.GcnError) as e:       # layer calls need a square matrix
+        S = oracle.slice_rows(A, 0, n // 2)
+        a = g.gcn_csr_create_from_csr_rect(S.n, n, dev(S.rowptr), dev(S.colidx), dev(S.val), g.BUILD_TRANSPOSE)
+        try:
+            W = torch.zeros(16, 16, device="cuda")
+            H = torch.zeros(n, 16, device="cuda")
+            g.gcn_layer_forward(a, H, W, H.clone(), H.clone(), H.clone())
+        finally:
+            a.close()
+    assert e.value.code == -1
+
+
 @pytest.mark.parametrize("f", [16, 41])
 def test_spmm_epilogues(f):
     g = G()

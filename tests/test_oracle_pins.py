@@ -149,6 +149,32 @@ def test_normalised_matrix_has_sqrt_degree_eigenvector():
     np.testing.assert_allclose(y, x, rtol=1e-6)
 
 
+def test_row_slice_and_transpose_pins():
+    """Block rows of the 1D algorithm: the slice's product is the matching rows of the full product;
+    transposing twice gives the matrix back; the transposed slice matches the dense transpose."""
+    n, src, dst = small_graph(60, 240, 29)
+    A = oracle.build_csr(n, src, dst, symmetrise=False)
+    S = oracle.slice_rows(A, 13, 41)
+    assert (S.n, S.n_cols) == (28, n)
+    D = np.array(py_dense(A))
+    X = synth.normal_features(n, 4, 6).astype(np.float64)
+    np.testing.assert_array_equal(oracle.spmm(S, X), oracle.spmm(A, X)[13:41])
+    St = oracle.transpose(S)
+    assert (St.n, St.n_cols) == (n, 28)
+    Dt = np.zeros((n, 28))
+    for i in range(n):
+        for k in range(int(St.rowptr[i]), int(St.rowptr[i + 1])):
+            Dt[i, St.colidx[k]] = St.val[k]
+    np.testing.assert_array_equal(Dt, D[13:41].T)
+    Stt = oracle.transpose(St)
+    for a, b in [(Stt.rowptr, S.rowptr), (Stt.colidx, S.colidx), (Stt.val, S.val)]:
+        np.testing.assert_array_equal(a, b)
+    At = oracle.build_csr(n, src, dst, symmetrise=False, transpose=True)      # independent construction
+    T = oracle.transpose(A)
+    for a, b in [(T.rowptr, At.rowptr), (T.colidx, At.colidx), (T.val, At.val)]:
+        np.testing.assert_array_equal(a, b)
+
+
 def test_row_normalisation_pins():
     """D^-1 (A+I) on a directed graph: every row sums to one, the values are 1/d_i by hand, and the
     transposed structure carries the transposed values."""
