@@ -63,23 +63,24 @@ struct Blocked {
 struct Matrix;
 
 // Sweep copy of a matrix for operands far larger than the caches.  Rows are cut into tasks of
-// `rb` consecutive rows; a task's entries are re-sorted by column block, so a wavefront that owns
-// a task (accumulating its rows in LDS) walks the columns left to right.  All wavefronts of a
-// launch start together and advance at the same pace, so at any moment the whole GPU gathers from
-// a narrow band of X that stays in L2.  Rows longer than `heavy_threshold` are kept apart and go
-// through the nonzero-split kernel.
+// `rb` consecutive rows; a wavefront owns a task, accumulates its rows in LDS and walks the task's
+// entries in ascending column order, so all wavefronts of a launch (started together, equal length)
+// gather from one narrow band of X at a time and that band stays in L2.  Inside a task every row
+// belongs to one of `groups` queues (balanced by entry count); the stored order interleaves the
+// queues -- position k*groups + g is the k-th entry of queue g -- so the lane groups of one step
+// always hold different rows and add to LDS without any conflict.  Rows longer than
+// `heavy_threshold` are kept apart and go through the nonzero-split kernel.
 struct Sweep {
-    int64_t cols_per_block = 0;
+    int32_t groups = 0;
     int32_t rb = 0;
     int32_t heavy_threshold = 0;
     int64_t ntasks = 0, nnz_light = 0, nnz_heavy = 0, n_heavy = 0;
-    int64_t padded = 0;           // entries stored: every task starts at a multiple of 16
-    int32_t* colidx = nullptr;    // [padded] task-major, column-block-major inside a task
+    int64_t padded = 0;           // entries stored, padding included
+    int32_t* colidx = nullptr;    // [padded]
     float* val = nullptr;         // [padded]
-    uint8_t* lrow = nullptr;      // [padded] bits 0-6: row inside the task; bit 7 of the first entry of an
-                                  //          aligned group of 16: the group holds some row twice
-    int64_t* task_base = nullptr; // [ntasks] first stored entry of the task
-    int32_t* task_len = nullptr;  // [ntasks] entries of the task
+    uint8_t* lrow = nullptr;      // [padded] bits 0-6: row inside the task; bit 7: padding, skip
+    int64_t* task_base = nullptr; // [ntasks] first stored entry of the task (multiple of 16)
+    int32_t* task_len = nullptr;  // [ntasks] stored entries of the task (multiple of groups)
     int32_t* task_order = nullptr;// [ntasks] task ids, longest first
     Matrix* heavy = nullptr;      // the heavy rows as a row-subset matrix (ne_rows = their ids)
 };
@@ -130,8 +131,8 @@ int scratch_get(void** p, size_t bytes);
 struct Config {
     int spmm_algo = 0;
     int spmm_blocks = 0;
-    int sweep_heavy = 4096;
-    int sweep_waves = 16;
+    int sweep_heavy = 1024;
+    int sweep_waves = 10;
     int timing = 0;
 };
 Config& config();
@@ -143,8 +144,7 @@ void timing_end(hipStream_t s);
 int build_schedule(Matrix& m, int64_t n, int64_t nnz, hipStream_t s);
 int build_blocked(Matrix& m, int64_t nnz, int64_t cols_per_block, hipStream_t s);
 void free_blocked(Blocked& b);
-int build_sweep(Matrix& m, int64_t nnz, int64_t cols_per_block, int32_t rb, int32_t heavy_threshold,
-                hipStream_t s);
+int build_sweep(Matrix& m, int64_t nnz, int32_t groups, int32_t rb, int32_t heavy_threshold, hipStream_t s);
 void free_sweep(Sweep& w);
 void free_matrix(Matrix& m);
 

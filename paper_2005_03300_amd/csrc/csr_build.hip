@@ -419,12 +419,48 @@ int build_blocked(Matrix& m, int64_t nnz, int64_t cpb, hipStream_t s) {
 
 struct SweepPayload { int32_t col; float val; int32_t row; };
 
-// key = task << jbits | column block for entries of light rows, all-ones for entries of heavy rows
-// (they sort behind everything and keep their (row, col) order because the sort is stable).
+// One thread per task: deal the task's light rows to `groups` queues, longest row first, each to the
+// queue with the fewest entries so far.  Writes the queue of every row and the task's stored length
+// (groups x the longest queue).
+__global__ void k_sweep_assign(int64_t ntasks, int64_t n, const int64_t* __restrict__ rowptr, int32_t rb, int32_t groups,
+                               int32_t heavy_th, uint8_t* __restrict__ qrow, int32_t* __restrict__ task_len,
+                               uint32_t* __restrict__ sort_key, int64_t* __restrict__ padded_len) {
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= ntasks) return;
+    const int64_t r0 = t * rb;
+    const int cnt = (int)(n - r0 < rb ? n - r0 : rb);
+    int deg[128];
+    int load[16];
+    for (int g = 0; g < 16; ++g) load[g] = 0;
+    for (int i = 0; i < cnt; ++i) {
+        const int64_t d = rowptr[r0 + i + 1] - rowptr[r0 + i];
+        deg[i] = d > heavy_th ? 0 : (int)d;
+    }
+    for (int k = 0; k < cnt; ++k) {
+        int best = 0, bd = -1;
+        for (int i = 0; i < cnt; ++i)
+            if (deg[i] > bd) { bd = deg[i]; best = i; }
+        int gmin = 0;
+        for (int g = 1; g < groups; ++g)
+            if (load[g] < load[gmin]) gmin = g;
+        qrow[r0 + best] = (uint8_t)gmin;
+        load[gmin] += bd;
+        deg[best] = -1;
+    }
+    int longest = 0;
+    for (int g = 0; g < groups; ++g) longest = load[g] > longest ? load[g] : longest;
+    const int64_t len = (int64_t)longest * groups;
+    task_len[t] = (int32_t)len;
+    sort_key[t] = (uint32_t)len;
+    padded_len[t] = (len + 15) & ~15ll;
+}
+
+// key = task | queue(4 bits) | column for entries of light rows, one bit above that for entries of
+// heavy rows (they sort behind everything and keep their (row, col) order: the sort is stable).
 __global__ void k_sweep_keys(int64_t nnz, int64_t n, const int64_t* __restrict__ rowptr,
-                             const int32_t* __restrict__ colidx, const float* __restrict__ val, int64_t cpb, int32_t rb,
-                             int32_t heavy_th, unsigned jbits, uint64_t heavy_key, uint64_t* __restrict__ keys,
-                             SweepPayload* __restrict__ payload) {
+                             const int32_t* __restrict__ colidx, const float* __restrict__ val, int32_t rb,
+                             int32_t heavy_th, unsigned cbits, uint64_t heavy_key, const uint8_t* __restrict__ qrow,
+                             uint64_t* __restrict__ keys, SweepPayload* __restrict__ payload) {
     int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (k >= nnz) return;
     int64_t lo = 0, hi = n;
@@ -434,66 +470,47 @@ __global__ void k_sweep_keys(int64_t nnz, int64_t n, const int64_t* __restrict__
     }
     const int32_t col = colidx[k];
     const bool heavy = rowptr[lo + 1] - rowptr[lo] > heavy_th;
-    keys[k] = heavy ? heavy_key : (((uint64_t)(lo / rb) << jbits) | (uint64_t)(col / cpb));
+    keys[k] = heavy ? heavy_key
+                    : ((((uint64_t)(lo / rb) << 4) | (uint64_t)qrow[lo]) << cbits) | (uint64_t)(uint32_t)col;
     payload[k] = SweepPayload{col, val[k], (int32_t)lo};
 }
 
-// raw_ptr[t] = first sorted position whose key is >= t << jbits; raw_ptr[ntasks] = number of light entries
-__global__ void k_sweep_task_ptr(int64_t ntasks, int64_t nnz, unsigned jbits, uint64_t heavy_key,
-                                 const uint64_t* __restrict__ keys, int64_t* __restrict__ raw_ptr,
-                                 int32_t* __restrict__ task_id) {
-    int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (t > ntasks) return;
-    const uint64_t want = t == ntasks ? heavy_key : ((uint64_t)t << jbits);
+// seg_ptr[t*16 + g] = first sorted position of queue g of task t; seg_ptr[ntasks*16] = light entries
+__global__ void k_sweep_seg_ptr(int64_t nseg, int64_t nnz, unsigned cbits, uint64_t heavy_key,
+                                const uint64_t* __restrict__ keys, int64_t* __restrict__ seg_ptr) {
+    int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (q > nseg) return;
+    const uint64_t want = q == nseg ? heavy_key : ((uint64_t)q << cbits);
     int64_t lo = 0, hi = nnz;      // first position with keys[pos] >= want
     while (lo < hi) {
         int64_t mid = (lo + hi) >> 1;
         if (keys[mid] < want) lo = mid + 1; else hi = mid;
     }
-    raw_ptr[t] = lo;
-    if (t < ntasks) task_id[t] = (int32_t)t;
+    seg_ptr[q] = lo;
 }
 
-// lengths, and lengths rounded up to 16 (every task starts on a multiple of 16 entries)
-__global__ void k_sweep_task_len(int64_t ntasks, const int64_t* __restrict__ raw_ptr, int32_t* __restrict__ len,
-                                 uint32_t* __restrict__ sort_key, int64_t* __restrict__ padded_len) {
+__global__ void k_iota_i32(int64_t count, int32_t* __restrict__ out) {
     int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (t >= ntasks) return;
-    const int64_t l = raw_ptr[t + 1] - raw_ptr[t];
-    len[t] = (int32_t)l;
-    sort_key[t] = (uint32_t)l;
-    padded_len[t] = (l + 15) & ~15ll;
+    if (t < count) out[t] = (int32_t)t;
 }
 
-// sorted position p of task t goes to task_base[t] + (p - raw_ptr[t]); with task_base == NULL the
-// output is dense (used for the heavy rows, whose local row is not needed)
-__global__ void k_sweep_unpack(int64_t count, int64_t first, int32_t rb, unsigned jbits, const uint64_t* __restrict__ keys,
-                               const SweepPayload* __restrict__ payload, const int64_t* __restrict__ raw_ptr,
-                               const int64_t* __restrict__ task_base, int32_t* __restrict__ colidx,
-                               float* __restrict__ val, uint8_t* __restrict__ lrow) {
+// Sorted position p of queue g of task t goes to task_base[t] + rank*groups + g (rank inside the
+// queue); with task_base == NULL the output is dense (the heavy rows, whose local row is not needed).
+__global__ void k_sweep_unpack(int64_t count, int64_t first, int32_t rb, int32_t groups, unsigned cbits,
+                               const uint64_t* __restrict__ keys, const SweepPayload* __restrict__ payload,
+                               const int64_t* __restrict__ seg_ptr, const int64_t* __restrict__ task_base,
+                               int32_t* __restrict__ colidx, float* __restrict__ val, uint8_t* __restrict__ lrow) {
     int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (k >= count) return;
     const SweepPayload p = payload[first + k];
     int64_t dst = k;
     if (task_base) {
-        const int64_t t = (int64_t)(keys[k] >> jbits);
-        dst = task_base[t] + (k - raw_ptr[t]);
+        const int64_t seg = (int64_t)(keys[k] >> cbits);          // task*16 + queue
+        dst = task_base[seg >> 4] + (k - seg_ptr[seg]) * groups + (seg & 15);
     }
     colidx[dst] = p.col;
     val[dst] = p.val;
     if (lrow) lrow[dst] = (uint8_t)(p.row % rb);
-}
-
-// bit 7 of the first local-row byte of every aligned group of 16 entries: set when two of the 16 share a row
-__global__ void k_sweep_dirty(int64_t ngroups, uint8_t* __restrict__ lrow) {
-    int64_t b = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (b >= ngroups) return;
-    uint8_t r[16];
-    for (int i = 0; i < 16; ++i) r[i] = lrow[b * 16 + i] & 0x7f;
-    bool dup = false;
-    for (int i = 1; i < 16; ++i)
-        for (int j = 0; j < i; ++j) dup |= (r[i] == r[j]);
-    if (dup) lrow[b * 16] = r[0] | 0x80;
 }
 
 struct HeavyRow {
@@ -509,52 +526,34 @@ __global__ void k_heavy_len(int64_t nh, const int32_t* __restrict__ rows, const 
     if (q == nh) len[q] = 0;
 }
 
-int build_sweep(Matrix& m, int64_t nnz, int64_t cpb, int32_t rb, int32_t heavy_th, hipStream_t s) {
+int build_sweep(Matrix& m, int64_t nnz, int32_t groups, int32_t rb, int32_t heavy_th, hipStream_t s) {
     free_sweep(m.swp);
     Sweep& w = m.swp;
-    if (nnz <= 0 || cpb <= 0 || rb <= 0 || rb > 128) return fail(GCN_ERR_BADARG, "build_sweep: bad parameters");
+    if (nnz <= 0 || rb <= 0 || rb > 128 || (groups != 8 && groups != 16))
+        return fail(GCN_ERR_BADARG, "build_sweep: bad parameters");
     const int64_t n = m.nrows;
     const int64_t ntasks = (n + rb - 1) / rb;
-    const int64_t nj = (m.ncols + cpb - 1) / cpb;
-    const unsigned jbits = bits_for(nj + 1);
+    const unsigned cbits = bits_for(m.ncols);
     const unsigned tbits = bits_for(ntasks + 1);
-    if (jbits + tbits + 1 > 63) return fail(GCN_ERR_RANGE, "build_sweep: key does not fit");
-    const uint64_t heavy_key = 1ull << (jbits + tbits);
-    TempBuf k0, k1, p0, p1, tmp;
-    GCN_TRY(k0.alloc((size_t)nnz * 8));
-    GCN_TRY(k1.alloc((size_t)nnz * 8));
-    GCN_TRY(p0.alloc((size_t)nnz * sizeof(SweepPayload)));
-    GCN_TRY(p1.alloc((size_t)nnz * sizeof(SweepPayload)));
-    hipLaunchKernelGGL(k_sweep_keys, dim3(blocks_for(nnz)), dim3(TPB), 0, s, nnz, n, m.rowptr, m.colidx, m.val, cpb, rb,
-                       heavy_th, jbits, heavy_key, k0.as<uint64_t>(), p0.as<SweepPayload>());
-    GCN_LAUNCH_CHECK();
-    size_t tmp_bytes = 0;
-    const unsigned end_bit = jbits + tbits + 1;
-    GCN_HIP_TRY(rocprim::radix_sort_pairs(nullptr, tmp_bytes, k0.as<uint64_t>(), k1.as<uint64_t>(), p0.as<SweepPayload>(),
-                                          p1.as<SweepPayload>(), (size_t)nnz, 0u, end_bit, s));
-    GCN_TRY(tmp.alloc(tmp_bytes));
-    GCN_HIP_TRY(rocprim::radix_sort_pairs(tmp.p, tmp_bytes, k0.as<uint64_t>(), k1.as<uint64_t>(), p0.as<SweepPayload>(),
-                                          p1.as<SweepPayload>(), (size_t)nnz, 0u, end_bit, s));
-    GCN_HIP_TRY(hipStreamSynchronize(s));
-    k0.alloc(16);
-    p0.alloc(16);
+    if (cbits + 4 + tbits + 1 > 63) return fail(GCN_ERR_RANGE, "build_sweep: key does not fit");
+    const uint64_t heavy_key = 1ull << (cbits + 4 + tbits);
 
     GCN_TRY(device_alloc_t(&w.task_base, (size_t)ntasks));
     GCN_TRY(device_alloc_t(&w.task_len, (size_t)ntasks));
     GCN_TRY(device_alloc_t(&w.task_order, (size_t)ntasks));
-    TempBuf raw, ids, len, len_sorted, plen;
-    GCN_TRY(raw.alloc(((size_t)ntasks + 1) * 8));
+    TempBuf qrow, ids, len, len_sorted, plen, tmp;
+    GCN_TRY(qrow.alloc((size_t)n));
     GCN_TRY(ids.alloc((size_t)ntasks * 4));
     GCN_TRY(len.alloc((size_t)ntasks * 4));
     GCN_TRY(len_sorted.alloc((size_t)ntasks * 4));
     GCN_TRY(plen.alloc((size_t)ntasks * 8));
-    hipLaunchKernelGGL(k_sweep_task_ptr, dim3(blocks_for(ntasks + 1)), dim3(TPB), 0, s, ntasks, nnz, jbits, heavy_key,
-                       k1.as<uint64_t>(), raw.as<int64_t>(), ids.as<int32_t>());
+    GCN_HIP_TRY(hipMemsetAsync(qrow.p, 0, (size_t)n, s));
+    hipLaunchKernelGGL(k_sweep_assign, dim3(blocks_for(ntasks, 64)), dim3(64), 0, s, ntasks, n, m.rowptr, rb, groups, heavy_th,
+                       qrow.as<uint8_t>(), w.task_len, len.as<uint32_t>(), plen.as<int64_t>());
     GCN_LAUNCH_CHECK();
-    hipLaunchKernelGGL(k_sweep_task_len, dim3(blocks_for(ntasks)), dim3(TPB), 0, s, ntasks, raw.as<int64_t>(), w.task_len,
-                       len.as<uint32_t>(), plen.as<int64_t>());
+    hipLaunchKernelGGL(k_iota_i32, dim3(blocks_for(ntasks)), dim3(TPB), 0, s, ntasks, ids.as<int32_t>());
     GCN_LAUNCH_CHECK();
-    tmp_bytes = 0;
+    size_t tmp_bytes = 0;
     GCN_HIP_TRY(rocprim::radix_sort_pairs_desc(nullptr, tmp_bytes, len.as<uint32_t>(), len_sorted.as<uint32_t>(),
                                                ids.as<int32_t>(), w.task_order, (size_t)ntasks, 0u, 32u, s));
     GCN_TRY(tmp.alloc(tmp_bytes));
@@ -566,8 +565,33 @@ int build_sweep(Matrix& m, int64_t nnz, int64_t cpb, int32_t rb, int32_t heavy_t
     GCN_TRY(tmp.alloc(tmp_bytes));
     GCN_HIP_TRY(rocprim::exclusive_scan(tmp.p, tmp_bytes, plen.as<int64_t>(), w.task_base, (int64_t)0, (size_t)ntasks,
                                         rocprim::plus<int64_t>(), s));
+
+    TempBuf k0, k1, p0, p1, seg;
+    GCN_TRY(k0.alloc((size_t)nnz * 8));
+    GCN_TRY(k1.alloc((size_t)nnz * 8));
+    GCN_TRY(p0.alloc((size_t)nnz * sizeof(SweepPayload)));
+    GCN_TRY(p1.alloc((size_t)nnz * sizeof(SweepPayload)));
+    hipLaunchKernelGGL(k_sweep_keys, dim3(blocks_for(nnz)), dim3(TPB), 0, s, nnz, n, m.rowptr, m.colidx, m.val, rb, heavy_th,
+                       cbits, heavy_key, qrow.as<uint8_t>(), k0.as<uint64_t>(), p0.as<SweepPayload>());
+    GCN_LAUNCH_CHECK();
+    tmp_bytes = 0;
+    const unsigned end_bit = cbits + 4 + tbits + 1;
+    GCN_HIP_TRY(rocprim::radix_sort_pairs(nullptr, tmp_bytes, k0.as<uint64_t>(), k1.as<uint64_t>(), p0.as<SweepPayload>(),
+                                          p1.as<SweepPayload>(), (size_t)nnz, 0u, end_bit, s));
+    GCN_TRY(tmp.alloc(tmp_bytes));
+    GCN_HIP_TRY(rocprim::radix_sort_pairs(tmp.p, tmp_bytes, k0.as<uint64_t>(), k1.as<uint64_t>(), p0.as<SweepPayload>(),
+                                          p1.as<SweepPayload>(), (size_t)nnz, 0u, end_bit, s));
+    GCN_HIP_TRY(hipStreamSynchronize(s));
+    k0.alloc(16);
+    p0.alloc(16);
+
+    const int64_t nseg = ntasks * 16;
+    GCN_TRY(seg.alloc(((size_t)nseg + 1) * 8));
+    hipLaunchKernelGGL(k_sweep_seg_ptr, dim3(blocks_for(nseg + 1)), dim3(TPB), 0, s, nseg, nnz, cbits, heavy_key,
+                       k1.as<uint64_t>(), seg.as<int64_t>());
+    GCN_LAUNCH_CHECK();
     int64_t nnz_light = 0, last_base = 0, last_plen = 0;
-    GCN_HIP_TRY(hipMemcpyAsync(&nnz_light, raw.as<int64_t>() + ntasks, 8, hipMemcpyDeviceToHost, s));
+    GCN_HIP_TRY(hipMemcpyAsync(&nnz_light, seg.as<int64_t>() + nseg, 8, hipMemcpyDeviceToHost, s));
     GCN_HIP_TRY(hipMemcpyAsync(&last_base, w.task_base + (ntasks - 1), 8, hipMemcpyDeviceToHost, s));
     GCN_HIP_TRY(hipMemcpyAsync(&last_plen, plen.as<int64_t>() + (ntasks - 1), 8, hipMemcpyDeviceToHost, s));
     GCN_HIP_TRY(hipStreamSynchronize(s));
@@ -581,13 +605,12 @@ int build_sweep(Matrix& m, int64_t nnz, int64_t cpb, int32_t rb, int32_t heavy_t
     if (padded > 0) {
         GCN_HIP_TRY(hipMemsetAsync(w.colidx, 0, (size_t)padded * 4, s));
         GCN_HIP_TRY(hipMemsetAsync(w.val, 0, (size_t)padded * 4, s));
-        GCN_HIP_TRY(hipMemsetAsync(w.lrow, 0, (size_t)padded, s));
+        GCN_HIP_TRY(hipMemsetAsync(w.lrow, 0x80, (size_t)padded, s));       // everything is padding until written
     }
     if (nnz_light > 0) {
-        hipLaunchKernelGGL(k_sweep_unpack, dim3(blocks_for(nnz_light)), dim3(TPB), 0, s, nnz_light, (int64_t)0, rb, jbits,
-                           k1.as<uint64_t>(), p1.as<SweepPayload>(), raw.as<int64_t>(), w.task_base, w.colidx, w.val, w.lrow);
-        GCN_LAUNCH_CHECK();
-        hipLaunchKernelGGL(k_sweep_dirty, dim3(blocks_for(padded / 16)), dim3(TPB), 0, s, padded / 16, w.lrow);
+        hipLaunchKernelGGL(k_sweep_unpack, dim3(blocks_for(nnz_light)), dim3(TPB), 0, s, nnz_light, (int64_t)0, rb, groups,
+                           cbits, k1.as<uint64_t>(), p1.as<SweepPayload>(), seg.as<int64_t>(), w.task_base, w.colidx, w.val,
+                           w.lrow);
         GCN_LAUNCH_CHECK();
     }
     if (nnz_heavy > 0) {
@@ -596,9 +619,9 @@ int build_sweep(Matrix& m, int64_t nnz, int64_t cpb, int32_t rb, int32_t heavy_t
         w.heavy = h;
         GCN_TRY(device_alloc_t(&h->colidx, (size_t)nnz_heavy));
         GCN_TRY(device_alloc_t(&h->val, (size_t)nnz_heavy));
-        hipLaunchKernelGGL(k_sweep_unpack, dim3(blocks_for(nnz_heavy)), dim3(TPB), 0, s, nnz_heavy, nnz_light, rb, jbits,
-                           k1.as<uint64_t>(), p1.as<SweepPayload>(), (const int64_t*)nullptr, (const int64_t*)nullptr,
-                           h->colidx, h->val, (uint8_t*)nullptr);
+        hipLaunchKernelGGL(k_sweep_unpack, dim3(blocks_for(nnz_heavy)), dim3(TPB), 0, s, nnz_heavy, nnz_light, rb, groups,
+                           cbits, k1.as<uint64_t>(), p1.as<SweepPayload>(), (const int64_t*)nullptr,
+                           (const int64_t*)nullptr, h->colidx, h->val, (uint8_t*)nullptr);
         GCN_LAUNCH_CHECK();
         // the heavy rows in ascending order, and their offsets into the heavy entry arrays
         TempBuf cnt, hl;
@@ -625,6 +648,11 @@ int build_sweep(Matrix& m, int64_t nnz, int64_t cpb, int32_t rb, int32_t heavy_t
         GCN_TRY(tmp.alloc(tmp_bytes));
         GCN_HIP_TRY(rocprim::exclusive_scan(tmp.p, tmp_bytes, hl.as<int64_t>(), h->ne_rowptr, (int64_t)0, nh + 1,
                                             rocprim::plus<int64_t>(), s));
+        // as a compact matrix of its own: nh rows, rowptr = the offsets just computed
+        h->nrows = (int64_t)nh;
+        h->ncols = m.ncols;
+        GCN_TRY(device_alloc_t(&h->rowptr, nh + 1));
+        GCN_HIP_TRY(hipMemcpyAsync(h->rowptr, h->ne_rowptr, (nh + 1) * sizeof(int64_t), hipMemcpyDeviceToDevice, s));
         h->nsub = (nnz_heavy + SUB - 1) / SUB;
         h->nchunks = (nnz_heavy + CHUNK - 1) / CHUNK;
         const size_t padded = (size_t)h->nsub + SUBS_PER_CHUNK;
@@ -639,7 +667,7 @@ int build_sweep(Matrix& m, int64_t nnz, int64_t cpb, int32_t rb, int32_t heavy_t
         GCN_HIP_TRY(hipStreamSynchronize(s));
     }
     GCN_HIP_TRY(hipStreamSynchronize(s));
-    w.cols_per_block = cpb;
+    w.groups = groups;
     w.rb = rb;
     w.heavy_threshold = heavy_th;
     w.ntasks = ntasks;

@@ -331,7 +331,8 @@ static inline bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; 
 // Adds the partial rows of the column-blocked product in ascending block order, then the epilogue.
 template <int VEC, int EPI>
 __global__ __launch_bounds__(256) void k_block_reduce(int64_t n, int32_t f, int32_t lanes, const int64_t* __restrict__ rq_ptr,
-                                                      const int32_t* __restrict__ rq_idx, const float* __restrict__ P,
+                                                      const int32_t* __restrict__ rq_idx, const int32_t* __restrict__ row_map,
+                                                      const float* __restrict__ P,
                                                       float* __restrict__ Z, int64_t ldz, const float* __restrict__ Zprev,
                                                       int64_t ldzprev) {
     const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -347,19 +348,20 @@ __global__ __launch_bounds__(256) void k_block_reduce(int64_t n, int32_t f, int3
 #pragma unroll
         for (int v = 0; v < VEC; ++v) acc[v] += part[v];
     }
-    epilogue_store<VEC, EPI>(Z + i * ldz + col0, EPI == GCN_EPI_MASK ? Zprev + i * ldzprev + col0 : nullptr, acc);
+    const int64_t row = row_map ? row_map[i] : i;    // a row-subset matrix writes only its own rows
+    epilogue_store<VEC, EPI>(Z + row * ldz + col0, EPI == GCN_EPI_MASK ? Zprev + row * ldzprev + col0 : nullptr, acc);
 }
 
 template <int VEC>
-static int launch_block_reduce(int64_t n, int32_t f, const Blocked& b, const float* P, float* Z, int64_t ldz, int epilogue,
-                               const float* Zprev, int64_t ldzprev, hipStream_t s) {
+static int launch_block_reduce(int64_t n, int32_t f, const Blocked& b, const int32_t* row_map, const float* P, float* Z,
+                               int64_t ldz, int epilogue, const float* Zprev, int64_t ldzprev, hipStream_t s) {
     const int lanes = f / VEC;
     const int64_t threads = n * lanes;
     const dim3 grid((unsigned)((threads + 255) / 256));
     switch (epilogue) {
-        case GCN_EPI_NONE: hipLaunchKernelGGL((k_block_reduce<VEC, GCN_EPI_NONE>), grid, dim3(256), 0, s, n, f, lanes, b.rq_ptr, b.rq_idx, P, Z, ldz, Zprev, ldzprev); break;
-        case GCN_EPI_RELU: hipLaunchKernelGGL((k_block_reduce<VEC, GCN_EPI_RELU>), grid, dim3(256), 0, s, n, f, lanes, b.rq_ptr, b.rq_idx, P, Z, ldz, Zprev, ldzprev); break;
-        default: hipLaunchKernelGGL((k_block_reduce<VEC, GCN_EPI_MASK>), grid, dim3(256), 0, s, n, f, lanes, b.rq_ptr, b.rq_idx, P, Z, ldz, Zprev, ldzprev); break;
+        case GCN_EPI_NONE: hipLaunchKernelGGL((k_block_reduce<VEC, GCN_EPI_NONE>), grid, dim3(256), 0, s, n, f, lanes, b.rq_ptr, b.rq_idx, row_map, P, Z, ldz, Zprev, ldzprev); break;
+        case GCN_EPI_RELU: hipLaunchKernelGGL((k_block_reduce<VEC, GCN_EPI_RELU>), grid, dim3(256), 0, s, n, f, lanes, b.rq_ptr, b.rq_idx, row_map, P, Z, ldz, Zprev, ldzprev); break;
+        default: hipLaunchKernelGGL((k_block_reduce<VEC, GCN_EPI_MASK>), grid, dim3(256), 0, s, n, f, lanes, b.rq_ptr, b.rq_idx, row_map, P, Z, ldz, Zprev, ldzprev); break;
     }
     GCN_LAUNCH_CHECK();
     return GCN_OK;
@@ -367,12 +369,14 @@ static int launch_block_reduce(int64_t n, int32_t f, const Blocked& b, const flo
 
 // ---- column sweep ---------------------------------------------------------------------------------------
 // One wavefront owns a task: `rb` consecutive rows whose results live in LDS (rb x W floats, W = 16
-// or 32) for the whole launch.  Its entries come sorted by column block, so it walks X left to
-// right; all wavefronts of a launch start together and advance at the same pace, which keeps the
-// band of X being gathered inside L2 even when X is far larger than every cache.  Each lane group
-// takes every G-th entry, multiplies the gathered row by the value and adds it to the task's row
-// in LDS.  Only this wavefront touches these accumulators, so plain LDS reads and writes in program
-// order suffice once two groups of one step are kept off the same row (see the claim loop).
+// or 32) for the whole launch.  Its entries come in ascending column order, so it walks X left to
+// right; all wavefronts of a launch start together and have about the same length, so at any moment
+// the whole GPU gathers from a narrow band of X, which therefore stays in L2 even when X is far
+// larger than every cache.  The stored order interleaves G balanced queues of rows (see Sweep), so
+// the G lane groups of one step always hold different rows: each multiplies its gathered row by the
+// value and adds it to the task's row in LDS with a plain read-modify-write.  Only this wavefront
+// touches these accumulators and its LDS operations complete in program order, so the sum order is
+// fixed and the result reproducible.
 struct SweepArgs {
     const int32_t* colidx;
     const float* val;
@@ -389,14 +393,12 @@ struct SweepArgs {
 
 template <int LPR, int EPI>
 __global__ __launch_bounds__(64) void k_spmm_sweep(SweepArgs a, int64_t first_task) {
-    constexpr int G = 64 / LPR;                  // entries per step (16 or 8)
+    constexpr int G = 64 / LPR;                  // entries per step (16 or 8) = queues of the task
     constexpr int W = LPR * 4;                   // panel width in floats
     constexpr int SPT = 64 / G;                  // steps per 64 entries
     constexpr int U = 2;                         // 64-entry loads per trip
     constexpr int STEPS = SPT * U;
-    extern __shared__ float smem[];              // acc[rb][W], then owner[rb]
-    float* acc = smem;
-    volatile int* owner = reinterpret_cast<volatile int*>(smem + a.rb * W);
+    extern __shared__ float acc[];               // [rb][W]
     const int lane = threadIdx.x;
     const int g = lane / LPR, li = lane % LPR;
     const int col0 = li * 4;
@@ -407,14 +409,14 @@ __global__ __launch_bounds__(64) void k_spmm_sweep(SweepArgs a, int64_t first_ta
     __builtin_amdgcn_wave_barrier();
 
     const int64_t e0 = a.task_base[task];        // multiple of 16
-    const int len = a.task_len[task];
+    const int len = a.task_len[task];            // multiple of G; padding entries carry bit 7 in lrow
     const float* xbase = a.X + col0;
     // the entries of the next trip are fetched while the current one is gathered and added
     int32_t c[U]; float v[U]; int r[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         const int k = 64 * u + lane;
-        c[u] = 0; v[u] = 0.f; r[u] = 0;
+        c[u] = 0; v[u] = 0.f; r[u] = 0x80;
         if (k < len) {
             c[u] = __builtin_nontemporal_load(a.colidx + e0 + k);
             v[u] = __builtin_nontemporal_load(a.val + e0 + k);
@@ -426,7 +428,7 @@ __global__ __launch_bounds__(64) void k_spmm_sweep(SweepArgs a, int64_t first_ta
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int k = base + 64 * U + 64 * u + lane;
-            nc[u] = 0; nv[u] = 0.f; nr[u] = 0;
+            nc[u] = 0; nv[u] = 0.f; nr[u] = 0x80;
             if (k < len) {
                 nc[u] = __builtin_nontemporal_load(a.colidx + e0 + k);
                 nv[u] = __builtin_nontemporal_load(a.val + e0 + k);
@@ -445,7 +447,7 @@ __global__ __launch_bounds__(64) void k_spmm_sweep(SweepArgs a, int64_t first_ta
                 const int32_t cs = __shfl(c[u], src, 64);
                 vs[q] = __shfl(v[u], src, 64);
                 rs[q] = __shfl(r[u], src, 64);
-                if (base + 64 * u + src < len && col_ok) {
+                if (!(rs[q] & 0x80) && col_ok) {
                     const float4 w4 = *reinterpret_cast<const float4*>(xbase + (int64_t)cs * a.ldx);
                     x[q][0] = w4.x; x[q][1] = w4.y; x[q][2] = w4.z; x[q][3] = w4.w;
                 } else {
@@ -453,48 +455,17 @@ __global__ __launch_bounds__(64) void k_spmm_sweep(SweepArgs a, int64_t first_ta
                 }
             }
 #pragma unroll
-        for (int u = 0; u < U; ++u)
-#pragma unroll
-            for (int t = 0; t < SPT; ++t) {
-                const int q = u * SPT + t;
-                bool pending = (base + 64 * u + t * G + g < len) && col_ok;
-                // bit 7 of the first entry of the aligned 16-entry group says whether two of its entries share
-                // a row; it is the same for the whole step (G = 8 looks at its half-group's leader, which
-                // carries the flag only for the first half, so both halves read the group leader)
-                const int flag = __shfl(r[u], (t * G) & ~15, 64) & 0x80;
-                float4* dst = reinterpret_cast<float4*>(acc + (rs[q] & 0x7f) * W + col0);
-                if (!flag) {                     // all rows of the step differ: plain read-modify-write
-                    if (pending) {
-                        float4 cur = *dst;
-                        cur.x = fmaf(vs[q], x[q][0], cur.x);
-                        cur.y = fmaf(vs[q], x[q][1], cur.y);
-                        cur.z = fmaf(vs[q], x[q][2], cur.z);
-                        cur.w = fmaf(vs[q], x[q][3], cur.w);
-                        *dst = cur;
-                    }
-                } else {
-                    // Some row appears twice.  Each group claims its row by writing its number; the group
-                    // whose number is read back adds (it is alone on that row); the others try again.
-                    while (true) {
-                        if (pending) owner[rs[q] & 0x7f] = g;
-                        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
-                        __builtin_amdgcn_wave_barrier();
-                        if (pending && owner[rs[q] & 0x7f] == g) {
-                            float4 cur = *dst;
-                            cur.x = fmaf(vs[q], x[q][0], cur.x);
-                            cur.y = fmaf(vs[q], x[q][1], cur.y);
-                            cur.z = fmaf(vs[q], x[q][2], cur.z);
-                            cur.w = fmaf(vs[q], x[q][3], cur.w);
-                            *dst = cur;
-                            pending = false;
-                        }
-                        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
-                        __builtin_amdgcn_wave_barrier();
-                        if (!__any(pending)) break;
-                    }
-                }
-                __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+        for (int q = 0; q < STEPS; ++q) {
+            if (!(rs[q] & 0x80) && col_ok) {     // the groups of a step hold rows of different queues
+                float4* dst = reinterpret_cast<float4*>(acc + rs[q] * W + col0);
+                float4 cur = *dst;
+                cur.x = fmaf(vs[q], x[q][0], cur.x);
+                cur.y = fmaf(vs[q], x[q][1], cur.y);
+                cur.z = fmaf(vs[q], x[q][2], cur.z);
+                cur.w = fmaf(vs[q], x[q][3], cur.w);
+                *dst = cur;
             }
+        }
 #pragma unroll
         for (int u = 0; u < U; ++u) { c[u] = nc[u]; v[u] = nv[u]; r[u] = nr[u]; }
     }
@@ -517,7 +488,7 @@ static constexpr int SWEEP_CUS = 256;
 template <int LPR>
 static int launch_sweep(const SweepArgs& args, int64_t ntasks, int epilogue, hipStream_t s) {
     constexpr int W = LPR * 4;
-    const size_t lds = (size_t)args.rb * (W + 1) * sizeof(float);
+    const size_t lds = (size_t)args.rb * W * sizeof(float);
     const unsigned ytiles = (unsigned)((args.f + W - 1) / W);
     const int64_t gen = (int64_t)SWEEP_CUS * config().sweep_waves;    // tasks that are resident at once
     timing_begin(s);
@@ -579,16 +550,50 @@ static int grow(float** buf, size_t* have, size_t need) {
 
 // How many column blocks to cut X into so that one block of the gathered panel stays in one L2
 // (4 MB per XCD).  Blocking costs one partial row per non-empty (block,row) pair, so it only pays
-// when rows are long compared with the number of blocks; otherwise 1 (no blocking).
-static int64_t choose_blocks(int64_t n, int64_t ncols, int64_t nnz, int32_t f) {
+// when rows are long compared with the number of blocks (`per_block` entries per partial row at
+// least); otherwise 1 (no blocking).
+static int64_t choose_blocks(int64_t nrows, int64_t ncols, int64_t nnz, int32_t f, int64_t per_block) {
     const int forced = config().spmm_blocks;
     if (forced >= 1) return forced;
     const int64_t panel = f < 32 ? f : 32;
     const int64_t xbytes = ncols * panel * 4;
     if (xbytes <= (7ll << 19)) return 1;                  // 3.5 MB: already L2-resident
     const int64_t want = (xbytes + (2ll << 20) - 1) / (2ll << 20);
-    const int64_t cap = (nnz / n) / 24;
+    const int64_t cap = (nnz / (nrows > 0 ? nrows : 1)) / per_block;
     return want <= cap ? want : 1;
+}
+
+// The nonzero-split product of one stored matrix -- the whole matrix, or the heavy rows of a sweep
+// copy (then row_map gives the row each of its rows stands for) -- with or without column blocks.
+static int run_matrix(gcn_csr* a, Matrix& mm, const int32_t* row_map, int64_t nnz, int64_t nblocks, int32_t f,
+                      const float* X, int64_t ldx, float* Z, int64_t ldz, int epilogue, const float* Zprev,
+                      int64_t ldzprev, hipStream_t s) {
+    if ((mm.nchunks + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK >= (1ll << 31))
+        return fail(GCN_ERR_RANGE, "gcn_spmm: too many chunks for one launch");
+    GCN_TRY(grow(&a->carry, &a->carry_bytes, (size_t)mm.nchunks * (size_t)f * sizeof(float)));
+    SplitArgs args;
+    args.nnz = nnz; args.nsub = mm.nsub; args.nchunks = mm.nchunks; args.f = f;
+    args.X = X; args.ldx = ldx; args.carry = a->carry;
+    if (nblocks >= 2) {
+        int64_t cpb = (mm.ncols + nblocks - 1) / nblocks;
+        cpb = (cpb + 1023) & ~1023ll;
+        if (mm.blk.cols_per_block != cpb) GCN_TRY(build_blocked(mm, nnz, cpb, s));
+        const Blocked& b = mm.blk;
+        GCN_TRY(grow(&a->partial, &a->partial_bytes, (size_t)b.nrows * (size_t)f * sizeof(float)));
+        args.colidx = b.colidx; args.val = b.val; args.flags = b.flags; args.sub_row = b.sub_row;
+        args.ne_rows = nullptr; args.rp = b.rp;
+        args.Z = a->partial; args.ldz = f; args.Zprev = nullptr; args.ldzprev = 0;
+        GCN_TRY(run_split(args, GCN_EPI_NONE, s));
+        const bool vec4 = (f % 4 == 0) && (ldz % 4 == 0) && aligned16(Z) &&
+                          (epilogue != GCN_EPI_MASK || ((ldzprev % 4 == 0) && aligned16(Zprev)));
+        if (vec4) return launch_block_reduce<4>(mm.nrows, f, b, row_map, a->partial, Z, ldz, epilogue, Zprev, ldzprev, s);
+        return launch_block_reduce<1>(mm.nrows, f, b, row_map, a->partial, Z, ldz, epilogue, Zprev, ldzprev, s);
+    }
+    args.colidx = mm.colidx; args.val = mm.val; args.flags = mm.flags; args.sub_row = mm.sub_row;
+    args.ne_rows = row_map ? row_map : mm.ne_rows;
+    args.rp = mm.ne_rowptr ? mm.ne_rowptr : mm.rowptr;
+    args.Z = Z; args.ldz = ldz; args.Zprev = Zprev; args.ldzprev = ldzprev;
+    return run_split(args, epilogue, s);
 }
 
 int spmm_launch(gcn_csr* a, Matrix& m, int32_t f, const float* X, int64_t ldx, float* Z, int64_t ldz,
@@ -603,36 +608,34 @@ int spmm_launch(gcn_csr* a, Matrix& m, int32_t f, const float* X, int64_t ldx, f
     int algo = config().spmm_algo;
     const bool vec4_all = (f % 4 == 0) && (ldx % 4 == 0) && (ldz % 4 == 0) && aligned16(X) && aligned16(Z) &&
                           (epilogue != GCN_EPI_MASK || ((ldzprev % 4 == 0) && aligned16(Zprev)));
-    if (algo == 0) algo = 2;   // the column sweep (3) is only taken on request: it is not yet faster
+    const int64_t nblocks = choose_blocks(n, ncols, nnz, f, 24);
+    if (algo == 0) {
+        // Column sweep when X is far beyond the caches, rows are long enough to give every task a
+        // real walk over the columns, and too short for partial-row blocking; else nonzero-split.
+        const int64_t panel = f < 32 ? f : 32;
+        const bool huge = ncols * panel * 4 > (64ll << 20);
+        algo = (huge && vec4_all && nblocks < 2 && nnz / n >= 64) ? 3 : 2;
+    }
     if (algo == 3 && !vec4_all) algo = 2;
     if (algo == 3) {
         const int LPRs = f <= 16 ? 4 : 8;
         const int W = LPRs * 4;
         const int32_t rb = 2048 / W;                       // 8 KB of accumulators per wavefront
-        // measured: the finer the column blocks the better the wavefronts stay together (the gain
-        // levels off near a thousand blocks), so by default a block is 256 columns
-        int64_t nj = config().spmm_blocks >= 2 ? config().spmm_blocks : (ncols + 255) / 256;
-        if (nj < 1) nj = 1;
-        const int64_t cpb = (ncols + nj - 1) / nj;
         const int32_t th = config().sweep_heavy;
-        if (m.swp.cols_per_block != cpb || m.swp.rb != rb || m.swp.heavy_threshold != th)
-            GCN_TRY(build_sweep(m, nnz, cpb, rb, th, s));
+        if (m.swp.groups != 64 / LPRs || m.swp.rb != rb || m.swp.heavy_threshold != th)
+            GCN_TRY(build_sweep(m, nnz, 64 / LPRs, rb, th, s));
         const Sweep& w = m.swp;
         SweepArgs sa;
         sa.colidx = w.colidx; sa.val = w.val; sa.lrow = w.lrow; sa.task_base = w.task_base; sa.task_len = w.task_len; sa.task_order = w.task_order;
         sa.n = n; sa.f = f; sa.rb = rb; sa.X = X; sa.ldx = ldx; sa.Z = Z; sa.ldz = ldz; sa.Zprev = Zprev; sa.ldzprev = ldzprev;
         if (LPRs == 4) GCN_TRY(launch_sweep<4>(sa, w.ntasks, epilogue, s));
         else GCN_TRY(launch_sweep<8>(sa, w.ntasks, epilogue, s));
-        if (w.heavy) {                                       // long rows: nonzero-split kernel over the row subset
-            const Matrix& h = *w.heavy;
-            GCN_TRY(grow(&a->carry, &a->carry_bytes, (size_t)h.nchunks * (size_t)f * sizeof(float)));
-            SplitArgs args;
-            args.nnz = w.nnz_heavy; args.nsub = h.nsub; args.nchunks = h.nchunks; args.f = f;
-            args.X = X; args.ldx = ldx; args.carry = a->carry;
-            args.colidx = h.colidx; args.val = h.val; args.flags = h.flags; args.sub_row = h.sub_row;
-            args.ne_rows = h.ne_rows; args.rp = h.ne_rowptr;
-            args.Z = Z; args.ldz = ldz; args.Zprev = Zprev; args.ldzprev = ldzprev;
-            GCN_TRY(run_split(args, epilogue, s));
+        if (w.heavy) {
+            // long rows: nonzero-split kernel over the row subset; their rows are long enough for the
+            // column-blocked form to pay even with many blocks
+            Matrix& h = *w.heavy;
+            const int64_t hb = choose_blocks(h.nrows, ncols, w.nnz_heavy, f, 8);
+            GCN_TRY(run_matrix(a, h, h.ne_rows, w.nnz_heavy, hb, f, X, ldx, Z, ldz, epilogue, Zprev, ldzprev, s));
         }
         return GCN_OK;
     }
@@ -650,40 +653,12 @@ int spmm_launch(gcn_csr* a, Matrix& m, int32_t f, const float* X, int64_t ldx, f
         GCN_LAUNCH_CHECK();
         return GCN_OK;
     }
-    if ((m.nchunks + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK >= (1ll << 31))
-        return fail(GCN_ERR_RANGE, "gcn_spmm: too many chunks for one launch");
-    GCN_TRY(grow(&a->carry, &a->carry_bytes, (size_t)m.nchunks * (size_t)f * sizeof(float)));
-
-    SplitArgs args;
-    args.nnz = nnz; args.nsub = m.nsub; args.nchunks = m.nchunks; args.f = f;
-    args.X = X; args.ldx = ldx; args.carry = a->carry;
-
-    const int64_t nblocks = choose_blocks(n, ncols, nnz, f);
-    if (nblocks >= 2) {
-        int64_t cpb = (ncols + nblocks - 1) / nblocks;
-        cpb = (cpb + 1023) & ~1023ll;
-        if (m.blk.cols_per_block != cpb) GCN_TRY(build_blocked(m, nnz, cpb, s));
-        const Blocked& b = m.blk;
-        GCN_TRY(grow(&a->partial, &a->partial_bytes, (size_t)b.nrows * (size_t)f * sizeof(float)));
-        args.colidx = b.colidx; args.val = b.val; args.flags = b.flags; args.sub_row = b.sub_row;
-        args.ne_rows = nullptr; args.rp = b.rp;
-        args.Z = a->partial; args.ldz = f; args.Zprev = nullptr; args.ldzprev = 0;
-        GCN_TRY(run_split(args, GCN_EPI_NONE, s));
-        const bool vec4 = (f % 4 == 0) && (ldz % 4 == 0) && aligned16(Z) &&
-                          (epilogue != GCN_EPI_MASK || ((ldzprev % 4 == 0) && aligned16(Zprev)));
-        if (vec4) return launch_block_reduce<4>(n, f, b, a->partial, Z, ldz, epilogue, Zprev, ldzprev, s);
-        return launch_block_reduce<1>(n, f, b, a->partial, Z, ldz, epilogue, Zprev, ldzprev, s);
-    }
-
-    if (m.n_ne < n) {
+    if (nblocks < 2 && m.n_ne < n) {
         const int64_t work = n * f;
         hipLaunchKernelGGL(k_zero_empty_rows, dim3((unsigned)((work + 255) / 256)), dim3(256), 0, s, n, m.rowptr, f, Z, ldz);
         GCN_LAUNCH_CHECK();
     }
-    args.colidx = m.colidx; args.val = m.val; args.flags = m.flags; args.sub_row = m.sub_row;
-    args.ne_rows = m.ne_rows; args.rp = m.ne_rowptr ? m.ne_rowptr : m.rowptr;
-    args.Z = Z; args.ldz = ldz; args.Zprev = Zprev; args.ldzprev = ldzprev;
-    return run_split(args, epilogue, s);
+    return run_matrix(a, m, nullptr, nnz, nblocks, f, X, ldx, Z, ldz, epilogue, Zprev, ldzprev, s);
 }
 
 }  // namespace gcn

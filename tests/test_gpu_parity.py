@@ -417,7 +417,7 @@ def test_spmm_column_sweep_forced(name, heavy):
             np.testing.assert_array_equal(first.view(np.uint32), run_spmm(a, X, algo=3).view(np.uint32))
     finally:
         g.gcn_config(g.CFG_SPMM_BLOCKS, 0)
-        g.gcn_config(g.CFG_SWEEP_HEAVY, 4096)
+        g.gcn_config(g.CFG_SWEEP_HEAVY, 1024)
     a.close()
 
 
@@ -432,7 +432,7 @@ def test_spmm_column_sweep_directed_with_empty_rows():
         assert_close(run_spmm(a, X, trans=0, algo=3), oracle.spmm(ref, X), "A")
         assert_close(run_spmm(a, X, trans=1, algo=3), oracle.spmm(ref_t, X), "A^T")
     finally:
-        g.gcn_config(g.CFG_SWEEP_HEAVY, 4096)
+        g.gcn_config(g.CFG_SWEEP_HEAVY, 1024)
     a.close()
 
 
