@@ -61,7 +61,7 @@ extern "C" {
 #define GCN_CFG_TIMING 2    /* 1 = bracket the dominant kernels with HIP events (see gcn_timing_read) */
 #define GCN_CFG_SPMM_BLOCKS 3 /* column blocks of the SpMM: 0 = automatic, 1 = never block, k >= 2 = k blocks */
 #define GCN_CFG_SWEEP_HEAVY 4 /* rows longer than this bypass the column sweep (default 1024; >= 1) */
-#define GCN_CFG_SWEEP_WAVES 5 /* column sweep: tasks per compute unit in one launch (default 10; 1..18) */
+#define GCN_CFG_SWEEP_WAVES 5 /* column sweep: tasks per compute unit in one launch (default 8: 8 x 16 KB of LDS accumulators per compute unit; 1..18) */
 
 typedef struct gcn_csr gcn_csr; /* opaque: A (and A^T) in compressed rows, degrees, schedules */
 

@@ -76,9 +76,9 @@ struct Sweep {
     int32_t heavy_threshold = 0;
     int64_t ntasks = 0, nnz_light = 0, nnz_heavy = 0, n_heavy = 0;
     int64_t padded = 0;           // entries stored, padding included
-    int32_t* colidx = nullptr;    // [padded]
+    int32_t* colidx = nullptr;    // [padded] column, or -1 for a padding entry
     float* val = nullptr;         // [padded]
-    uint8_t* lrow = nullptr;      // [padded] bits 0-6: row inside the task; bit 7: padding, skip
+    uint8_t* lrow = nullptr;      // [padded] row inside the task
     int64_t* task_base = nullptr; // [ntasks] first stored entry of the task (multiple of 16)
     int32_t* task_len = nullptr;  // [ntasks] stored entries of the task (multiple of groups)
     int32_t* task_order = nullptr;// [ntasks] task ids, longest first
@@ -132,7 +132,7 @@ struct Config {
     int spmm_algo = 0;
     int spmm_blocks = 0;
     int sweep_heavy = 1024;
-    int sweep_waves = 10;
+    int sweep_waves = 8;
     int timing = 0;
 };
 Config& config();

@@ -429,7 +429,7 @@ __global__ void k_sweep_assign(int64_t ntasks, int64_t n, const int64_t* __restr
     if (t >= ntasks) return;
     const int64_t r0 = t * rb;
     const int cnt = (int)(n - r0 < rb ? n - r0 : rb);
-    int deg[128];
+    int deg[256];
     int load[16];
     for (int g = 0; g < 16; ++g) load[g] = 0;
     for (int i = 0; i < cnt; ++i) {
@@ -529,7 +529,7 @@ __global__ void k_heavy_len(int64_t nh, const int32_t* __restrict__ rows, const 
 int build_sweep(Matrix& m, int64_t nnz, int32_t groups, int32_t rb, int32_t heavy_th, hipStream_t s) {
     free_sweep(m.swp);
     Sweep& w = m.swp;
-    if (nnz <= 0 || rb <= 0 || rb > 128 || (groups != 8 && groups != 16))
+    if (nnz <= 0 || rb <= 0 || rb > 256 || (groups != 8 && groups != 16))
         return fail(GCN_ERR_BADARG, "build_sweep: bad parameters");
     const int64_t n = m.nrows;
     const int64_t ntasks = (n + rb - 1) / rb;
@@ -603,9 +603,9 @@ int build_sweep(Matrix& m, int64_t nnz, int32_t groups, int32_t rb, int32_t heav
     GCN_TRY(device_alloc_t(&w.val, (size_t)padded));
     GCN_TRY(device_alloc_t(&w.lrow, (size_t)padded));
     if (padded > 0) {
-        GCN_HIP_TRY(hipMemsetAsync(w.colidx, 0, (size_t)padded * 4, s));
+        GCN_HIP_TRY(hipMemsetAsync(w.colidx, 0xff, (size_t)padded * 4, s));  // column -1: padding until written
         GCN_HIP_TRY(hipMemsetAsync(w.val, 0, (size_t)padded * 4, s));
-        GCN_HIP_TRY(hipMemsetAsync(w.lrow, 0x80, (size_t)padded, s));       // everything is padding until written
+        GCN_HIP_TRY(hipMemsetAsync(w.lrow, 0, (size_t)padded, s));
     }
     if (nnz_light > 0) {
         hipLaunchKernelGGL(k_sweep_unpack, dim3(blocks_for(nnz_light)), dim3(TPB), 0, s, nnz_light, (int64_t)0, rb, groups,

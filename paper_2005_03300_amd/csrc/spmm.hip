@@ -409,14 +409,14 @@ __global__ __launch_bounds__(64) void k_spmm_sweep(SweepArgs a, int64_t first_ta
     __builtin_amdgcn_wave_barrier();
 
     const int64_t e0 = a.task_base[task];        // multiple of 16
-    const int len = a.task_len[task];            // multiple of G; padding entries carry bit 7 in lrow
+    const int len = a.task_len[task];            // multiple of G; padding entries have column -1
     const float* xbase = a.X + col0;
     // the entries of the next trip are fetched while the current one is gathered and added
     int32_t c[U]; float v[U]; int r[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         const int k = 64 * u + lane;
-        c[u] = 0; v[u] = 0.f; r[u] = 0x80;
+        c[u] = -1; v[u] = 0.f; r[u] = 0;
         if (k < len) {
             c[u] = __builtin_nontemporal_load(a.colidx + e0 + k);
             v[u] = __builtin_nontemporal_load(a.val + e0 + k);
@@ -428,7 +428,7 @@ __global__ __launch_bounds__(64) void k_spmm_sweep(SweepArgs a, int64_t first_ta
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int k = base + 64 * U + 64 * u + lane;
-            nc[u] = 0; nv[u] = 0.f; nr[u] = 0x80;
+            nc[u] = -1; nv[u] = 0.f; nr[u] = 0;
             if (k < len) {
                 nc[u] = __builtin_nontemporal_load(a.colidx + e0 + k);
                 nv[u] = __builtin_nontemporal_load(a.val + e0 + k);
@@ -437,7 +437,7 @@ __global__ __launch_bounds__(64) void k_spmm_sweep(SweepArgs a, int64_t first_ta
         }
         float x[STEPS][4];
         float vs[STEPS];
-        int rs[STEPS];
+        int rs[STEPS];                           // row inside the task, or -1 for a padding entry
 #pragma unroll
         for (int u = 0; u < U; ++u)
 #pragma unroll
@@ -446,8 +446,9 @@ __global__ __launch_bounds__(64) void k_spmm_sweep(SweepArgs a, int64_t first_ta
                 const int src = t * G + g;
                 const int32_t cs = __shfl(c[u], src, 64);
                 vs[q] = __shfl(v[u], src, 64);
-                rs[q] = __shfl(r[u], src, 64);
-                if (!(rs[q] & 0x80) && col_ok) {
+                const int rr = __shfl(r[u], src, 64);
+                rs[q] = cs >= 0 ? rr : -1;
+                if (rs[q] >= 0 && col_ok) {
                     const float4 w4 = *reinterpret_cast<const float4*>(xbase + (int64_t)cs * a.ldx);
                     x[q][0] = w4.x; x[q][1] = w4.y; x[q][2] = w4.z; x[q][3] = w4.w;
                 } else {
@@ -456,7 +457,7 @@ __global__ __launch_bounds__(64) void k_spmm_sweep(SweepArgs a, int64_t first_ta
             }
 #pragma unroll
         for (int q = 0; q < STEPS; ++q) {
-            if (!(rs[q] & 0x80) && col_ok) {     // the groups of a step hold rows of different queues
+            if (rs[q] >= 0 && col_ok) {          // the groups of a step hold rows of different queues
                 float4* dst = reinterpret_cast<float4*>(acc + rs[q] * W + col0);
                 float4 cur = *dst;
                 cur.x = fmaf(vs[q], x[q][0], cur.x);
@@ -614,13 +615,17 @@ int spmm_launch(gcn_csr* a, Matrix& m, int32_t f, const float* X, int64_t ldx, f
         // real walk over the columns, and too short for partial-row blocking; else nonzero-split.
         const int64_t panel = f < 32 ? f : 32;
         const bool huge = ncols * panel * 4 > (64ll << 20);
-        algo = (huge && vec4_all && nblocks < 2 && nnz / n >= 64) ? 3 : 2;
+        // one step of a task spans about groups^2 * ncols * rowbytes / (rows_per_task * mean_degree) bytes
+        // of X (64 * ncols / degree at width 16); the sweep pays while that stays within an L2
+        const int64_t deg = nnz / n;
+        const bool narrow_steps = deg >= 64 && 64 * ncols / deg <= (6ll << 20);
+        algo = (huge && vec4_all && nblocks < 2 && narrow_steps) ? 3 : 2;
     }
     if (algo == 3 && !vec4_all) algo = 2;
     if (algo == 3) {
         const int LPRs = f <= 16 ? 4 : 8;
         const int W = LPRs * 4;
-        const int32_t rb = 2048 / W;                       // 8 KB of accumulators per wavefront
+        const int32_t rb = 4096 / W;                       // 16 KB of accumulators per wavefront
         const int32_t th = config().sweep_heavy;
         if (m.swp.groups != 64 / LPRs || m.swp.rb != rb || m.swp.heavy_threshold != th)
             GCN_TRY(build_sweep(m, nnz, 64 / LPRs, rb, th, s));
