@@ -33,7 +33,16 @@ HBM_PEAK_GBPS = 8000.0
 # (workload, f); workloads without a committed counter profile report null.
 MEASURED_TRAFFIC_BYTES = {
     ("rmat20_spmm_f128", 128): int((4.67104e6 * 1.9999 + 555976 * 1.0) * 1024),
+    # whole product on the config 5 graph: 17 sweep launches + split, fix-up and block-reduce kernels of the
+    # long rows (profiles/spmm_sweep_chunglu_protein_f16.txt); the event bracket covers the same kernels
+    ("chunglu_protein_gcn_128_16_16_256", 16): int(((17 * 2.42669e6 + 6.88363e6 + 159288 + 1.79904e6) * 1.9999
+                                                    + (17 * 32152.7 + 2.41813e6 + 42535.8 + 7828.04) * 1.0) * 1024),
 }
+
+
+# kernels inside the library's event bracket of one product, by config (schedule chosen by the library)
+SPMM_KERNELS = {3: "k_spmm_split (column-blocked) + k_block_reduce",
+                5: "k_spmm_sweep (rows <= 1024 entries) + k_spmm_split (column-blocked, longer rows)"}
 
 
 def spmm_alg_bytes(n: int, nnz: int, f: int) -> int:
@@ -51,6 +60,9 @@ def main() -> int:
     ap.add_argument("--algo", type=int, default=0, help="SpMM kernel: 0 auto, 1 row-wise, 2 nonzero-split")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--f", type=int, default=0, help="override the dense width of config 2")
+    ap.add_argument("--spmm", action="store_true",
+                    help="configs 1, 3, 4, 5: time the stand-alone SpMM (A X and A^T X at width --f, default 16) on "
+                         "that config's graph instead of the epoch")
     ap.add_argument("--slice", type=int, default=0,
                     help="config 2 only: time one block row of P = SLICE (rows [0, n/P) of A against all of X), "
                          "one process's share of the paper's 1D algorithm")
@@ -91,8 +103,8 @@ def main() -> int:
     extra = {"n": n, "nnz": nnz, "max_degree": a.max_degree, "gen_s": round(t_gen, 2),
              "csr_build_s": round(t_build, 3), "n_raw_pairs": int(src.shape[0])}
 
-    if len(w.dims) == 1:
-        f = args.f or w.dims[0]
+    if len(w.dims) == 1 or args.spmm:
+        f = args.f or (w.dims[0] if len(w.dims) == 1 else 16)
         X = synth.uniform_features(n, f, args.seed)
         Xd = dev(X)
         zrows = n
@@ -147,15 +159,19 @@ def main() -> int:
         achieved = b_alg / (avg_kernel_ms * 1e-3) / 1e9
         out.update(metric="SpMM algorithmic GB/s (CSR fp32, A X and A^T X)", value=round(value, 2), unit="GB/s",
                    ms_per_step=round(ms_step, 4),
-                   config={"workload": f"config 2: {w.name} (R-MAT scale 20, edge factor 16, symmetrised, "
-                                       f"self loops, sym-normalised, relabelled), X {n}x{f} uniform[-1,1]",
+                   config={"workload": (f"config 2: {w.name} (R-MAT scale 20, edge factor 16, symmetrised, "
+                                        f"self loops, sym-normalised, relabelled), X {n}x{f} uniform[-1,1]")
+                           if args.config == 2 else
+                           f"config {args.config} graph: {w.name} (symmetrised, self loops, sym-normalised, "
+                           f"relabelled), stand-alone SpMM, X {n}x{f} uniform[-1,1]",
                            "n": n, "nnz": nnz, "f": f, "step": "Z=A X then Z=A^T X",
                            **({"block_row": f"rows [0, n/{args.slice}) of A ({zrows} x {n})"} if args.slice > 1 else {})})
         extra.update(spmm_gflops=round(2 * 2.0 * nnz * f / (ms_step * 1e-3) / 1e9, 1),
                      pct_hbm_peak=round(100 * value / HBM_PEAK_GBPS, 2),
                      bytes_alg_per_spmm=b_alg, bytes_nocache_per_spmm=8 * nnz + 8 * (n + 1) + 4 * f * nnz + 4 * n * f,
                      spmm_products_timed=2 * args.steps, event_brackets=launches)
-        out["roofline"] = {"bound": "hbm", "kernel": "k_spmm_split", "achieved": round(achieved, 2),
+        out["roofline"] = {"bound": "hbm", "kernel": SPMM_KERNELS.get(args.config, "k_spmm_split"),
+                           "achieved": round(achieved, 2),
                            "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
                            "avg_kernel_ms": round(avg_kernel_ms, 4),
                            "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, f)) if args.slice <= 1 else None}
@@ -223,7 +239,8 @@ def main() -> int:
                            "order": args.order})
         extra.update(loss=float(loss.item()), spmm_widths=widths, spmm_ms_per_epoch=round(kern_ms / args.steps, 4),
                      spmm_share=round(kern_ms / args.steps / ms_step, 3))
-        out["roofline"] = {"bound": "hbm", "kernel": "k_spmm_split", "achieved": round(achieved, 2),
+        out["roofline"] = {"bound": "hbm", "kernel": SPMM_KERNELS.get(args.config, "k_spmm_split"),
+                           "achieved": round(achieved, 2),
                            "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
                            "avg_kernel_ms": round(kern_ms / max(len(widths) * args.steps, 1), 4), "traffic": None}
         if not args.no_cpu:

@@ -491,7 +491,10 @@ static int launch_sweep(const SweepArgs& args, int64_t ntasks, int epilogue, hip
     constexpr int W = LPR * 4;
     const size_t lds = (size_t)args.rb * W * sizeof(float);
     const unsigned ytiles = (unsigned)((args.f + W - 1) / W);
-    const int64_t gen = (int64_t)SWEEP_CUS * config().sweep_waves;    // tasks that are resident at once
+    // tasks that are resident at once; the launches get equal shares so that the last one is not a stub
+    const int64_t cap = (int64_t)SWEEP_CUS * config().sweep_waves;
+    const int64_t nlaunch = (ntasks + cap - 1) / cap;
+    const int64_t gen = (ntasks + nlaunch - 1) / nlaunch;
     timing_begin(s);
     for (unsigned y = 0; y < ytiles; ++y) {
         for (int64_t first = 0; first < ntasks; first += gen) {
