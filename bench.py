@@ -66,6 +66,9 @@ def main() -> int:
     ap.add_argument("--slice", type=int, default=0,
                     help="config 2 only: time one block row of P = SLICE (rows [0, n/P) of A against all of X), "
                          "one process's share of the paper's 1D algorithm")
+    ap.add_argument("--pattern", action="store_true",
+                    help="SpMM mode: also time the value-free product (row pre-scaling + gcn_spmm_pattern) and report "
+                         "it under extra")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain device copy of the dense operand (known size) for scaling PMC byte counters")
     args = ap.parse_args()
@@ -151,6 +154,32 @@ def main() -> int:
             step()
         torch.cuda.synchronize()
         dt = min(dt, time.perf_counter() - t0)
+
+        if args.pattern and args.slice <= 1:
+            sc = torch.empty(n, device="cuda")
+            g.gcn_csr_inv_sqrt_degrees(a, sc)
+            Xsc = torch.empty_like(Xd)
+            for timed in (False, True):
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for _ in range(args.steps if timed else max(args.warmup, 1)):
+                    g.gcn_scale_rows(Xd, sc, Xsc)
+                    g.gcn_spmm_pattern(a, 0, Xsc, Z, sc)
+                    g.gcn_scale_rows(Xd, sc, Xsc)
+                    g.gcn_spmm_pattern(a, 1, Xsc, Zt, sc)
+                torch.cuda.synchronize()
+                t_pat = (time.perf_counter() - t0) / args.steps * 1e3
+            for timed in (False, True):
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for _ in range(args.steps if timed else max(args.warmup, 1)):
+                    g.gcn_scale_rows(Xd, sc, Xsc)
+                    g.gcn_scale_rows(Xd, sc, Xsc)
+                torch.cuda.synchronize()
+                t_sc = (time.perf_counter() - t0) / args.steps * 1e3
+            extra.update(pattern_ms_per_step=round(t_pat, 4), pattern_prescale_ms_per_step=round(t_sc, 4),
+                         pattern_bytes_alg_per_spmm=4 * nnz + 8 * (n + 1) + 4 * n + 8 * n * f,
+                         pattern_max_abs_diff_vs_valued=float((Zt - g.gcn_spmm(a, 1, Xd, torch.empty_like(Zt))).abs().max()))
 
         b_alg = spmm_alg_bytes(n, nnz, f) if args.slice <= 1 else 8 * nnz + 8 * (zrows + 1) + 4 * n * f + 4 * zrows * f
         ms_step = dt / args.steps * 1e3

@@ -63,6 +63,8 @@ extern "C" {
 #define GCN_CFG_SWEEP_HEAVY 4 /* rows longer than this bypass the column sweep (default 1024; >= 1) */
 #define GCN_CFG_SWEEP_WAVES 5 /* column sweep: tasks per compute unit in one launch (default 8: 8 x 16 KB of LDS accumulators per compute unit; 1..18) */
 
+#define GCN_CFG_PATTERN_SPMM 6 /* gcn_epoch on a matrix made by gcn_csr_create with GCN_NORM_SYM: use the value-free SpMM (operand rows pre-scaled by d^-1/2, output rows scaled by d^-1/2) instead of reading the stored values. 0 never, 1 always, 2 (default) when the mean row has at least 64 entries */
+
 typedef struct gcn_csr gcn_csr; /* opaque: A (and A^T) in compressed rows, degrees, schedules */
 
 /* -------------------------------------------------------------------------------------------
@@ -125,6 +127,25 @@ int gcn_csr_export(const gcn_csr* a, int transposed, int64_t* rowptr, int32_t* c
  * ----------------------------------------------------------------------------------------- */
 int gcn_spmm(gcn_csr* a, int trans, int32_t f, const float* X, int64_t ldx, float* Z, int64_t ldz,
              int epilogue, const float* Zprev, int64_t ldzprev, void* stream);
+
+/* -------------------------------------------------------------------------------------------
+ * Value-free SpMM for the symmetric normalisation of section "Graph Neural Networks":
+ * D^-1/2 (A+I) D^-1/2 X = D^-1/2 ((A+I) (D^-1/2 X)), so the stored values need not be read.
+ *   gcn_spmm_pattern:  Z[i,:] = epilogue(row_scale[i] * sum over stored entries k of row i of
+ *                      op(A) of X[col[k],:]);  the stored values are ignored; row_scale (device,
+ *                      one float per row of op(A)) may be NULL (= 1).  Other arguments, layout,
+ *                      reproducibility and errors as gcn_spmm.
+ *   gcn_scale_rows:    Y[i,:] = scale[i] * X[i,:]  (rows x cols, device; Y may be X).
+ *   gcn_csr_inv_sqrt_degrees:  out[i] = (float)(1/sqrt((double)d_i)) with d the stored entries per
+ *                      row of A (device, n floats; BADARG for a rectangular matrix).
+ * With s = inv_sqrt_degrees, gcn_scale_rows(X, s) followed by gcn_spmm_pattern(row_scale = s)
+ * equals gcn_spmm on a GCN_NORM_SYM matrix up to fp32 rounding (about 2^-23 relative per term).
+ * ----------------------------------------------------------------------------------------- */
+int gcn_spmm_pattern(gcn_csr* a, int trans, int32_t f, const float* X, int64_t ldx, float* Z, int64_t ldz,
+                     const float* row_scale, int epilogue, const float* Zprev, int64_t ldzprev, void* stream);
+int gcn_scale_rows(int64_t rows, int32_t cols, const float* X, int64_t ldx, const float* scale, float* Y, int64_t ldy,
+                   void* stream);
+int gcn_csr_inv_sqrt_degrees(const gcn_csr* a, float* out, void* stream);
 
 /* -------------------------------------------------------------------------------------------
  * Dense products of "Forward Propagation" (H W) and of Equations 2 and 3 (S W^T, H^T S):

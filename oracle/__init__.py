@@ -183,6 +183,38 @@ def spmm_rows(A: Csr, X: np.ndarray, rows) -> np.ndarray:
     return Z
 
 
+def inv_sqrt_degrees(A: Csr) -> np.ndarray:
+    """s_i = (float)(1/sqrt(d_i)) with d the stored entries per row of the untransposed matrix."""
+    s = np.empty(A.deg.shape[0], np.float32)
+    _lib("f32").orc_inv_sqrt_deg(C.c_int64(s.shape[0]), _p(A.deg), _p(s))
+    return s
+
+
+def scale_rows(X: np.ndarray, scale: np.ndarray) -> np.ndarray:
+    """Y[i,:] = scale[i] X[i,:], rounded once to the type of X."""
+    k = _kind(X)
+    scale = np.ascontiguousarray(scale, np.float32)
+    assert scale.shape[0] == X.shape[0]
+    Y = np.empty(X.shape, X.dtype)
+    _lib(k).orc_scale_rows(C.c_int64(X.shape[0]), C.c_int32(X.shape[1]), _p(X), C.c_int64(_ld(X)), _p(scale),
+                           _p(Y), C.c_int64(X.shape[1]))
+    return Y
+
+
+def spmm_pattern(A: Csr, X: np.ndarray, row_scale=None) -> np.ndarray:
+    """Z[i,:] = row_scale[i] * sum over stored entries k of row i of X[col[k],:] (stored values ignored)."""
+    assert X.shape[0] == A.n_cols
+    k = _kind(X)
+    f = X.shape[1]
+    Z = np.empty((A.n, f), X.dtype)
+    if row_scale is not None:
+        row_scale = np.ascontiguousarray(row_scale, np.float32)
+        assert row_scale.shape[0] == A.n
+    _lib(k).orc_spmm_pattern(C.c_int64(A.n), _p(A.rowptr), _p(A.colidx), _p(row_scale) if row_scale is not None else None,
+                             C.c_int32(f), _p(X), C.c_int64(_ld(X)), _p(Z), C.c_int64(f))
+    return Z
+
+
 def gemm(A: np.ndarray, B: np.ndarray, ta: bool = False, tb: bool = False) -> np.ndarray:
     """op(A) op(B) by the textbook triple loop."""
     A = np.ascontiguousarray(A)

@@ -137,6 +137,31 @@ void orc_spmm_rows(int64_t nsel, const int64_t* rows, const int64_t* rowptr, con
     }
 }
 
+/* Value-free form of the same product for the symmetric normalisation of section "Graph Neural
+ * Networks": with s_i = (float)(1/sqrt(d_i)),  D^-1/2 (A+I) D^-1/2 X = D^-1/2 ((A+I) (D^-1/2 X)).
+ * The three steps are kept apart as the definition states them: scale the rows of X (stored in
+ * REAL), sum the gathered rows without values, scale the output rows (scale may be NULL = 1). */
+void orc_inv_sqrt_deg(int64_t n, const int32_t* deg, float* s) {
+    for (int64_t i = 0; i < n; ++i) s[i] = deg[i] > 0 ? (float)(1.0 / sqrt((double)deg[i])) : 0.0f;
+}
+
+void orc_scale_rows(int64_t n, int32_t f, const REAL* X, int64_t ldx, const float* scale, REAL* Y, int64_t ldy) {
+    for (int64_t i = 0; i < n; ++i)
+        for (int32_t j = 0; j < f; ++j) Y[i * ldy + j] = (REAL)((double)scale[i] * (double)X[i * ldx + j]);
+}
+
+void orc_spmm_pattern(int64_t n, const int64_t* rowptr, const int32_t* colidx, const float* row_scale, int32_t f,
+                      const REAL* X, int64_t ldx, REAL* Z, int64_t ldz) {
+#pragma omp parallel for schedule(dynamic, 256)
+    for (int64_t i = 0; i < n; ++i) {
+        for (int32_t j = 0; j < f; ++j) {
+            double acc = 0.0;
+            for (int64_t k = rowptr[i]; k < rowptr[i + 1]; ++k) acc += (double)X[(int64_t)colidx[k] * ldx + j];
+            Z[i * ldz + j] = (REAL)(row_scale ? (double)row_scale[i] * acc : acc);
+        }
+    }
+}
+
 /* ------------------------------------------------------------------------------------------
  * Dense product C = op(A) op(B), textbook triple loop.  op(A) is M x K, op(B) is K x N.
  * ta/tb nonzero means the stored matrix is the transpose (stored A is K x M, stored B is N x K).

@@ -7,11 +7,12 @@ library has not been built (there is no CPU fallback).
 """
 from .binding import (  # noqa: F401
     GcnError, Csr, lib, library_path, exported_symbols,
-    gcn_csr_create, gcn_csr_create_from_csr, gcn_csr_create_from_csr_rect, gcn_spmm, gcn_gemm, gcn_relu, gcn_relu_mask,
+    gcn_csr_create, gcn_csr_create_from_csr, gcn_csr_create_from_csr_rect, gcn_spmm, gcn_spmm_pattern, gcn_scale_rows,
+    gcn_csr_inv_sqrt_degrees, gcn_gemm, gcn_relu, gcn_relu_mask,
     gcn_softmax_nll, gcn_softmax_nll_masked, gcn_layer_forward, gcn_layer_backward, gcn_epoch, gcn_epoch_masked,
     gcn_epoch_workspace_bytes,
     gcn_epoch_view, gcn_config, gcn_timing_read, gcn_version,
     SYMMETRISE, ADD_SELF_LOOPS, NORM_SYM, BUILD_TRANSPOSE, NORM_ROW,
     EPI_NONE, EPI_RELU, EPI_MASK, ORDER_AUTO, ORDER_GEMM_FIRST, ORDER_SPMM_FIRST, ACT_NONE, ACT_RELU,
-    CFG_SPMM_ALGO, CFG_TIMING, CFG_SPMM_BLOCKS, CFG_SWEEP_HEAVY, CFG_SWEEP_WAVES,
+    CFG_SPMM_ALGO, CFG_TIMING, CFG_SPMM_BLOCKS, CFG_SWEEP_HEAVY, CFG_SWEEP_WAVES, CFG_PATTERN_SPMM,
 )

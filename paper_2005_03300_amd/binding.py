@@ -13,7 +13,7 @@ SYMMETRISE, ADD_SELF_LOOPS, NORM_SYM, BUILD_TRANSPOSE, NORM_ROW = 1, 2, 4, 8, 16
 EPI_NONE, EPI_RELU, EPI_MASK = 0, 1, 2
 ORDER_AUTO, ORDER_GEMM_FIRST, ORDER_SPMM_FIRST = 0, 1, 2
 ACT_NONE, ACT_RELU = 0, 1
-CFG_SPMM_ALGO, CFG_TIMING, CFG_SPMM_BLOCKS, CFG_SWEEP_HEAVY, CFG_SWEEP_WAVES = 1, 2, 3, 4, 5
+CFG_SPMM_ALGO, CFG_TIMING, CFG_SPMM_BLOCKS, CFG_SWEEP_HEAVY, CFG_SWEEP_WAVES, CFG_PATTERN_SPMM = 1, 2, 3, 4, 5, 6
 
 _lib = None
 
@@ -157,6 +157,39 @@ def gcn_spmm(a: Csr, trans: int, X, Z, epilogue: int = EPI_NONE, Zprev=None):
     _check(lib().gcn_spmm(a._h, int(trans), C.c_int32(f), _ptr(X), C.c_int64(_ld(X)), _ptr(Z), C.c_int64(_ld(Z)),
                           int(epilogue), _ptr(Zprev), C.c_int64(_ld(Zprev) if Zprev is not None else 0), _stream()))
     return Z
+
+
+def gcn_spmm_pattern(a: Csr, trans: int, X, Z, row_scale=None, epilogue: int = EPI_NONE, Zprev=None):
+    import torch
+    _dev(X, torch.float32), _dev(Z, torch.float32)
+    f = X.shape[1]
+    xr, zr = (a.n_rows, a.n_cols) if trans else (a.n_cols, a.n_rows)
+    assert X.shape[0] == xr and tuple(Z.shape) == (zr, f)
+    if row_scale is not None:
+        _dev(row_scale, torch.float32)
+        assert row_scale.numel() == zr and row_scale.is_contiguous()
+    _check(lib().gcn_spmm_pattern(a._h, int(trans), C.c_int32(f), _ptr(X), C.c_int64(_ld(X)), _ptr(Z),
+                                  C.c_int64(_ld(Z)), _ptr(row_scale), int(epilogue), _ptr(Zprev),
+                                  C.c_int64(_ld(Zprev) if Zprev is not None else 0), _stream()))
+    return Z
+
+
+def gcn_scale_rows(X, scale, Y):
+    import torch
+    _dev(X, torch.float32), _dev(scale, torch.float32), _dev(Y, torch.float32)
+    rows, cols = X.shape
+    assert tuple(Y.shape) == (rows, cols) and scale.numel() == rows and scale.is_contiguous()
+    _check(lib().gcn_scale_rows(C.c_int64(rows), C.c_int32(cols), _ptr(X), C.c_int64(_ld(X)), _ptr(scale), _ptr(Y),
+                                C.c_int64(_ld(Y)), _stream()))
+    return Y
+
+
+def gcn_csr_inv_sqrt_degrees(a: Csr, out):
+    import torch
+    _dev(out, torch.float32)
+    assert out.numel() == a.n_rows and out.is_contiguous()
+    _check(lib().gcn_csr_inv_sqrt_degrees(a._h, _ptr(out), _stream()))
+    return out
 
 
 def gcn_gemm(ta: int, tb: int, A, B, Cm, bias=None, epilogue: int = EPI_NONE, Zprev=None):

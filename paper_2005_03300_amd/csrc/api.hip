@@ -164,6 +164,10 @@ int gcn_config(int key, int value) {
             if (value < 1) return fail(GCN_ERR_BADARG, "GCN_CFG_SWEEP_HEAVY must be at least 1");
             config().sweep_heavy = value;
             return GCN_OK;
+        case GCN_CFG_PATTERN_SPMM:
+            if (value < 0 || value > 2) return fail(GCN_ERR_BADARG, "GCN_CFG_PATTERN_SPMM must be 0, 1 or 2");
+            config().pattern_spmm = value;
+            return GCN_OK;
         case GCN_CFG_TIMING:
             if (value != 0 && value != 1) return fail(GCN_ERR_BADARG, "GCN_CFG_TIMING must be 0 or 1");
             config().timing = value;
@@ -204,6 +208,7 @@ int gcn_csr_destroy(gcn_csr* a) {
     free_matrix(a->A);
     free_matrix(a->At);
     device_free(a->deg);
+    device_free(a->inv_sqrt_deg);
     device_free(a->carry);
     device_free(a->partial);
     delete a;

@@ -111,6 +111,8 @@ struct gcn_csr {
     bool has_t = false;
     gcn::Matrix A, At;
     int32_t* deg = nullptr;      // [n] entries per row of A
+    float* inv_sqrt_deg = nullptr; // [n] (float)(1/sqrt(deg)); set only when this library normalised the matrix
+                                 // symmetrically, i.e. val_ij == 1/sqrt(deg_i deg_j) for every stored entry
     float* carry = nullptr;      // per-chunk partial rows for the nonzero-split SpMM
     size_t carry_bytes = 0;
     float* partial = nullptr;    // P of the column-blocked SpMM
@@ -133,6 +135,7 @@ struct Config {
     int spmm_blocks = 0;
     int sweep_heavy = 1024;
     int sweep_waves = 8;
+    int pattern_spmm = 2;        // epoch: value-free SpMM for symmetric normalisation (0 never, 1 always, 2 by row length)
     int timing = 0;
 };
 Config& config();
@@ -148,8 +151,17 @@ int build_sweep(Matrix& m, int64_t nnz, int32_t groups, int32_t rb, int32_t heav
 void free_sweep(Sweep& w);
 void free_matrix(Matrix& m);
 
+// Variants of the sparse product: `pattern` ignores the stored values (every entry counts as 1),
+// `row_scale` multiplies output row i by row_scale[i] before the epilogue.
+struct SpmmOpt {
+    bool pattern = false;
+    const float* row_scale = nullptr;
+};
+int scale_rows_launch(int64_t rows, int32_t cols, const float* X, int64_t ldx, const float* scale, float* Y, int64_t ldy,
+                      hipStream_t s);
+int inv_sqrt_deg_launch(int64_t n, const int32_t* deg, float* out, hipStream_t s);
 int spmm_launch(gcn_csr* a, Matrix& m, int32_t f, const float* X, int64_t ldx, float* Z, int64_t ldz,
-                int epilogue, const float* Zprev, int64_t ldzprev, hipStream_t s);
+                int epilogue, const float* Zprev, int64_t ldzprev, hipStream_t s, const SpmmOpt& o = SpmmOpt());
 
 int gemm_launch(int ta, int tb, int64_t M, int64_t N, int64_t K, const float* A, int64_t lda, const float* B,
                 int64_t ldb, float* C, int64_t ldc, const float* bias, int epilogue, const float* Zprev,

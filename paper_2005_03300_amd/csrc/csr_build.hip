@@ -765,6 +765,10 @@ static int create_impl(gcn_csr* a, int64_t n, int64_t m, const int32_t* src, con
                            (flags & GCN_NORM_ROW) ? 2 : ((flags & GCN_NORM_SYM) ? 1 : 0), a->A.val);
         GCN_LAUNCH_CHECK();
     }
+    if ((flags & GCN_NORM_SYM) && n > 0) {
+        GCN_TRY(device_alloc_t(&a->inv_sqrt_deg, (size_t)n));
+        GCN_TRY(inv_sqrt_deg_launch(n, a->deg, a->inv_sqrt_deg, s));
+    }
     GCN_HIP_TRY(hipStreamSynchronize(s));
     GCN_TRY(build_schedule(a->A, n, nnz, s));
     if (flags & GCN_BUILD_TRANSPOSE) GCN_TRY(build_transpose(a, keys, k1.as<uint64_t>(), s));

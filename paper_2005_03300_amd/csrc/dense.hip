@@ -95,6 +95,30 @@ __global__ void k_bias_add(int64_t rows, int32_t cols, float* __restrict__ Z, in
     Z[i * ldz + j] = (relu && !(v > 0.f)) ? 0.f : v;
 }
 
+// Y[i,:] = scale[i] * X[i,:]; 16 bytes per thread when the layout allows it.
+template <int VEC>
+__global__ __launch_bounds__(256) void k_scale_rows(int64_t rows, int32_t lanes, const float* __restrict__ X, int64_t ldx,
+                                                    const float* __restrict__ scale, float* __restrict__ Y, int64_t ldy) {
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t i = t / lanes;
+    const int j = (int)(t % lanes) * VEC;
+    if (i >= rows) return;
+    const float sc = scale[i];
+    if constexpr (VEC == 4) {
+        float4 v = *reinterpret_cast<const float4*>(X + i * ldx + j);
+        v.x *= sc; v.y *= sc; v.z *= sc; v.w *= sc;
+        *reinterpret_cast<float4*>(Y + i * ldy + j) = v;
+    } else {
+        Y[i * ldy + j] = sc * X[i * ldx + j];
+    }
+}
+
+// out[i] = (float)(1 / sqrt((double)deg[i])), 0 for an empty row.
+__global__ void k_inv_sqrt_deg(int64_t n, const int32_t* __restrict__ deg, float* __restrict__ out) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) out[i] = deg[i] > 0 ? (float)__ddiv_rn(1.0, __dsqrt_rn((double)deg[i])) : 0.f;
+}
+
 __global__ void k_axpy(int64_t count, float* __restrict__ W, const float* __restrict__ Y, float lr) {
     const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (t < count) W[t] = W[t] - lr * Y[t];
@@ -172,6 +196,26 @@ int bias_add_launch(int64_t rows, int32_t cols, float* Z, int64_t ldz, const flo
     return GCN_OK;
 }
 
+int scale_rows_launch(int64_t rows, int32_t cols, const float* X, int64_t ldx, const float* scale, float* Y, int64_t ldy,
+                      hipStream_t s) {
+    const bool vec4 = (cols % 4 == 0) && (ldx % 4 == 0) && (ldy % 4 == 0) && (((uintptr_t)X & 15u) == 0) &&
+                      (((uintptr_t)Y & 15u) == 0);
+    if (vec4) {
+        const int lanes = cols / 4;
+        hipLaunchKernelGGL(k_scale_rows<4>, dim3(nblocks(rows * lanes)), dim3(256), 0, s, rows, lanes, X, ldx, scale, Y, ldy);
+    } else {
+        hipLaunchKernelGGL(k_scale_rows<1>, dim3(nblocks(rows * cols)), dim3(256), 0, s, rows, cols, X, ldx, scale, Y, ldy);
+    }
+    GCN_LAUNCH_CHECK();
+    return GCN_OK;
+}
+
+int inv_sqrt_deg_launch(int64_t n, const int32_t* deg, float* out, hipStream_t s) {
+    hipLaunchKernelGGL(k_inv_sqrt_deg, dim3(nblocks(n)), dim3(256), 0, s, n, deg, out);
+    GCN_LAUNCH_CHECK();
+    return GCN_OK;
+}
+
 int axpy_launch(int64_t count, float* W, const float* Y, float lr, hipStream_t s) {
     hipLaunchKernelGGL(k_axpy, dim3(nblocks(count)), dim3(256), 0, s, count, W, Y, lr);
     GCN_LAUNCH_CHECK();
@@ -209,6 +253,19 @@ int gcn_relu_mask(int64_t rows, int32_t cols, const float* G, int64_t ldg, const
                        Zprev, ldzprev, out, ldo);
     GCN_LAUNCH_CHECK();
     return GCN_OK;
+}
+
+int gcn_scale_rows(int64_t rows, int32_t cols, const float* X, int64_t ldx, const float* scale, float* Y, int64_t ldy,
+                   void* stream) {
+    if (!X || !scale || !Y || rows <= 0 || cols <= 0 || ldx < cols || ldy < cols)
+        return fail(GCN_ERR_BADARG, "gcn_scale_rows: bad argument");
+    return scale_rows_launch(rows, cols, X, ldx, scale, Y, ldy, (hipStream_t)stream);
+}
+
+int gcn_csr_inv_sqrt_degrees(const gcn_csr* a, float* out, void* stream) {
+    if (!a || !out) return fail(GCN_ERR_BADARG, "gcn_csr_inv_sqrt_degrees: NULL argument");
+    if (a->n != a->ncols) return fail(GCN_ERR_BADARG, "gcn_csr_inv_sqrt_degrees: the matrix must be square");
+    return inv_sqrt_deg_launch(a->n, a->deg, out, (hipStream_t)stream);
 }
 
 }  // extern "C"

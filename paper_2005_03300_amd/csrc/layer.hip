@@ -14,8 +14,33 @@ static int resolve_order(int order, int32_t f_in, int32_t f_out) {
     return f_out <= f_in ? GCN_ORDER_GEMM_FIRST : GCN_ORDER_SPMM_FIRST;
 }
 
+// For a matrix this library normalised symmetrically, D^-1/2 (A+I) D^-1/2 X = D^-1/2 ((A+I) (D^-1/2 X))
+// (section "Graph Neural Networks"): the product can skip the stored values, which halves the
+// index/value stream.  It pays when rows are long (the pre-scaling pass over X is amortised).
+static bool use_pattern(const gcn_csr* a) {
+    const int mode = config().pattern_spmm;
+    if (!a->inv_sqrt_deg || mode == 0) return false;
+    return mode == 1 || a->nnz / (a->n > 0 ? a->n : 1) >= 64;
+}
+
+// Z = epilogue(op(A) X) with the handle's normalised matrix.  `xs` (n x f, ld f) receives the
+// pre-scaled operand of the value-free form; it may be X itself when X is a temporary with ld f,
+// or NULL to force the valued product.
+static int norm_spmm(gcn_csr* a, Matrix& m, int32_t f, const float* X, int64_t ldx, float* xs, float* Z, int64_t ldz,
+                     int epilogue, const float* Zprev, int64_t ldzprev, hipStream_t s) {
+    if (!xs || !use_pattern(a)) return spmm_launch(a, m, f, X, ldx, Z, ldz, epilogue, Zprev, ldzprev, s);
+    GCN_TRY(scale_rows_launch(a->n, f, X, ldx, a->inv_sqrt_deg, xs, f, s));
+    SpmmOpt o;
+    o.pattern = true;
+    o.row_scale = a->inv_sqrt_deg;
+    return spmm_launch(a, m, f, xs, f, Z, ldz, epilogue, Zprev, ldzprev, s, o);
+}
+
+// `xs`: scratch for the value-free product (n x the SpMM width) or NULL; `t_scratch` says that T is
+// a pure temporary which may be overwritten by its scaled copy.
 static int layer_forward_impl(gcn_csr* a, int32_t f_in, int32_t f_out, const float* Hin, int64_t ldh, const float* W,
-                              const float* bias, float* Z, float* Hout, float* T, int order, int act, hipStream_t s) {
+                              const float* bias, float* Z, float* Hout, float* T, int order, int act, hipStream_t s,
+                              float* xs = nullptr, bool t_scratch = false) {
     const int64_t n = a->n;
     order = resolve_order(order, f_in, f_out);
     // When the caller passes Hout == Z only the activated matrix is wanted and ReLU is fused into
@@ -23,11 +48,11 @@ static int layer_forward_impl(gcn_csr* a, int32_t f_in, int32_t f_out, const flo
     const bool in_place = (act == GCN_ACT_RELU) && Hout == Z;
     if (order == GCN_ORDER_GEMM_FIRST) {
         GCN_TRY(gemm_launch(0, 0, n, f_out, f_in, Hin, ldh, W, f_out, T, f_out, nullptr, GCN_EPI_NONE, nullptr, 0, s));
-        GCN_TRY(spmm_launch(a, a->At, f_out, T, f_out, Z, f_out, (in_place && !bias) ? GCN_EPI_RELU : GCN_EPI_NONE,
-                            nullptr, 0, s));
+        GCN_TRY(norm_spmm(a, a->At, f_out, T, f_out, t_scratch ? T : xs, Z, f_out,
+                          (in_place && !bias) ? GCN_EPI_RELU : GCN_EPI_NONE, nullptr, 0, s));
         if (bias) GCN_TRY(bias_add_launch(n, f_out, Z, f_out, bias, in_place ? 1 : 0, s));
     } else {
-        GCN_TRY(spmm_launch(a, a->At, f_in, Hin, ldh, T, f_in, GCN_EPI_NONE, nullptr, 0, s));
+        GCN_TRY(norm_spmm(a, a->At, f_in, Hin, ldh, xs, T, f_in, GCN_EPI_NONE, nullptr, 0, s));
         GCN_TRY(gemm_launch(0, 0, n, f_out, f_in, T, f_in, W, f_out, Z, f_out, bias,
                             in_place ? GCN_EPI_RELU : GCN_EPI_NONE, nullptr, 0, s));
     }
@@ -39,13 +64,14 @@ static int layer_forward_impl(gcn_csr* a, int32_t f_in, int32_t f_out, const flo
 
 static int layer_backward_impl(gcn_csr* a, int32_t f_in, int32_t f_out, const float* Hin, int64_t ldh,
                                const float* Zprev, const float* W, const float* G, const float* T, float* S, float* Y,
-                               float* dbias, float* Gprev, int order, hipStream_t s) {
+                               float* dbias, float* Gprev, int order, hipStream_t s, float* xs = nullptr,
+                               bool s_scratch = false) {
     const int64_t n = a->n;
     order = resolve_order(order, f_in, f_out);
     if (dbias) GCN_TRY(colsum_launch(n, f_out, G, f_out, dbias, s));
     if (order == GCN_ORDER_GEMM_FIRST) {
         // S = A G;  Y = Hin^T S;  Gprev = (S W^T) (.) sigma'(Zprev)
-        GCN_TRY(spmm_launch(a, a->A, f_out, G, f_out, S, f_out, GCN_EPI_NONE, nullptr, 0, s));
+        GCN_TRY(norm_spmm(a, a->A, f_out, G, f_out, xs, S, f_out, GCN_EPI_NONE, nullptr, 0, s));
         GCN_TRY(gemm_launch(1, 0, f_in, f_out, n, Hin, ldh, S, f_out, Y, f_out, nullptr, GCN_EPI_NONE, nullptr, 0, s));
         if (Gprev)
             GCN_TRY(gemm_launch(0, 1, n, f_in, f_out, S, f_out, W, f_out, Gprev, f_in, nullptr, GCN_EPI_MASK, Zprev, f_in, s));
@@ -55,7 +81,7 @@ static int layer_backward_impl(gcn_csr* a, int32_t f_in, int32_t f_out, const fl
         GCN_TRY(gemm_launch(1, 0, f_in, f_out, n, T, f_in, G, f_out, Y, f_out, nullptr, GCN_EPI_NONE, nullptr, 0, s));
         if (Gprev) {
             GCN_TRY(gemm_launch(0, 1, n, f_in, f_out, G, f_out, W, f_out, S, f_in, nullptr, GCN_EPI_NONE, nullptr, 0, s));
-            GCN_TRY(spmm_launch(a, a->A, f_in, S, f_in, Gprev, f_in, GCN_EPI_MASK, Zprev, f_in, s));
+            GCN_TRY(norm_spmm(a, a->A, f_in, S, f_in, s_scratch ? S : xs, Gprev, f_in, GCN_EPI_MASK, Zprev, f_in, s));
         }
     }
     return GCN_OK;
@@ -64,7 +90,7 @@ static int layer_backward_impl(gcn_csr* a, int32_t f_in, int32_t f_out, const fl
 // ---- epoch workspace layout -------------------------------------------------------------------
 struct EpochLayout {
     std::vector<size_t> Z, H, T, G;   // byte offsets per layer index 0..L_w-1 (layer l = index + 1)
-    size_t S = 0, total = 0;
+    size_t S = 0, XS = 0, total = 0;  // XS: pre-scaled SpMM operand of the value-free product
     std::vector<int> order;
 };
 
@@ -88,6 +114,7 @@ static EpochLayout epoch_layout(int64_t n, int32_t L, const int32_t* dims, int o
         if (sneed > smax) smax = sneed;
     }
     lay.S = take(smax);
+    lay.XS = take(smax);
     lay.total = off;
     return lay;
 }
@@ -177,7 +204,7 @@ int gcn_epoch_masked(gcn_csr* a, int32_t L_w, const int32_t* dims, const float* 
         const bool last = (l + 1 == L_w);
         GCN_TRY(layer_forward_impl(a, dims[l], dims[l + 1], Hin, dims[l], W[l], nullptr, at(lay.Z[l]),
                                    last ? nullptr : at(lay.Z[l]), at(lay.T[l]), lay.order[l],
-                                   last ? GCN_ACT_NONE : GCN_ACT_RELU, s));
+                                   last ? GCN_ACT_NONE : GCN_ACT_RELU, s, at(lay.XS), true));
         Hin = at(lay.H[l]);
     }
     GCN_TRY(gcn_softmax_nll_masked(n, dims[L_w], at(lay.Z[L_w - 1]), dims[L_w], labels, n_labelled, loss,
@@ -186,7 +213,7 @@ int gcn_epoch_masked(gcn_csr* a, int32_t L_w, const int32_t* dims, const float* 
         const float* Hl = l > 0 ? at(lay.H[l - 1]) : H0;
         GCN_TRY(layer_backward_impl(a, dims[l], dims[l + 1], Hl, dims[l], l > 0 ? at(lay.Z[l - 1]) : nullptr, W[l],
                                     at(lay.G[l]), at(lay.T[l]), at(lay.S), Y[l], nullptr, l > 0 ? at(lay.G[l - 1]) : nullptr,
-                                    lay.order[l], s));
+                                    lay.order[l], s, at(lay.XS), true));
     }
     if (lr != 0.f)
         for (int l = 0; l < L_w; ++l) GCN_TRY(axpy_launch((int64_t)dims[l] * dims[l + 1], W[l], Y[l], lr, s));

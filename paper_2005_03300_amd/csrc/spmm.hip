@@ -25,7 +25,8 @@ static constexpr int LDS_PER_WAVE = SUBS_PER_CHUNK * SUB_STRIDE;   // ints
 
 struct SplitArgs {
     const int32_t* colidx;
-    const float* val;
+    const float* val;         // NULL: value-free product (every stored entry counts as 1)
+    const float* row_scale;   // NULL, or one factor per output row applied before the epilogue
     const uint32_t* flags;
     const int32_t* sub_row;
     const int32_t* ne_rows;   // NULL: row index == non-empty-row index
@@ -78,7 +79,9 @@ __device__ __forceinline__ void store_vec(float* p, const float (&d)[VEC]) {
 }
 
 template <int VEC, int EPI>
-__device__ __forceinline__ void epilogue_store(float* z, const float* zprev, float (&v)[VEC]) {
+__device__ __forceinline__ void epilogue_store(float* z, const float* zprev, float (&v)[VEC], float scale = 1.f) {
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) v[e] *= scale;           // exact for scale = 1
     if constexpr (EPI == GCN_EPI_RELU) {
 #pragma unroll
         for (int e = 0; e < VEC; ++e) v[e] = v[e] > 0.f ? v[e] : 0.f;
@@ -116,7 +119,16 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void k_spmm_split(SplitArgs a
         const int64_t k = k0 + i;
         int4 cc = make_int4(0, 0, 0, 0);
         float4 vv = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (k + 4 <= a.nnz) {
+        if (!a.val) {                           // value-free: only the column stream is read
+            vv = make_float4(1.f, 1.f, 1.f, 1.f);
+            if (k + 4 <= a.nnz) {
+                cc = stream_load_i4(a.colidx + k);
+            } else {
+                if (k + 0 < a.nnz) cc.x = a.colidx[k + 0];
+                if (k + 1 < a.nnz) cc.y = a.colidx[k + 1];
+                if (k + 2 < a.nnz) cc.z = a.colidx[k + 2];
+            }
+        } else if (k + 4 <= a.nnz) {
             cc = stream_load_i4(a.colidx + k);
             vv = stream_load_f4(a.val + k);
         } else {
@@ -172,7 +184,7 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void k_spmm_split(SplitArgs a
                                 const int64_t row = a.ne_rows ? a.ne_rows[q] : q;
                                 epilogue_store<VEC, EPI>(a.Z + row * a.ldz + col0,
                                                          EPI == GCN_EPI_MASK ? a.Zprev + row * a.ldzprev + col0 : nullptr,
-                                                         acc);
+                                                         acc, a.row_scale ? a.row_scale[row] : 1.f);
                             }
                         } else {
 #pragma unroll
@@ -235,7 +247,8 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void k_spmm_split(SplitArgs a
         const int64_t row = a.ne_rows ? a.ne_rows[q] : q;
         if (runs_on) store_vec<VEC>(a.Z + row * a.ldz + col0, acc);     // finished by k_spmm_fixup
         else epilogue_store<VEC, EPI>(a.Z + row * a.ldz + col0,
-                                      EPI == GCN_EPI_MASK ? a.Zprev + row * a.ldzprev + col0 : nullptr, acc);
+                                      EPI == GCN_EPI_MASK ? a.Zprev + row * a.ldzprev + col0 : nullptr, acc,
+                                      a.row_scale ? a.row_scale[row] : 1.f);
     }
 }
 
@@ -270,7 +283,8 @@ __global__ __launch_bounds__(256) void k_spmm_fixup(SplitArgs a) {
     load_vec<VEC>(cur, z);
 #pragma unroll
     for (int v = 0; v < VEC; ++v) cur[v] += sum[v];
-    epilogue_store<VEC, EPI>(z, EPI == GCN_EPI_MASK ? a.Zprev + row * a.ldzprev + col0 : nullptr, cur);
+    epilogue_store<VEC, EPI>(z, EPI == GCN_EPI_MASK ? a.Zprev + row * a.ldzprev + col0 : nullptr, cur,
+                             a.row_scale ? a.row_scale[row] : 1.f);
 }
 
 // Rows without stored entries produce zeros (any epilogue maps 0 to 0).
@@ -287,14 +301,17 @@ __global__ void k_zero_empty_rows(int64_t n, const int64_t* __restrict__ rowptr,
 // second implementation (GCN_CFG_SPMM_ALGO = 1) for cross-checks; never chosen automatically.
 template <int EPI>
 __global__ void k_spmm_rowwise(int64_t n, const int64_t* __restrict__ rowptr, const int32_t* __restrict__ colidx,
-                               const float* __restrict__ val, int32_t f, const float* __restrict__ X, int64_t ldx,
+                               const float* __restrict__ val, const float* __restrict__ row_scale, int32_t f,
+                               const float* __restrict__ X, int64_t ldx,
                                float* __restrict__ Z, int64_t ldz, const float* __restrict__ Zprev, int64_t ldzprev) {
     const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const int64_t i = t / f;
     const int j = (int)(t % f);
     if (i >= n) return;
     float acc = 0.f;
-    for (int64_t k = rowptr[i]; k < rowptr[i + 1]; ++k) acc = fmaf(val[k], X[(int64_t)colidx[k] * ldx + j], acc);
+    for (int64_t k = rowptr[i]; k < rowptr[i + 1]; ++k)
+        acc = fmaf(val ? val[k] : 1.f, X[(int64_t)colidx[k] * ldx + j], acc);
+    if (row_scale) acc *= row_scale[i];
     if (EPI == GCN_EPI_RELU) acc = acc > 0.f ? acc : 0.f;
     if (EPI == GCN_EPI_MASK) acc = Zprev[i * ldzprev + j] > 0.f ? acc : 0.f;
     Z[i * ldz + j] = acc;
@@ -332,7 +349,7 @@ static inline bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; 
 template <int VEC, int EPI>
 __global__ __launch_bounds__(256) void k_block_reduce(int64_t n, int32_t f, int32_t lanes, const int64_t* __restrict__ rq_ptr,
                                                       const int32_t* __restrict__ rq_idx, const int32_t* __restrict__ row_map,
-                                                      const float* __restrict__ P,
+                                                      const float* __restrict__ row_scale, const float* __restrict__ P,
                                                       float* __restrict__ Z, int64_t ldz, const float* __restrict__ Zprev,
                                                       int64_t ldzprev) {
     const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -349,19 +366,21 @@ __global__ __launch_bounds__(256) void k_block_reduce(int64_t n, int32_t f, int3
         for (int v = 0; v < VEC; ++v) acc[v] += part[v];
     }
     const int64_t row = row_map ? row_map[i] : i;    // a row-subset matrix writes only its own rows
-    epilogue_store<VEC, EPI>(Z + row * ldz + col0, EPI == GCN_EPI_MASK ? Zprev + row * ldzprev + col0 : nullptr, acc);
+    epilogue_store<VEC, EPI>(Z + row * ldz + col0, EPI == GCN_EPI_MASK ? Zprev + row * ldzprev + col0 : nullptr, acc,
+                             row_scale ? row_scale[row] : 1.f);
 }
 
 template <int VEC>
-static int launch_block_reduce(int64_t n, int32_t f, const Blocked& b, const int32_t* row_map, const float* P, float* Z,
+static int launch_block_reduce(int64_t n, int32_t f, const Blocked& b, const int32_t* row_map, const float* row_scale,
+                               const float* P, float* Z,
                                int64_t ldz, int epilogue, const float* Zprev, int64_t ldzprev, hipStream_t s) {
     const int lanes = f / VEC;
     const int64_t threads = n * lanes;
     const dim3 grid((unsigned)((threads + 255) / 256));
     switch (epilogue) {
-        case GCN_EPI_NONE: hipLaunchKernelGGL((k_block_reduce<VEC, GCN_EPI_NONE>), grid, dim3(256), 0, s, n, f, lanes, b.rq_ptr, b.rq_idx, row_map, P, Z, ldz, Zprev, ldzprev); break;
-        case GCN_EPI_RELU: hipLaunchKernelGGL((k_block_reduce<VEC, GCN_EPI_RELU>), grid, dim3(256), 0, s, n, f, lanes, b.rq_ptr, b.rq_idx, row_map, P, Z, ldz, Zprev, ldzprev); break;
-        default: hipLaunchKernelGGL((k_block_reduce<VEC, GCN_EPI_MASK>), grid, dim3(256), 0, s, n, f, lanes, b.rq_ptr, b.rq_idx, row_map, P, Z, ldz, Zprev, ldzprev); break;
+        case GCN_EPI_NONE: hipLaunchKernelGGL((k_block_reduce<VEC, GCN_EPI_NONE>), grid, dim3(256), 0, s, n, f, lanes, b.rq_ptr, b.rq_idx, row_map, row_scale, P, Z, ldz, Zprev, ldzprev); break;
+        case GCN_EPI_RELU: hipLaunchKernelGGL((k_block_reduce<VEC, GCN_EPI_RELU>), grid, dim3(256), 0, s, n, f, lanes, b.rq_ptr, b.rq_idx, row_map, row_scale, P, Z, ldz, Zprev, ldzprev); break;
+        default: hipLaunchKernelGGL((k_block_reduce<VEC, GCN_EPI_MASK>), grid, dim3(256), 0, s, n, f, lanes, b.rq_ptr, b.rq_idx, row_map, row_scale, P, Z, ldz, Zprev, ldzprev); break;
     }
     GCN_LAUNCH_CHECK();
     return GCN_OK;
@@ -379,7 +398,8 @@ static int launch_block_reduce(int64_t n, int32_t f, const Blocked& b, const int
 // fixed and the result reproducible.
 struct SweepArgs {
     const int32_t* colidx;
-    const float* val;
+    const float* val;            // NULL: value-free product
+    const float* row_scale;      // NULL, or one factor per output row
     const uint8_t* lrow;
     const int64_t* task_base;
     const int32_t* task_len;
@@ -419,7 +439,7 @@ __global__ __launch_bounds__(64) void k_spmm_sweep(SweepArgs a, int64_t first_ta
         c[u] = -1; v[u] = 0.f; r[u] = 0;
         if (k < len) {
             c[u] = __builtin_nontemporal_load(a.colidx + e0 + k);
-            v[u] = __builtin_nontemporal_load(a.val + e0 + k);
+            v[u] = a.val ? __builtin_nontemporal_load(a.val + e0 + k) : 1.f;
             r[u] = (int)__builtin_nontemporal_load(a.lrow + e0 + k);
         }
     }
@@ -431,7 +451,7 @@ __global__ __launch_bounds__(64) void k_spmm_sweep(SweepArgs a, int64_t first_ta
             nc[u] = -1; nv[u] = 0.f; nr[u] = 0;
             if (k < len) {
                 nc[u] = __builtin_nontemporal_load(a.colidx + e0 + k);
-                nv[u] = __builtin_nontemporal_load(a.val + e0 + k);
+                nv[u] = a.val ? __builtin_nontemporal_load(a.val + e0 + k) : 1.f;
                 nr[u] = (int)__builtin_nontemporal_load(a.lrow + e0 + k);
             }
         }
@@ -479,7 +499,8 @@ __global__ __launch_bounds__(64) void k_spmm_sweep(SweepArgs a, int64_t first_ta
         if (row < a.n && col_ok) {
             const float4 w4 = *reinterpret_cast<const float4*>(acc + i * W + col0);
             float out[4] = {w4.x, w4.y, w4.z, w4.w};
-            epilogue_store<4, EPI>(a.Z + row * a.ldz + col0, EPI == GCN_EPI_MASK ? a.Zprev + row * a.ldzprev + col0 : nullptr, out);
+            epilogue_store<4, EPI>(a.Z + row * a.ldz + col0, EPI == GCN_EPI_MASK ? a.Zprev + row * a.ldzprev + col0 : nullptr, out,
+                                   a.row_scale ? a.row_scale[row] : 1.f);
         }
     }
 }
@@ -571,7 +592,7 @@ static int64_t choose_blocks(int64_t nrows, int64_t ncols, int64_t nnz, int32_t 
 // copy (then row_map gives the row each of its rows stands for) -- with or without column blocks.
 static int run_matrix(gcn_csr* a, Matrix& mm, const int32_t* row_map, int64_t nnz, int64_t nblocks, int32_t f,
                       const float* X, int64_t ldx, float* Z, int64_t ldz, int epilogue, const float* Zprev,
-                      int64_t ldzprev, hipStream_t s) {
+                      int64_t ldzprev, const SpmmOpt& o, hipStream_t s) {
     if ((mm.nchunks + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK >= (1ll << 31))
         return fail(GCN_ERR_RANGE, "gcn_spmm: too many chunks for one launch");
     GCN_TRY(grow(&a->carry, &a->carry_bytes, (size_t)mm.nchunks * (size_t)f * sizeof(float)));
@@ -584,16 +605,17 @@ static int run_matrix(gcn_csr* a, Matrix& mm, const int32_t* row_map, int64_t nn
         if (mm.blk.cols_per_block != cpb) GCN_TRY(build_blocked(mm, nnz, cpb, s));
         const Blocked& b = mm.blk;
         GCN_TRY(grow(&a->partial, &a->partial_bytes, (size_t)b.nrows * (size_t)f * sizeof(float)));
-        args.colidx = b.colidx; args.val = b.val; args.flags = b.flags; args.sub_row = b.sub_row;
-        args.ne_rows = nullptr; args.rp = b.rp;
+        args.colidx = b.colidx; args.val = o.pattern ? nullptr : b.val; args.flags = b.flags; args.sub_row = b.sub_row;
+        args.ne_rows = nullptr; args.rp = b.rp; args.row_scale = nullptr;     // the scale belongs to the reduced row
         args.Z = a->partial; args.ldz = f; args.Zprev = nullptr; args.ldzprev = 0;
         GCN_TRY(run_split(args, GCN_EPI_NONE, s));
         const bool vec4 = (f % 4 == 0) && (ldz % 4 == 0) && aligned16(Z) &&
                           (epilogue != GCN_EPI_MASK || ((ldzprev % 4 == 0) && aligned16(Zprev)));
-        if (vec4) return launch_block_reduce<4>(mm.nrows, f, b, row_map, a->partial, Z, ldz, epilogue, Zprev, ldzprev, s);
-        return launch_block_reduce<1>(mm.nrows, f, b, row_map, a->partial, Z, ldz, epilogue, Zprev, ldzprev, s);
+        if (vec4) return launch_block_reduce<4>(mm.nrows, f, b, row_map, o.row_scale, a->partial, Z, ldz, epilogue, Zprev, ldzprev, s);
+        return launch_block_reduce<1>(mm.nrows, f, b, row_map, o.row_scale, a->partial, Z, ldz, epilogue, Zprev, ldzprev, s);
     }
-    args.colidx = mm.colidx; args.val = mm.val; args.flags = mm.flags; args.sub_row = mm.sub_row;
+    args.colidx = mm.colidx; args.val = o.pattern ? nullptr : mm.val; args.flags = mm.flags; args.sub_row = mm.sub_row;
+    args.row_scale = o.row_scale;
     args.ne_rows = row_map ? row_map : mm.ne_rows;
     args.rp = mm.ne_rowptr ? mm.ne_rowptr : mm.rowptr;
     args.Z = Z; args.ldz = ldz; args.Zprev = Zprev; args.ldzprev = ldzprev;
@@ -601,7 +623,7 @@ static int run_matrix(gcn_csr* a, Matrix& mm, const int32_t* row_map, int64_t nn
 }
 
 int spmm_launch(gcn_csr* a, Matrix& m, int32_t f, const float* X, int64_t ldx, float* Z, int64_t ldz,
-                int epilogue, const float* Zprev, int64_t ldzprev, hipStream_t s) {
+                int epilogue, const float* Zprev, int64_t ldzprev, hipStream_t s, const SpmmOpt& o) {
     const int64_t n = m.nrows, ncols = m.ncols, nnz = a->nnz;
     if (nnz == 0) {
         const int64_t work = n * f;
@@ -634,7 +656,7 @@ int spmm_launch(gcn_csr* a, Matrix& m, int32_t f, const float* X, int64_t ldx, f
             GCN_TRY(build_sweep(m, nnz, 64 / LPRs, rb, th, s));
         const Sweep& w = m.swp;
         SweepArgs sa;
-        sa.colidx = w.colidx; sa.val = w.val; sa.lrow = w.lrow; sa.task_base = w.task_base; sa.task_len = w.task_len; sa.task_order = w.task_order;
+        sa.colidx = w.colidx; sa.val = o.pattern ? nullptr : w.val; sa.row_scale = o.row_scale; sa.lrow = w.lrow; sa.task_base = w.task_base; sa.task_len = w.task_len; sa.task_order = w.task_order;
         sa.n = n; sa.f = f; sa.rb = rb; sa.X = X; sa.ldx = ldx; sa.Z = Z; sa.ldz = ldz; sa.Zprev = Zprev; sa.ldzprev = ldzprev;
         if (LPRs == 4) GCN_TRY(launch_sweep<4>(sa, w.ntasks, epilogue, s));
         else GCN_TRY(launch_sweep<8>(sa, w.ntasks, epilogue, s));
@@ -643,7 +665,7 @@ int spmm_launch(gcn_csr* a, Matrix& m, int32_t f, const float* X, int64_t ldx, f
             // column-blocked form to pay even with many blocks
             Matrix& h = *w.heavy;
             const int64_t hb = choose_blocks(h.nrows, ncols, w.nnz_heavy, f, 8);
-            GCN_TRY(run_matrix(a, h, h.ne_rows, w.nnz_heavy, hb, f, X, ldx, Z, ldz, epilogue, Zprev, ldzprev, s));
+            GCN_TRY(run_matrix(a, h, h.ne_rows, w.nnz_heavy, hb, f, X, ldx, Z, ldz, epilogue, Zprev, ldzprev, o, s));
         }
         return GCN_OK;
     }
@@ -653,9 +675,9 @@ int spmm_launch(gcn_csr* a, Matrix& m, int32_t f, const float* X, int64_t ldx, f
         if (work / 256 >= (1ll << 31)) return fail(GCN_ERR_RANGE, "gcn_spmm: n*f too large for the row-wise kernel");
         timing_begin(s);
         switch (epilogue) {
-            case GCN_EPI_NONE: hipLaunchKernelGGL(k_spmm_rowwise<GCN_EPI_NONE>, grid, dim3(256), 0, s, n, m.rowptr, m.colidx, m.val, f, X, ldx, Z, ldz, Zprev, ldzprev); break;
-            case GCN_EPI_RELU: hipLaunchKernelGGL(k_spmm_rowwise<GCN_EPI_RELU>, grid, dim3(256), 0, s, n, m.rowptr, m.colidx, m.val, f, X, ldx, Z, ldz, Zprev, ldzprev); break;
-            default: hipLaunchKernelGGL(k_spmm_rowwise<GCN_EPI_MASK>, grid, dim3(256), 0, s, n, m.rowptr, m.colidx, m.val, f, X, ldx, Z, ldz, Zprev, ldzprev); break;
+            case GCN_EPI_NONE: hipLaunchKernelGGL(k_spmm_rowwise<GCN_EPI_NONE>, grid, dim3(256), 0, s, n, m.rowptr, m.colidx, o.pattern ? nullptr : m.val, o.row_scale, f, X, ldx, Z, ldz, Zprev, ldzprev); break;
+            case GCN_EPI_RELU: hipLaunchKernelGGL(k_spmm_rowwise<GCN_EPI_RELU>, grid, dim3(256), 0, s, n, m.rowptr, m.colidx, o.pattern ? nullptr : m.val, o.row_scale, f, X, ldx, Z, ldz, Zprev, ldzprev); break;
+            default: hipLaunchKernelGGL(k_spmm_rowwise<GCN_EPI_MASK>, grid, dim3(256), 0, s, n, m.rowptr, m.colidx, o.pattern ? nullptr : m.val, o.row_scale, f, X, ldx, Z, ldz, Zprev, ldzprev); break;
         }
         timing_end(s);
         GCN_LAUNCH_CHECK();
@@ -666,7 +688,7 @@ int spmm_launch(gcn_csr* a, Matrix& m, int32_t f, const float* X, int64_t ldx, f
         hipLaunchKernelGGL(k_zero_empty_rows, dim3((unsigned)((work + 255) / 256)), dim3(256), 0, s, n, m.rowptr, f, Z, ldz);
         GCN_LAUNCH_CHECK();
     }
-    return run_matrix(a, m, nullptr, nnz, nblocks, f, X, ldx, Z, ldz, epilogue, Zprev, ldzprev, s);
+    return run_matrix(a, m, nullptr, nnz, nblocks, f, X, ldx, Z, ldz, epilogue, Zprev, ldzprev, o, s);
 }
 
 }  // namespace gcn
@@ -687,4 +709,25 @@ extern "C" int gcn_spmm(gcn_csr* a, int trans, int32_t f, const float* X, int64_
         if (xb < ze && zb < xe) return fail(GCN_ERR_BADARG, "gcn_spmm: X and Z overlap");
     }
     return spmm_launch(a, trans ? a->At : a->A, f, X, ldx, Z, ldz, epilogue, Zprev, ldzprev, (hipStream_t)stream);
+}
+
+extern "C" int gcn_spmm_pattern(gcn_csr* a, int trans, int32_t f, const float* X, int64_t ldx, float* Z, int64_t ldz,
+                                const float* row_scale, int epilogue, const float* Zprev, int64_t ldzprev,
+                                void* stream) {
+    if (!a || !X || !Z) return fail(GCN_ERR_BADARG, "gcn_spmm_pattern: NULL argument");
+    if (f <= 0 || ldx < f || ldz < f) return fail(GCN_ERR_BADARG, "gcn_spmm_pattern: need f > 0, ldx >= f, ldz >= f");
+    if (epilogue < GCN_EPI_NONE || epilogue > GCN_EPI_MASK) return fail(GCN_ERR_BADARG, "gcn_spmm_pattern: unknown epilogue");
+    if (epilogue == GCN_EPI_MASK && (!Zprev || ldzprev < f))
+        return fail(GCN_ERR_BADARG, "gcn_spmm_pattern: mask epilogue needs Zprev with ld >= f");
+    if (trans && !a->has_t) return fail(GCN_ERR_NOTRANSPOSE, "gcn_spmm_pattern: trans=1 needs GCN_BUILD_TRANSPOSE");
+    {
+        const int64_t xrows = trans ? a->n : a->ncols, zrows = trans ? a->ncols : a->n;
+        const char* xb = (const char*)X; const char* xe = xb + ((size_t)(xrows - 1) * ldx + f) * sizeof(float);
+        const char* zb = (const char*)Z; const char* ze = zb + ((size_t)(zrows - 1) * ldz + f) * sizeof(float);
+        if (xb < ze && zb < xe) return fail(GCN_ERR_BADARG, "gcn_spmm_pattern: X and Z overlap");
+    }
+    SpmmOpt o;
+    o.pattern = true;
+    o.row_scale = row_scale;
+    return spmm_launch(a, trans ? a->At : a->A, f, X, ldx, Z, ldz, epilogue, Zprev, ldzprev, (hipStream_t)stream, o);
 }

@@ -436,6 +436,86 @@ def test_spmm_column_sweep_directed_with_empty_rows():
     a.close()
 
 
+# value-free product for the symmetric normalisation: D^-1/2 (A+I) D^-1/2 X = D^-1/2 ((A+I) (D^-1/2 X))
+
+def run_pattern(a, Xs, scale, trans=0, epilogue=0, Zprev=None, algo=0):
+    g = G()
+    g.gcn_config(g.CFG_SPMM_ALGO, algo)
+    try:
+        Z = torch.full(Xs.shape, float("nan"), device="cuda")
+        g.gcn_spmm_pattern(a, trans, dev(Xs), Z, None if scale is None else dev(scale), epilogue,
+                           None if Zprev is None else dev(Zprev))
+        torch.cuda.synchronize()
+        return host(Z)
+    finally:
+        g.gcn_config(g.CFG_SPMM_ALGO, 0)
+
+
+@pytest.mark.parametrize("name", ["c1", "c2s", "c3s", "c5s", "star", "tiny"])
+def test_spmm_pattern_parity(name):
+    g = G()
+    a = gpu_csr(name)
+    ref = oracle_csr(name)
+    s_ref = oracle.inv_sqrt_degrees(ref)
+    s = torch.empty(ref.n, device="cuda")
+    g.gcn_csr_inv_sqrt_degrees(a, s)
+    np.testing.assert_array_equal(host(s), s_ref)                      # correctly rounded on both sides
+    for f in (16, 128, 41):
+        X = synth.normal_features(ref.n, f, 31)
+        Xs_ref = oracle.scale_rows(X, s_ref)
+        Xs = torch.empty(ref.n, f, device="cuda")
+        g.gcn_scale_rows(dev(X), s, Xs)
+        np.testing.assert_array_equal(host(Xs), Xs_ref)                # one rounding of an exact product
+        want = oracle.spmm_pattern(ref, Xs_ref, s_ref)
+        assert_close(run_pattern(a, Xs_ref, s_ref), want, f"{name} f={f}")
+        assert_close(run_pattern(a, Xs_ref, s_ref, trans=1), want, f"{name} f={f} A^T")     # symmetric pattern
+        assert_close(run_pattern(a, Xs_ref, None), oracle.spmm_pattern(ref, Xs_ref), "no row scale")
+        # and it is the product with the normalised matrix, up to the float roundings of val and s
+        assert_close(run_pattern(a, Xs_ref, s_ref), oracle.spmm(ref, X), f"{name} f={f} vs valued")
+    a.close()
+
+
+@pytest.mark.parametrize("algo,blocks,heavy", [(1, 0, 1024), (2, 5, 1024), (3, 0, 1 << 20), (3, 7, 64)])
+def test_spmm_pattern_every_schedule_with_epilogues(algo, blocks, heavy):
+    g = G()
+    a = gpu_csr("c3s")
+    ref = oracle_csr("c3s")
+    s_ref = oracle.inv_sqrt_degrees(ref)
+    g.gcn_config(g.CFG_SPMM_BLOCKS, blocks)
+    g.gcn_config(g.CFG_SWEEP_HEAVY, heavy)
+    try:
+        for f in (16, 32, 100):
+            Xs = oracle.scale_rows(synth.normal_features(ref.n, f, 33), s_ref)
+            Zp = synth.normal_features(ref.n, f, 34)
+            plain = oracle.spmm_pattern(ref, Xs, s_ref)
+            assert_close(run_pattern(a, Xs, s_ref, algo=algo), plain, f"algo={algo} f={f}")
+            assert_close(run_pattern(a, Xs, s_ref, epilogue=g.EPI_RELU, algo=algo), np.maximum(plain, 0), "relu")
+            assert_close(run_pattern(a, Xs, s_ref, epilogue=g.EPI_MASK, Zprev=Zp, algo=algo),
+                         oracle.relu_mask(plain, Zp), "mask")
+    finally:
+        g.gcn_config(g.CFG_SPMM_BLOCKS, 0)
+        g.gcn_config(g.CFG_SWEEP_HEAVY, 1024)
+    a.close()
+
+
+def test_spmm_pattern_directed_transpose_and_errors():
+    g = G()
+    a = gpu_csr("c4s", symmetrise=False)
+    ref = oracle_csr("c4s", symmetrise=False)
+    ref_t = oracle_csr("c4s", symmetrise=False, transpose=True)
+    s_ref = oracle.inv_sqrt_degrees(ref)
+    X = synth.uniform_features(ref.n, 16, 35)
+    Xs = oracle.scale_rows(X, s_ref)
+    assert_close(run_pattern(a, Xs, s_ref, trans=0), oracle.spmm_pattern(ref, Xs, s_ref), "A")
+    assert_close(run_pattern(a, Xs, s_ref, trans=1), oracle.spmm_pattern(ref_t, Xs, s_ref), "A^T")
+    assert_close(run_pattern(a, Xs, s_ref, trans=1), oracle.spmm(ref_t, X), "A^T vs valued")
+    Z = torch.empty(ref.n, 16, device="cuda")
+    with pytest.raises(g.GcnError) as e:
+        g.gcn_spmm_pattern(a, 0, Z, Z, None)                  # X and Z overlap
+    assert e.value.code == -1
+    a.close()
+
+
 # ------------------------------------------------------------------------------------------------
 # a4 / a5 / a6: dense products and element-wise
 # ------------------------------------------------------------------------------------------------
@@ -655,6 +735,45 @@ def test_epoch_scaled_configs_parity(name, cfg, shrink):
     for l in range(len(dims) - 1):
         assert rel_fro(host(Yd[l]), ref["Y"][l]) <= 2e-4, (l, rel_fro(host(Yd[l]), ref["Y"][l]))
     a.close()
+
+
+@pytest.mark.parametrize("name,dims,classes", [("c1", (64, 64, 8), 8),             # two weight matrices, hidden 64
+                                               ("c2s", (128, 64, 64, 16), 16),     # three, hidden 64
+                                               ("c3s", (100, 64, 41), 41)])
+@pytest.mark.parametrize("order", [0, 2])
+def test_epoch_wide_hidden_and_two_weight_matrices(name, dims, classes, order):
+    """Hidden width 64 (the paper's 2D-vs-3D runs) and the reading of "3-layer" as three embedding
+    matrices with two weight matrices: the number of weight matrices is a run-time argument."""
+    import dataclasses
+    w = dataclasses.replace(synth.CONFIGS[1], dims=dims, n_classes=classes, features="normal")
+    g, a, A, dl, Wd, Yd, ws, loss, ref, _ = run_epoch(name, w, order)
+    assert abs(loss.item() - ref["loss"]) <= 1e-4 * abs(ref["loss"])
+    for l in range(len(dl) - 1):
+        assert rel_fro(host(Yd[l]), ref["Y"][l]) <= 2e-4, (l, rel_fro(host(Yd[l]), ref["Y"][l]))
+    Zl, _ = g.gcn_epoch_view(A.n, dl, order, ws, len(dl) - 1)
+    assert rel_fro(host(Zl), ref["Z"][len(dl) - 2]) <= 1e-4
+    a.close()
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+@pytest.mark.parametrize("order", [0, 1, 2])
+def test_epoch_value_free_spmm_on_and_off(mode, order):
+    """The epoch with the value-free SpMM (operand rows pre-scaled by d^-1/2) forced on or off gives the
+    oracle's loss and gradients either way."""
+    g = G()
+    g.gcn_config(g.CFG_PATTERN_SPMM, mode)
+    try:
+        w = synth.CONFIGS[1]
+        _, a, A, dims, Wd, Yd, ws, loss, ref, _ = run_epoch("c1", w, order)
+        assert abs(loss.item() - ref["loss"]) <= 1e-4 * abs(ref["loss"])
+        for l in range(len(dims) - 1):
+            assert rel_fro(host(Yd[l]), ref["Y"][l]) <= 1e-4, l
+            Zl, Gl = g.gcn_epoch_view(A.n, dims, order, ws, l + 1)
+            assert rel_fro(host(Zl), ref["Z"][l] if l + 2 == len(dims) else ref["H"][l + 1]) <= 1e-4
+            assert rel_fro(host(Gl), ref["G"][l]) <= 1e-3
+        a.close()
+    finally:
+        g.gcn_config(g.CFG_PATTERN_SPMM, 2)
 
 
 def test_epoch_sgd_step_and_workspace_check():

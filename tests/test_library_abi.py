@@ -28,13 +28,14 @@ def test_host_only_calls():
     g.gcn_config(g.CFG_SPMM_ALGO, 2)
     g.gcn_config(g.CFG_SPMM_ALGO, 0)
     # workspace sizing is pure host arithmetic: sum over layers of H (last layer: Z), T, G plus the shared S
+    # and the scaled-operand buffer of the same size
     n, dims = 1000, [64, 16, 8]
     want = 0
     r = lambda e: (e * 4 + 255) // 256 * 256
     for l in range(2):
         fo = dims[l + 1]
         want += r(n * fo) + r(n * fo) + r(n * fo)          # H (or last Z), T, G
-    want += r(n * 16)
+    want += 2 * r(n * 16)
     assert g.gcn_epoch_workspace_bytes(n, dims, g.ORDER_GEMM_FIRST) == want
     assert g.gcn_epoch_workspace_bytes(n, [64, 0, 8], 0) == 0
 

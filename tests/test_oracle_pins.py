@@ -255,6 +255,49 @@ def test_spmm_rows_equals_rows_of_full_product():
     np.testing.assert_array_equal(oracle.spmm_rows(A, X, rows), oracle.spmm(A, X)[rows])
 
 
+# value-free form for the symmetric normalisation: D^-1/2 (A+I) D^-1/2 X = D^-1/2 ((A+I) (D^-1/2 X))
+
+def test_pattern_product_brute_force_and_unit_cases():
+    n, src, dst = small_graph(36, 100, 23)
+    A = oracle.build_csr(n, src, dst, symmetrise=False)          # unsymmetric pattern
+    entries = py_entry_set(n, src, dst, False, True)
+    X = synth.normal_features(n, 4, 6).astype(np.float64)
+    rs = (np.arange(n) % 5 + 1).astype(np.float32) / 4           # exactly representable scales
+    want = [[float(rs[i]) * math.fsum(X[j, c] for (r, j) in entries if r == i) for c in range(4)] for i in range(n)]
+    np.testing.assert_allclose(oracle.spmm_pattern(A, X, rs), np.array(want), rtol=1e-14, atol=1e-14)
+    # no scale, operand of ones: the integer row lengths, whatever the stored values are
+    ones = np.ones((n, 2), np.float32)
+    np.testing.assert_array_equal(oracle.spmm_pattern(A, ones), np.repeat(A.deg.astype(np.float32)[:, None], 2, axis=1))
+    # scale_rows and the inverse square roots against their definitions
+    s = oracle.inv_sqrt_degrees(A)
+    np.testing.assert_array_equal(s, np.array([np.float32(1.0 / math.sqrt(int(d))) for d in A.deg]))
+    Y = oracle.scale_rows(X, rs)
+    np.testing.assert_array_equal(Y, X * rs.astype(np.float64)[:, None])
+
+
+@pytest.mark.parametrize("directed", [False, True])
+def test_pattern_product_equals_normalised_product(directed):
+    """The factorised form gives the product with the normalised matrix: in the double build the two
+    differ only by the float roundings of val_ij and s_i (a few 2^-24 relative per term)."""
+    n, src, dst = synth.make_graph(synth.scaled(3, 128))
+    A = oracle.build_csr(n, src, dst, symmetrise=not directed)
+    At = oracle.build_csr(n, src, dst, symmetrise=not directed, transpose=True)
+    X = np.abs(synth.normal_features(n, 3, 8).astype(np.float64)) + 0.1      # positive: no cancellation
+    s = oracle.inv_sqrt_degrees(A)
+    for M in (A, At):
+        got = oracle.spmm_pattern(M, oracle.scale_rows(X, s), s)
+        want = oracle.spmm(M, X)
+        np.testing.assert_allclose(got, want, rtol=4e-7, atol=0)
+    # closed form on a ring: every row holds two neighbours and the loop, so all degrees are 3
+    src, dst = synth.ring(12)
+    R = oracle.build_csr(12, src, dst)
+    x = np.arange(12, dtype=np.float64)[:, None]
+    sr = oracle.inv_sqrt_degrees(R)
+    got = oracle.spmm_pattern(R, oracle.scale_rows(x, sr), sr)[:, 0]
+    want = np.array([(x[(i - 1) % 12, 0] + x[i, 0] + x[(i + 1) % 12, 0]) * float(sr[0]) ** 2 for i in range(12)])
+    np.testing.assert_allclose(got, want, rtol=1e-15)
+
+
 # ------------------------------------------------------------------------------------------------
 # dense products
 # ------------------------------------------------------------------------------------------------
