@@ -66,6 +66,11 @@ def main() -> int:
     ap.add_argument("--slice", type=int, default=0,
                     help="config 2 only: time one block row of P = SLICE (rows [0, n/P) of A against all of X), "
                          "one process's share of the paper's 1D algorithm")
+    ap.add_argument("--directed", action="store_true",
+                    help="SpMM mode: keep the drawn pairs as directed edges (no symmetrisation) with row normalisation, "
+                         "so that A and A^T differ")
+    ap.add_argument("--no-permute", action="store_true",
+                    help="skip the random vertex relabelling (hubs then sit at low ids, which flatters the caches)")
     ap.add_argument("--pattern", action="store_true",
                     help="SpMM mode: also time the value-free product (row pre-scaling + gcn_spmm_pattern) and report "
                          "it under extra")
@@ -87,6 +92,12 @@ def main() -> int:
     torch.cuda.set_device(0)
     g.lib()
     w = synth.CONFIGS[args.config]
+    if args.no_permute:
+        import dataclasses
+        w = dataclasses.replace(w, permute=False)
+    if args.directed and not (len(w.dims) == 1 or args.spmm):
+        print("bench.py: --directed applies to the stand-alone SpMM (config 2 or --spmm)", file=sys.stderr)
+        return 2
     dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
     t0 = time.time()
@@ -94,7 +105,9 @@ def main() -> int:
     t_gen = time.time() - t0
     t0 = time.time()
     src_d, dst_d = dev(src), dev(dst)
-    a = g.gcn_csr_create(n, src_d, dst_d, g.SYMMETRISE | g.ADD_SELF_LOOPS | g.NORM_SYM | g.BUILD_TRANSPOSE)
+    flags = (g.ADD_SELF_LOOPS | g.NORM_ROW | g.BUILD_TRANSPOSE) if args.directed else \
+            (g.SYMMETRISE | g.ADD_SELF_LOOPS | g.NORM_SYM | g.BUILD_TRANSPOSE)
+    a = g.gcn_csr_create(n, src_d, dst_d, flags)
     torch.cuda.synchronize()
     t_build = time.time() - t0
     del src_d, dst_d
@@ -155,7 +168,7 @@ def main() -> int:
         torch.cuda.synchronize()
         dt = min(dt, time.perf_counter() - t0)
 
-        if args.pattern and args.slice <= 1:
+        if args.pattern and args.slice <= 1 and not args.directed:
             sc = torch.empty(n, device="cuda")
             g.gcn_csr_inv_sqrt_degrees(a, sc)
             Xsc = torch.empty_like(Xd)
@@ -194,6 +207,8 @@ def main() -> int:
                            f"config {args.config} graph: {w.name} (symmetrised, self loops, sym-normalised, "
                            f"relabelled), stand-alone SpMM, X {n}x{f} uniform[-1,1]",
                            "n": n, "nnz": nnz, "f": f, "step": "Z=A X then Z=A^T X",
+                           **({"variant": "directed, row-normalised (A and A^T differ)"} if args.directed else {}),
+                           **({"relabelled": False} if args.no_permute else {}),
                            **({"block_row": f"rows [0, n/{args.slice}) of A ({zrows} x {n})"} if args.slice > 1 else {})})
         extra.update(spmm_gflops=round(2 * 2.0 * nnz * f / (ms_step * 1e-3) / 1e9, 1),
                      pct_hbm_peak=round(100 * value / HBM_PEAK_GBPS, 2),
@@ -203,12 +218,13 @@ def main() -> int:
                            "achieved": round(achieved, 2),
                            "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
                            "avg_kernel_ms": round(avg_kernel_ms, 4),
-                           "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, f)) if args.slice <= 1 else None}
+                           "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, f))
+                           if args.slice <= 1 and not args.directed and not args.no_permute else None}
 
         if not args.no_cpu:
             import oracle
             t0 = time.time()
-            A = oracle.build_csr(n, src, dst)
+            A = oracle.build_csr(n, src, dst, symmetrise=not args.directed, norm="row" if args.directed else "sym")
             if args.slice > 1:
                 A = oracle.slice_rows(A, 0, zrows)
             t_ob = time.time() - t0
@@ -244,7 +260,8 @@ def main() -> int:
             step()
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
-        launches, kern_ms = g.gcn_timing_read()
+        phases = g.gcn_timing_read_phases()
+        launches, kern_ms = phases["spmm_kernel"]
         g.gcn_config(g.CFG_TIMING, 0)
         t0 = time.perf_counter()
         for _ in range(args.steps):
@@ -252,6 +269,9 @@ def main() -> int:
         torch.cuda.synchronize()
         dt = min(dt, time.perf_counter() - t0)
         ms_step = dt / args.steps * 1e3
+        extra["phase_ms_per_epoch"] = {"spmm": round(phases["spmm"][1] / args.steps, 4),
+                                       "gemm": round(phases["gemm"][1] / args.steps, 4),
+                                       "loss_elementwise_update": round(phases["other"][1] / args.steps, 4)}
         # widths of the SpMM launches of one epoch under the chosen association order
         widths = []
         for l in range(L):

@@ -234,8 +234,20 @@ int gcn_config(int key, int value);
 
 /* With GCN_CFG_TIMING = 1 the SpMM main kernel is bracketed by HIP events on its own stream.
  * gcn_timing_read synchronises with the recorded events, returns the number of bracketed
- * launches and their total milliseconds since the last read, and resets the record. */
+ * launches and their total milliseconds since the last read, and resets the record.
+ * The layer and epoch calls also bracket their phases: gcn_timing_read_phases fills
+ * spans[GCN_PHASE_COUNT] and total_ms[GCN_PHASE_COUNT] (host arrays) and resets the record:
+ *   GCN_PHASE_SPMM_KERNEL  the SpMM main kernels alone (what gcn_timing_read returns)
+ *   GCN_PHASE_SPMM         whole sparse products (pre-scaling, main, fix-up and reduce kernels)
+ *   GCN_PHASE_GEMM         dense products
+ *   GCN_PHASE_OTHER        loss, activation, bias and update kernels */
+#define GCN_PHASE_SPMM_KERNEL 0
+#define GCN_PHASE_SPMM 1
+#define GCN_PHASE_GEMM 2
+#define GCN_PHASE_OTHER 3
+#define GCN_PHASE_COUNT 4
 int gcn_timing_read(int64_t* launches, double* total_ms);
+int gcn_timing_read_phases(int64_t* spans, double* total_ms);
 
 const char* gcn_last_error(void);
 const char* gcn_version(void);

@@ -307,5 +307,14 @@ def gcn_timing_read():
     return cnt.value, ms.value
 
 
+def gcn_timing_read_phases():
+    """Returns {phase name: (spans, total ms)} and resets the record."""
+    cnt = (C.c_int64 * 4)()
+    ms = (C.c_double * 4)()
+    _check(lib().gcn_timing_read_phases(cnt, ms))
+    names = ("spmm_kernel", "spmm", "gemm", "other")
+    return {k: (cnt[i], ms[i]) for i, k in enumerate(names)}
+
+
 def gcn_version() -> str:
     return lib().gcn_version().decode()

@@ -71,30 +71,31 @@ Config& config() {
 }
 
 // ---- event timing ---------------------------------------------------------------------------
+struct TimedSpan { hipEvent_t a, b; int phase; };
 static std::mutex g_time_mu;
-static std::vector<std::pair<hipEvent_t, hipEvent_t>> g_events;
-static thread_local hipEvent_t g_open = nullptr;
+static std::vector<TimedSpan> g_events;
+static thread_local hipEvent_t g_open[GCN_PHASE_COUNT] = {};
 
-void timing_begin(hipStream_t s) {
-    if (!config().timing) return;
+void timing_begin(hipStream_t s, int phase) {
+    if (!config().timing || g_open[phase]) return;
     hipEvent_t a;
     if (hipEventCreate(&a) != hipSuccess) return;
     (void)hipEventRecord(a, s);
-    g_open = a;
+    g_open[phase] = a;
 }
 
-void timing_end(hipStream_t s) {
-    if (!config().timing || !g_open) return;
+void timing_end(hipStream_t s, int phase) {
+    if (!g_open[phase]) return;
     hipEvent_t b;
     if (hipEventCreate(&b) != hipSuccess) {
-        (void)hipEventDestroy(g_open);
-        g_open = nullptr;
+        (void)hipEventDestroy(g_open[phase]);
+        g_open[phase] = nullptr;
         return;
     }
     (void)hipEventRecord(b, s);
     std::lock_guard<std::mutex> lk(g_time_mu);
-    g_events.emplace_back(g_open, b);
-    g_open = nullptr;
+    g_events.push_back({g_open[phase], b, phase});
+    g_open[phase] = nullptr;
 }
 
 void free_blocked(Blocked& b) {
@@ -177,28 +178,35 @@ int gcn_config(int key, int value) {
     }
 }
 
-int gcn_timing_read(int64_t* launches, double* total_ms) {
-    if (!launches || !total_ms) return fail(GCN_ERR_BADARG, "gcn_timing_read: NULL output");
+int gcn_timing_read_phases(int64_t* spans, double* total_ms) {
+    if (!spans || !total_ms) return fail(GCN_ERR_BADARG, "gcn_timing_read_phases: NULL output");
     std::lock_guard<std::mutex> lk(g_time_mu);
-    double ms = 0.0;
-    int64_t cnt = 0;
+    for (int p = 0; p < GCN_PHASE_COUNT; ++p) { spans[p] = 0; total_ms[p] = 0.0; }
     int rc = GCN_OK;
     for (auto& ev : g_events) {
         float t = 0.f;
-        hipError_t e = hipEventSynchronize(ev.second);
-        if (e == hipSuccess) e = hipEventElapsedTime(&t, ev.first, ev.second);
+        hipError_t e = hipEventSynchronize(ev.b);
+        if (e == hipSuccess) e = hipEventElapsedTime(&t, ev.a, ev.b);
         if (e == hipSuccess) {
-            ms += t;
-            cnt += 1;
+            total_ms[ev.phase] += t;
+            spans[ev.phase] += 1;
         } else {
             rc = fail(GCN_ERR_HIP, "event timing failed: %s", hipGetErrorString(e));
         }
-        (void)hipEventDestroy(ev.first);
-        (void)hipEventDestroy(ev.second);
+        (void)hipEventDestroy(ev.a);
+        (void)hipEventDestroy(ev.b);
     }
     g_events.clear();
-    *launches = cnt;
-    *total_ms = ms;
+    return rc;
+}
+
+int gcn_timing_read(int64_t* launches, double* total_ms) {
+    if (!launches || !total_ms) return fail(GCN_ERR_BADARG, "gcn_timing_read: NULL output");
+    int64_t spans[GCN_PHASE_COUNT];
+    double ms[GCN_PHASE_COUNT];
+    const int rc = gcn_timing_read_phases(spans, ms);
+    *launches = spans[GCN_PHASE_SPMM_KERNEL];
+    *total_ms = ms[GCN_PHASE_SPMM_KERNEL];
     return rc;
 }
 

@@ -141,8 +141,15 @@ struct Config {
 Config& config();
 
 // event bracketing of the dominant kernel (GCN_CFG_TIMING)
-void timing_begin(hipStream_t s);
-void timing_end(hipStream_t s);
+void timing_begin(hipStream_t s, int phase = GCN_PHASE_SPMM_KERNEL);
+void timing_end(hipStream_t s, int phase = GCN_PHASE_SPMM_KERNEL);
+// brackets a scope of host code (all kernels it queues on `s`) under one phase
+struct PhaseTimer {
+    hipStream_t s;
+    int phase;
+    PhaseTimer(hipStream_t s_, int phase_) : s(s_), phase(phase_) { timing_begin(s, phase); }
+    ~PhaseTimer() { timing_end(s, phase); }
+};
 
 int build_schedule(Matrix& m, int64_t n, int64_t nnz, hipStream_t s);
 int build_blocked(Matrix& m, int64_t nnz, int64_t cols_per_block, hipStream_t s);

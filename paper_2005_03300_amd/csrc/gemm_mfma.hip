@@ -44,7 +44,10 @@ struct TallArgs {
     int a_aligned;     // A rows are 16-byte aligned
 };
 
-template <int NT, int EPI>
+// TR: the two MFMA operands are swapped, so a lane ends up with four consecutive columns of one
+// row of C (element v of tile t is C[row0 + l%16][16t + 4*(l/16) + v]) and stores them with one
+// 16-byte instruction; needs N % 4 == 0 and 16-byte aligned rows of C (and of Zprev for the mask).
+template <int NT, int EPI, bool TR>
 __global__ __launch_bounds__(256) void k_gemm_tall(TallArgs a) {
     extern __shared__ float Bs[];                       // [Kpad][S]
     const int n0 = blockIdx.y * (NT * 16);
@@ -82,7 +85,8 @@ __global__ __launch_bounds__(256) void k_gemm_tall(TallArgs a) {
                     const float* bp = Bs + (k0 + 16 * s + 4 * kq + e) * a.S + r;
 #pragma unroll
                     for (int t = 0; t < NT; ++t)
-                        acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(ae[e], bp[16 * t], acc[t], 0, 0, 0);
+                        acc[t] = TR ? __builtin_amdgcn_mfma_f32_16x16x4f32(bp[16 * t], ae[e], acc[t], 0, 0, 0)
+                                    : __builtin_amdgcn_mfma_f32_16x16x4f32(ae[e], bp[16 * t], acc[t], 0, 0, 0);
                 }
             }
         }
@@ -94,7 +98,8 @@ __global__ __launch_bounds__(256) void k_gemm_tall(TallArgs a) {
                 const float* bp = Bs + (k0 + 4 * kq + e) * a.S + r;
 #pragma unroll
                 for (int t = 0; t < NT; ++t)
-                    acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(ae[e], bp[16 * t], acc[t], 0, 0, 0);
+                    acc[t] = TR ? __builtin_amdgcn_mfma_f32_16x16x4f32(bp[16 * t], ae[e], acc[t], 0, 0, 0)
+                                : __builtin_amdgcn_mfma_f32_16x16x4f32(ae[e], bp[16 * t], acc[t], 0, 0, 0);
             }
         }
         if (k0 < a.K) {                                 // ragged tail: element-wise guarded loads
@@ -105,8 +110,31 @@ __global__ __launch_bounds__(256) void k_gemm_tall(TallArgs a) {
                 const float* bp = Bs + k * a.S + r;     // rows K..Kpad-1 of Bs are zero
 #pragma unroll
                 for (int t = 0; t < NT; ++t)
-                    acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(ae, bp[16 * t], acc[t], 0, 0, 0);
+                    acc[t] = TR ? __builtin_amdgcn_mfma_f32_16x16x4f32(bp[16 * t], ae, acc[t], 0, 0, 0)
+                                : __builtin_amdgcn_mfma_f32_16x16x4f32(ae, bp[16 * t], acc[t], 0, 0, 0);
             }
+        }
+        if constexpr (TR) {
+            const int64_t row = row0 + r;
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                const int col = n0 + 16 * t + 4 * kq;           // N % 4 == 0: the four columns exist together
+                if (col >= a.N || row >= a.M) continue;
+                float4 o = make_float4(acc[t][0], acc[t][1], acc[t][2], acc[t][3]);
+                if (a.bias) {
+                    o.x += a.bias[col]; o.y += a.bias[col + 1]; o.z += a.bias[col + 2]; o.w += a.bias[col + 3];
+                }
+                if (EPI == GCN_EPI_RELU) {
+                    o.x = o.x > 0.f ? o.x : 0.f; o.y = o.y > 0.f ? o.y : 0.f;
+                    o.z = o.z > 0.f ? o.z : 0.f; o.w = o.w > 0.f ? o.w : 0.f;
+                } else if (EPI == GCN_EPI_MASK) {
+                    const float4 m = *reinterpret_cast<const float4*>(a.Zprev + row * a.ldzprev + col);
+                    o.x = m.x > 0.f ? o.x : 0.f; o.y = m.y > 0.f ? o.y : 0.f;
+                    o.z = m.z > 0.f ? o.z : 0.f; o.w = m.w > 0.f ? o.w : 0.f;
+                }
+                *reinterpret_cast<float4*>(a.C + row * a.ldc + col) = o;
+            }
+            continue;
         }
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
@@ -276,13 +304,22 @@ __global__ void k_tn_reduce(int32_t M, int32_t N, int parts, int transposed, con
 
 static inline bool al16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
 
+template <int NT, bool TR>
+static void launch_tall_tr(const TallArgs& args, int epilogue, dim3 grid, size_t lds, hipStream_t s) {
+    switch (epilogue) {
+        case GCN_EPI_NONE: hipLaunchKernelGGL((k_gemm_tall<NT, GCN_EPI_NONE, TR>), grid, dim3(256), lds, s, args); break;
+        case GCN_EPI_RELU: hipLaunchKernelGGL((k_gemm_tall<NT, GCN_EPI_RELU, TR>), grid, dim3(256), lds, s, args); break;
+        default: hipLaunchKernelGGL((k_gemm_tall<NT, GCN_EPI_MASK, TR>), grid, dim3(256), lds, s, args); break;
+    }
+}
+
 template <int NT>
 static void launch_tall(const TallArgs& args, int epilogue, dim3 grid, size_t lds, hipStream_t s) {
-    switch (epilogue) {
-        case GCN_EPI_NONE: hipLaunchKernelGGL((k_gemm_tall<NT, GCN_EPI_NONE>), grid, dim3(256), lds, s, args); break;
-        case GCN_EPI_RELU: hipLaunchKernelGGL((k_gemm_tall<NT, GCN_EPI_RELU>), grid, dim3(256), lds, s, args); break;
-        default: hipLaunchKernelGGL((k_gemm_tall<NT, GCN_EPI_MASK>), grid, dim3(256), lds, s, args); break;
-    }
+    // 16-byte stores when every row of C (and of the mask operand) allows them
+    const bool wide = (args.N % 4 == 0) && (args.ldc % 4 == 0) && al16(args.C) &&
+                      (epilogue != GCN_EPI_MASK || ((args.ldzprev % 4 == 0) && al16(args.Zprev)));
+    if (wide) launch_tall_tr<NT, true>(args, epilogue, grid, lds, s);
+    else launch_tall_tr<NT, false>(args, epilogue, grid, lds, s);
 }
 
 template <int MG, int NT, bool NARROW>
@@ -297,7 +334,12 @@ int gemm_mfma_launch(int ta, int tb, int64_t M, int64_t N, int64_t K, const floa
     if (!ta) {
         if (K > 4096 || N > 4096 || M < 64) return GCN_OK;
         const int nt_total = (int)((N + 15) / 16);
-        const int NT = nt_total >= 4 ? 4 : nt_total;
+        // tiles per wavefront: as many as fit (whole rows of C from one wavefront when N <= 256), while
+        // op(B) for them stays within 40 KB of LDS
+        const int64_t kpad = (K + 15) & ~15ll;
+        int NT = nt_total >= 4 ? 4 : nt_total;
+        if (nt_total >= 16 && kpad * (16 * 16 + 4) * 4 <= 40 * 1024) NT = 16;
+        else if (nt_total >= 8 && kpad * (16 * 8 + 4) * 4 <= 40 * 1024) NT = 8;
         TallArgs args;
         args.M = M; args.N = (int32_t)N; args.K = (int32_t)K;
         args.A = A; args.lda = lda; args.B = B; args.ldb = ldb; args.tb = tb;
@@ -316,7 +358,9 @@ int gemm_mfma_launch(int ta, int tb, int64_t M, int64_t N, int64_t K, const floa
             case 1: launch_tall<1>(args, epilogue, grid, lds, s); break;
             case 2: launch_tall<2>(args, epilogue, grid, lds, s); break;
             case 3: launch_tall<3>(args, epilogue, grid, lds, s); break;
-            default: launch_tall<4>(args, epilogue, grid, lds, s); break;
+            case 4: launch_tall<4>(args, epilogue, grid, lds, s); break;
+            case 8: launch_tall<8>(args, epilogue, grid, lds, s); break;
+            default: launch_tall<16>(args, epilogue, grid, lds, s); break;
         }
         GCN_LAUNCH_CHECK();
         *handled = true;

@@ -28,6 +28,7 @@ static bool use_pattern(const gcn_csr* a) {
 // or NULL to force the valued product.
 static int norm_spmm(gcn_csr* a, Matrix& m, int32_t f, const float* X, int64_t ldx, float* xs, float* Z, int64_t ldz,
                      int epilogue, const float* Zprev, int64_t ldzprev, hipStream_t s) {
+    PhaseTimer pt(s, GCN_PHASE_SPMM);
     if (!xs || !use_pattern(a)) return spmm_launch(a, m, f, X, ldx, Z, ldz, epilogue, Zprev, ldzprev, s);
     GCN_TRY(scale_rows_launch(a->n, f, X, ldx, a->inv_sqrt_deg, xs, f, s));
     SpmmOpt o;
@@ -38,6 +39,13 @@ static int norm_spmm(gcn_csr* a, Matrix& m, int32_t f, const float* X, int64_t l
 
 // `xs`: scratch for the value-free product (n x the SpMM width) or NULL; `t_scratch` says that T is
 // a pure temporary which may be overwritten by its scaled copy.
+static int timed_gemm(int ta, int tb, int64_t M, int64_t N, int64_t K, const float* A, int64_t lda, const float* B,
+                      int64_t ldb, float* C, int64_t ldc, const float* bias, int epilogue, const float* Zprev,
+                      int64_t ldzprev, hipStream_t s) {
+    PhaseTimer pt(s, GCN_PHASE_GEMM);
+    return gemm_launch(ta, tb, M, N, K, A, lda, B, ldb, C, ldc, bias, epilogue, Zprev, ldzprev, s);
+}
+
 static int layer_forward_impl(gcn_csr* a, int32_t f_in, int32_t f_out, const float* Hin, int64_t ldh, const float* W,
                               const float* bias, float* Z, float* Hout, float* T, int order, int act, hipStream_t s,
                               float* xs = nullptr, bool t_scratch = false) {
@@ -47,15 +55,19 @@ static int layer_forward_impl(gcn_csr* a, int32_t f_in, int32_t f_out, const flo
     // the kernel that produces Z; otherwise Z is kept (backward needs it) and H is a second pass.
     const bool in_place = (act == GCN_ACT_RELU) && Hout == Z;
     if (order == GCN_ORDER_GEMM_FIRST) {
-        GCN_TRY(gemm_launch(0, 0, n, f_out, f_in, Hin, ldh, W, f_out, T, f_out, nullptr, GCN_EPI_NONE, nullptr, 0, s));
+        GCN_TRY(timed_gemm(0, 0, n, f_out, f_in, Hin, ldh, W, f_out, T, f_out, nullptr, GCN_EPI_NONE, nullptr, 0, s));
         GCN_TRY(norm_spmm(a, a->At, f_out, T, f_out, t_scratch ? T : xs, Z, f_out,
                           (in_place && !bias) ? GCN_EPI_RELU : GCN_EPI_NONE, nullptr, 0, s));
-        if (bias) GCN_TRY(bias_add_launch(n, f_out, Z, f_out, bias, in_place ? 1 : 0, s));
+        if (bias) {
+            PhaseTimer pt(s, GCN_PHASE_OTHER);
+            GCN_TRY(bias_add_launch(n, f_out, Z, f_out, bias, in_place ? 1 : 0, s));
+        }
     } else {
         GCN_TRY(norm_spmm(a, a->At, f_in, Hin, ldh, xs, T, f_in, GCN_EPI_NONE, nullptr, 0, s));
-        GCN_TRY(gemm_launch(0, 0, n, f_out, f_in, T, f_in, W, f_out, Z, f_out, bias,
+        GCN_TRY(timed_gemm(0, 0, n, f_out, f_in, T, f_in, W, f_out, Z, f_out, bias,
                             in_place ? GCN_EPI_RELU : GCN_EPI_NONE, nullptr, 0, s));
     }
+    PhaseTimer pt(s, GCN_PHASE_OTHER);
     if (act == GCN_ACT_RELU && !in_place) GCN_TRY(relu_launch(n, f_out, Z, f_out, Hout, f_out, s));
     if (act == GCN_ACT_NONE && Hout && Hout != Z)
         GCN_HIP_TRY(hipMemcpyAsync(Hout, Z, (size_t)n * f_out * sizeof(float), hipMemcpyDeviceToDevice, s));
@@ -68,19 +80,22 @@ static int layer_backward_impl(gcn_csr* a, int32_t f_in, int32_t f_out, const fl
                                bool s_scratch = false) {
     const int64_t n = a->n;
     order = resolve_order(order, f_in, f_out);
-    if (dbias) GCN_TRY(colsum_launch(n, f_out, G, f_out, dbias, s));
+    if (dbias) {
+        PhaseTimer pt(s, GCN_PHASE_OTHER);
+        GCN_TRY(colsum_launch(n, f_out, G, f_out, dbias, s));
+    }
     if (order == GCN_ORDER_GEMM_FIRST) {
         // S = A G;  Y = Hin^T S;  Gprev = (S W^T) (.) sigma'(Zprev)
         GCN_TRY(norm_spmm(a, a->A, f_out, G, f_out, xs, S, f_out, GCN_EPI_NONE, nullptr, 0, s));
-        GCN_TRY(gemm_launch(1, 0, f_in, f_out, n, Hin, ldh, S, f_out, Y, f_out, nullptr, GCN_EPI_NONE, nullptr, 0, s));
+        GCN_TRY(timed_gemm(1, 0, f_in, f_out, n, Hin, ldh, S, f_out, Y, f_out, nullptr, GCN_EPI_NONE, nullptr, 0, s));
         if (Gprev)
-            GCN_TRY(gemm_launch(0, 1, n, f_in, f_out, S, f_out, W, f_out, Gprev, f_in, nullptr, GCN_EPI_MASK, Zprev, f_in, s));
+            GCN_TRY(timed_gemm(0, 1, n, f_in, f_out, S, f_out, W, f_out, Gprev, f_in, nullptr, GCN_EPI_MASK, Zprev, f_in, s));
     } else {
         // Y = (A^T Hin)^T G = T^T G;  Gprev = (A (G W^T)) (.) sigma'(Zprev): the same matrices, with the
         // SpMM at width f_in.
-        GCN_TRY(gemm_launch(1, 0, f_in, f_out, n, T, f_in, G, f_out, Y, f_out, nullptr, GCN_EPI_NONE, nullptr, 0, s));
+        GCN_TRY(timed_gemm(1, 0, f_in, f_out, n, T, f_in, G, f_out, Y, f_out, nullptr, GCN_EPI_NONE, nullptr, 0, s));
         if (Gprev) {
-            GCN_TRY(gemm_launch(0, 1, n, f_in, f_out, G, f_out, W, f_out, S, f_in, nullptr, GCN_EPI_NONE, nullptr, 0, s));
+            GCN_TRY(timed_gemm(0, 1, n, f_in, f_out, G, f_out, W, f_out, S, f_in, nullptr, GCN_EPI_NONE, nullptr, 0, s));
             GCN_TRY(norm_spmm(a, a->A, f_in, S, f_in, s_scratch ? S : xs, Gprev, f_in, GCN_EPI_MASK, Zprev, f_in, s));
         }
     }
@@ -207,14 +222,18 @@ int gcn_epoch_masked(gcn_csr* a, int32_t L_w, const int32_t* dims, const float* 
                                    last ? GCN_ACT_NONE : GCN_ACT_RELU, s, at(lay.XS), true));
         Hin = at(lay.H[l]);
     }
-    GCN_TRY(gcn_softmax_nll_masked(n, dims[L_w], at(lay.Z[L_w - 1]), dims[L_w], labels, n_labelled, loss,
-                                   at(lay.G[L_w - 1]), dims[L_w], stream));
+    {
+        PhaseTimer pt(s, GCN_PHASE_OTHER);
+        GCN_TRY(gcn_softmax_nll_masked(n, dims[L_w], at(lay.Z[L_w - 1]), dims[L_w], labels, n_labelled, loss,
+                                       at(lay.G[L_w - 1]), dims[L_w], stream));
+    }
     for (int l = L_w - 1; l >= 0; --l) {
         const float* Hl = l > 0 ? at(lay.H[l - 1]) : H0;
         GCN_TRY(layer_backward_impl(a, dims[l], dims[l + 1], Hl, dims[l], l > 0 ? at(lay.Z[l - 1]) : nullptr, W[l],
                                     at(lay.G[l]), at(lay.T[l]), at(lay.S), Y[l], nullptr, l > 0 ? at(lay.G[l - 1]) : nullptr,
                                     lay.order[l], s, at(lay.XS), true));
     }
+    PhaseTimer pt(s, GCN_PHASE_OTHER);
     if (lr != 0.f)
         for (int l = 0; l < L_w; ++l) GCN_TRY(axpy_launch((int64_t)dims[l] * dims[l + 1], W[l], Y[l], lr, s));
     return GCN_OK;
