@@ -221,6 +221,16 @@ int gcn_epoch(gcn_csr* a, int32_t L_w, const int32_t* dims, const float* H0, con
 int gcn_epoch_masked(gcn_csr* a, int32_t L_w, const int32_t* dims, const float* H0, const int32_t* labels,
                      int64_t n_labelled, float* const* W, float* const* Y, float lr, float* loss, void* workspace,
                      size_t workspace_bytes, int order, void* stream);
+
+/* The same epoch for a caller that trains many epochs on fixed input features: "Forward Propagation"
+ * computes Z^1 = (A^T H^0) W^1 and Equation 3 gives Y^1 = (A^T H^0)^T G^1, and A^T H^0 does not change
+ * between epochs.  P0 (device, n x dims[0] dense) is that product, computed once by the caller with
+ * gcn_spmm(a, 1, dims[0], H0, ...); the first layer then needs no sparse product in either direction.
+ * Everything else (arguments, workspace, views, results up to fp32 summation order) as gcn_epoch_masked;
+ * `order` applies to layers 2..L_w. */
+int gcn_epoch_preaggregated(gcn_csr* a, int32_t L_w, const int32_t* dims, const float* P0, const int32_t* labels,
+                            int64_t n_labelled, float* const* W, float* const* Y, float lr, float* loss,
+                            void* workspace, size_t workspace_bytes, int order, void* stream);
 size_t gcn_epoch_workspace_bytes(int64_t n, int32_t L_w, const int32_t* dims, int order);
 
 /* After gcn_epoch: device pointers into the workspace for layer l in [1, L_w], both n x dims[l]

@@ -281,6 +281,19 @@ def gcn_epoch_masked(a: Csr, dims, H0, labels, n_labelled: int, W, Y, lr: float,
     return loss
 
 
+def gcn_epoch_preaggregated(a: Csr, dims, P0, labels, n_labelled: int, W, Y, lr: float, loss, workspace,
+                            order: int = ORDER_AUTO):
+    L = len(dims) - 1
+    assert len(W) == L and len(Y) == L and P0.is_contiguous() and tuple(P0.shape) == (a.n, dims[0])
+    Wp = (C.c_void_p * L)(*[w.data_ptr() for w in W])
+    Yp = (C.c_void_p * L)(*[y.data_ptr() for y in Y])
+    _check(lib().gcn_epoch_preaggregated(a._h, C.c_int32(L), _dims_array(dims), _ptr(P0), _ptr(labels),
+                                         C.c_int64(n_labelled), Wp, Yp, C.c_float(lr), _ptr(loss), _ptr(workspace),
+                                         C.c_size_t(workspace.numel() * workspace.element_size()), int(order),
+                                         _stream()))
+    return loss
+
+
 def gcn_epoch_view(n: int, dims, order: int, workspace, layer: int):
     """(Z^l, G^l) of the last gcn_epoch call as torch tensors aliasing the workspace."""
     import torch

@@ -48,7 +48,7 @@ static int timed_gemm(int ta, int tb, int64_t M, int64_t N, int64_t K, const flo
 
 static int layer_forward_impl(gcn_csr* a, int32_t f_in, int32_t f_out, const float* Hin, int64_t ldh, const float* W,
                               const float* bias, float* Z, float* Hout, float* T, int order, int act, hipStream_t s,
-                              float* xs = nullptr, bool t_scratch = false) {
+                              float* xs = nullptr, bool t_scratch = false, bool t_given = false) {
     const int64_t n = a->n;
     order = resolve_order(order, f_in, f_out);
     // When the caller passes Hout == Z only the activated matrix is wanted and ReLU is fused into
@@ -63,7 +63,8 @@ static int layer_forward_impl(gcn_csr* a, int32_t f_in, int32_t f_out, const flo
             GCN_TRY(bias_add_launch(n, f_out, Z, f_out, bias, in_place ? 1 : 0, s));
         }
     } else {
-        GCN_TRY(norm_spmm(a, a->At, f_in, Hin, ldh, xs, T, f_in, GCN_EPI_NONE, nullptr, 0, s));
+        // t_given: T already holds A^T Hin (aggregated once by the caller; Hin itself is not read)
+        if (!t_given) GCN_TRY(norm_spmm(a, a->At, f_in, Hin, ldh, xs, T, f_in, GCN_EPI_NONE, nullptr, 0, s));
         GCN_TRY(timed_gemm(0, 0, n, f_out, f_in, T, f_in, W, f_out, Z, f_out, bias,
                             in_place ? GCN_EPI_RELU : GCN_EPI_NONE, nullptr, 0, s));
     }
@@ -194,10 +195,10 @@ int gcn_epoch(gcn_csr* a, int32_t L_w, const int32_t* dims, const float* H0, con
     return gcn_epoch_masked(a, L_w, dims, H0, labels, a->n, W, Y, lr, loss, workspace, workspace_bytes, order, stream);
 }
 
-int gcn_epoch_masked(gcn_csr* a, int32_t L_w, const int32_t* dims, const float* H0, const int32_t* labels,
-                     int64_t n_labelled, float* const* W, float* const* Y, float lr, float* loss, void* workspace,
-                     size_t workspace_bytes, int order, void* stream) {
-    if (!a || !H0 || !labels || !W || !Y || !loss || !workspace) return fail(GCN_ERR_BADARG, "gcn_epoch: NULL argument");
+static int epoch_impl(gcn_csr* a, int32_t L_w, const int32_t* dims, const float* H0, const float* P0,
+                      const int32_t* labels, int64_t n_labelled, float* const* W, float* const* Y, float lr, float* loss,
+                      void* workspace, size_t workspace_bytes, int order, void* stream) {
+    if (!a || !(H0 || P0) || !labels || !W || !Y || !loss || !workspace) return fail(GCN_ERR_BADARG, "gcn_epoch: NULL argument");
     if (n_labelled <= 0 || n_labelled > a->n) return fail(GCN_ERR_BADARG, "gcn_epoch: n_labelled must be in [1, n]");
     GCN_TRY(check_dims(a->n, L_w, dims));
     if (order < GCN_ORDER_AUTO || order > GCN_ORDER_SPMM_FIRST) return fail(GCN_ERR_BADARG, "gcn_epoch: unknown order");
@@ -213,13 +214,17 @@ int gcn_epoch_masked(gcn_csr* a, int32_t L_w, const int32_t* dims, const float* 
     hipStream_t s = (hipStream_t)stream;
     char* ws = (char*)workspace;
     auto at = [&](size_t off) { return (float*)(ws + off); };
+    // With P0 = A^T H0 given, layer 1 runs in SpMM-first order on it: Z^1 = P0 W^1, Y^1 = P0^T G^1, and
+    // neither direction needs a sparse product.
+    auto layer_order = [&](int l) { return (l == 0 && P0) ? (int)GCN_ORDER_SPMM_FIRST : lay.order[l]; };
+    auto layer_T = [&](int l) { return (l == 0 && P0) ? const_cast<float*>(P0) : at(lay.T[l]); };
 
     const float* Hin = H0;
     for (int l = 0; l < L_w; ++l) {
         const bool last = (l + 1 == L_w);
         GCN_TRY(layer_forward_impl(a, dims[l], dims[l + 1], Hin, dims[l], W[l], nullptr, at(lay.Z[l]),
-                                   last ? nullptr : at(lay.Z[l]), at(lay.T[l]), lay.order[l],
-                                   last ? GCN_ACT_NONE : GCN_ACT_RELU, s, at(lay.XS), true));
+                                   last ? nullptr : at(lay.Z[l]), layer_T(l), layer_order(l),
+                                   last ? GCN_ACT_NONE : GCN_ACT_RELU, s, at(lay.XS), true, l == 0 && P0));
         Hin = at(lay.H[l]);
     }
     {
@@ -230,13 +235,29 @@ int gcn_epoch_masked(gcn_csr* a, int32_t L_w, const int32_t* dims, const float* 
     for (int l = L_w - 1; l >= 0; --l) {
         const float* Hl = l > 0 ? at(lay.H[l - 1]) : H0;
         GCN_TRY(layer_backward_impl(a, dims[l], dims[l + 1], Hl, dims[l], l > 0 ? at(lay.Z[l - 1]) : nullptr, W[l],
-                                    at(lay.G[l]), at(lay.T[l]), at(lay.S), Y[l], nullptr, l > 0 ? at(lay.G[l - 1]) : nullptr,
-                                    lay.order[l], s, at(lay.XS), true));
+                                    at(lay.G[l]), layer_T(l), at(lay.S), Y[l], nullptr, l > 0 ? at(lay.G[l - 1]) : nullptr,
+                                    layer_order(l), s, at(lay.XS), true));
     }
     PhaseTimer pt(s, GCN_PHASE_OTHER);
     if (lr != 0.f)
         for (int l = 0; l < L_w; ++l) GCN_TRY(axpy_launch((int64_t)dims[l] * dims[l + 1], W[l], Y[l], lr, s));
     return GCN_OK;
+}
+
+int gcn_epoch_masked(gcn_csr* a, int32_t L_w, const int32_t* dims, const float* H0, const int32_t* labels,
+                     int64_t n_labelled, float* const* W, float* const* Y, float lr, float* loss, void* workspace,
+                     size_t workspace_bytes, int order, void* stream) {
+    if (!H0) return fail(GCN_ERR_BADARG, "gcn_epoch: NULL argument");
+    return epoch_impl(a, L_w, dims, H0, nullptr, labels, n_labelled, W, Y, lr, loss, workspace, workspace_bytes, order,
+                      stream);
+}
+
+int gcn_epoch_preaggregated(gcn_csr* a, int32_t L_w, const int32_t* dims, const float* P0, const int32_t* labels,
+                            int64_t n_labelled, float* const* W, float* const* Y, float lr, float* loss,
+                            void* workspace, size_t workspace_bytes, int order, void* stream) {
+    if (!P0) return fail(GCN_ERR_BADARG, "gcn_epoch_preaggregated: NULL argument");
+    return epoch_impl(a, L_w, dims, nullptr, P0, labels, n_labelled, W, Y, lr, loss, workspace, workspace_bytes, order,
+                      stream);
 }
 
 }  // extern "C"

@@ -776,6 +776,33 @@ def test_epoch_value_free_spmm_on_and_off(mode, order):
         g.gcn_config(g.CFG_PATTERN_SPMM, 2)
 
 
+@pytest.mark.parametrize("name,cfg,shrink", [("c1", 1, 1), ("c3s", 3, 32), ("c4s", 4, 256)])
+def test_epoch_with_first_layer_aggregated_once(name, cfg, shrink):
+    """A^T H0 computed once outside the epoch: Z^1 = (A^T H0) W^1 and Y^1 = (A^T H0)^T G^1 are the paper's
+    own association order, so loss and gradients equal the oracle's epoch."""
+    g = G()
+    w = synth.scaled(cfg, shrink)
+    a = gpu_csr(name)
+    A = oracle_csr(name)
+    H0, y, Ws = synth.make_model_inputs(dataclass_with_n(w, A.n))
+    dims = list(w.dims)
+    P0 = torch.empty(A.n, dims[0], device="cuda")
+    g.gcn_spmm(a, 1, dev(H0), P0)
+    Wd = [dev(x) for x in Ws]
+    Yd = [torch.empty_like(x) for x in Wd]
+    ws = torch.empty(g.gcn_epoch_workspace_bytes(A.n, dims, 0), dtype=torch.uint8, device="cuda")
+    loss = torch.zeros(1, device="cuda")
+    g.gcn_epoch_preaggregated(a, dims, P0, dev(y), A.n, Wd, Yd, 0.0, loss, ws, 0)
+    torch.cuda.synchronize()
+    ref = oracle.epoch(A, A, H0, y, Ws, 0.0)
+    assert abs(loss.item() - ref["loss"]) <= 1e-4 * abs(ref["loss"])
+    for l in range(len(dims) - 1):
+        assert rel_fro(host(Yd[l]), ref["Y"][l]) <= 2e-4, (l, rel_fro(host(Yd[l]), ref["Y"][l]))
+    Zl, Gl = g.gcn_epoch_view(A.n, dims, 0, ws, len(dims) - 1)
+    assert rel_fro(host(Zl), ref["Z"][len(dims) - 2]) <= 1e-4
+    a.close()
+
+
 def test_epoch_sgd_step_and_workspace_check():
     w = synth.CONFIGS[1]
     g, a, A, dims, Wd, Yd, ws, loss, ref, (H0, y, Ws) = run_epoch("c1", w, 0, lr=0.5)
