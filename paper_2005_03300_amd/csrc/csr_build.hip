@@ -419,47 +419,81 @@ int build_blocked(Matrix& m, int64_t nnz, int64_t cpb, hipStream_t s) {
 
 struct SweepPayload { int32_t col; float val; int32_t row; };
 
-// One thread per task: deal the task's light rows to `groups` queues, longest row first, each to the
-// queue with the fewest entries so far.  Writes the queue of every row and the task's stored length
-// (groups x the longest queue).
-__global__ void k_sweep_assign(int64_t ntasks, int64_t n, const int64_t* __restrict__ rowptr, int32_t rb, int32_t groups,
-                               int32_t heavy_th, uint8_t* __restrict__ qrow, int32_t* __restrict__ task_len,
-                               uint32_t* __restrict__ sort_key, int64_t* __restrict__ padded_len) {
+// One thread per task walks the task's entries in ascending column order and packs them into steps
+// of `groups` entries whose rows are all different (the lane groups of a step then add to different
+// rows in LDS).  An entry whose row is already in the step waits in a short list and opens one of the
+// next steps, so the stored order stays within a few steps of the column order.  With out == NULL
+// only the number of steps is counted (task_len, sort_key, padded_len); otherwise the entries are
+// written to task_base[t] + step*groups + slot.
+__global__ void k_sweep_pack(int64_t ntasks, int32_t rb, int32_t groups, const int64_t* __restrict__ task_ptr,
+                             const SweepPayload* __restrict__ payload, const int64_t* __restrict__ task_base,
+                             int32_t* __restrict__ colidx, float* __restrict__ val, uint8_t* __restrict__ lrow,
+                             int32_t* __restrict__ task_len, uint32_t* __restrict__ sort_key,
+                             int64_t* __restrict__ padded_len) {
     const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (t >= ntasks) return;
-    const int64_t r0 = t * rb;
-    const int cnt = (int)(n - r0 < rb ? n - r0 : rb);
-    int deg[256];
-    int load[16];
-    for (int g = 0; g < 16; ++g) load[g] = 0;
-    for (int i = 0; i < cnt; ++i) {
-        const int64_t d = rowptr[r0 + i + 1] - rowptr[r0 + i];
-        deg[i] = d > heavy_th ? 0 : (int)d;
+    constexpr int D = 24;                       // entries that may wait at one time
+    const int64_t lo = task_ptr[t], hi = task_ptr[t + 1];
+    const int64_t base = task_base ? task_base[t] : 0;
+    int64_t wait[D];
+    int nw = 0;
+    int64_t i = lo, step = 0;
+    while (i < hi || nw > 0) {
+        uint64_t m0 = 0, m1 = 0, m2 = 0, m3 = 0;                    // rows (0..255) present in this step
+        int cnt = 0;
+        auto taken = [&](int r) {
+            const uint64_t bit = 1ull << (r & 63);
+            const int q = r >> 6;
+            return ((q == 0 ? m0 : q == 1 ? m1 : q == 2 ? m2 : m3) & bit) != 0;
+        };
+        auto take = [&](int r) {
+            const uint64_t bit = 1ull << (r & 63);
+            const int q = r >> 6;
+            if (q == 0) m0 |= bit; else if (q == 1) m1 |= bit; else if (q == 2) m2 |= bit; else m3 |= bit;
+        };
+        auto emit = [&](int64_t pos, int r) {
+            if (colidx) {
+                const SweepPayload pl = payload[pos];
+                const int64_t dst = base + step * groups + cnt;
+                colidx[dst] = pl.col;
+                val[dst] = pl.val;
+                lrow[dst] = (uint8_t)r;
+            }
+            ++cnt;
+        };
+        int keep = 0;
+        for (int d = 0; d < nw; ++d) {                              // waiting entries first, oldest first
+            const int64_t pos = wait[d];
+            const int r = payload[pos].row % rb;
+            if (cnt < groups && !taken(r)) { take(r); emit(pos, r); }
+            else wait[keep++] = pos;
+        }
+        nw = keep;
+        while (cnt < groups && i < hi) {
+            const int r = payload[i].row % rb;
+            if (taken(r)) {
+                if (nw == D) break;                                 // close the step short rather than reorder further
+                wait[nw++] = i++;
+            } else {
+                take(r);
+                emit(i++, r);
+            }
+        }
+        ++step;                                                     // every step places at least one entry
     }
-    for (int k = 0; k < cnt; ++k) {
-        int best = 0, bd = -1;
-        for (int i = 0; i < cnt; ++i)
-            if (deg[i] > bd) { bd = deg[i]; best = i; }
-        int gmin = 0;
-        for (int g = 1; g < groups; ++g)
-            if (load[g] < load[gmin]) gmin = g;
-        qrow[r0 + best] = (uint8_t)gmin;
-        load[gmin] += bd;
-        deg[best] = -1;
+    if (!colidx) {
+        const int64_t len = step * groups;
+        task_len[t] = (int32_t)len;
+        sort_key[t] = (uint32_t)len;
+        padded_len[t] = (len + 15) & ~15ll;
     }
-    int longest = 0;
-    for (int g = 0; g < groups; ++g) longest = load[g] > longest ? load[g] : longest;
-    const int64_t len = (int64_t)longest * groups;
-    task_len[t] = (int32_t)len;
-    sort_key[t] = (uint32_t)len;
-    padded_len[t] = (len + 15) & ~15ll;
 }
 
-// key = task | queue(4 bits) | column for entries of light rows, one bit above that for entries of
-// heavy rows (they sort behind everything and keep their (row, col) order: the sort is stable).
+// key = task | column for entries of light rows, one bit above that for entries of heavy rows (they
+// sort behind everything and keep their (row, col) order: the sort is stable).
 __global__ void k_sweep_keys(int64_t nnz, int64_t n, const int64_t* __restrict__ rowptr,
                              const int32_t* __restrict__ colidx, const float* __restrict__ val, int32_t rb,
-                             int32_t heavy_th, unsigned cbits, uint64_t heavy_key, const uint8_t* __restrict__ qrow,
+                             int32_t heavy_th, unsigned cbits, uint64_t heavy_key,
                              uint64_t* __restrict__ keys, SweepPayload* __restrict__ payload) {
     int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (k >= nnz) return;
@@ -471,11 +505,11 @@ __global__ void k_sweep_keys(int64_t nnz, int64_t n, const int64_t* __restrict__
     const int32_t col = colidx[k];
     const bool heavy = rowptr[lo + 1] - rowptr[lo] > heavy_th;
     keys[k] = heavy ? heavy_key
-                    : ((((uint64_t)(lo / rb) << 4) | (uint64_t)qrow[lo]) << cbits) | (uint64_t)(uint32_t)col;
+                    : ((uint64_t)(lo / rb) << cbits) | (uint64_t)(uint32_t)col;
     payload[k] = SweepPayload{col, val[k], (int32_t)lo};
 }
 
-// seg_ptr[t*16 + g] = first sorted position of queue g of task t; seg_ptr[ntasks*16] = light entries
+// seg_ptr[t] = first sorted position of task t; seg_ptr[ntasks] = number of light entries
 __global__ void k_sweep_seg_ptr(int64_t nseg, int64_t nnz, unsigned cbits, uint64_t heavy_key,
                                 const uint64_t* __restrict__ keys, int64_t* __restrict__ seg_ptr) {
     int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -494,23 +528,14 @@ __global__ void k_iota_i32(int64_t count, int32_t* __restrict__ out) {
     if (t < count) out[t] = (int32_t)t;
 }
 
-// Sorted position p of queue g of task t goes to task_base[t] + rank*groups + g (rank inside the
-// queue); with task_base == NULL the output is dense (the heavy rows, whose local row is not needed).
-__global__ void k_sweep_unpack(int64_t count, int64_t first, int32_t rb, int32_t groups, unsigned cbits,
-                               const uint64_t* __restrict__ keys, const SweepPayload* __restrict__ payload,
-                               const int64_t* __restrict__ seg_ptr, const int64_t* __restrict__ task_base,
-                               int32_t* __restrict__ colidx, float* __restrict__ val, uint8_t* __restrict__ lrow) {
+// Heavy rows: sorted position first + k goes to position k of their own arrays.
+__global__ void k_sweep_unpack(int64_t count, int64_t first, const SweepPayload* __restrict__ payload,
+                               int32_t* __restrict__ colidx, float* __restrict__ val) {
     int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (k >= count) return;
     const SweepPayload p = payload[first + k];
-    int64_t dst = k;
-    if (task_base) {
-        const int64_t seg = (int64_t)(keys[k] >> cbits);          // task*16 + queue
-        dst = task_base[seg >> 4] + (k - seg_ptr[seg]) * groups + (seg & 15);
-    }
-    colidx[dst] = p.col;
-    val[dst] = p.val;
-    if (lrow) lrow[dst] = (uint8_t)(p.row % rb);
+    colidx[k] = p.col;
+    val[k] = p.val;
 }
 
 struct HeavyRow {
@@ -535,25 +560,50 @@ int build_sweep(Matrix& m, int64_t nnz, int32_t groups, int32_t rb, int32_t heav
     const int64_t ntasks = (n + rb - 1) / rb;
     const unsigned cbits = bits_for(m.ncols);
     const unsigned tbits = bits_for(ntasks + 1);
-    if (cbits + 4 + tbits + 1 > 63) return fail(GCN_ERR_RANGE, "build_sweep: key does not fit");
-    const uint64_t heavy_key = 1ull << (cbits + 4 + tbits);
+    if (cbits + tbits + 1 > 63) return fail(GCN_ERR_RANGE, "build_sweep: key does not fit");
+    const uint64_t heavy_key = 1ull << (cbits + tbits);
 
+    // entries sorted by (task, column); heavy rows behind them in (row, column) order
+    TempBuf k0, k1, p0, p1, seg, tmp;
+    GCN_TRY(k0.alloc((size_t)nnz * 8));
+    GCN_TRY(k1.alloc((size_t)nnz * 8));
+    GCN_TRY(p0.alloc((size_t)nnz * sizeof(SweepPayload)));
+    GCN_TRY(p1.alloc((size_t)nnz * sizeof(SweepPayload)));
+    hipLaunchKernelGGL(k_sweep_keys, dim3(blocks_for(nnz)), dim3(TPB), 0, s, nnz, n, m.rowptr, m.colidx, m.val, rb, heavy_th,
+                       cbits, heavy_key, k0.as<uint64_t>(), p0.as<SweepPayload>());
+    GCN_LAUNCH_CHECK();
+    size_t tmp_bytes = 0;
+    const unsigned end_bit = cbits + tbits + 1;
+    GCN_HIP_TRY(rocprim::radix_sort_pairs(nullptr, tmp_bytes, k0.as<uint64_t>(), k1.as<uint64_t>(), p0.as<SweepPayload>(),
+                                          p1.as<SweepPayload>(), (size_t)nnz, 0u, end_bit, s));
+    GCN_TRY(tmp.alloc(tmp_bytes));
+    GCN_HIP_TRY(rocprim::radix_sort_pairs(tmp.p, tmp_bytes, k0.as<uint64_t>(), k1.as<uint64_t>(), p0.as<SweepPayload>(),
+                                          p1.as<SweepPayload>(), (size_t)nnz, 0u, end_bit, s));
+    GCN_HIP_TRY(hipStreamSynchronize(s));
+    k0.alloc(16);
+    p0.alloc(16);
+    GCN_TRY(seg.alloc(((size_t)ntasks + 1) * 8));
+    hipLaunchKernelGGL(k_sweep_seg_ptr, dim3(blocks_for(ntasks + 1)), dim3(TPB), 0, s, ntasks, nnz, cbits, heavy_key,
+                       k1.as<uint64_t>(), seg.as<int64_t>());
+    GCN_LAUNCH_CHECK();
+    k1.alloc(16);
+
+    // pass 1: steps per task; then the longest-first order and the offsets of the tasks
     GCN_TRY(device_alloc_t(&w.task_base, (size_t)ntasks));
     GCN_TRY(device_alloc_t(&w.task_len, (size_t)ntasks));
     GCN_TRY(device_alloc_t(&w.task_order, (size_t)ntasks));
-    TempBuf qrow, ids, len, len_sorted, plen, tmp;
-    GCN_TRY(qrow.alloc((size_t)n));
+    TempBuf ids, len, len_sorted, plen;
     GCN_TRY(ids.alloc((size_t)ntasks * 4));
     GCN_TRY(len.alloc((size_t)ntasks * 4));
     GCN_TRY(len_sorted.alloc((size_t)ntasks * 4));
     GCN_TRY(plen.alloc((size_t)ntasks * 8));
-    GCN_HIP_TRY(hipMemsetAsync(qrow.p, 0, (size_t)n, s));
-    hipLaunchKernelGGL(k_sweep_assign, dim3(blocks_for(ntasks, 64)), dim3(64), 0, s, ntasks, n, m.rowptr, rb, groups, heavy_th,
-                       qrow.as<uint8_t>(), w.task_len, len.as<uint32_t>(), plen.as<int64_t>());
+    hipLaunchKernelGGL(k_sweep_pack, dim3(blocks_for(ntasks, 64)), dim3(64), 0, s, ntasks, rb, groups, seg.as<int64_t>(),
+                       p1.as<SweepPayload>(), (const int64_t*)nullptr, (int32_t*)nullptr, (float*)nullptr,
+                       (uint8_t*)nullptr, w.task_len, len.as<uint32_t>(), plen.as<int64_t>());
     GCN_LAUNCH_CHECK();
     hipLaunchKernelGGL(k_iota_i32, dim3(blocks_for(ntasks)), dim3(TPB), 0, s, ntasks, ids.as<int32_t>());
     GCN_LAUNCH_CHECK();
-    size_t tmp_bytes = 0;
+    tmp_bytes = 0;
     GCN_HIP_TRY(rocprim::radix_sort_pairs_desc(nullptr, tmp_bytes, len.as<uint32_t>(), len_sorted.as<uint32_t>(),
                                                ids.as<int32_t>(), w.task_order, (size_t)ntasks, 0u, 32u, s));
     GCN_TRY(tmp.alloc(tmp_bytes));
@@ -565,33 +615,8 @@ int build_sweep(Matrix& m, int64_t nnz, int32_t groups, int32_t rb, int32_t heav
     GCN_TRY(tmp.alloc(tmp_bytes));
     GCN_HIP_TRY(rocprim::exclusive_scan(tmp.p, tmp_bytes, plen.as<int64_t>(), w.task_base, (int64_t)0, (size_t)ntasks,
                                         rocprim::plus<int64_t>(), s));
-
-    TempBuf k0, k1, p0, p1, seg;
-    GCN_TRY(k0.alloc((size_t)nnz * 8));
-    GCN_TRY(k1.alloc((size_t)nnz * 8));
-    GCN_TRY(p0.alloc((size_t)nnz * sizeof(SweepPayload)));
-    GCN_TRY(p1.alloc((size_t)nnz * sizeof(SweepPayload)));
-    hipLaunchKernelGGL(k_sweep_keys, dim3(blocks_for(nnz)), dim3(TPB), 0, s, nnz, n, m.rowptr, m.colidx, m.val, rb, heavy_th,
-                       cbits, heavy_key, qrow.as<uint8_t>(), k0.as<uint64_t>(), p0.as<SweepPayload>());
-    GCN_LAUNCH_CHECK();
-    tmp_bytes = 0;
-    const unsigned end_bit = cbits + 4 + tbits + 1;
-    GCN_HIP_TRY(rocprim::radix_sort_pairs(nullptr, tmp_bytes, k0.as<uint64_t>(), k1.as<uint64_t>(), p0.as<SweepPayload>(),
-                                          p1.as<SweepPayload>(), (size_t)nnz, 0u, end_bit, s));
-    GCN_TRY(tmp.alloc(tmp_bytes));
-    GCN_HIP_TRY(rocprim::radix_sort_pairs(tmp.p, tmp_bytes, k0.as<uint64_t>(), k1.as<uint64_t>(), p0.as<SweepPayload>(),
-                                          p1.as<SweepPayload>(), (size_t)nnz, 0u, end_bit, s));
-    GCN_HIP_TRY(hipStreamSynchronize(s));
-    k0.alloc(16);
-    p0.alloc(16);
-
-    const int64_t nseg = ntasks * 16;
-    GCN_TRY(seg.alloc(((size_t)nseg + 1) * 8));
-    hipLaunchKernelGGL(k_sweep_seg_ptr, dim3(blocks_for(nseg + 1)), dim3(TPB), 0, s, nseg, nnz, cbits, heavy_key,
-                       k1.as<uint64_t>(), seg.as<int64_t>());
-    GCN_LAUNCH_CHECK();
     int64_t nnz_light = 0, last_base = 0, last_plen = 0;
-    GCN_HIP_TRY(hipMemcpyAsync(&nnz_light, seg.as<int64_t>() + nseg, 8, hipMemcpyDeviceToHost, s));
+    GCN_HIP_TRY(hipMemcpyAsync(&nnz_light, seg.as<int64_t>() + ntasks, 8, hipMemcpyDeviceToHost, s));
     GCN_HIP_TRY(hipMemcpyAsync(&last_base, w.task_base + (ntasks - 1), 8, hipMemcpyDeviceToHost, s));
     GCN_HIP_TRY(hipMemcpyAsync(&last_plen, plen.as<int64_t>() + (ntasks - 1), 8, hipMemcpyDeviceToHost, s));
     GCN_HIP_TRY(hipStreamSynchronize(s));
@@ -608,9 +633,10 @@ int build_sweep(Matrix& m, int64_t nnz, int32_t groups, int32_t rb, int32_t heav
         GCN_HIP_TRY(hipMemsetAsync(w.lrow, 0, (size_t)padded, s));
     }
     if (nnz_light > 0) {
-        hipLaunchKernelGGL(k_sweep_unpack, dim3(blocks_for(nnz_light)), dim3(TPB), 0, s, nnz_light, (int64_t)0, rb, groups,
-                           cbits, k1.as<uint64_t>(), p1.as<SweepPayload>(), seg.as<int64_t>(), w.task_base, w.colidx, w.val,
-                           w.lrow);
+        // pass 2: the same walk, now writing the entries
+        hipLaunchKernelGGL(k_sweep_pack, dim3(blocks_for(ntasks, 64)), dim3(64), 0, s, ntasks, rb, groups, seg.as<int64_t>(),
+                           p1.as<SweepPayload>(), w.task_base, w.colidx, w.val, w.lrow, (int32_t*)nullptr,
+                           (uint32_t*)nullptr, (int64_t*)nullptr);
         GCN_LAUNCH_CHECK();
     }
     if (nnz_heavy > 0) {
@@ -619,9 +645,8 @@ int build_sweep(Matrix& m, int64_t nnz, int32_t groups, int32_t rb, int32_t heav
         w.heavy = h;
         GCN_TRY(device_alloc_t(&h->colidx, (size_t)nnz_heavy));
         GCN_TRY(device_alloc_t(&h->val, (size_t)nnz_heavy));
-        hipLaunchKernelGGL(k_sweep_unpack, dim3(blocks_for(nnz_heavy)), dim3(TPB), 0, s, nnz_heavy, nnz_light, rb, groups,
-                           cbits, k1.as<uint64_t>(), p1.as<SweepPayload>(), (const int64_t*)nullptr,
-                           (const int64_t*)nullptr, h->colidx, h->val, (uint8_t*)nullptr);
+        hipLaunchKernelGGL(k_sweep_unpack, dim3(blocks_for(nnz_heavy)), dim3(TPB), 0, s, nnz_heavy, nnz_light,
+                           p1.as<SweepPayload>(), h->colidx, h->val);
         GCN_LAUNCH_CHECK();
         // the heavy rows in ascending order, and their offsets into the heavy entry arrays
         TempBuf cnt, hl;
