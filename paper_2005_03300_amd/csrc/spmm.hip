@@ -575,8 +575,10 @@ static int grow(float** buf, size_t* have, size_t need) {
 
 // How many column blocks to cut X into so that one block of the gathered panel stays in one L2
 // (4 MB per XCD).  Blocking costs one partial row per non-empty (block,row) pair, so it only pays
-// when rows are long compared with the number of blocks (`per_block` entries per partial row at
-// least); otherwise 1 (no blocking).
+// when rows are long compared with the number of blocks: at least `per_block` entries per partial
+// row.  When 2 MB blocks would make the partial rows shorter than that, blocks of up to 6 MB are
+// still worth it (measured on the long rows of config 5: 5.6 MB blocks beat 2 MB ones); beyond
+// that 1 (no blocking).
 static int64_t choose_blocks(int64_t nrows, int64_t ncols, int64_t nnz, int32_t f, int64_t per_block) {
     const int forced = config().spmm_blocks;
     if (forced >= 1) return forced;
@@ -585,7 +587,8 @@ static int64_t choose_blocks(int64_t nrows, int64_t ncols, int64_t nnz, int32_t 
     if (xbytes <= (7ll << 19)) return 1;                  // 3.5 MB: already L2-resident
     const int64_t want = (xbytes + (2ll << 20) - 1) / (2ll << 20);
     const int64_t cap = (nnz / (nrows > 0 ? nrows : 1)) / per_block;
-    return want <= cap ? want : 1;
+    if (want <= cap) return want;
+    return (cap >= 2 && 3 * cap >= want) ? cap : 1;
 }
 
 // The nonzero-split product of one stored matrix -- the whole matrix, or the heavy rows of a sweep
@@ -664,7 +667,7 @@ int spmm_launch(gcn_csr* a, Matrix& m, int32_t f, const float* X, int64_t ldx, f
             // long rows: nonzero-split kernel over the row subset; their rows are long enough for the
             // column-blocked form to pay even with many blocks
             Matrix& h = *w.heavy;
-            const int64_t hb = choose_blocks(h.nrows, ncols, w.nnz_heavy, f, 8);
+            const int64_t hb = choose_blocks(h.nrows, ncols, w.nnz_heavy, f, 30);
             GCN_TRY(run_matrix(a, h, h.ne_rows, w.nnz_heavy, hb, f, X, ldx, Z, ldz, epilogue, Zprev, ldzprev, o, s));
         }
         return GCN_OK;
