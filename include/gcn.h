@@ -57,13 +57,18 @@ extern "C" {
 #define GCN_ACT_RELU 1
 
 /* gcn_config keys */
-#define GCN_CFG_SPMM_ALGO 1 /* 0 = automatic, 1 = one thread per output element, 2 = nonzero-split, 3 = column sweep */
+#define GCN_CFG_SPMM_ALGO 1 /* 0 = automatic, 1 = one thread per output element, 2 = nonzero-split, 3 = column sweep, 4 = hub schedule (long rows x hot columns over a packed buffer, the rest as 2) */
 #define GCN_CFG_TIMING 2    /* 1 = bracket the dominant kernels with HIP events (see gcn_timing_read) */
 #define GCN_CFG_SPMM_BLOCKS 3 /* column blocks of the SpMM: 0 = automatic, 1 = never block, k >= 2 = k blocks */
 #define GCN_CFG_SWEEP_HEAVY 4 /* rows longer than this bypass the column sweep (default 1024; >= 1) */
 #define GCN_CFG_SWEEP_WAVES 5 /* column sweep: tasks per compute unit in one launch (default 8: 8 x 16 KB of LDS accumulators per compute unit; 1..18) */
 
 #define GCN_CFG_PATTERN_SPMM 6 /* gcn_epoch on a matrix made by gcn_csr_create with GCN_NORM_SYM: use the value-free SpMM (operand rows pre-scaled by d^-1/2, output rows scaled by d^-1/2) instead of reading the stored values. 0 never, 1 always, 2 (default) when the mean row has at least 64 entries */
+
+#define GCN_CFG_HUB_MB 7   /* hub schedule: size in MB of the packed buffer that holds the rows of X selected by the columns with the most entries (default 32) */
+#define GCN_CFG_HUB_DMIN 8 /* hub schedule: rows with at least this many entries are treated as long rows (default 64) */
+
+#define GCN_CFG_HUB_BLOCK_COLS 9 /* hub schedule: columns per block of the packed buffer (0, default: about 2 MB of the gathered panel; a multiple of 64) */
 
 typedef struct gcn_csr gcn_csr; /* opaque: A (and A^T) in compressed rows, degrees, schedules */
 
@@ -258,6 +263,15 @@ int gcn_config(int key, int value);
 #define GCN_PHASE_COUNT 4
 int gcn_timing_read(int64_t* launches, double* total_ms);
 int gcn_timing_read_phases(int64_t* spans, double* total_ms);
+
+/* Which schedule the most recent sparse product of this process took (for tests and reports; not
+ * meaningful while several threads run products). */
+#define GCN_SCHED_ROWWISE 1
+#define GCN_SCHED_SPLIT 2    /* nonzero-split over the stored order */
+#define GCN_SCHED_SWEEP 3    /* column sweep (+ nonzero-split for its long rows) */
+#define GCN_SCHED_HUB 4      /* hub schedule */
+#define GCN_SCHED_BLOCKED 5  /* nonzero-split over the column-blocked copy */
+int gcn_last_spmm_schedule(void);
 
 const char* gcn_last_error(void);
 const char* gcn_version(void);

@@ -70,6 +70,8 @@ Config& config() {
     return c;
 }
 
+int g_last_schedule = 0;
+
 // ---- event timing ---------------------------------------------------------------------------
 struct TimedSpan { hipEvent_t a, b; int phase; };
 static std::mutex g_time_mu;
@@ -125,6 +127,16 @@ void free_sweep(Sweep& w) {
     w = Sweep();
 }
 
+void free_hub(Hub& h) {
+    device_free(h.hot_col);
+    device_free(h.heavy_rows);
+    device_free(h.defer);
+    device_free(h.xhot);
+    if (h.hot) { free_matrix(*h.hot); delete h.hot; }
+    if (h.rest) { free_matrix(*h.rest); delete h.rest; }
+    h = Hub();
+}
+
 void free_matrix(Matrix& m) {
     device_free(m.rowptr);
     device_free(m.colidx);
@@ -133,8 +145,10 @@ void free_matrix(Matrix& m) {
     device_free(m.sub_row);
     device_free(m.ne_rows);
     device_free(m.ne_rowptr);
+    device_free(m.empty_rows);
     free_blocked(m.blk);
     free_sweep(m.swp);
+    free_hub(m.hub);
     m = Matrix();
 }
 
@@ -147,10 +161,12 @@ extern "C" {
 const char* gcn_last_error(void) { return g_err; }
 const char* gcn_version(void) { return "gcn-hip 0.1 (gfx950)"; }
 
+int gcn_last_spmm_schedule(void) { return gcn::g_last_schedule; }
+
 int gcn_config(int key, int value) {
     switch (key) {
         case GCN_CFG_SPMM_ALGO:
-            if (value < 0 || value > 3) return fail(GCN_ERR_BADARG, "GCN_CFG_SPMM_ALGO must be 0, 1, 2 or 3");
+            if (value < 0 || value > 4) return fail(GCN_ERR_BADARG, "GCN_CFG_SPMM_ALGO must be 0, 1, 2, 3 or 4");
             config().spmm_algo = value;
             return GCN_OK;
         case GCN_CFG_SPMM_BLOCKS:
@@ -164,6 +180,18 @@ int gcn_config(int key, int value) {
         case GCN_CFG_SWEEP_HEAVY:
             if (value < 1) return fail(GCN_ERR_BADARG, "GCN_CFG_SWEEP_HEAVY must be at least 1");
             config().sweep_heavy = value;
+            return GCN_OK;
+        case GCN_CFG_HUB_MB:
+            if (value < 1 || value > 4096) return fail(GCN_ERR_BADARG, "GCN_CFG_HUB_MB must be in [1, 4096]");
+            config().hub_mb = value;
+            return GCN_OK;
+        case GCN_CFG_HUB_BLOCK_COLS:
+            if (value < 0 || (value % 64) != 0) return fail(GCN_ERR_BADARG, "GCN_CFG_HUB_BLOCK_COLS must be 0 or a multiple of 64");
+            config().hub_block_cols = value;
+            return GCN_OK;
+        case GCN_CFG_HUB_DMIN:
+            if (value < 1) return fail(GCN_ERR_BADARG, "GCN_CFG_HUB_DMIN must be at least 1");
+            config().hub_dmin = value;
             return GCN_OK;
         case GCN_CFG_PATTERN_SPMM:
             if (value < 0 || value > 2) return fail(GCN_ERR_BADARG, "GCN_CFG_PATTERN_SPMM must be 0, 1 or 2");
@@ -215,6 +243,7 @@ int gcn_csr_destroy(gcn_csr* a) {
     (void)hipDeviceSynchronize();
     free_matrix(a->A);
     free_matrix(a->At);
+    device_free(a->carry2);
     device_free(a->deg);
     device_free(a->inv_sqrt_deg);
     device_free(a->carry);

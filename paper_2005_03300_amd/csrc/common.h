@@ -85,6 +85,26 @@ struct Sweep {
     Matrix* heavy = nullptr;      // the heavy rows as a row-subset matrix (ne_rows = their ids)
 };
 
+// Hub copy of a matrix with a skewed degree distribution: A = A_hot + A_rest, where A_hot holds the
+// entries of long rows (at least `dmin` entries) whose column is one of the `H` columns with the most
+// entries, and A_rest everything else.  The rows of X that the hot columns select are packed, in
+// descending order of column length, into a buffer of their own at every product; A_hot runs over it
+// in column blocks that stay in one L2 each (every XCD works on its own blocks), A_rest runs over X
+// unchanged, and the partial rows of A_hot are added to the rows that A_rest wrote.
+struct Hub {
+    int state = 0;                // 0 not tried, 1 built, -1 tried and rejected (not skewed enough)
+    int64_t H = 0, cpb = 0;       // hot columns, columns per block (H is a multiple of cpb)
+    int32_t dmin = 0;
+    int64_t nnz_hot = 0, nnz_rest = 0, n_heavy = 0;
+    int32_t* hot_col = nullptr;   // [H] position in the packed buffer -> column
+    int32_t* heavy_rows = nullptr;// [n_heavy] the long rows, ascending
+    uint8_t* defer = nullptr;     // [nrows] 1 for a long row: A_rest stores its sum raw, A_hot's pass finishes it
+    Matrix* hot = nullptr;        // n_heavy x H, column = position in the packed buffer
+    Matrix* rest = nullptr;       // nrows x ncols
+    float* xhot = nullptr;        // [H][f] packed rows of X, grown on demand
+    size_t xhot_bytes = 0;
+};
+
 // One stored matrix in compressed rows plus its nonzero-split schedule.
 struct Matrix {
     int64_t nrows = 0, ncols = 0;
@@ -96,11 +116,13 @@ struct Matrix {
     int32_t* sub_row = nullptr;  // [nsub]  index (among non-empty rows) of the row holding entry 32j
     int32_t* ne_rows = nullptr;  // [n_ne]  non-empty row index -> row, or NULL when no row is empty
     int64_t* ne_rowptr = nullptr;// [n_ne+1] rowptr restricted to non-empty rows, or NULL (= rowptr)
+    int32_t* empty_rows = nullptr;// [nrows - n_ne] the rows without entries, or NULL when there are none
     int64_t n_ne = 0;
     int64_t nsub = 0, nchunks = 0;
     int32_t max_degree = 0;
     Blocked blk;                 // built on first use for one block width
     Sweep swp;                   // built on first use for one block width / task height
+    Hub hub;                     // built on first use for one packed-buffer size / block width
 };
 
 }  // namespace gcn
@@ -115,6 +137,8 @@ struct gcn_csr {
                                  // symmetrically, i.e. val_ij == 1/sqrt(deg_i deg_j) for every stored entry
     float* carry = nullptr;      // per-chunk partial rows for the nonzero-split SpMM
     size_t carry_bytes = 0;
+    float* carry2 = nullptr;     // the same for the second matrix of a paired launch
+    size_t carry2_bytes = 0;
     float* partial = nullptr;    // P of the column-blocked SpMM
     size_t partial_bytes = 0;
 };
@@ -135,10 +159,15 @@ struct Config {
     int spmm_blocks = 0;
     int sweep_heavy = 1024;
     int sweep_waves = 8;
+    int hub_mb = 32;             // hub schedule: size of the packed buffer of hot rows of X, MB
+    int hub_block_cols = 0;      // hub schedule: columns per block (0: about 2 MB of the gathered panel)
+    int hub_dmin = 64;           // hub schedule: rows with at least this many entries are long rows
     int pattern_spmm = 2;        // epoch: value-free SpMM for symmetric normalisation (0 never, 1 always, 2 by row length)
     int timing = 0;
 };
 Config& config();
+// schedule taken by the most recent sparse product of this process (GCN_SCHED_*), for tests and reports
+extern int g_last_schedule;
 
 // event bracketing of the dominant kernel (GCN_CFG_TIMING)
 void timing_begin(hipStream_t s, int phase = GCN_PHASE_SPMM_KERNEL);
@@ -156,6 +185,8 @@ int build_blocked(Matrix& m, int64_t nnz, int64_t cols_per_block, hipStream_t s)
 void free_blocked(Blocked& b);
 int build_sweep(Matrix& m, int64_t nnz, int32_t groups, int32_t rb, int32_t heavy_threshold, hipStream_t s);
 void free_sweep(Sweep& w);
+int build_hub(Matrix& m, int64_t nnz, int64_t H, int64_t cpb, int32_t dmin, hipStream_t s);
+void free_hub(Hub& h);
 void free_matrix(Matrix& m);
 
 // Variants of the sparse product: `pattern` ignores the stored values (every entry counts as 1),
@@ -163,6 +194,9 @@ void free_matrix(Matrix& m);
 struct SpmmOpt {
     bool pattern = false;
     const float* row_scale = nullptr;
+    // internal to the hub schedule:
+    const uint8_t* defer = nullptr;   // rows whose sum is stored raw (no scale, no epilogue)
+    bool accumulate = false;          // column-blocked reduce adds to what Z already holds
 };
 int scale_rows_launch(int64_t rows, int32_t cols, const float* X, int64_t ldx, const float* scale, float* Y, int64_t ldy,
                       hipStream_t s);

@@ -166,6 +166,10 @@ struct NonEmpty {
     const int64_t* rowptr;
     __device__ bool operator()(const int32_t& r) const { return rowptr[r + 1] > rowptr[r]; }
 };
+struct IsEmpty {
+    const int64_t* rowptr;
+    __device__ bool operator()(const int32_t& r) const { return rowptr[r + 1] == rowptr[r]; }
+};
 
 __global__ void k_ne_rowptr(int64_t n_ne, int64_t nnz, const int32_t* __restrict__ ne_rows,
                             const int64_t* __restrict__ rowptr, int64_t* __restrict__ out) {
@@ -250,6 +254,12 @@ int build_schedule(Matrix& m, int64_t n, int64_t nnz, hipStream_t s) {
         hipLaunchKernelGGL(k_ne_rowptr, dim3(blocks_for(m.n_ne + 1)), dim3(TPB), 0, s, m.n_ne, nnz, m.ne_rows,
                            m.rowptr, m.ne_rowptr);
         GCN_LAUNCH_CHECK();
+        GCN_TRY(device_alloc_t(&m.empty_rows, (size_t)(n - m.n_ne)));
+        IsEmpty epred{m.rowptr};
+        tmp_bytes = 0;
+        GCN_HIP_TRY(rocprim::select(nullptr, tmp_bytes, rows, m.empty_rows, cnt.as<size_t>(), (size_t)n, epred, s));
+        GCN_TRY(tmp.alloc(tmp_bytes));
+        GCN_HIP_TRY(rocprim::select(tmp.p, tmp_bytes, rows, m.empty_rows, cnt.as<size_t>(), (size_t)n, epred, s));
         GCN_HIP_TRY(hipStreamSynchronize(s));
         rp = m.ne_rowptr;
     }
@@ -699,6 +709,181 @@ int build_sweep(Matrix& m, int64_t nnz, int32_t groups, int32_t rb, int32_t heav
     w.nnz_light = nnz_light;
     w.nnz_heavy = nnz_heavy;
     w.n_heavy = w.heavy ? w.heavy->n_ne : 0;
+    return GCN_OK;
+}
+
+// ---- hub copy --------------------------------------------------------------------------------------------
+
+__global__ void k_col_count(int64_t nnz, const int32_t* __restrict__ colidx, int32_t* __restrict__ cnt) {
+    const int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (k < nnz) atomicAdd(cnt + colidx[k], 1);           // integer counts: the order does not matter
+}
+
+__global__ void k_hub_rank(int64_t H, const int32_t* __restrict__ hot_col, int32_t* __restrict__ rank) {
+    const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (r < H) rank[hot_col[r]] = (int32_t)r;
+}
+
+__global__ void k_hub_defer(int64_t n, const int64_t* __restrict__ rowptr, int32_t dmin, uint8_t* __restrict__ defer) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) defer[i] = rowptr[i + 1] - rowptr[i] >= dmin ? 1 : 0;
+}
+
+// flag[k] = 1 when entry k belongs to A_hot (long row, hot column); flag[nnz] = 0.
+__global__ void k_hub_flags(int64_t nnz, int64_t n, const int64_t* __restrict__ rowptr, const int32_t* __restrict__ colidx,
+                            const uint8_t* __restrict__ defer, const int32_t* __restrict__ rank,
+                            int64_t* __restrict__ flag) {
+    const int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (k > nnz) return;
+    if (k == nnz) { flag[k] = 0; return; }
+    int64_t lo = 0, hi = n;
+    while (hi - lo > 1) {
+        const int64_t mid = (lo + hi) >> 1;
+        if (rowptr[mid] <= k) lo = mid; else hi = mid;
+    }
+    flag[k] = (defer[lo] && rank[colidx[k]] >= 0) ? 1 : 0;
+}
+
+// pos = exclusive prefix sums of flag: entry k goes to A_hot[pos[k]] or to A_rest[k - pos[k]].
+__global__ void k_hub_scatter(int64_t nnz, const int32_t* __restrict__ colidx, const float* __restrict__ val,
+                              const int64_t* __restrict__ flag, const int64_t* __restrict__ pos,
+                              const int32_t* __restrict__ rank, int32_t* __restrict__ hot_colidx,
+                              float* __restrict__ hot_val, int32_t* __restrict__ rest_colidx, float* __restrict__ rest_val) {
+    const int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (k >= nnz) return;
+    const int32_t c = colidx[k];
+    if (flag[k]) {
+        hot_colidx[pos[k]] = rank[c];
+        hot_val[pos[k]] = val[k];
+    } else {
+        rest_colidx[k - pos[k]] = c;
+        rest_val[k - pos[k]] = val[k];
+    }
+}
+
+__global__ void k_hub_rest_rowptr(int64_t n, const int64_t* __restrict__ rowptr, const int64_t* __restrict__ pos,
+                                  int64_t* __restrict__ out) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i <= n) out[i] = rowptr[i] - pos[rowptr[i]];
+}
+
+__global__ void k_hub_hot_rowptr(int64_t nh, int64_t nnz_hot, const int32_t* __restrict__ heavy_rows,
+                                 const int64_t* __restrict__ rowptr, const int64_t* __restrict__ pos,
+                                 int64_t* __restrict__ out) {
+    const int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (q < nh) out[q] = pos[rowptr[heavy_rows[q]]];
+    if (q == nh) out[q] = nnz_hot;
+}
+
+void free_hub(Hub& h);
+
+int build_hub(Matrix& m, int64_t nnz, int64_t H, int64_t cpb, int32_t dmin, hipStream_t s) {
+    free_hub(m.hub);
+    Hub& h = m.hub;
+    h.state = -1;                                            // until everything below has succeeded
+    h.H = H; h.cpb = cpb; h.dmin = dmin;
+    const int64_t n = m.nrows, nc = m.ncols;
+    if (nnz <= 0 || H <= 0 || cpb <= 0 || H % cpb != 0 || H > nc || dmin < 1)
+        return fail(GCN_ERR_BADARG, "build_hub: bad parameters");
+    TempBuf cnt, cnt_sorted, ids, cols_sorted, rank, flag, pos, tmp, hc;
+    size_t tmp_bytes = 0;
+
+    // the H columns with the most entries, in descending order of length
+    GCN_TRY(cnt.alloc((size_t)nc * 4));
+    GCN_TRY(cnt_sorted.alloc((size_t)nc * 4));
+    GCN_TRY(ids.alloc((size_t)nc * 4));
+    GCN_TRY(cols_sorted.alloc((size_t)nc * 4));
+    GCN_HIP_TRY(hipMemsetAsync(cnt.p, 0, (size_t)nc * 4, s));
+    hipLaunchKernelGGL(k_col_count, dim3(blocks_for(nnz)), dim3(TPB), 0, s, nnz, m.colidx, cnt.as<int32_t>());
+    GCN_LAUNCH_CHECK();
+    hipLaunchKernelGGL(k_iota_i32, dim3(blocks_for(nc)), dim3(TPB), 0, s, nc, ids.as<int32_t>());
+    GCN_LAUNCH_CHECK();
+    GCN_HIP_TRY(rocprim::radix_sort_pairs_desc(nullptr, tmp_bytes, cnt.as<uint32_t>(), cnt_sorted.as<uint32_t>(),
+                                               ids.as<int32_t>(), cols_sorted.as<int32_t>(), (size_t)nc, 0u, 32u, s));
+    GCN_TRY(tmp.alloc(tmp_bytes));
+    GCN_HIP_TRY(rocprim::radix_sort_pairs_desc(tmp.p, tmp_bytes, cnt.as<uint32_t>(), cnt_sorted.as<uint32_t>(),
+                                               ids.as<int32_t>(), cols_sorted.as<int32_t>(), (size_t)nc, 0u, 32u, s));
+    GCN_TRY(hc.alloc((size_t)H * 4));
+    GCN_HIP_TRY(hipMemcpyAsync(hc.p, cols_sorted.p, (size_t)H * 4, hipMemcpyDeviceToDevice, s));
+    GCN_TRY(rank.alloc((size_t)nc * 4));
+    GCN_HIP_TRY(hipMemsetAsync(rank.p, 0xff, (size_t)nc * 4, s));                 // -1: not a hot column
+    hipLaunchKernelGGL(k_hub_rank, dim3(blocks_for(H)), dim3(TPB), 0, s, H, hc.as<int32_t>(), rank.as<int32_t>());
+    GCN_LAUNCH_CHECK();
+
+    // the long rows
+    TempBuf defer, hrows, nsel;
+    GCN_TRY(defer.alloc((size_t)n));
+    hipLaunchKernelGGL(k_hub_defer, dim3(blocks_for(n)), dim3(TPB), 0, s, n, m.rowptr, dmin, defer.as<uint8_t>());
+    GCN_LAUNCH_CHECK();
+    GCN_TRY(hrows.alloc((size_t)(nnz / dmin + 1) * 4));
+    GCN_TRY(nsel.alloc(sizeof(size_t)));
+    rocprim::counting_iterator<int32_t> rows(0);
+    HeavyRow pred{m.rowptr, dmin - 1};
+    tmp_bytes = 0;
+    GCN_HIP_TRY(rocprim::select(nullptr, tmp_bytes, rows, hrows.as<int32_t>(), nsel.as<size_t>(), (size_t)n, pred, s));
+    GCN_TRY(tmp.alloc(tmp_bytes));
+    GCN_HIP_TRY(rocprim::select(tmp.p, tmp_bytes, rows, hrows.as<int32_t>(), nsel.as<size_t>(), (size_t)n, pred, s));
+    size_t nh = 0;
+    GCN_HIP_TRY(hipMemcpyAsync(&nh, nsel.p, sizeof(size_t), hipMemcpyDeviceToHost, s));
+    GCN_HIP_TRY(hipStreamSynchronize(s));
+    if (nh == 0) return GCN_OK;                              // rejected: no long rows
+
+    // split the entries
+    GCN_TRY(flag.alloc(((size_t)nnz + 1) * 8));
+    GCN_TRY(pos.alloc(((size_t)nnz + 1) * 8));
+    hipLaunchKernelGGL(k_hub_flags, dim3(blocks_for(nnz + 1)), dim3(TPB), 0, s, nnz, n, m.rowptr, m.colidx,
+                       defer.as<uint8_t>(), rank.as<int32_t>(), flag.as<int64_t>());
+    GCN_LAUNCH_CHECK();
+    tmp_bytes = 0;
+    GCN_HIP_TRY(rocprim::exclusive_scan(nullptr, tmp_bytes, flag.as<int64_t>(), pos.as<int64_t>(), (int64_t)0,
+                                        (size_t)nnz + 1, rocprim::plus<int64_t>(), s));
+    GCN_TRY(tmp.alloc(tmp_bytes));
+    GCN_HIP_TRY(rocprim::exclusive_scan(tmp.p, tmp_bytes, flag.as<int64_t>(), pos.as<int64_t>(), (int64_t)0,
+                                        (size_t)nnz + 1, rocprim::plus<int64_t>(), s));
+    int64_t nnz_hot = 0;
+    GCN_HIP_TRY(hipMemcpyAsync(&nnz_hot, pos.as<int64_t>() + nnz, 8, hipMemcpyDeviceToHost, s));
+    GCN_HIP_TRY(hipStreamSynchronize(s));
+    const int64_t nnz_rest = nnz - nnz_hot;
+    h.nnz_hot = nnz_hot; h.nnz_rest = nnz_rest; h.n_heavy = (int64_t)nh;
+    if (nnz_hot * 2 < nnz || nnz_rest <= 0) return GCN_OK;   // rejected: less than half of the entries would gain
+
+    Matrix* hot = new (std::nothrow) Matrix();
+    Matrix* rest = new (std::nothrow) Matrix();
+    h.hot = hot; h.rest = rest;
+    if (!hot || !rest) return fail(GCN_ERR_OOM, "host allocation failed");
+    hot->nrows = (int64_t)nh; hot->ncols = H;
+    rest->nrows = n; rest->ncols = nc;
+    GCN_TRY(device_alloc_t(&hot->rowptr, nh + 1));
+    GCN_TRY(device_alloc_t(&hot->colidx, (size_t)nnz_hot));
+    GCN_TRY(device_alloc_t(&hot->val, (size_t)nnz_hot));
+    GCN_TRY(device_alloc_t(&rest->rowptr, (size_t)n + 1));
+    GCN_TRY(device_alloc_t(&rest->colidx, (size_t)nnz_rest));
+    GCN_TRY(device_alloc_t(&rest->val, (size_t)nnz_rest));
+    hipLaunchKernelGGL(k_hub_scatter, dim3(blocks_for(nnz)), dim3(TPB), 0, s, nnz, m.colidx, m.val, flag.as<int64_t>(),
+                       pos.as<int64_t>(), rank.as<int32_t>(), hot->colidx, hot->val, rest->colidx, rest->val);
+    GCN_LAUNCH_CHECK();
+    hipLaunchKernelGGL(k_hub_rest_rowptr, dim3(blocks_for(n + 1)), dim3(TPB), 0, s, n, m.rowptr, pos.as<int64_t>(),
+                       rest->rowptr);
+    GCN_LAUNCH_CHECK();
+    hipLaunchKernelGGL(k_hub_hot_rowptr, dim3(blocks_for((int64_t)nh + 1)), dim3(TPB), 0, s, (int64_t)nh, nnz_hot,
+                       hrows.as<int32_t>(), m.rowptr, pos.as<int64_t>(), hot->rowptr);
+    GCN_LAUNCH_CHECK();
+    GCN_HIP_TRY(hipStreamSynchronize(s));
+    flag.alloc(16);
+    pos.alloc(16);
+    GCN_TRY(build_schedule(*rest, n, nnz_rest, s));
+    hot->nsub = (nnz_hot + SUB - 1) / SUB;
+    hot->nchunks = (nnz_hot + CHUNK - 1) / CHUNK;
+    GCN_TRY(build_blocked(*hot, nnz_hot, cpb, s));
+
+    GCN_TRY(device_alloc_t(&h.hot_col, (size_t)H));
+    GCN_TRY(device_alloc_t(&h.heavy_rows, nh));
+    GCN_TRY(device_alloc_t(&h.defer, (size_t)n));
+    GCN_HIP_TRY(hipMemcpyAsync(h.hot_col, hc.p, (size_t)H * 4, hipMemcpyDeviceToDevice, s));
+    GCN_HIP_TRY(hipMemcpyAsync(h.heavy_rows, hrows.p, nh * 4, hipMemcpyDeviceToDevice, s));
+    GCN_HIP_TRY(hipMemcpyAsync(h.defer, defer.p, (size_t)n, hipMemcpyDeviceToDevice, s));
+    GCN_HIP_TRY(hipStreamSynchronize(s));
+    h.state = 1;
     return GCN_OK;
 }
 

@@ -15,6 +15,8 @@
 // No floating-point atomics are used anywhere: results are bit-reproducible run to run.
 // Column indices and values are read with coalesced 16-byte loads into LDS first and consumed
 // from there; the gathered rows of X are read with one 16-byte load per lane.
+#include <algorithm>
+
 #include "common.h"
 
 namespace gcn {
@@ -27,6 +29,7 @@ struct SplitArgs {
     const int32_t* colidx;
     const float* val;         // NULL: value-free product (every stored entry counts as 1)
     const float* row_scale;   // NULL, or one factor per output row applied before the epilogue
+    const uint8_t* defer;     // NULL, or 1 for rows whose sum is stored raw (another pass finishes them)
     const uint32_t* flags;
     const int32_t* sub_row;
     const int32_t* ne_rows;   // NULL: row index == non-empty-row index
@@ -79,7 +82,12 @@ __device__ __forceinline__ void store_vec(float* p, const float (&d)[VEC]) {
 }
 
 template <int VEC, int EPI>
-__device__ __forceinline__ void epilogue_store(float* z, const float* zprev, float (&v)[VEC], float scale = 1.f) {
+__device__ __forceinline__ void epilogue_store(float* z, const float* zprev, float (&v)[VEC], float scale = 1.f,
+                                               bool raw = false) {
+    if (raw) {
+        store_vec<VEC>(z, v);
+        return;
+    }
 #pragma unroll
     for (int e = 0; e < VEC; ++e) v[e] *= scale;           // exact for scale = 1
     if constexpr (EPI == GCN_EPI_RELU) {
@@ -94,8 +102,9 @@ __device__ __forceinline__ void epilogue_store(float* z, const float* zprev, flo
     store_vec<VEC>(z, v);
 }
 
+// The work of one workgroup: the four chunks 4*grp .. 4*grp+3 of the matrix described by `a`.
 template <int LPR, int VEC, int EPI>
-__global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void k_spmm_split(SplitArgs a) {
+__device__ __forceinline__ void split_body(const SplitArgs& a, int64_t grp) {
     constexpr int G = 64 / LPR;                 // lane groups per wavefront
     constexpr int NW = SUBS_PER_CHUNK / G;      // flag words per group
     static_assert(NW >= 1, "a group needs at least one flag word");
@@ -103,7 +112,7 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void k_spmm_split(SplitArgs a
     __shared__ float s_val[WAVES_PER_BLOCK][LDS_PER_WAVE];
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int64_t c = (int64_t)blockIdx.x * WAVES_PER_BLOCK + wave;
+    const int64_t c = grp * WAVES_PER_BLOCK + wave;
     if (c >= a.nchunks) return;                 // whole wavefront leaves; no block-wide barrier below
     const int g = lane / LPR, li = lane % LPR;
     const int col0 = blockIdx.y * (LPR * VEC) + li * VEC;
@@ -184,7 +193,8 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void k_spmm_split(SplitArgs a
                                 const int64_t row = a.ne_rows ? a.ne_rows[q] : q;
                                 epilogue_store<VEC, EPI>(a.Z + row * a.ldz + col0,
                                                          EPI == GCN_EPI_MASK ? a.Zprev + row * a.ldzprev + col0 : nullptr,
-                                                         acc, a.row_scale ? a.row_scale[row] : 1.f);
+                                                         acc, a.row_scale ? a.row_scale[row] : 1.f,
+                                                         a.defer && a.defer[row]);
                             }
                         } else {
 #pragma unroll
@@ -248,8 +258,25 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void k_spmm_split(SplitArgs a
         if (runs_on) store_vec<VEC>(a.Z + row * a.ldz + col0, acc);     // finished by k_spmm_fixup
         else epilogue_store<VEC, EPI>(a.Z + row * a.ldz + col0,
                                       EPI == GCN_EPI_MASK ? a.Zprev + row * a.ldzprev + col0 : nullptr, acc,
-                                      a.row_scale ? a.row_scale[row] : 1.f);
+                                      a.row_scale ? a.row_scale[row] : 1.f, a.defer && a.defer[row]);
     }
+}
+
+template <int LPR, int VEC, int EPI>
+__global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void k_spmm_split(SplitArgs a) {
+    split_body<LPR, VEC, EPI>(a, blockIdx.x);
+}
+
+// Two matrices in one launch: of every ra + rb consecutive workgroups the first ra work on `a` (with
+// the epilogue) and the other rb on `b` (plain sums).  Used when one part is bound by line fills and
+// the other by L2 hits, so that both kinds of work are resident on every compute unit together.
+template <int LPR, int VEC, int EPI>
+__global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void k_spmm_split_pair(SplitArgs a, SplitArgs b, int ra, int rb) {
+    // ra + rb == 8.  Workgroups go to the eight XCDs round-robin; the rotation by q lets every XCD see
+    // both kinds of work in turn.
+    const unsigned q = blockIdx.x / 8, r = (blockIdx.x + q) % 8;
+    if ((int)r < ra) split_body<LPR, VEC, EPI>(a, (int64_t)q * ra + r);
+    else split_body<LPR, VEC, GCN_EPI_NONE>(b, (int64_t)q * rb + (r - ra));
 }
 
 // Adds, in ascending chunk order, the carries of the chunks a row runs on into, then applies the
@@ -284,7 +311,7 @@ __global__ __launch_bounds__(256) void k_spmm_fixup(SplitArgs a) {
 #pragma unroll
     for (int v = 0; v < VEC; ++v) cur[v] += sum[v];
     epilogue_store<VEC, EPI>(z, EPI == GCN_EPI_MASK ? a.Zprev + row * a.ldzprev + col0 : nullptr, cur,
-                             a.row_scale ? a.row_scale[row] : 1.f);
+                             a.row_scale ? a.row_scale[row] : 1.f, a.defer && a.defer[row]);
 }
 
 // Rows without stored entries produce zeros (any epilogue maps 0 to 0).
@@ -295,6 +322,14 @@ __global__ void k_zero_empty_rows(int64_t n, const int64_t* __restrict__ rowptr,
     const int j = (int)(t % f);
     if (i >= n) return;
     if (rowptr[i + 1] == rowptr[i]) Z[i * ldz + j] = 0.f;
+}
+
+// The same from the list of empty rows that the schedule keeps (only their elements are touched).
+__global__ void k_zero_listed_rows(int64_t count, const int32_t* __restrict__ rows, int32_t f, float* __restrict__ Z,
+                                   int64_t ldz) {
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t q = t / f;
+    if (q < count) Z[(int64_t)rows[q] * ldz + (int)(t % f)] = 0.f;
 }
 
 // Reference-shaped kernel: one thread per output element walks its row.  Kept as a selectable
@@ -351,36 +386,37 @@ __global__ __launch_bounds__(256) void k_block_reduce(int64_t n, int32_t f, int3
                                                       const int32_t* __restrict__ rq_idx, const int32_t* __restrict__ row_map,
                                                       const float* __restrict__ row_scale, const float* __restrict__ P,
                                                       float* __restrict__ Z, int64_t ldz, const float* __restrict__ Zprev,
-                                                      int64_t ldzprev) {
+                                                      int64_t ldzprev, int accumulate) {
     const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const int64_t i = t / lanes;
     const int col0 = (int)(t % lanes) * VEC;
     if (i >= n) return;
+    const int64_t row = row_map ? row_map[i] : i;    // a row-subset matrix writes only its own rows
     float acc[VEC];
 #pragma unroll
     for (int v = 0; v < VEC; ++v) acc[v] = 0.f;
+    if (accumulate) load_vec<VEC>(acc, Z + row * ldz + col0);   // what an earlier pass stored raw for this row
     for (int64_t k = rq_ptr[i]; k < rq_ptr[i + 1]; ++k) {
         float part[VEC];
         load_vec<VEC>(part, P + (int64_t)rq_idx[k] * f + col0);
 #pragma unroll
         for (int v = 0; v < VEC; ++v) acc[v] += part[v];
     }
-    const int64_t row = row_map ? row_map[i] : i;    // a row-subset matrix writes only its own rows
     epilogue_store<VEC, EPI>(Z + row * ldz + col0, EPI == GCN_EPI_MASK ? Zprev + row * ldzprev + col0 : nullptr, acc,
                              row_scale ? row_scale[row] : 1.f);
 }
 
 template <int VEC>
 static int launch_block_reduce(int64_t n, int32_t f, const Blocked& b, const int32_t* row_map, const float* row_scale,
-                               const float* P, float* Z,
+                               int accumulate, const float* P, float* Z,
                                int64_t ldz, int epilogue, const float* Zprev, int64_t ldzprev, hipStream_t s) {
     const int lanes = f / VEC;
     const int64_t threads = n * lanes;
     const dim3 grid((unsigned)((threads + 255) / 256));
     switch (epilogue) {
-        case GCN_EPI_NONE: hipLaunchKernelGGL((k_block_reduce<VEC, GCN_EPI_NONE>), grid, dim3(256), 0, s, n, f, lanes, b.rq_ptr, b.rq_idx, row_map, row_scale, P, Z, ldz, Zprev, ldzprev); break;
-        case GCN_EPI_RELU: hipLaunchKernelGGL((k_block_reduce<VEC, GCN_EPI_RELU>), grid, dim3(256), 0, s, n, f, lanes, b.rq_ptr, b.rq_idx, row_map, row_scale, P, Z, ldz, Zprev, ldzprev); break;
-        default: hipLaunchKernelGGL((k_block_reduce<VEC, GCN_EPI_MASK>), grid, dim3(256), 0, s, n, f, lanes, b.rq_ptr, b.rq_idx, row_map, row_scale, P, Z, ldz, Zprev, ldzprev); break;
+        case GCN_EPI_NONE: hipLaunchKernelGGL((k_block_reduce<VEC, GCN_EPI_NONE>), grid, dim3(256), 0, s, n, f, lanes, b.rq_ptr, b.rq_idx, row_map, row_scale, P, Z, ldz, Zprev, ldzprev, accumulate); break;
+        case GCN_EPI_RELU: hipLaunchKernelGGL((k_block_reduce<VEC, GCN_EPI_RELU>), grid, dim3(256), 0, s, n, f, lanes, b.rq_ptr, b.rq_idx, row_map, row_scale, P, Z, ldz, Zprev, ldzprev, accumulate); break;
+        default: hipLaunchKernelGGL((k_block_reduce<VEC, GCN_EPI_MASK>), grid, dim3(256), 0, s, n, f, lanes, b.rq_ptr, b.rq_idx, row_map, row_scale, P, Z, ldz, Zprev, ldzprev, accumulate); break;
     }
     GCN_LAUNCH_CHECK();
     return GCN_OK;
@@ -602,6 +638,7 @@ static int run_matrix(gcn_csr* a, Matrix& mm, const int32_t* row_map, int64_t nn
     SplitArgs args;
     args.nnz = nnz; args.nsub = mm.nsub; args.nchunks = mm.nchunks; args.f = f;
     args.X = X; args.ldx = ldx; args.carry = a->carry;
+    args.defer = nullptr;
     if (nblocks >= 2) {
         int64_t cpb = (mm.ncols + nblocks - 1) / nblocks;
         cpb = (cpb + 1023) & ~1023ll;
@@ -614,15 +651,137 @@ static int run_matrix(gcn_csr* a, Matrix& mm, const int32_t* row_map, int64_t nn
         GCN_TRY(run_split(args, GCN_EPI_NONE, s));
         const bool vec4 = (f % 4 == 0) && (ldz % 4 == 0) && aligned16(Z) &&
                           (epilogue != GCN_EPI_MASK || ((ldzprev % 4 == 0) && aligned16(Zprev)));
-        if (vec4) return launch_block_reduce<4>(mm.nrows, f, b, row_map, o.row_scale, a->partial, Z, ldz, epilogue, Zprev, ldzprev, s);
-        return launch_block_reduce<1>(mm.nrows, f, b, row_map, o.row_scale, a->partial, Z, ldz, epilogue, Zprev, ldzprev, s);
+        if (vec4) return launch_block_reduce<4>(mm.nrows, f, b, row_map, o.row_scale, o.accumulate ? 1 : 0, a->partial, Z, ldz, epilogue, Zprev, ldzprev, s);
+        return launch_block_reduce<1>(mm.nrows, f, b, row_map, o.row_scale, o.accumulate ? 1 : 0, a->partial, Z, ldz, epilogue, Zprev, ldzprev, s);
     }
     args.colidx = mm.colidx; args.val = o.pattern ? nullptr : mm.val; args.flags = mm.flags; args.sub_row = mm.sub_row;
     args.row_scale = o.row_scale;
+    args.defer = o.defer;
     args.ne_rows = row_map ? row_map : mm.ne_rows;
     args.rp = mm.ne_rowptr ? mm.ne_rowptr : mm.rowptr;
     args.Z = Z; args.ldz = ldz; args.Zprev = Zprev; args.ldzprev = ldzprev;
     return run_split(args, epilogue, s);
+}
+
+static int zero_empty_rows(const Matrix& m, int32_t f, float* Z, int64_t ldz, hipStream_t s) {
+    const int64_t n_empty = m.nrows - m.n_ne;
+    if (m.empty_rows && n_empty > 0) {
+        const int64_t work = n_empty * f;
+        hipLaunchKernelGGL(k_zero_listed_rows, dim3((unsigned)((work + 255) / 256)), dim3(256), 0, s, n_empty, m.empty_rows, f, Z, ldz);
+    } else {
+        const int64_t work = m.nrows * f;
+        hipLaunchKernelGGL(k_zero_empty_rows, dim3((unsigned)((work + 255) / 256)), dim3(256), 0, s, m.nrows, m.rowptr, f, Z, ldz);
+    }
+    GCN_LAUNCH_CHECK();
+    return GCN_OK;
+}
+
+// ---- hub schedule -----------------------------------------------------------------------------------------
+// xhot[r,:] = X[hot_col[r],:], 16 bytes per thread.
+__global__ __launch_bounds__(256) void k_pack_rows(int64_t H, int32_t lanes, const float* __restrict__ X, int64_t ldx,
+                                                   const int32_t* __restrict__ hot_col, float* __restrict__ xhot) {
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t r = t / lanes;
+    const int j = (int)(t % lanes) * 4;
+    if (r >= H) return;
+    *reinterpret_cast<float4*>(xhot + r * (int64_t)lanes * 4 + j) =
+        *reinterpret_cast<const float4*>(X + (int64_t)hot_col[r] * ldx + j);
+}
+
+// Packed-buffer size and block width of the hub copy for operands of width f: blocks of about 2 MB
+// of the gathered panel, as many hot columns as fit `budget` bytes (a multiple of the block width).
+static void hub_shape(int64_t ncols, int32_t f, int64_t* H, int64_t* cpb) {
+    const int64_t panel = f < 32 ? f : 32;
+    *cpb = config().hub_block_cols > 0 ? config().hub_block_cols : (2ll << 20) / (panel * 4);
+    const int64_t budget = (int64_t)config().hub_mb << 20;
+    int64_t h = budget / ((int64_t)f * 4);
+    if (h > ncols) h = ncols;
+    *H = h / *cpb * *cpb;
+}
+
+template <int LPR>
+static int launch_pair(const SplitArgs& ra_args, const SplitArgs& rb_args, int epilogue, hipStream_t s) {
+    const int tile = LPR * 4;
+    const unsigned ytiles = (unsigned)((ra_args.f + tile - 1) / tile);
+    const int64_t ga = (ra_args.nchunks + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK;
+    const int64_t gb = (rb_args.nchunks + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK;
+    // shares of the two matrices among eight consecutive workgroups, in proportion to their chunk groups
+    int ra = (int)((8 * ga + (ga + gb) / 2) / (ga + gb));
+    ra = ra < 1 ? 1 : (ra > 7 ? 7 : ra);
+    const int rb = 8 - ra;
+    const int64_t periods = std::max((ga + ra - 1) / ra, (gb + rb - 1) / rb);
+    if (periods * 8 >= (1ll << 31)) return fail(GCN_ERR_RANGE, "gcn_spmm: too many chunks for one launch");
+    const dim3 grid((unsigned)(periods * 8), ytiles);
+    timing_begin(s);
+    switch (epilogue) {
+        case GCN_EPI_NONE: hipLaunchKernelGGL((k_spmm_split_pair<LPR, 4, GCN_EPI_NONE>), grid, dim3(64 * WAVES_PER_BLOCK), 0, s, ra_args, rb_args, ra, rb); break;
+        case GCN_EPI_RELU: hipLaunchKernelGGL((k_spmm_split_pair<LPR, 4, GCN_EPI_RELU>), grid, dim3(64 * WAVES_PER_BLOCK), 0, s, ra_args, rb_args, ra, rb); break;
+        default: hipLaunchKernelGGL((k_spmm_split_pair<LPR, 4, GCN_EPI_MASK>), grid, dim3(64 * WAVES_PER_BLOCK), 0, s, ra_args, rb_args, ra, rb); break;
+    }
+    timing_end(s);
+    GCN_LAUNCH_CHECK();
+    const SplitArgs* both[2] = {&ra_args, &rb_args};
+    for (int k = 0; k < 2; ++k) {
+        const SplitArgs& args = *both[k];
+        const int64_t fix_threads = (args.nchunks - 1) * LPR;
+        if (fix_threads <= 0) continue;
+        const dim3 fgrid((unsigned)((fix_threads + 255) / 256), ytiles);
+        const int epi = k == 0 ? epilogue : GCN_EPI_NONE;
+        switch (epi) {
+            case GCN_EPI_NONE: hipLaunchKernelGGL((k_spmm_fixup<LPR, 4, GCN_EPI_NONE>), fgrid, dim3(256), 0, s, args); break;
+            case GCN_EPI_RELU: hipLaunchKernelGGL((k_spmm_fixup<LPR, 4, GCN_EPI_RELU>), fgrid, dim3(256), 0, s, args); break;
+            default: hipLaunchKernelGGL((k_spmm_fixup<LPR, 4, GCN_EPI_MASK>), fgrid, dim3(256), 0, s, args); break;
+        }
+        GCN_LAUNCH_CHECK();
+    }
+    return GCN_OK;
+}
+
+// Z = A_rest X (long rows stored raw) and the partial rows of A_hot X_hot in one paired launch, then
+// the long rows get their partial rows added, are scaled and finished.  Needs 16-byte aligned operands.
+static int run_hub(gcn_csr* a, Matrix& m, int32_t f, const float* X, int64_t ldx, float* Z, int64_t ldz, int epilogue,
+                   const float* Zprev, int64_t ldzprev, const SpmmOpt& o, hipStream_t s) {
+    Hub& h = m.hub;
+    const size_t need = (size_t)h.H * (size_t)f * sizeof(float);
+    if (need > h.xhot_bytes) {
+        if (h.xhot) {
+            GCN_HIP_TRY(hipDeviceSynchronize());
+            device_free(h.xhot);
+            h.xhot = nullptr;
+            h.xhot_bytes = 0;
+        }
+        GCN_TRY(device_alloc((void**)&h.xhot, need));
+        h.xhot_bytes = need;
+    }
+    Matrix& rest = *h.rest;
+    Matrix& hot = *h.hot;
+    const Blocked& b = hot.blk;
+    if ((rest.nchunks + hot.nchunks) / WAVES_PER_BLOCK + 16 >= (1ll << 31))
+        return fail(GCN_ERR_RANGE, "gcn_spmm: too many chunks for one launch");
+    GCN_TRY(grow(&a->carry, &a->carry_bytes, (size_t)rest.nchunks * (size_t)f * sizeof(float)));
+    GCN_TRY(grow(&a->carry2, &a->carry2_bytes, (size_t)hot.nchunks * (size_t)f * sizeof(float)));
+    GCN_TRY(grow(&a->partial, &a->partial_bytes, (size_t)b.nrows * (size_t)f * sizeof(float)));
+    const int lanes = f / 4;
+    hipLaunchKernelGGL(k_pack_rows, dim3((unsigned)((h.H * lanes + 255) / 256)), dim3(256), 0, s, h.H, lanes, X, ldx,
+                       h.hot_col, h.xhot);
+    GCN_LAUNCH_CHECK();
+    if (rest.n_ne < rest.nrows) GCN_TRY(zero_empty_rows(rest, f, Z, ldz, s));
+
+    SplitArgs ar;                                  // A_rest over X, into Z
+    ar.colidx = rest.colidx; ar.val = o.pattern ? nullptr : rest.val; ar.flags = rest.flags; ar.sub_row = rest.sub_row;
+    ar.row_scale = o.row_scale; ar.defer = h.defer;
+    ar.ne_rows = rest.ne_rows; ar.rp = rest.ne_rowptr ? rest.ne_rowptr : rest.rowptr;
+    ar.nnz = h.nnz_rest; ar.nsub = rest.nsub; ar.nchunks = rest.nchunks; ar.f = f;
+    ar.X = X; ar.ldx = ldx; ar.Z = Z; ar.ldz = ldz; ar.Zprev = Zprev; ar.ldzprev = ldzprev; ar.carry = a->carry;
+    SplitArgs ah;                                  // A_hot over the packed rows, into the partial rows
+    ah.colidx = b.colidx; ah.val = o.pattern ? nullptr : b.val; ah.flags = b.flags; ah.sub_row = b.sub_row;
+    ah.row_scale = nullptr; ah.defer = nullptr; ah.ne_rows = nullptr; ah.rp = b.rp;
+    ah.nnz = h.nnz_hot; ah.nsub = hot.nsub; ah.nchunks = hot.nchunks; ah.f = f;
+    ah.X = h.xhot; ah.ldx = f; ah.Z = a->partial; ah.ldz = f; ah.Zprev = nullptr; ah.ldzprev = 0; ah.carry = a->carry2;
+    if (f > 16) GCN_TRY(launch_pair<8>(ar, ah, epilogue, s));
+    else GCN_TRY(launch_pair<4>(ar, ah, epilogue, s));
+    return launch_block_reduce<4>(hot.nrows, f, b, h.heavy_rows, o.row_scale, 1, a->partial, Z, ldz, epilogue, Zprev,
+                                  ldzprev, s);
 }
 
 int spmm_launch(gcn_csr* a, Matrix& m, int32_t f, const float* X, int64_t ldx, float* Z, int64_t ldz,
@@ -650,7 +809,31 @@ int spmm_launch(gcn_csr* a, Matrix& m, int32_t f, const float* X, int64_t ldx, f
         algo = (huge && vec4_all && nblocks < 2 && narrow_steps) ? 3 : 2;
     }
     if (algo == 3 && !vec4_all) algo = 2;
+    if ((algo == 2 && config().spmm_algo == 0) || algo == 4) {
+        // Hub schedule: for operands beyond the L2s when most entries sit in long rows and hot columns
+        // (decided from the matrix itself when the copy is built; a rejected shape is remembered).
+        const bool forced = algo == 4;
+        algo = 2;
+        const int64_t panel = f < 32 ? f : 32;
+        int64_t H = 0, cpb = 0;
+        hub_shape(ncols, f, &H, &cpb);
+        // Measured: it pays when a gathered row is narrower than a 128-byte line (packing then also puts
+        // two hot rows into one line: config 4, width 16, 4.33 -> 3.15 ms) and not at 128 bytes per row
+        // (config 2: 1.44 -> 1.48 ms), so the automatic choice is limited to panels below 32 floats.
+        const bool eligible = vec4_all && nblocks < 2 && H >= 2 * cpb && nnz >= (forced ? 1 : (4ll << 20)) &&
+                              (forced || (panel < 32 && ncols * panel * 4 > (32ll << 20)));
+        if (eligible) {
+            const int32_t dmin = config().hub_dmin;
+            if (m.hub.H != H || m.hub.cpb != cpb || m.hub.dmin != dmin || m.hub.state == 0)
+                GCN_TRY(build_hub(m, nnz, H, cpb, dmin, s));
+            if (m.hub.state == 1) {
+                g_last_schedule = GCN_SCHED_HUB;
+                return run_hub(a, m, f, X, ldx, Z, ldz, epilogue, Zprev, ldzprev, o, s);
+            }
+        }
+    }
     if (algo == 3) {
+        g_last_schedule = GCN_SCHED_SWEEP;
         const int LPRs = f <= 16 ? 4 : 8;
         const int W = LPRs * 4;
         const int32_t rb = 4096 / W;                       // 16 KB of accumulators per wavefront
@@ -673,6 +856,7 @@ int spmm_launch(gcn_csr* a, Matrix& m, int32_t f, const float* X, int64_t ldx, f
         return GCN_OK;
     }
     if (algo == 1) {
+        g_last_schedule = GCN_SCHED_ROWWISE;
         const int64_t work = n * f;
         const dim3 grid((unsigned)((work + 255) / 256));
         if (work / 256 >= (1ll << 31)) return fail(GCN_ERR_RANGE, "gcn_spmm: n*f too large for the row-wise kernel");
@@ -686,11 +870,8 @@ int spmm_launch(gcn_csr* a, Matrix& m, int32_t f, const float* X, int64_t ldx, f
         GCN_LAUNCH_CHECK();
         return GCN_OK;
     }
-    if (nblocks < 2 && m.n_ne < n) {
-        const int64_t work = n * f;
-        hipLaunchKernelGGL(k_zero_empty_rows, dim3((unsigned)((work + 255) / 256)), dim3(256), 0, s, n, m.rowptr, f, Z, ldz);
-        GCN_LAUNCH_CHECK();
-    }
+    g_last_schedule = nblocks >= 2 ? GCN_SCHED_BLOCKED : GCN_SCHED_SPLIT;
+    if (nblocks < 2 && m.n_ne < n) GCN_TRY(zero_empty_rows(m, f, Z, ldz, s));
     return run_matrix(a, m, nullptr, nnz, nblocks, f, X, ldx, Z, ldz, epilogue, Zprev, ldzprev, o, s);
 }
 

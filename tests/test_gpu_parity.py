@@ -436,6 +436,77 @@ def test_spmm_column_sweep_directed_with_empty_rows():
     a.close()
 
 
+def hub_settings(g, mb=1, block_cols=256, dmin=8):
+    g.gcn_config(g.CFG_HUB_MB, mb)
+    g.gcn_config(g.CFG_HUB_BLOCK_COLS, block_cols)
+    g.gcn_config(g.CFG_HUB_DMIN, dmin)
+
+
+def hub_defaults(g):
+    g.gcn_config(g.CFG_HUB_MB, 32)
+    g.gcn_config(g.CFG_HUB_BLOCK_COLS, 0)
+    g.gcn_config(g.CFG_HUB_DMIN, 64)
+
+
+@pytest.mark.parametrize("name", ["c2s", "c4s", "c3s", "star", "c1"])
+@pytest.mark.parametrize("dmin", [8, 40])
+def test_spmm_hub_schedule_forced(name, dmin):
+    """The hub schedule (long rows x hot columns over a packed buffer in column blocks, everything else
+    through the plain kernel, both in one paired launch) forced on small graphs with small blocks; graphs
+    without long rows (c1) fall back to the plain kernel."""
+    g = G()
+    a = gpu_csr(name)
+    ref = oracle_csr(name)
+    hub_settings(g, dmin=dmin)
+    try:
+        for f in (16, 8, 32, 128, 100):
+            X = synth.normal_features(ref.n, f, 21)
+            Zp = synth.normal_features(ref.n, f, 22)
+            plain = oracle.spmm(ref, X)
+            assert_close(run_spmm(a, X, algo=4), plain, f"{name} dmin={dmin} f={f}")
+            # skewed graphs really take the hub schedule; the uniform one has no long rows and falls back
+            if name in ("c2s", "c4s", "c3s") and dmin == 8 and f <= 32:   # else it may be rejected: too few hot entries
+                assert g.gcn_last_spmm_schedule() == g.SCHED_HUB, (name, f, g.gcn_last_spmm_schedule())
+            assert_close(run_spmm(a, X, trans=1, algo=4), plain, "A^T (symmetric)")
+            assert_close(run_spmm(a, X, algo=4, epilogue=g.EPI_MASK, Zprev=Zp), oracle.relu_mask(plain, Zp), "mask")
+            assert_close(run_spmm(a, X, algo=4, epilogue=g.EPI_RELU, ld_pad=4), np.maximum(plain, 0), "relu, padded ld")
+        first = run_spmm(a, X, algo=4)
+        for _ in range(3):
+            np.testing.assert_array_equal(first.view(np.uint32), run_spmm(a, X, algo=4).view(np.uint32))
+    finally:
+        hub_defaults(g)
+    a.close()
+
+
+def test_spmm_hub_schedule_directed_empty_rows_and_value_free():
+    g = G()
+    a = gpu_csr("c4s", symmetrise=False, self_loops=False, norm="none")
+    ref = oracle_csr("c4s", False, False, "none", False)
+    ref_t = oracle_csr("c4s", False, False, "none", True)
+    X = synth.uniform_features(ref.n, 16, 23)
+    hub_settings(g)
+    try:
+        assert_close(run_spmm(a, X, trans=0, algo=4), oracle.spmm(ref, X), "A")
+        assert_close(run_spmm(a, X, trans=1, algo=4), oracle.spmm(ref_t, X), "A^T")
+    finally:
+        hub_defaults(g)
+    a.close()
+    a = gpu_csr("c2s")
+    ref = oracle_csr("c2s")
+    s_ref = oracle.inv_sqrt_degrees(ref)
+    hub_settings(g)
+    try:
+        for f in (16, 64):
+            Xs = oracle.scale_rows(synth.normal_features(ref.n, f, 24), s_ref)
+            Zp = synth.normal_features(ref.n, f, 25)
+            plain = oracle.spmm_pattern(ref, Xs, s_ref)
+            assert_close(run_pattern(a, Xs, s_ref, algo=4), plain, f"value-free f={f}")
+            assert_close(run_pattern(a, Xs, s_ref, epilogue=g.EPI_MASK, Zprev=Zp, algo=4), oracle.relu_mask(plain, Zp), "mask")
+    finally:
+        hub_defaults(g)
+    a.close()
+
+
 # value-free product for the symmetric normalisation: D^-1/2 (A+I) D^-1/2 X = D^-1/2 ((A+I) (D^-1/2 X))
 
 def run_pattern(a, Xs, scale, trans=0, epilogue=0, Zprev=None, algo=0):
