@@ -103,13 +103,14 @@ __device__ __forceinline__ void epilogue_store(float* z, const float* zprev, flo
 }
 
 // The work of one workgroup: the four chunks 4*grp .. 4*grp+3 of the matrix described by `a`.
+// s_col / s_val: the workgroup's staging arrays, [WAVES_PER_BLOCK][LDS_PER_WAVE] each (owned by the kernel,
+// so that two instantiations of this body in one kernel share them).
 template <int LPR, int VEC, int EPI>
-__device__ __forceinline__ void split_body(const SplitArgs& a, int64_t grp) {
+__device__ __forceinline__ void split_body(const SplitArgs& a, int64_t grp, int32_t (*s_col)[LDS_PER_WAVE],
+                                           float (*s_val)[LDS_PER_WAVE]) {
     constexpr int G = 64 / LPR;                 // lane groups per wavefront
     constexpr int NW = SUBS_PER_CHUNK / G;      // flag words per group
     static_assert(NW >= 1, "a group needs at least one flag word");
-    __shared__ int32_t s_col[WAVES_PER_BLOCK][LDS_PER_WAVE];
-    __shared__ float s_val[WAVES_PER_BLOCK][LDS_PER_WAVE];
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t c = grp * WAVES_PER_BLOCK + wave;
@@ -264,7 +265,9 @@ __device__ __forceinline__ void split_body(const SplitArgs& a, int64_t grp) {
 
 template <int LPR, int VEC, int EPI>
 __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void k_spmm_split(SplitArgs a) {
-    split_body<LPR, VEC, EPI>(a, blockIdx.x);
+    __shared__ int32_t s_col[WAVES_PER_BLOCK][LDS_PER_WAVE];
+    __shared__ float s_val[WAVES_PER_BLOCK][LDS_PER_WAVE];
+    split_body<LPR, VEC, EPI>(a, blockIdx.x, s_col, s_val);
 }
 
 // Two matrices in one launch: of every ra + rb consecutive workgroups the first ra work on `a` (with
@@ -274,9 +277,11 @@ template <int LPR, int VEC, int EPI>
 __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void k_spmm_split_pair(SplitArgs a, SplitArgs b, int ra, int rb) {
     // ra + rb == 8.  Workgroups go to the eight XCDs round-robin; the rotation by q lets every XCD see
     // both kinds of work in turn.
+    __shared__ int32_t s_col[WAVES_PER_BLOCK][LDS_PER_WAVE];
+    __shared__ float s_val[WAVES_PER_BLOCK][LDS_PER_WAVE];
     const unsigned q = blockIdx.x / 8, r = (blockIdx.x + q) % 8;
-    if ((int)r < ra) split_body<LPR, VEC, EPI>(a, (int64_t)q * ra + r);
-    else split_body<LPR, VEC, GCN_EPI_NONE>(b, (int64_t)q * rb + (r - ra));
+    if ((int)r < ra) split_body<LPR, VEC, EPI>(a, (int64_t)q * ra + r, s_col, s_val);
+    else split_body<LPR, VEC, GCN_EPI_NONE>(b, (int64_t)q * rb + (r - ra), s_col, s_val);
 }
 
 // Adds, in ascending chunk order, the carries of the chunks a row runs on into, then applies the
