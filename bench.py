@@ -40,9 +40,11 @@ MEASURED_TRAFFIC_BYTES = {
 }
 
 
-# kernels inside the library's event bracket of one product, by config (schedule chosen by the library)
-SPMM_KERNELS = {3: "k_spmm_split (column-blocked) + k_block_reduce",
-                5: "k_spmm_sweep (rows <= 1024 entries) + k_spmm_split (column-blocked, longer rows)"}
+# kernels inside the library's event bracket of one product, by the schedule the library reports
+SCHEDULE_KERNELS = {1: "k_spmm_rowwise", 2: "k_spmm_split",
+                    3: "k_spmm_sweep (rows <= 1024 entries) + k_spmm_split (column-blocked, longer rows)",
+                    4: "k_spmm_split_pair (hub schedule: long rows x hot columns over packed rows + the rest)",
+                    5: "k_spmm_split (column-blocked)"}
 
 
 def spmm_alg_bytes(n: int, nnz: int, f: int) -> int:
@@ -217,7 +219,7 @@ def main() -> int:
                      pct_hbm_peak=round(100 * value / HBM_PEAK_GBPS, 2),
                      bytes_alg_per_spmm=b_alg, bytes_nocache_per_spmm=8 * nnz + 8 * (n + 1) + 4 * f * nnz + 4 * n * f,
                      spmm_products_timed=2 * args.steps, event_brackets=launches)
-        out["roofline"] = {"bound": "hbm", "kernel": SPMM_KERNELS.get(args.config, "k_spmm_split"),
+        out["roofline"] = {"bound": "hbm", "kernel": SCHEDULE_KERNELS.get(g.gcn_last_spmm_schedule(), "k_spmm_split"),
                            "achieved": round(achieved, 2),
                            "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
                            "avg_kernel_ms": round(avg_kernel_ms, 4),
@@ -306,7 +308,7 @@ def main() -> int:
                            "order": args.order})
         extra.update(loss=float(loss.item()), spmm_widths=widths, spmm_ms_per_epoch=round(kern_ms / args.steps, 4),
                      spmm_share=round(kern_ms / args.steps / ms_step, 3))
-        out["roofline"] = {"bound": "hbm", "kernel": SPMM_KERNELS.get(args.config, "k_spmm_split"),
+        out["roofline"] = {"bound": "hbm", "kernel": SCHEDULE_KERNELS.get(g.gcn_last_spmm_schedule(), "k_spmm_split"),
                            "achieved": round(achieved, 2),
                            "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
                            "avg_kernel_ms": round(kern_ms / max(len(widths) * args.steps, 1), 4), "traffic": None}

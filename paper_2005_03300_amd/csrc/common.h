@@ -95,6 +95,7 @@ struct Hub {
     int state = 0;                // 0 not tried, 1 built, -1 tried and rejected (not skewed enough)
     int64_t H = 0, cpb = 0;       // hot columns, columns per block (H is a multiple of cpb)
     int32_t dmin = 0;
+    int32_t cfg_mb = 0, cfg_block_cols = 0;   // settings at build time: a change of settings rebuilds, a change of f does not
     int64_t nnz_hot = 0, nnz_rest = 0, n_heavy = 0;
     int32_t* hot_col = nullptr;   // [H] position in the packed buffer -> column
     int32_t* heavy_rows = nullptr;// [n_heavy] the long rows, ascending

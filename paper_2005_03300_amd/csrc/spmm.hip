@@ -828,9 +828,14 @@ int spmm_launch(gcn_csr* a, Matrix& m, int32_t f, const float* X, int64_t ldx, f
         const bool eligible = vec4_all && nblocks < 2 && H >= 2 * cpb && nnz >= (forced ? 1 : (4ll << 20)) &&
                               (forced || (panel < 32 && ncols * panel * 4 > (32ll << 20)));
         if (eligible) {
+            // built once per matrix for the width of the first product that qualifies; later widths reuse it
             const int32_t dmin = config().hub_dmin;
-            if (m.hub.H != H || m.hub.cpb != cpb || m.hub.dmin != dmin || m.hub.state == 0)
+            if (m.hub.state == 0 || m.hub.dmin != dmin || m.hub.cfg_mb != config().hub_mb ||
+                m.hub.cfg_block_cols != config().hub_block_cols) {
                 GCN_TRY(build_hub(m, nnz, H, cpb, dmin, s));
+                m.hub.cfg_mb = config().hub_mb;
+                m.hub.cfg_block_cols = config().hub_block_cols;
+            }
             if (m.hub.state == 1) {
                 g_last_schedule = GCN_SCHED_HUB;
                 return run_hub(a, m, f, X, ldx, Z, ldz, epilogue, Zprev, ldzprev, o, s);
