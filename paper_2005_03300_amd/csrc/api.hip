@@ -106,6 +106,7 @@ void free_blocked(Blocked& b) {
     device_free(b.flags);
     device_free(b.sub_row);
     device_free(b.rp);
+    device_free(b.fix_list);
     device_free(b.rq_ptr);
     device_free(b.rq_idx);
     b = Blocked();
@@ -146,6 +147,7 @@ void free_matrix(Matrix& m) {
     device_free(m.ne_rows);
     device_free(m.ne_rowptr);
     device_free(m.empty_rows);
+    device_free(m.fix_list);
     free_blocked(m.blk);
     free_sweep(m.swp);
     free_hub(m.hub);

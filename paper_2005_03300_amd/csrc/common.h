@@ -56,6 +56,8 @@ struct Blocked {
     uint32_t* flags = nullptr;   // [nsub + pad]
     int32_t* sub_row = nullptr;  // [nsub + pad]
     int64_t* rp = nullptr;       // [R+1] first entry of each partial row
+    int32_t* fix_list = nullptr; // [n_fix] chunks that lead the continuation of a row begun in an earlier chunk
+    int64_t n_fix = -1;          // -1: no list (every chunk is examined)
     int64_t* rq_ptr = nullptr;   // [n+1]  row i owns partial rows rq_idx[rq_ptr[i] .. rq_ptr[i+1])
     int32_t* rq_idx = nullptr;   // [R]    ascending block order inside a row
 };
@@ -119,6 +121,8 @@ struct Matrix {
     int64_t* ne_rowptr = nullptr;// [n_ne+1] rowptr restricted to non-empty rows, or NULL (= rowptr)
     int32_t* empty_rows = nullptr;// [nrows - n_ne] the rows without entries, or NULL when there are none
     int64_t n_ne = 0;
+    int32_t* fix_list = nullptr; // [n_fix] chunks that lead the continuation of a row begun in an earlier chunk
+    int64_t n_fix = -1;          // -1: no list (every chunk is examined)
     int64_t nsub = 0, nchunks = 0;
     int32_t max_degree = 0;
     Blocked blk;                 // built on first use for one block width
@@ -182,6 +186,8 @@ struct PhaseTimer {
 };
 
 int build_schedule(Matrix& m, int64_t n, int64_t nnz, hipStream_t s);
+int build_fix_list(const uint32_t* flags, const int32_t* sub_row, const int64_t* rp, int64_t nchunks, int32_t** list,
+                   int64_t* count, hipStream_t s);
 int build_blocked(Matrix& m, int64_t nnz, int64_t cols_per_block, hipStream_t s);
 void free_blocked(Blocked& b);
 int build_sweep(Matrix& m, int64_t nnz, int32_t groups, int32_t rb, int32_t heavy_threshold, hipStream_t s);

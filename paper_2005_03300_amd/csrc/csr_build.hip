@@ -225,6 +225,53 @@ static int compress_keys(Matrix& m, int64_t n, int64_t nnz, const uint64_t* keys
     return GCN_OK;
 }
 
+// The chunks c >= 1 whose first entry continues a row begun earlier and that are the first such chunk
+// of that row: exactly the chunks for which the fix-up kernel has work.
+struct LeadsCarry {
+    const uint32_t* flags;
+    const int32_t* sub_row;
+    const int64_t* rp;
+    __device__ bool operator()(const int32_t& c0) const {
+        const int64_t c = (int64_t)c0 + 1;
+        const int64_t j0 = c * SUBS_PER_CHUNK;
+        if (flags[j0] & 1u) return false;
+        return c == rp[sub_row[j0]] / CHUNK + 1;
+    }
+};
+
+__global__ void k_add_one(int64_t count, int32_t* __restrict__ v) {
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t < count) v[t] += 1;
+}
+
+int build_fix_list(const uint32_t* flags, const int32_t* sub_row, const int64_t* rp, int64_t nchunks, int32_t** list,
+                   int64_t* count, hipStream_t s) {
+    *count = 0;
+    if (nchunks <= 1) return GCN_OK;
+    if (nchunks >= (1ll << 31)) { *count = -1; return GCN_OK; }          // keep the exhaustive form
+    TempBuf sel, cnt, tmp;
+    GCN_TRY(sel.alloc((size_t)(nchunks - 1) * 4));
+    GCN_TRY(cnt.alloc(sizeof(size_t)));
+    rocprim::counting_iterator<int32_t> ids(0);
+    LeadsCarry pred{flags, sub_row, rp};
+    size_t tmp_bytes = 0;
+    GCN_HIP_TRY(rocprim::select(nullptr, tmp_bytes, ids, sel.as<int32_t>(), cnt.as<size_t>(), (size_t)(nchunks - 1), pred, s));
+    GCN_TRY(tmp.alloc(tmp_bytes));
+    GCN_HIP_TRY(rocprim::select(tmp.p, tmp_bytes, ids, sel.as<int32_t>(), cnt.as<size_t>(), (size_t)(nchunks - 1), pred, s));
+    size_t nsel = 0;
+    GCN_HIP_TRY(hipMemcpyAsync(&nsel, cnt.p, sizeof(size_t), hipMemcpyDeviceToHost, s));
+    GCN_HIP_TRY(hipStreamSynchronize(s));
+    if (nsel > 0) {
+        GCN_TRY(device_alloc_t(list, nsel));
+        GCN_HIP_TRY(hipMemcpyAsync(*list, sel.p, nsel * 4, hipMemcpyDeviceToDevice, s));
+        hipLaunchKernelGGL(k_add_one, dim3(blocks_for((int64_t)nsel)), dim3(TPB), 0, s, (int64_t)nsel, *list);
+        GCN_LAUNCH_CHECK();
+        GCN_HIP_TRY(hipStreamSynchronize(s));
+    }
+    *count = (int64_t)nsel;
+    return GCN_OK;
+}
+
 int build_schedule(Matrix& m, int64_t n, int64_t nnz, hipStream_t s) {
     m.nsub = (nnz + SUB - 1) / SUB;
     m.nchunks = (nnz + CHUNK - 1) / CHUNK;
@@ -274,6 +321,7 @@ int build_schedule(Matrix& m, int64_t n, int64_t nnz, hipStream_t s) {
         GCN_LAUNCH_CHECK();
     }
     GCN_HIP_TRY(hipStreamSynchronize(s));
+    if (nnz > 0) GCN_TRY(build_fix_list(m.flags, m.sub_row, rp, m.nchunks, &m.fix_list, &m.n_fix, s));
     return GCN_OK;
 }
 
@@ -422,6 +470,7 @@ int build_blocked(Matrix& m, int64_t nnz, int64_t cpb, hipStream_t s) {
     b.cols_per_block = cpb;
     b.nblocks = (int32_t)nblocks;
     b.nrows = R;
+    GCN_TRY(build_fix_list(b.flags, b.sub_row, b.rp, (nnz + CHUNK - 1) / CHUNK, &b.fix_list, &b.n_fix, s));
     return GCN_OK;
 }
 
@@ -700,6 +749,7 @@ int build_sweep(Matrix& m, int64_t nnz, int32_t groups, int32_t rb, int32_t heav
         hipLaunchKernelGGL(k_sub_rows, dim3(blocks_for(h->nsub)), dim3(TPB), 0, s, h->nsub, h->n_ne, h->ne_rowptr, h->sub_row);
         GCN_LAUNCH_CHECK();
         GCN_HIP_TRY(hipStreamSynchronize(s));
+        GCN_TRY(build_fix_list(h->flags, h->sub_row, h->ne_rowptr, h->nchunks, &h->fix_list, &h->n_fix, s));
     }
     GCN_HIP_TRY(hipStreamSynchronize(s));
     w.groups = groups;

@@ -34,6 +34,8 @@ struct SplitArgs {
     const int32_t* sub_row;
     const int32_t* ne_rows;   // NULL: row index == non-empty-row index
     const int64_t* rp;        // rowptr over non-empty rows
+    const int32_t* fix_list;  // chunks with work for the fix-up kernel (n_fix of them), or n_fix < 0: all chunks
+    int64_t n_fix;
     int64_t nnz, nsub, nchunks;
     int32_t f;
     const float* X;
@@ -289,8 +291,12 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void k_spmm_split_pair(SplitA
 template <int LPR, int VEC, int EPI>
 __global__ __launch_bounds__(256) void k_spmm_fixup(SplitArgs a) {
     const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const int64_t c = t / LPR + 1;              // chunk 0 starts a row by definition
     const int li = (int)(t % LPR);
+    int64_t c = t / LPR + 1;                    // chunk 0 starts a row by definition
+    if (a.n_fix >= 0) {                         // only the listed chunks have work
+        if (t / LPR >= a.n_fix) return;
+        c = a.fix_list[t / LPR];
+    }
     if (c >= a.nchunks) return;
     const int col0 = blockIdx.y * (LPR * VEC) + li * VEC;
     if (col0 >= a.f) return;
@@ -362,7 +368,7 @@ static int launch_split(const SplitArgs& args, int epilogue, hipStream_t s) {
     const int tile = LPR * VEC;
     const unsigned ytiles = (unsigned)((args.f + tile - 1) / tile);
     const dim3 grid((unsigned)((args.nchunks + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK), ytiles);
-    const int64_t fix_threads = (args.nchunks - 1) * LPR;
+    const int64_t fix_threads = (args.n_fix >= 0 ? args.n_fix : args.nchunks - 1) * LPR;
     const dim3 fgrid((unsigned)((fix_threads + 255) / 256), ytiles);
     timing_begin(s);
     switch (epilogue) {
@@ -652,6 +658,7 @@ static int run_matrix(gcn_csr* a, Matrix& mm, const int32_t* row_map, int64_t nn
         GCN_TRY(grow(&a->partial, &a->partial_bytes, (size_t)b.nrows * (size_t)f * sizeof(float)));
         args.colidx = b.colidx; args.val = o.pattern ? nullptr : b.val; args.flags = b.flags; args.sub_row = b.sub_row;
         args.ne_rows = nullptr; args.rp = b.rp; args.row_scale = nullptr;     // the scale belongs to the reduced row
+        args.fix_list = b.fix_list; args.n_fix = b.n_fix;
         args.Z = a->partial; args.ldz = f; args.Zprev = nullptr; args.ldzprev = 0;
         GCN_TRY(run_split(args, GCN_EPI_NONE, s));
         const bool vec4 = (f % 4 == 0) && (ldz % 4 == 0) && aligned16(Z) &&
@@ -664,6 +671,7 @@ static int run_matrix(gcn_csr* a, Matrix& mm, const int32_t* row_map, int64_t nn
     args.defer = o.defer;
     args.ne_rows = row_map ? row_map : mm.ne_rows;
     args.rp = mm.ne_rowptr ? mm.ne_rowptr : mm.rowptr;
+    args.fix_list = mm.fix_list; args.n_fix = mm.n_fix;
     args.Z = Z; args.ldz = ldz; args.Zprev = Zprev; args.ldzprev = ldzprev;
     return run_split(args, epilogue, s);
 }
@@ -728,7 +736,7 @@ static int launch_pair(const SplitArgs& ra_args, const SplitArgs& rb_args, int e
     const SplitArgs* both[2] = {&ra_args, &rb_args};
     for (int k = 0; k < 2; ++k) {
         const SplitArgs& args = *both[k];
-        const int64_t fix_threads = (args.nchunks - 1) * LPR;
+        const int64_t fix_threads = (args.n_fix >= 0 ? args.n_fix : args.nchunks - 1) * LPR;
         if (fix_threads <= 0) continue;
         const dim3 fgrid((unsigned)((fix_threads + 255) / 256), ytiles);
         const int epi = k == 0 ? epilogue : GCN_EPI_NONE;
@@ -776,11 +784,13 @@ static int run_hub(gcn_csr* a, Matrix& m, int32_t f, const float* X, int64_t ldx
     ar.colidx = rest.colidx; ar.val = o.pattern ? nullptr : rest.val; ar.flags = rest.flags; ar.sub_row = rest.sub_row;
     ar.row_scale = o.row_scale; ar.defer = h.defer;
     ar.ne_rows = rest.ne_rows; ar.rp = rest.ne_rowptr ? rest.ne_rowptr : rest.rowptr;
+    ar.fix_list = rest.fix_list; ar.n_fix = rest.n_fix;
     ar.nnz = h.nnz_rest; ar.nsub = rest.nsub; ar.nchunks = rest.nchunks; ar.f = f;
     ar.X = X; ar.ldx = ldx; ar.Z = Z; ar.ldz = ldz; ar.Zprev = Zprev; ar.ldzprev = ldzprev; ar.carry = a->carry;
     SplitArgs ah;                                  // A_hot over the packed rows, into the partial rows
     ah.colidx = b.colidx; ah.val = o.pattern ? nullptr : b.val; ah.flags = b.flags; ah.sub_row = b.sub_row;
     ah.row_scale = nullptr; ah.defer = nullptr; ah.ne_rows = nullptr; ah.rp = b.rp;
+    ah.fix_list = b.fix_list; ah.n_fix = b.n_fix;
     ah.nnz = h.nnz_hot; ah.nsub = hot.nsub; ah.nchunks = hot.nchunks; ah.f = f;
     ah.X = h.xhot; ah.ldx = f; ah.Z = a->partial; ah.ldz = f; ah.Zprev = nullptr; ah.ldzprev = 0; ah.carry = a->carry2;
     if (f > 16) GCN_TRY(launch_pair<8>(ar, ah, epilogue, s));
