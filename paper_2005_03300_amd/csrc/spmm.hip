@@ -623,7 +623,7 @@ static int grow(float** buf, size_t* have, size_t need) {
 // How many column blocks to cut X into so that one block of the gathered panel stays in one L2
 // (4 MB per XCD).  Blocking costs one partial row per non-empty (block,row) pair, so it only pays
 // when rows are long compared with the number of blocks: at least `per_block` entries per partial
-// row.  When 2 MB blocks would make the partial rows shorter than that, blocks of up to 6 MB are
+// row.  When 2 MB blocks would make the partial rows shorter than that, blocks of up to 8 MB are
 // still worth it (measured on the long rows of config 5: 5.6 MB blocks beat 2 MB ones); beyond
 // that 1 (no blocking).
 static int64_t choose_blocks(int64_t nrows, int64_t ncols, int64_t nnz, int32_t f, int64_t per_block) {
@@ -635,7 +635,7 @@ static int64_t choose_blocks(int64_t nrows, int64_t ncols, int64_t nnz, int32_t 
     const int64_t want = (xbytes + (2ll << 20) - 1) / (2ll << 20);
     const int64_t cap = (nnz / (nrows > 0 ? nrows : 1)) / per_block;
     if (want <= cap) return want;
-    return (cap >= 2 && 3 * cap >= want) ? cap : 1;
+    return (cap >= 2 && 4 * cap >= want) ? cap : 1;
 }
 
 // The nonzero-split product of one stored matrix -- the whole matrix, or the heavy rows of a sweep
