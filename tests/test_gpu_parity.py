@@ -3,6 +3,7 @@ inputs.  Integer outputs (rowptr, colidx, degrees, the transposed arrays) and th
 values must match bit for bit; floating-point outputs must satisfy tests/util.assert_close
 (1e-4 relative, with an rms floor for cancelling sums)."""
 import functools
+import os
 
 import numpy as np
 import pytest
@@ -952,4 +953,60 @@ def test_spmm_full_size_config2_sampled_rows():
     Z16 = torch.empty(n, 16, device="cuda")
     g.gcn_spmm(a, 0, sq, Z16)
     assert float(((Z16 - sq).abs() / sq).max()) < 1e-4
+    a.close()
+
+
+@pytest.mark.skipif(os.environ.get("GCN_TEST_HUGE", "1") != "1",
+                    reason="switched off with GCN_TEST_HUGE=0 (needs ~150 GB of device memory)")
+def test_more_than_2_31_stored_entries():
+    """A graph with more than 2^31 stored entries: every offset into the entry arrays must be 64-bit.  The
+    oracle is too slow at this size, so the checks are properties that hold at any size: structure of
+    sampled rows, A 1 = row lengths exactly, two independent schedules agreeing, and sampled rows of the
+    product against a float64 gather-sum of the exported arrays."""
+    g = G()
+    n = 1 << 24
+    src, dst = synth.erdos_renyi(n, 1_110_000_000, 5)
+    a = g.gcn_csr_create(n, dev(src), dev(dst), g.SYMMETRISE | g.ADD_SELF_LOOPS)     # unit values
+    del src, dst
+    assert a.nnz > (1 << 31)
+    rowptr, colidx, val, deg = a.arrays(False)
+    assert int(rowptr[0]) == 0 and int(rowptr[-1]) == a.nnz
+    assert bool((rowptr[1:] - rowptr[:-1] == deg.long()).all()) and int(deg.long().sum()) == a.nnz
+    assert bool((val == 1.0).all())
+    rs = np.random.default_rng(7)
+    rows = np.unique(np.concatenate([rs.integers(0, n, 2000), [0, 1, n - 2, n - 1],
+                                     torch.topk(deg, 50).indices.cpu().numpy()]))
+    for i in rows[:300].tolist():
+        c = colidx[int(rowptr[i]):int(rowptr[i + 1])].long()
+        assert bool((c[1:] > c[:-1]).all()) and bool((c == i).any())          # sorted, distinct, self loop
+        j = int(c[len(c) // 2])                                                # symmetric: (j, i) is stored too
+        cj = colidx[int(rowptr[j]):int(rowptr[j + 1])]
+        assert bool((cj == i).any())
+    ones = torch.ones(n, 16, device="cuda")
+    Z = torch.empty(n, 16, device="cuda")
+    g.gcn_spmm(a, 0, ones, Z)
+    assert bool((Z == deg.float()[:, None]).all())                             # exact: small integers
+    X = torch.rand(n, 16, device="cuda") * 2 - 1
+    g.gcn_spmm(a, 0, X, Z)
+    auto = g.gcn_last_spmm_schedule()
+    Z2 = torch.empty_like(Z)
+    g.gcn_config(g.CFG_SPMM_ALGO, 2)
+    try:
+        g.gcn_spmm(a, 0, X, Z2)
+    finally:
+        g.gcn_config(g.CFG_SPMM_ALGO, 0)
+    rms = float(Z2.double().pow(2).mean().sqrt())
+    assert float((Z - Z2).abs().max()) <= 1e-5 * rms, (auto, float((Z - Z2).abs().max()), rms)
+    g.gcn_config(g.CFG_SPMM_ALGO, 3)                      # the sweep copy: offsets of tasks beyond 2^31 too
+    try:
+        g.gcn_spmm(a, 0, X, Z2)
+        assert g.gcn_last_spmm_schedule() == g.SCHED_SWEEP
+    finally:
+        g.gcn_config(g.CFG_SPMM_ALGO, 0)
+    assert float((Z - Z2).abs().max()) <= 1e-5 * rms, ("sweep", float((Z - Z2).abs().max()), rms)
+    Xd = X.double()
+    for i in rows.tolist():
+        c = colidx[int(rowptr[i]):int(rowptr[i + 1])].long()
+        ref = Xd[c].sum(0)
+        assert float((Z[i].double() - ref).abs().max()) <= 1e-5 * rms + 1e-5 * float(ref.abs().max()), i
     a.close()
