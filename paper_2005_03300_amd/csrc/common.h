@@ -67,10 +67,10 @@ struct Matrix;
 // Sweep copy of a matrix for operands far larger than the caches.  Rows are cut into tasks of
 // `rb` consecutive rows; a wavefront owns a task, accumulates its rows in LDS and walks the task's
 // entries in ascending column order, so all wavefronts of a launch (started together, equal length)
-// gather from one narrow band of X at a time and that band stays in L2.  Inside a task every row
-// belongs to one of `groups` queues (balanced by entry count); the stored order interleaves the
-// queues -- position k*groups + g is the k-th entry of queue g -- so the lane groups of one step
-// always hold different rows and add to LDS without any conflict.  Rows longer than
+// gather from one narrow band of X at a time and that band stays in L2.  The entries of a task are
+// stored in steps of `groups` entries whose rows all differ (packed that way when the copy is built,
+// an entry whose row is already in the step moving to one of the next steps), so the lane groups of
+// one step add to LDS without any conflict; padding entries have column -1.  Rows longer than
 // `heavy_threshold` are kept apart and go through the nonzero-split kernel.
 struct Sweep {
     int32_t groups = 0;

@@ -438,8 +438,8 @@ static int launch_block_reduce(int64_t n, int32_t f, const Blocked& b, const int
 // or 32) for the whole launch.  Its entries come in ascending column order, so it walks X left to
 // right; all wavefronts of a launch start together and have about the same length, so at any moment
 // the whole GPU gathers from a narrow band of X, which therefore stays in L2 even when X is far
-// larger than every cache.  The stored order interleaves G balanced queues of rows (see Sweep), so
-// the G lane groups of one step always hold different rows: each multiplies its gathered row by the
+// larger than every cache.  The stored order puts G entries of different rows into every step (see
+// Sweep), so the G lane groups of one step always hold different rows: each multiplies its gathered row by the
 // value and adds it to the task's row in LDS with a plain read-modify-write.  Only this wavefront
 // touches these accumulators and its LDS operations complete in program order, so the sum order is
 // fixed and the result reproducible.
@@ -460,7 +460,7 @@ struct SweepArgs {
 
 template <int LPR, int EPI>
 __global__ __launch_bounds__(64) void k_spmm_sweep(SweepArgs a, int64_t first_task) {
-    constexpr int G = 64 / LPR;                  // entries per step (16 or 8) = queues of the task
+    constexpr int G = 64 / LPR;                  // entries per step (16 or 8), all of different rows
     constexpr int W = LPR * 4;                   // panel width in floats
     constexpr int SPT = 64 / G;                  // steps per 64 entries
     constexpr int U = 2;                         // 64-entry loads per trip
@@ -524,7 +524,7 @@ __global__ __launch_bounds__(64) void k_spmm_sweep(SweepArgs a, int64_t first_ta
             }
 #pragma unroll
         for (int q = 0; q < STEPS; ++q) {
-            if (rs[q] >= 0 && col_ok) {          // the groups of a step hold rows of different queues
+            if (rs[q] >= 0 && col_ok) {          // the groups of a step hold different rows
                 float4* dst = reinterpret_cast<float4*>(acc + rs[q] * W + col0);
                 float4 cur = *dst;
                 cur.x = fmaf(vs[q], x[q][0], cur.x);
