@@ -875,6 +875,59 @@ def test_epoch_with_first_layer_aggregated_once(name, cfg, shrink):
     a.close()
 
 
+@pytest.mark.parametrize("algo", [3, 4])
+@pytest.mark.parametrize("pattern", [0, 1])
+def test_epoch_with_forced_schedules(algo, pattern):
+    """The whole epoch with every sparse product forced through the column sweep or the hub schedule
+    (small blocks so that the small graph qualifies), with and without the value-free form."""
+    g = G()
+    g.gcn_config(g.CFG_SPMM_ALGO, algo)
+    g.gcn_config(g.CFG_PATTERN_SPMM, pattern)
+    g.gcn_config(g.CFG_SWEEP_HEAVY, 64)
+    hub_settings(g)
+    try:
+        w = synth.scaled(4, 256)
+        _, a, A, dims, Wd, Yd, ws, loss, ref, _ = run_epoch("c4s", w, 0)
+        assert g.gcn_last_spmm_schedule() == (g.SCHED_SWEEP if algo == 3 else g.SCHED_HUB)
+        assert abs(loss.item() - ref["loss"]) <= 1e-4 * abs(ref["loss"])
+        for l in range(len(dims) - 1):
+            assert rel_fro(host(Yd[l]), ref["Y"][l]) <= 2e-4, (l, rel_fro(host(Yd[l]), ref["Y"][l]))
+        a.close()
+    finally:
+        g.gcn_config(g.CFG_SPMM_ALGO, 0)
+        g.gcn_config(g.CFG_PATTERN_SPMM, 2)
+        g.gcn_config(g.CFG_SWEEP_HEAVY, 1024)
+        hub_defaults(g)
+
+
+def test_spmm_rectangular_block_row_through_sweep_and_hub():
+    """One process's block row (rectangular, rows != columns) through the forced sweep and hub schedules."""
+    g = G()
+    full = oracle_csr("c2s")
+    r1 = full.n // 4
+    sl = oracle.slice_rows(full, 0, r1)
+    a = g.gcn_csr_create_from_csr_rect(r1, full.n, dev(sl.rowptr), dev(sl.colidx), dev(sl.val), g.BUILD_TRANSPOSE)
+    slt = oracle.transpose(sl)
+    X = synth.normal_features(full.n, 16, 41)
+    Xr = synth.normal_features(r1, 16, 42)
+    g.gcn_config(g.CFG_SWEEP_HEAVY, 64)
+    hub_settings(g)
+    try:
+        for algo in (3, 4):
+            g.gcn_config(g.CFG_SPMM_ALGO, algo)
+            Z = torch.empty(r1, 16, device="cuda")
+            g.gcn_spmm(a, 0, dev(X), Z)
+            assert_close(host(Z), oracle.spmm(sl, X), f"block row, algo {algo}")
+            Zt = torch.empty(full.n, 16, device="cuda")
+            g.gcn_spmm(a, 1, dev(Xr), Zt)
+            assert_close(host(Zt), oracle.spmm(slt, Xr), f"transposed block row, algo {algo}")
+    finally:
+        g.gcn_config(g.CFG_SPMM_ALGO, 0)
+        g.gcn_config(g.CFG_SWEEP_HEAVY, 1024)
+        hub_defaults(g)
+    a.close()
+
+
 def test_epoch_sgd_step_and_workspace_check():
     w = synth.CONFIGS[1]
     g, a, A, dims, Wd, Yd, ws, loss, ref, (H0, y, Ws) = run_epoch("c1", w, 0, lr=0.5)
