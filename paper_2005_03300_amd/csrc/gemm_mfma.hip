@@ -165,10 +165,11 @@ struct TnArgs {
     float* part;
     int64_t k_per_block;
     int a_aligned;
+    int waves;         // wavefronts per workgroup (the column groups are dealt to them round-robin); 4 when NARROW
 };
 
 template <int MG, int NT, bool NARROW>   // NARROW: MG counts 16-column tiles of A (M <= 16*MG)
-__global__ __launch_bounds__(256) void k_gemm_tn(TnArgs a) {
+__global__ __launch_bounds__(512) void k_gemm_tn(TnArgs a) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int i = lane & 15, kq = lane >> 4;
     const int64_t kb = (int64_t)blockIdx.x * a.k_per_block;
@@ -188,7 +189,7 @@ __global__ __launch_bounds__(256) void k_gemm_tn(TnArgs a) {
     int mvalid[MG];                                     // how many of the lane's 4 columns exist
 #pragma unroll
     for (int g = 0; g < MG; ++g) {
-        mcol[g] = NARROW ? i + 16 * g : (wave + 4 * g) * 64 + 4 * i;
+        mcol[g] = NARROW ? i + 16 * g : (wave + a.waves * g) * 64 + 4 * i;
         const int left = a.M - mcol[g];
         mvalid[g] = left >= (NARROW ? 1 : 4) ? (NARROW ? 1 : 4) : (left > 0 ? left : 0);
     }
@@ -258,7 +259,7 @@ __global__ __launch_bounds__(256) void k_gemm_tn(TnArgs a) {
                     }
         }
     } else {
-        // D[ii = 4*kq + v][j = i] of tile (g, t) is C[m = (wave+4g)*64 + 4*ii + t][n = 16u + j]
+        // D[ii = 4*kq + v][j = i] of tile (g, t) is C[m = (wave + waves*g)*64 + 4*ii + t][n = 16u + j]
 #pragma unroll
         for (int g = 0; g < MG; ++g)
 #pragma unroll
@@ -267,7 +268,7 @@ __global__ __launch_bounds__(256) void k_gemm_tn(TnArgs a) {
                 for (int u = 0; u < NT; ++u)
 #pragma unroll
                     for (int v = 0; v < 4; ++v) {
-                        const int m = (wave + 4 * g) * 64 + 4 * (4 * kq + v) + t;
+                        const int m = (wave + a.waves * g) * 64 + 4 * (4 * kq + v) + t;
                         const int n = 16 * u + i;
                         if (m < a.M && n < a.N) out[(int64_t)m * a.N + n] = acc[g][t][u][v];
                     }
@@ -324,7 +325,7 @@ static void launch_tall(const TallArgs& args, int epilogue, dim3 grid, size_t ld
 
 template <int MG, int NT, bool NARROW>
 static void launch_tn(const TnArgs& args, int blocks, hipStream_t s) {
-    hipLaunchKernelGGL((k_gemm_tn<MG, NT, NARROW>), dim3(blocks), dim3(256), 0, s, args);
+    hipLaunchKernelGGL((k_gemm_tn<MG, NT, NARROW>), dim3(blocks), dim3(64 * args.waves), 0, s, args);
 }
 
 int gemm_mfma_launch(int ta, int tb, int64_t M, int64_t N, int64_t K, const float* A, int64_t lda, const float* B,
@@ -378,7 +379,20 @@ int gemm_mfma_launch(int ta, int tb, int64_t M, int64_t N, int64_t K, const floa
     const int NTn = (int)((Nw + 15) / 16);
     const bool narrow = Mw <= 32;
     const int groups = (int)((Mw + 63) / 64);
-    const int MG = narrow ? (int)((Mw + 15) / 16) : (groups + 3) / 4;   // tiles (narrow) or column groups per wavefront
+    // wavefronts per workgroup: one per column group up to 8, else the count in 4..8 that leaves the
+    // fewest idle slots (300 columns: 5 groups on 5 wavefronts instead of 2+1+1+1 on 4)
+    int W = 4;
+    if (!narrow) {
+        if (groups <= 8) W = groups < 2 ? 2 : groups;
+        else {
+            int best = 1 << 30;
+            for (int w = 4; w <= 8; ++w) {
+                const int idle = (groups + w - 1) / w * w - groups;
+                if (idle < best) { best = idle; W = w; }
+            }
+        }
+    }
+    const int MG = narrow ? (int)((Mw + 15) / 16) : (groups + W - 1) / W;   // tiles (narrow) or column groups per wavefront
     int64_t blocks = K / 256;                             // at least 256 rows per workgroup
     if (blocks > 2048) blocks = 2048;
     if (blocks < 1) blocks = 1;
@@ -393,6 +407,7 @@ int gemm_mfma_launch(int ta, int tb, int64_t M, int64_t N, int64_t K, const floa
     args.A = Aw; args.lda = ldaw; args.B = Bw; args.ldb = ldbw;
     args.part = (float*)scratch; args.k_per_block = kpb;
     args.a_aligned = (ldaw % 4 == 0) && al16(Aw);
+    args.waves = W;
 #define GCN_TN_CASE(mg, nt) if (!narrow && MG == mg && NTn == nt) launch_tn<mg, nt, false>(args, (int)blocks, s)
     GCN_TN_CASE(1, 1); GCN_TN_CASE(2, 1); GCN_TN_CASE(3, 1); GCN_TN_CASE(4, 1);
     GCN_TN_CASE(1, 2); GCN_TN_CASE(2, 2); GCN_TN_CASE(3, 2); GCN_TN_CASE(4, 2);
