@@ -32,7 +32,7 @@ HBM_PEAK_GBPS = 8000.0
 # FETCH_SIZE x 2.0, WRITE_SIZE x 1.0); from profiles/spmm_split_rmat20_f128.txt.  Keyed by
 # (workload, f); workloads without a committed counter profile report null.
 MEASURED_TRAFFIC_BYTES = {
-    ("rmat20_spmm_f128", 128): int((4.67104e6 * 1.9999 + 555976 * 1.0) * 1024),
+    ("rmat20_spmm_f128", 128): int((4.56939e6 * 1.9999 + 555976 * 1.0) * 1024),
     # whole product on the config 5 graph: 17 sweep launches + split, fix-up and block-reduce kernels of the
     # long rows (profiles/spmm_sweep_chunglu_protein_f16.txt); the event bracket covers the same kernels
     ("chunglu_protein_gcn_128_16_16_256", 16): int(((17 * 1.99819e6 + 6.9298e6 + 159283 + 1.79962e6) * 1.9999
