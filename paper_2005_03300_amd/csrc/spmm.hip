@@ -842,7 +842,14 @@ int spmm_launch(gcn_csr* a, Matrix& m, int32_t f, const float* X, int64_t ldx, f
             const int32_t dmin = config().hub_dmin;
             if (m.hub.state == 0 || m.hub.dmin != dmin || m.hub.cfg_mb != config().hub_mb ||
                 m.hub.cfg_block_cols != config().hub_block_cols) {
-                GCN_TRY(build_hub(m, nnz, H, cpb, dmin, s));
+                const int rc = build_hub(m, nnz, H, cpb, dmin, s);
+                if (rc != GCN_OK) {
+                    // the copy is an optimisation: without it (for instance out of memory) the plain kernel runs
+                    if (forced) return rc;
+                    free_hub(m.hub);
+                    m.hub.state = -1;
+                    m.hub.dmin = dmin;
+                }
                 m.hub.cfg_mb = config().hub_mb;
                 m.hub.cfg_block_cols = config().hub_block_cols;
             }
