@@ -102,11 +102,22 @@ __global__ __launch_bounds__(256) void k_gemm_tall(TallArgs a) {
                                 : __builtin_amdgcn_mfma_f32_16x16x4f32(ae[e], bp[16 * t], acc[t], 0, 0, 0);
             }
         }
-        if (k0 < a.K) {                                 // ragged tail: element-wise guarded loads
+        if (k0 < a.K) {                                 // ragged tail (fewer than 16 columns left)
+            // whole 16-byte pieces when K is a multiple of 4 (300 = 18*16 + 12), else element-wise guarded loads
+            float tail[4] = {0.f, 0.f, 0.f, 0.f};
+            if ((a.K & 3) == 0) {
+                if (k0 + 4 * kq + 4 <= a.K) {
+                    const float4 av = load4(ap + k0, a.a_aligned);
+                    tail[0] = av.x; tail[1] = av.y; tail[2] = av.z; tail[3] = av.w;
+                }
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) tail[e] = k0 + 4 * kq + e < a.K ? ap[k0 + e] : 0.f;
+            }
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const int k = k0 + 4 * kq + e;
-                const float ae = k < a.K ? ap[k0 + e] : 0.f;
+                const float ae = tail[e];
                 const float* bp = Bs + k * a.S + r;     // rows K..Kpad-1 of Bs are zero
 #pragma unroll
                 for (int t = 0; t < NT; ++t)
