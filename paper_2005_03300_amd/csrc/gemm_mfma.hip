@@ -405,7 +405,11 @@ int gemm_mfma_launch(int ta, int tb, int64_t M, int64_t N, int64_t K, const floa
     }
     const int MG = narrow ? (int)((Mw + 15) / 16) : (groups + W - 1) / W;   // tiles (narrow) or column groups per wavefront
     int64_t blocks = K / 256;                             // at least 256 rows per workgroup
-    if (blocks > 2048) blocks = 2048;
+    // measured: more, shorter workgroups pay when a workgroup has five or more wavefronts (300 columns:
+    // 4.13 ms with 2048 workgroups, 3.84 ms with 8192), fewer otherwise (256 columns: 2.69 vs 2.84 ms)
+    // and when it has two or three, so that enough wavefronts exist (128 columns: 1.74 vs 1.47 ms)
+    const int64_t max_blocks = narrow ? 2048 : (W >= 5 ? 8192 : (W <= 3 ? 16384 / W : 2048));
+    if (blocks > max_blocks) blocks = max_blocks;
     if (blocks < 1) blocks = 1;
     int64_t kpb = (K + blocks - 1) / blocks;
     kpb = (kpb + 63) & ~63ll;
