@@ -587,7 +587,7 @@ static int launch_sweep(const SweepArgs& args, int64_t ntasks, int epilogue, hip
 }
 
 // Chooses the lane layout for one nonzero-split product and launches it.
-static int run_split(const SplitArgs& args, int epilogue, hipStream_t s) {
+static int run_split(const SplitArgs& args, int epilogue, hipStream_t s, bool l2_resident = false) {
     const int32_t f = args.f;
     const bool vec4 = (f % 4 == 0) && (args.ldx % 4 == 0) && (args.ldz % 4 == 0) && aligned16(args.X) && aligned16(args.Z) &&
                       (epilogue != GCN_EPI_MASK || ((args.ldzprev % 4 == 0) && aligned16(args.Zprev)));
@@ -595,6 +595,10 @@ static int run_split(const SplitArgs& args, int epilogue, hipStream_t s) {
         // Wider operands are processed in panels of 32 columns (one 128-byte line per gathered row):
         // the panel of X that the gathers touch is 4x smaller than at f = 128, so far more of it stays
         // in L2, at the price of re-reading the index/value stream once per panel.
+        // When the gathers are served by the L2 anyway (column-blocked copy) panels of 64 are better: half
+        // the passes over the index/value stream and half the requests (config 3 at f = 128: 3.55 -> 3.27 ms;
+        // config 2, bound by line fills: 1.46 -> 1.69 ms, so not there).
+        if (f >= 64 && l2_resident) return launch_split<16, 4>(args, epilogue, s);
         if (f > 32) return launch_split<8, 4>(args, epilogue, s);
         const int lanes = f / 4;
         if (lanes <= 4) return launch_split<4, 4>(args, epilogue, s);
@@ -660,7 +664,7 @@ static int run_matrix(gcn_csr* a, Matrix& mm, const int32_t* row_map, int64_t nn
         args.ne_rows = nullptr; args.rp = b.rp; args.row_scale = nullptr;     // the scale belongs to the reduced row
         args.fix_list = b.fix_list; args.n_fix = b.n_fix;
         args.Z = a->partial; args.ldz = f; args.Zprev = nullptr; args.ldzprev = 0;
-        GCN_TRY(run_split(args, GCN_EPI_NONE, s));
+        GCN_TRY(run_split(args, GCN_EPI_NONE, s, true));
         const bool vec4 = (f % 4 == 0) && (ldz % 4 == 0) && aligned16(Z) &&
                           (epilogue != GCN_EPI_MASK || ((ldzprev % 4 == 0) && aligned16(Zprev)));
         if (vec4) return launch_block_reduce<4>(mm.nrows, f, b, row_map, o.row_scale, o.accumulate ? 1 : 0, a->partial, Z, ldz, epilogue, Zprev, ldzprev, s);
