@@ -70,6 +70,8 @@ extern "C" {
 
 #define GCN_CFG_HUB_BLOCK_COLS 9 /* hub schedule: columns per block of the packed buffer (0, default: about 2 MB of the gathered panel; a multiple of 64) */
 
+#define GCN_CFG_SPLIT_LDS_KB 10 /* nonzero-split kernel for operands of up to 16 floats: LDS per workgroup in KB, padding included (18..64, default 28; 18 = no padding).  Padding lowers the number of resident wavefronts, which keep 64 gathers in flight each */
+
 typedef struct gcn_csr gcn_csr; /* opaque: A (and A^T) in compressed rows, degrees, schedules */
 
 /* -------------------------------------------------------------------------------------------

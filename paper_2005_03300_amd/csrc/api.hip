@@ -175,6 +175,10 @@ int gcn_config(int key, int value) {
             if (value < 0 || value > (1 << 24)) return fail(GCN_ERR_BADARG, "GCN_CFG_SPMM_BLOCKS must be in [0, 2^24]");
             config().spmm_blocks = value;
             return GCN_OK;
+        case GCN_CFG_SPLIT_LDS_KB:
+            if (value < 18 || value > 64) return fail(GCN_ERR_BADARG, "GCN_CFG_SPLIT_LDS_KB must be in [18, 64]");
+            config().split_lds_kb = value;
+            return GCN_OK;
         case GCN_CFG_SWEEP_WAVES:
             if (value < 1 || value > 18) return fail(GCN_ERR_BADARG, "GCN_CFG_SWEEP_WAVES must be in [1, 18]");
             config().sweep_waves = value;

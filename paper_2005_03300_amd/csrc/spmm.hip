@@ -363,6 +363,19 @@ __global__ void k_spmm_rowwise(int64_t n, const int64_t* __restrict__ rowptr, co
     Z[i * ldz + j] = acc;
 }
 
+// Dynamic LDS on top of the kernel's own 18 KB, to lower the number of resident workgroups.  The kernels
+// with 16 lane groups per wavefront (rows of up to 64 bytes) keep 64 gathers in flight per wavefront; at
+// full occupancy they run slower than with about two thirds of it (measured on config 3: 18 KB per
+// workgroup 0.66 / 0.57 ms valued / value-free, 28 KB 0.58 / 0.55 ms, 32 KB 0.61 / 0.58 ms; plain kernel
+// on config 4 4.40 -> 4.10 ms; long rows of config 5 -0.1 ms).  The 8-group kernels (config 2: 1.44 ->
+// 1.59 ms at half occupancy) and the paired launch (config 4: 3.15 -> 3.34 ms) want it all.
+static size_t occupancy_pad(int lpr) {
+    if (lpr != 4) return 0;
+    const size_t own = 2 * sizeof(int32_t) * WAVES_PER_BLOCK * LDS_PER_WAVE;     // s_col + s_val
+    const size_t want = (size_t)config().split_lds_kb * 1024;
+    return want > own ? want - own : 0;
+}
+
 template <int LPR, int VEC>
 static int launch_split(const SplitArgs& args, int epilogue, hipStream_t s) {
     const int tile = LPR * VEC;
@@ -372,9 +385,9 @@ static int launch_split(const SplitArgs& args, int epilogue, hipStream_t s) {
     const dim3 fgrid((unsigned)((fix_threads + 255) / 256), ytiles);
     timing_begin(s);
     switch (epilogue) {
-        case GCN_EPI_NONE: hipLaunchKernelGGL((k_spmm_split<LPR, VEC, GCN_EPI_NONE>), grid, dim3(64 * WAVES_PER_BLOCK), 0, s, args); break;
-        case GCN_EPI_RELU: hipLaunchKernelGGL((k_spmm_split<LPR, VEC, GCN_EPI_RELU>), grid, dim3(64 * WAVES_PER_BLOCK), 0, s, args); break;
-        default: hipLaunchKernelGGL((k_spmm_split<LPR, VEC, GCN_EPI_MASK>), grid, dim3(64 * WAVES_PER_BLOCK), 0, s, args); break;
+        case GCN_EPI_NONE: hipLaunchKernelGGL((k_spmm_split<LPR, VEC, GCN_EPI_NONE>), grid, dim3(64 * WAVES_PER_BLOCK), occupancy_pad(LPR), s, args); break;
+        case GCN_EPI_RELU: hipLaunchKernelGGL((k_spmm_split<LPR, VEC, GCN_EPI_RELU>), grid, dim3(64 * WAVES_PER_BLOCK), occupancy_pad(LPR), s, args); break;
+        default: hipLaunchKernelGGL((k_spmm_split<LPR, VEC, GCN_EPI_MASK>), grid, dim3(64 * WAVES_PER_BLOCK), occupancy_pad(LPR), s, args); break;
     }
     timing_end(s);
     GCN_LAUNCH_CHECK();
