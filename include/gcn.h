@@ -62,14 +62,10 @@ extern "C" {
 #define GCN_CFG_SPMM_BLOCKS 3 /* column blocks of the SpMM: 0 = automatic, 1 = never block, k >= 2 = k blocks */
 #define GCN_CFG_SWEEP_HEAVY 4 /* rows longer than this bypass the column sweep (default 1024; >= 1) */
 #define GCN_CFG_SWEEP_WAVES 5 /* column sweep: tasks per compute unit in one launch (default 8: 8 x 16 KB of LDS accumulators per compute unit; 1..18) */
-
 #define GCN_CFG_PATTERN_SPMM 6 /* gcn_epoch on a matrix made by gcn_csr_create with GCN_NORM_SYM: use the value-free SpMM (operand rows pre-scaled by d^-1/2, output rows scaled by d^-1/2) instead of reading the stored values. 0 never, 1 always, 2 (default) when the mean row has at least 64 entries */
-
 #define GCN_CFG_HUB_MB 7   /* hub schedule: size in MB of the packed buffer that holds the rows of X selected by the columns with the most entries (default 32) */
 #define GCN_CFG_HUB_DMIN 8 /* hub schedule: rows with at least this many entries are treated as long rows (default 64) */
-
 #define GCN_CFG_HUB_BLOCK_COLS 9 /* hub schedule: columns per block of the packed buffer (0, default: about 2 MB of the gathered panel; a multiple of 64) */
-
 #define GCN_CFG_SPLIT_LDS_KB 10 /* nonzero-split kernel for operands of up to 16 floats: LDS per workgroup in KB, padding included (18..64, default 28; 18 = no padding).  Padding lowers the number of resident wavefronts, which keep 64 gathers in flight each */
 
 typedef struct gcn_csr gcn_csr; /* opaque: A (and A^T) in compressed rows, degrees, schedules */
