@@ -22,6 +22,9 @@
 namespace gcn {
 
 static constexpr int WAVES_PER_BLOCK = 4;
+#ifndef SPLIT_UNROLL
+#define SPLIT_UNROLL 4
+#endif
 static constexpr int SUB_STRIDE = SUB + 4;                         // LDS padding: groups hit different banks
 static constexpr int LDS_PER_WAVE = SUBS_PER_CHUNK * SUB_STRIDE;   // ints
 
@@ -113,6 +116,7 @@ __device__ __forceinline__ void split_body(const SplitArgs& a, int64_t grp, int3
     constexpr int G = 64 / LPR;                 // lane groups per wavefront
     constexpr int NW = SUBS_PER_CHUNK / G;      // flag words per group
     static_assert(NW >= 1, "a group needs at least one flag word");
+    constexpr int UNR = SPLIT_UNROLL;           // gathers in flight per lane group
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t c = grp * WAVES_PER_BLOCK + wave;
@@ -173,14 +177,19 @@ __device__ __forceinline__ void split_body(const SplitArgs& a, int64_t grp, int3
         const int64_t left = a.nnz - j * SUB;
         const int cnt = left >= SUB ? SUB : (left > 0 ? (int)left : 0);
         const int base = (g * NW + w) * SUB_STRIDE;
-        for (int b = 0; b < cnt; b += 4) {
-            const int4 cc = *reinterpret_cast<const int4*>(lc + base + b);
-            const float4 vv = *reinterpret_cast<const float4*>(lv + base + b);
-            const int32_t cs[4] = {cc.x, cc.y, cc.z, cc.w};
-            const float vs[4] = {vv.x, vv.y, vv.z, vv.w};
-            float x[4][VEC];
+        for (int b = 0; b < cnt; b += UNR) {
+            int32_t cs[UNR];
+            float vs[UNR];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
+            for (int h = 0; h < UNR / 4; ++h) {
+                const int4 cc = *reinterpret_cast<const int4*>(lc + base + b + 4 * h);
+                const float4 vv = *reinterpret_cast<const float4*>(lv + base + b + 4 * h);
+                cs[4 * h] = cc.x; cs[4 * h + 1] = cc.y; cs[4 * h + 2] = cc.z; cs[4 * h + 3] = cc.w;
+                vs[4 * h] = vv.x; vs[4 * h + 1] = vv.y; vs[4 * h + 2] = vv.z; vs[4 * h + 3] = vv.w;
+            }
+            float x[UNR][VEC];
+#pragma unroll
+            for (int e = 0; e < UNR; ++e) {
                 if (b + e < cnt && col_ok) load_vec<VEC>(x[e], xbase + (int64_t)cs[e] * a.ldx);
                 else {
 #pragma unroll
@@ -188,7 +197,7 @@ __device__ __forceinline__ void split_body(const SplitArgs& a, int64_t grp, int3
                 }
             }
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
+            for (int e = 0; e < UNR; ++e) {
                 if (b + e < cnt) {
                     if (mask & 1u) {            // entry starts a row: close the fragment before it
                         if (owned) {
