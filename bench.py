@@ -35,8 +35,8 @@ MEASURED_TRAFFIC_BYTES = {
     ("rmat20_spmm_f128", 128): int((4.56939e6 * 1.9999 + 555976 * 1.0) * 1024),
     # whole product on the config 5 graph: 17 sweep launches + split, fix-up and block-reduce kernels of the
     # long rows (profiles/spmm_sweep_chunglu_protein_f16.txt); the event bracket covers the same kernels
-    ("chunglu_protein_gcn_128_16_16_256", 16): int(((17 * 1.99819e6 + 6.9298e6 + 159283 + 1.79962e6) * 1.9999
-                                                    + (17 * 32152.7 + 2.41611e6 + 42535.8 + 7828.05) * 1.0) * 1024),
+    ("chunglu_protein_gcn_128_16_16_256", 16): int(((17 * 1.98038e6 + 7.38595e6 + 159127 + 517412) * 1.9999
+                                                    + (17 * 32152.7 + 950118 + 45046.3 + 7828.04) * 1.0) * 1024),
 }
 
 
