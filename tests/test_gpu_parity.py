@@ -1009,6 +1009,62 @@ def test_spmm_full_size_config2_sampled_rows():
     a.close()
 
 
+def test_full_size_config4_hub_schedule_properties():
+    """Config 4 at full size (14 M vertices, 246 M entries) in the configuration the benchmark times: the
+    automatic choice is the hub schedule.  The oracle needs minutes here, so: the product equals the one of
+    the plain kernel (an independent schedule), and sqrt(d) is reproduced by the normalised matrix."""
+    g = G()
+    n, src, dst = synth.make_graph(synth.CONFIGS[4])
+    a = g.gcn_csr_create(n, dev(src), dev(dst), flags_all())
+    del src, dst
+    X = torch.rand(n, 16, device="cuda") * 2 - 1
+    Z = torch.full((n, 16), float("nan"), device="cuda")
+    Z2 = torch.empty_like(Z)
+    for trans in (0, 1):
+        g.gcn_spmm(a, trans, X, Z)
+        assert g.gcn_last_spmm_schedule() == g.SCHED_HUB
+        g.gcn_config(g.CFG_SPMM_ALGO, 2)
+        try:
+            g.gcn_spmm(a, trans, X, Z2)
+            assert g.gcn_last_spmm_schedule() == g.SCHED_SPLIT
+        finally:
+            g.gcn_config(g.CFG_SPMM_ALGO, 0)
+        rms = float(Z2.double().pow(2).mean().sqrt())
+        assert bool(torch.isfinite(Z).all()) and float((Z - Z2).abs().max()) <= 1e-5 * rms
+    deg = a.arrays(False)[3]
+    sq = torch.sqrt(deg.float())[:, None].repeat(1, 16).contiguous()
+    g.gcn_spmm(a, 0, sq, Z)
+    assert float(((Z - sq).abs() / sq).max()) < 1e-4
+    a.close()
+
+
+def test_quarter_size_config5_column_sweep_properties():
+    """Config 5 shrunk four times (2.2 M vertices, 330 M entries): still far beyond the caches, so the
+    automatic choice is the column sweep, as at full size.  Same size-independent checks as above."""
+    g = G()
+    n, src, dst = synth.make_graph(synth.scaled(5, 4))
+    a = g.gcn_csr_create(n, dev(src), dev(dst), flags_all())
+    del src, dst
+    X = torch.rand(n, 16, device="cuda") * 2 - 1
+    Z = torch.full((n, 16), float("nan"), device="cuda")
+    Z2 = torch.empty_like(Z)
+    for trans in (0, 1):
+        g.gcn_spmm(a, trans, X, Z)
+        assert g.gcn_last_spmm_schedule() == g.SCHED_SWEEP
+        g.gcn_config(g.CFG_SPMM_ALGO, 2)
+        try:
+            g.gcn_spmm(a, trans, X, Z2)
+        finally:
+            g.gcn_config(g.CFG_SPMM_ALGO, 0)
+        rms = float(Z2.double().pow(2).mean().sqrt())
+        assert bool(torch.isfinite(Z).all()) and float((Z - Z2).abs().max()) <= 1e-5 * rms
+    deg = a.arrays(False)[3]
+    sq = torch.sqrt(deg.float())[:, None].repeat(1, 16).contiguous()
+    g.gcn_spmm(a, 0, sq, Z)
+    assert float(((Z - sq).abs() / sq).max()) < 1e-4
+    a.close()
+
+
 @pytest.mark.skipif(os.environ.get("GCN_TEST_HUGE", "1") != "1",
                     reason="switched off with GCN_TEST_HUGE=0 (needs ~150 GB of device memory)")
 def test_more_than_2_31_stored_entries():
