@@ -61,7 +61,7 @@ extern "C" {
 #define GCN_CFG_TIMING 2    /* 1 = bracket the dominant kernels with HIP events (see gcn_timing_read) */
 #define GCN_CFG_SPMM_BLOCKS 3 /* column blocks of the SpMM: 0 = automatic, 1 = never block, k >= 2 = k blocks */
 #define GCN_CFG_SWEEP_HEAVY 4 /* rows longer than this bypass the column sweep (default 1024; >= 1) */
-#define GCN_CFG_SWEEP_WAVES 5 /* column sweep: tasks per compute unit in one launch (default 8: 8 x 16 KB of LDS accumulators per compute unit; 1..18) */
+#define GCN_CFG_SWEEP_WAVES 5 /* column sweep: tasks per compute unit in one launch (default 9: 9 x 16 KB of LDS accumulators per compute unit, the most that fit; 1..18) */
 #define GCN_CFG_PATTERN_SPMM 6 /* gcn_epoch on a matrix made by gcn_csr_create with GCN_NORM_SYM: use the value-free SpMM (operand rows pre-scaled by d^-1/2, output rows scaled by d^-1/2) instead of reading the stored values. 0 never, 1 always, 2 (default) when the mean row has at least 64 entries */
 #define GCN_CFG_HUB_MB 7   /* hub schedule: size in MB of the packed buffer that holds the rows of X selected by the columns with the most entries (default 32) */
 #define GCN_CFG_HUB_DMIN 8 /* hub schedule: rows with at least this many entries are treated as long rows (default 64) */

@@ -164,7 +164,7 @@ struct Config {
     int spmm_blocks = 0;
     int sweep_heavy = 1024;
     int split_lds_kb = 28;       // nonzero-split kernels for rows of up to 64 bytes: LDS per workgroup incl. padding (18: none)
-    int sweep_waves = 8;
+    int sweep_waves = 9;
     int hub_mb = 32;             // hub schedule: size of the packed buffer of hot rows of X, MB
     int hub_block_cols = 0;      // hub schedule: columns per block (0: about 2 MB of the gathered panel)
     int hub_dmin = 64;           // hub schedule: rows with at least this many entries are long rows
