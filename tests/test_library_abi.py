@@ -50,3 +50,12 @@ def test_binding_does_not_touch_the_oracle():
         if fn.endswith((".py", ".c")):
             text = open(os.path.join(here, "oracle", fn)).read()
             assert "paper_2005_03300_amd" not in text and "gcn.h" not in text
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode == 2 and "single-GPU" in r.stderr and r.stdout.strip() == ""
