@@ -7,16 +7,12 @@
 //
 // Entries are encoded as 64-bit keys row<<32|col; a radix sort of the keys followed by the
 // removal of equal neighbours yields the canonical row-major order with ascending columns.  The
-// device-wide sort, select and scan primitives come from rocPRIM; everything else is below.
+// device-wide sort, selection and prefix sum are the ones of prims.h.
 #include <cstring>
 #include <new>
 
-#include <rocprim/device/device_radix_sort.hpp>
-#include <rocprim/device/device_scan.hpp>
-#include <rocprim/device/device_select.hpp>
-#include <rocprim/iterator/counting_iterator.hpp>
-
 #include "common.h"
+#include "prims.h"
 
 namespace gcn {
 
@@ -201,13 +197,7 @@ __global__ void k_sub_rows(int64_t nsub, int64_t n_ne, const int64_t* __restrict
 static int sort_keys(uint64_t* in, uint64_t* out, int64_t count, int64_t n, hipStream_t s) {
     unsigned end_bit = 64;   // INVALID_KEY uses every bit
     (void)n;
-    size_t tmp_bytes = 0;
-    GCN_HIP_TRY(rocprim::radix_sort_keys(nullptr, tmp_bytes, in, out, (size_t)count, 0u, end_bit, s));
-    TempBuf tmp;
-    GCN_TRY(tmp.alloc(tmp_bytes));
-    GCN_HIP_TRY(rocprim::radix_sort_keys(tmp.p, tmp_bytes, in, out, (size_t)count, 0u, end_bit, s));
-    GCN_HIP_TRY(hipStreamSynchronize(s));
-    return GCN_OK;
+    return prims::sort_keys<uint64_t>(in, out, (size_t)count, end_bit, s);
 }
 
 static unsigned bits_for(int64_t n) {
@@ -249,26 +239,19 @@ int build_fix_list(const uint32_t* flags, const int32_t* sub_row, const int64_t*
     *count = 0;
     if (nchunks <= 1) return GCN_OK;
     if (nchunks >= (1ll << 31)) { *count = -1; return GCN_OK; }          // keep the exhaustive form
-    TempBuf sel, cnt, tmp;
+    TempBuf sel;
     GCN_TRY(sel.alloc((size_t)(nchunks - 1) * 4));
-    GCN_TRY(cnt.alloc(sizeof(size_t)));
-    rocprim::counting_iterator<int32_t> ids(0);
     LeadsCarry pred{flags, sub_row, rp};
-    size_t tmp_bytes = 0;
-    GCN_HIP_TRY(rocprim::select(nullptr, tmp_bytes, ids, sel.as<int32_t>(), cnt.as<size_t>(), (size_t)(nchunks - 1), pred, s));
-    GCN_TRY(tmp.alloc(tmp_bytes));
-    GCN_HIP_TRY(rocprim::select(tmp.p, tmp_bytes, ids, sel.as<int32_t>(), cnt.as<size_t>(), (size_t)(nchunks - 1), pred, s));
-    size_t nsel = 0;
-    GCN_HIP_TRY(hipMemcpyAsync(&nsel, cnt.p, sizeof(size_t), hipMemcpyDeviceToHost, s));
-    GCN_HIP_TRY(hipStreamSynchronize(s));
+    int64_t nsel = 0;
+    GCN_TRY(prims::select_indices(nchunks - 1, pred, sel.as<int32_t>(), &nsel, s));
     if (nsel > 0) {
-        GCN_TRY(device_alloc_t(list, nsel));
-        GCN_HIP_TRY(hipMemcpyAsync(*list, sel.p, nsel * 4, hipMemcpyDeviceToDevice, s));
-        hipLaunchKernelGGL(k_add_one, dim3(blocks_for((int64_t)nsel)), dim3(TPB), 0, s, (int64_t)nsel, *list);
+        GCN_TRY(device_alloc_t(list, (size_t)nsel));
+        GCN_HIP_TRY(hipMemcpyAsync(*list, sel.p, (size_t)nsel * 4, hipMemcpyDeviceToDevice, s));
+        hipLaunchKernelGGL(k_add_one, dim3(blocks_for(nsel)), dim3(TPB), 0, s, nsel, *list);
         GCN_LAUNCH_CHECK();
         GCN_HIP_TRY(hipStreamSynchronize(s));
     }
-    *count = (int64_t)nsel;
+    *count = nsel;
     return GCN_OK;
 }
 
@@ -290,23 +273,14 @@ int build_schedule(Matrix& m, int64_t n, int64_t nnz, hipStream_t s) {
     if (m.n_ne < n) {
         GCN_TRY(device_alloc_t(&m.ne_rows, (size_t)m.n_ne));
         GCN_TRY(device_alloc_t(&m.ne_rowptr, (size_t)m.n_ne + 1));
-        TempBuf cnt, tmp;
-        GCN_TRY(cnt.alloc(sizeof(size_t)));
-        size_t tmp_bytes = 0;
-        rocprim::counting_iterator<int32_t> rows(0);
         NonEmpty pred{m.rowptr};
-        GCN_HIP_TRY(rocprim::select(nullptr, tmp_bytes, rows, m.ne_rows, cnt.as<size_t>(), (size_t)n, pred, s));
-        GCN_TRY(tmp.alloc(tmp_bytes));
-        GCN_HIP_TRY(rocprim::select(tmp.p, tmp_bytes, rows, m.ne_rows, cnt.as<size_t>(), (size_t)n, pred, s));
+        GCN_TRY(prims::select_indices(n, pred, m.ne_rows, nullptr, s));
         hipLaunchKernelGGL(k_ne_rowptr, dim3(blocks_for(m.n_ne + 1)), dim3(TPB), 0, s, m.n_ne, nnz, m.ne_rows,
                            m.rowptr, m.ne_rowptr);
         GCN_LAUNCH_CHECK();
         GCN_TRY(device_alloc_t(&m.empty_rows, (size_t)(n - m.n_ne)));
         IsEmpty epred{m.rowptr};
-        tmp_bytes = 0;
-        GCN_HIP_TRY(rocprim::select(nullptr, tmp_bytes, rows, m.empty_rows, cnt.as<size_t>(), (size_t)n, epred, s));
-        GCN_TRY(tmp.alloc(tmp_bytes));
-        GCN_HIP_TRY(rocprim::select(tmp.p, tmp_bytes, rows, m.empty_rows, cnt.as<size_t>(), (size_t)n, epred, s));
+        GCN_TRY(prims::select_indices(n, epred, m.empty_rows, nullptr, s));
         GCN_HIP_TRY(hipStreamSynchronize(s));
         rp = m.ne_rowptr;
     }
@@ -399,7 +373,7 @@ int build_blocked(Matrix& m, int64_t nnz, int64_t cpb, hipStream_t s) {
     const int64_t n = m.nrows;
     const int64_t nblocks = (m.ncols + cpb - 1) / cpb;
     const int64_t nsub = m.nsub;
-    TempBuf k0, k1, p0, p1, cnt, pre, tmp;
+    TempBuf k0, k1, p0, p1, cnt, pre;
     GCN_TRY(k0.alloc((size_t)nnz * 8));
     GCN_TRY(k1.alloc((size_t)nnz * 8));
     GCN_TRY(p0.alloc((size_t)nnz * 8));
@@ -407,14 +381,9 @@ int build_blocked(Matrix& m, int64_t nnz, int64_t cpb, hipStream_t s) {
     hipLaunchKernelGGL(k_block_keys, dim3(blocks_for(nnz)), dim3(TPB), 0, s, nnz, n, m.rowptr, m.colidx, m.val, cpb,
                        k0.as<uint64_t>(), p0.as<uint64_t>());
     GCN_LAUNCH_CHECK();
-    size_t tmp_bytes = 0;
     const unsigned end_bit = 32 + bits_for(nblocks + 1);
-    GCN_HIP_TRY(rocprim::radix_sort_pairs(nullptr, tmp_bytes, k0.as<uint64_t>(), k1.as<uint64_t>(), p0.as<uint64_t>(),
-                                          p1.as<uint64_t>(), (size_t)nnz, 0u, end_bit, s));
-    GCN_TRY(tmp.alloc(tmp_bytes));
-    GCN_HIP_TRY(rocprim::radix_sort_pairs(tmp.p, tmp_bytes, k0.as<uint64_t>(), k1.as<uint64_t>(), p0.as<uint64_t>(),
-                                          p1.as<uint64_t>(), (size_t)nnz, 0u, end_bit, s));
-    GCN_HIP_TRY(hipStreamSynchronize(s));
+    GCN_TRY((prims::sort_pairs<uint64_t, uint64_t>(k0.as<uint64_t>(), k1.as<uint64_t>(), p0.as<uint64_t>(),
+                                                   p1.as<uint64_t>(), (size_t)nnz, end_bit, s)));
     k0.alloc(16);                                        // release the unsorted copies early
     p0.alloc(16);
 
@@ -428,12 +397,7 @@ int build_blocked(Matrix& m, int64_t nnz, int64_t cpb, hipStream_t s) {
     hipLaunchKernelGGL(k_block_flags, dim3(blocks_for(nsub)), dim3(TPB), 0, s, nnz, nsub, k1.as<uint64_t>(), b.flags,
                        cnt.as<int32_t>());
     GCN_LAUNCH_CHECK();
-    tmp_bytes = 0;
-    GCN_HIP_TRY(rocprim::exclusive_scan(nullptr, tmp_bytes, cnt.as<int32_t>(), pre.as<int32_t>(), (int32_t)0,
-                                        (size_t)nsub, rocprim::plus<int32_t>(), s));
-    GCN_TRY(tmp.alloc(tmp_bytes));
-    GCN_HIP_TRY(rocprim::exclusive_scan(tmp.p, tmp_bytes, cnt.as<int32_t>(), pre.as<int32_t>(), (int32_t)0,
-                                        (size_t)nsub, rocprim::plus<int32_t>(), s));
+    GCN_TRY(prims::exclusive_scan<int32_t>(cnt.as<int32_t>(), pre.as<int32_t>(), (size_t)nsub, s));
     int32_t last_pre = 0, last_cnt = 0;
     GCN_HIP_TRY(hipMemcpyAsync(&last_pre, pre.as<int32_t>() + (nsub - 1), 4, hipMemcpyDeviceToHost, s));
     GCN_HIP_TRY(hipMemcpyAsync(&last_cnt, cnt.as<int32_t>() + (nsub - 1), 4, hipMemcpyDeviceToHost, s));
@@ -455,13 +419,8 @@ int build_blocked(Matrix& m, int64_t nnz, int64_t cpb, hipStream_t s) {
     hipLaunchKernelGGL(k_block_unpack, dim3(blocks_for(nnz)), dim3(TPB), 0, s, nnz, p1.as<uint64_t>(), b.colidx, b.val);
     GCN_LAUNCH_CHECK();
     // group the partial rows by the row they belong to; inside a row q ascends, i.e. block order
-    tmp_bytes = 0;
     const unsigned end_bit2 = 32 + bits_for(n);
-    GCN_HIP_TRY(rocprim::radix_sort_keys(nullptr, tmp_bytes, rq0.as<uint64_t>(), rq1.as<uint64_t>(), (size_t)R, 0u,
-                                         end_bit2, s));
-    GCN_TRY(tmp.alloc(tmp_bytes));
-    GCN_HIP_TRY(rocprim::radix_sort_keys(tmp.p, tmp_bytes, rq0.as<uint64_t>(), rq1.as<uint64_t>(), (size_t)R, 0u,
-                                         end_bit2, s));
+    GCN_TRY(prims::sort_keys<uint64_t>(rq0.as<uint64_t>(), rq1.as<uint64_t>(), (size_t)R, end_bit2, s));
     GCN_TRY(device_alloc_t(&b.rq_ptr, (size_t)n + 1));
     GCN_TRY(device_alloc_t(&b.rq_idx, (size_t)R));
     hipLaunchKernelGGL(k_compress, dim3(blocks_for(R)), dim3(TPB), 0, s, R, n, rq1.as<uint64_t>(), b.rq_ptr, b.rq_idx);
@@ -623,7 +582,7 @@ int build_sweep(Matrix& m, int64_t nnz, int32_t groups, int32_t rb, int32_t heav
     const uint64_t heavy_key = 1ull << (cbits + tbits);
 
     // entries sorted by (task, column); heavy rows behind them in (row, column) order
-    TempBuf k0, k1, p0, p1, seg, tmp;
+    TempBuf k0, k1, p0, p1, seg;
     GCN_TRY(k0.alloc((size_t)nnz * 8));
     GCN_TRY(k1.alloc((size_t)nnz * 8));
     GCN_TRY(p0.alloc((size_t)nnz * sizeof(SweepPayload)));
@@ -631,14 +590,9 @@ int build_sweep(Matrix& m, int64_t nnz, int32_t groups, int32_t rb, int32_t heav
     hipLaunchKernelGGL(k_sweep_keys, dim3(blocks_for(nnz)), dim3(TPB), 0, s, nnz, n, m.rowptr, m.colidx, m.val, rb, heavy_th,
                        cbits, heavy_key, k0.as<uint64_t>(), p0.as<SweepPayload>());
     GCN_LAUNCH_CHECK();
-    size_t tmp_bytes = 0;
     const unsigned end_bit = cbits + tbits + 1;
-    GCN_HIP_TRY(rocprim::radix_sort_pairs(nullptr, tmp_bytes, k0.as<uint64_t>(), k1.as<uint64_t>(), p0.as<SweepPayload>(),
-                                          p1.as<SweepPayload>(), (size_t)nnz, 0u, end_bit, s));
-    GCN_TRY(tmp.alloc(tmp_bytes));
-    GCN_HIP_TRY(rocprim::radix_sort_pairs(tmp.p, tmp_bytes, k0.as<uint64_t>(), k1.as<uint64_t>(), p0.as<SweepPayload>(),
-                                          p1.as<SweepPayload>(), (size_t)nnz, 0u, end_bit, s));
-    GCN_HIP_TRY(hipStreamSynchronize(s));
+    GCN_TRY((prims::sort_pairs<uint64_t, SweepPayload>(k0.as<uint64_t>(), k1.as<uint64_t>(), p0.as<SweepPayload>(),
+                                                       p1.as<SweepPayload>(), (size_t)nnz, end_bit, s)));
     k0.alloc(16);
     p0.alloc(16);
     GCN_TRY(seg.alloc(((size_t)ntasks + 1) * 8));
@@ -662,18 +616,9 @@ int build_sweep(Matrix& m, int64_t nnz, int32_t groups, int32_t rb, int32_t heav
     GCN_LAUNCH_CHECK();
     hipLaunchKernelGGL(k_iota_i32, dim3(blocks_for(ntasks)), dim3(TPB), 0, s, ntasks, ids.as<int32_t>());
     GCN_LAUNCH_CHECK();
-    tmp_bytes = 0;
-    GCN_HIP_TRY(rocprim::radix_sort_pairs_desc(nullptr, tmp_bytes, len.as<uint32_t>(), len_sorted.as<uint32_t>(),
-                                               ids.as<int32_t>(), w.task_order, (size_t)ntasks, 0u, 32u, s));
-    GCN_TRY(tmp.alloc(tmp_bytes));
-    GCN_HIP_TRY(rocprim::radix_sort_pairs_desc(tmp.p, tmp_bytes, len.as<uint32_t>(), len_sorted.as<uint32_t>(),
-                                               ids.as<int32_t>(), w.task_order, (size_t)ntasks, 0u, 32u, s));
-    tmp_bytes = 0;
-    GCN_HIP_TRY(rocprim::exclusive_scan(nullptr, tmp_bytes, plen.as<int64_t>(), w.task_base, (int64_t)0, (size_t)ntasks,
-                                        rocprim::plus<int64_t>(), s));
-    GCN_TRY(tmp.alloc(tmp_bytes));
-    GCN_HIP_TRY(rocprim::exclusive_scan(tmp.p, tmp_bytes, plen.as<int64_t>(), w.task_base, (int64_t)0, (size_t)ntasks,
-                                        rocprim::plus<int64_t>(), s));
+    GCN_TRY((prims::sort_pairs_descending<uint32_t, int32_t>(len.as<uint32_t>(), len_sorted.as<uint32_t>(),
+                                                             ids.as<int32_t>(), w.task_order, (size_t)ntasks, 32u, s)));
+    GCN_TRY(prims::exclusive_scan<int64_t>(plen.as<int64_t>(), w.task_base, (size_t)ntasks, s));
     int64_t nnz_light = 0, last_base = 0, last_plen = 0;
     GCN_HIP_TRY(hipMemcpyAsync(&nnz_light, seg.as<int64_t>() + ntasks, 8, hipMemcpyDeviceToHost, s));
     GCN_HIP_TRY(hipMemcpyAsync(&last_base, w.task_base + (ntasks - 1), 8, hipMemcpyDeviceToHost, s));
@@ -708,30 +653,19 @@ int build_sweep(Matrix& m, int64_t nnz, int32_t groups, int32_t rb, int32_t heav
                            p1.as<SweepPayload>(), h->colidx, h->val);
         GCN_LAUNCH_CHECK();
         // the heavy rows in ascending order, and their offsets into the heavy entry arrays
-        TempBuf cnt, hl;
-        GCN_TRY(cnt.alloc(sizeof(size_t)));
+        TempBuf hl;
         GCN_TRY(device_alloc_t(&h->ne_rows, (size_t)(nnz_heavy / (heavy_th + 1)) + 1));
-        rocprim::counting_iterator<int32_t> rows(0);
         HeavyRow pred{m.rowptr, heavy_th};
-        tmp_bytes = 0;
-        GCN_HIP_TRY(rocprim::select(nullptr, tmp_bytes, rows, h->ne_rows, cnt.as<size_t>(), (size_t)n, pred, s));
-        GCN_TRY(tmp.alloc(tmp_bytes));
-        GCN_HIP_TRY(rocprim::select(tmp.p, tmp_bytes, rows, h->ne_rows, cnt.as<size_t>(), (size_t)n, pred, s));
-        size_t nh = 0;
-        GCN_HIP_TRY(hipMemcpyAsync(&nh, cnt.p, sizeof(size_t), hipMemcpyDeviceToHost, s));
-        GCN_HIP_TRY(hipStreamSynchronize(s));
-        h->n_ne = (int64_t)nh;
+        int64_t nh_sel = 0;
+        GCN_TRY(prims::select_indices(n, pred, h->ne_rows, &nh_sel, s));
+        const size_t nh = (size_t)nh_sel;
+        h->n_ne = nh_sel;
         GCN_TRY(hl.alloc((nh + 1) * 8));
         GCN_TRY(device_alloc_t(&h->ne_rowptr, nh + 1));
         hipLaunchKernelGGL(k_heavy_len, dim3(blocks_for((int64_t)nh + 1)), dim3(TPB), 0, s, (int64_t)nh, h->ne_rows, m.rowptr,
                            hl.as<int64_t>());
         GCN_LAUNCH_CHECK();
-        tmp_bytes = 0;
-        GCN_HIP_TRY(rocprim::exclusive_scan(nullptr, tmp_bytes, hl.as<int64_t>(), h->ne_rowptr, (int64_t)0, nh + 1,
-                                            rocprim::plus<int64_t>(), s));
-        GCN_TRY(tmp.alloc(tmp_bytes));
-        GCN_HIP_TRY(rocprim::exclusive_scan(tmp.p, tmp_bytes, hl.as<int64_t>(), h->ne_rowptr, (int64_t)0, nh + 1,
-                                            rocprim::plus<int64_t>(), s));
+        GCN_TRY(prims::exclusive_scan<int64_t>(hl.as<int64_t>(), h->ne_rowptr, nh + 1, s));
         // as a compact matrix of its own: nh rows, rowptr = the offsets just computed
         h->nrows = (int64_t)nh;
         h->ncols = m.ncols;
@@ -835,8 +769,7 @@ int build_hub(Matrix& m, int64_t nnz, int64_t H, int64_t cpb, int32_t dmin, hipS
     const int64_t n = m.nrows, nc = m.ncols;
     if (nnz <= 0 || H <= 0 || cpb <= 0 || H % cpb != 0 || H > nc || dmin < 1)
         return fail(GCN_ERR_BADARG, "build_hub: bad parameters");
-    TempBuf cnt, cnt_sorted, ids, cols_sorted, rank, flag, pos, tmp, hc;
-    size_t tmp_bytes = 0;
+    TempBuf cnt, cnt_sorted, ids, cols_sorted, rank, flag, pos, hc;
 
     // the H columns with the most entries, in descending order of length
     GCN_TRY(cnt.alloc((size_t)nc * 4));
@@ -848,11 +781,8 @@ int build_hub(Matrix& m, int64_t nnz, int64_t H, int64_t cpb, int32_t dmin, hipS
     GCN_LAUNCH_CHECK();
     hipLaunchKernelGGL(k_iota_i32, dim3(blocks_for(nc)), dim3(TPB), 0, s, nc, ids.as<int32_t>());
     GCN_LAUNCH_CHECK();
-    GCN_HIP_TRY(rocprim::radix_sort_pairs_desc(nullptr, tmp_bytes, cnt.as<uint32_t>(), cnt_sorted.as<uint32_t>(),
-                                               ids.as<int32_t>(), cols_sorted.as<int32_t>(), (size_t)nc, 0u, 32u, s));
-    GCN_TRY(tmp.alloc(tmp_bytes));
-    GCN_HIP_TRY(rocprim::radix_sort_pairs_desc(tmp.p, tmp_bytes, cnt.as<uint32_t>(), cnt_sorted.as<uint32_t>(),
-                                               ids.as<int32_t>(), cols_sorted.as<int32_t>(), (size_t)nc, 0u, 32u, s));
+    GCN_TRY((prims::sort_pairs_descending<uint32_t, int32_t>(cnt.as<uint32_t>(), cnt_sorted.as<uint32_t>(), ids.as<int32_t>(),
+                                                             cols_sorted.as<int32_t>(), (size_t)nc, 32u, s)));
     GCN_TRY(hc.alloc((size_t)H * 4));
     GCN_HIP_TRY(hipMemcpyAsync(hc.p, cols_sorted.p, (size_t)H * 4, hipMemcpyDeviceToDevice, s));
     GCN_TRY(rank.alloc((size_t)nc * 4));
@@ -861,21 +791,15 @@ int build_hub(Matrix& m, int64_t nnz, int64_t H, int64_t cpb, int32_t dmin, hipS
     GCN_LAUNCH_CHECK();
 
     // the long rows
-    TempBuf defer, hrows, nsel;
+    TempBuf defer, hrows;
     GCN_TRY(defer.alloc((size_t)n));
     hipLaunchKernelGGL(k_hub_defer, dim3(blocks_for(n)), dim3(TPB), 0, s, n, m.rowptr, dmin, defer.as<uint8_t>());
     GCN_LAUNCH_CHECK();
     GCN_TRY(hrows.alloc((size_t)(nnz / dmin + 1) * 4));
-    GCN_TRY(nsel.alloc(sizeof(size_t)));
-    rocprim::counting_iterator<int32_t> rows(0);
     HeavyRow pred{m.rowptr, dmin - 1};
-    tmp_bytes = 0;
-    GCN_HIP_TRY(rocprim::select(nullptr, tmp_bytes, rows, hrows.as<int32_t>(), nsel.as<size_t>(), (size_t)n, pred, s));
-    GCN_TRY(tmp.alloc(tmp_bytes));
-    GCN_HIP_TRY(rocprim::select(tmp.p, tmp_bytes, rows, hrows.as<int32_t>(), nsel.as<size_t>(), (size_t)n, pred, s));
-    size_t nh = 0;
-    GCN_HIP_TRY(hipMemcpyAsync(&nh, nsel.p, sizeof(size_t), hipMemcpyDeviceToHost, s));
-    GCN_HIP_TRY(hipStreamSynchronize(s));
+    int64_t nh_sel = 0;
+    GCN_TRY(prims::select_indices(n, pred, hrows.as<int32_t>(), &nh_sel, s));
+    const size_t nh = (size_t)nh_sel;
     if (nh == 0) return GCN_OK;                              // rejected: no long rows
 
     // split the entries
@@ -884,12 +808,7 @@ int build_hub(Matrix& m, int64_t nnz, int64_t H, int64_t cpb, int32_t dmin, hipS
     hipLaunchKernelGGL(k_hub_flags, dim3(blocks_for(nnz + 1)), dim3(TPB), 0, s, nnz, n, m.rowptr, m.colidx,
                        defer.as<uint8_t>(), rank.as<int32_t>(), flag.as<int64_t>());
     GCN_LAUNCH_CHECK();
-    tmp_bytes = 0;
-    GCN_HIP_TRY(rocprim::exclusive_scan(nullptr, tmp_bytes, flag.as<int64_t>(), pos.as<int64_t>(), (int64_t)0,
-                                        (size_t)nnz + 1, rocprim::plus<int64_t>(), s));
-    GCN_TRY(tmp.alloc(tmp_bytes));
-    GCN_HIP_TRY(rocprim::exclusive_scan(tmp.p, tmp_bytes, flag.as<int64_t>(), pos.as<int64_t>(), (int64_t)0,
-                                        (size_t)nnz + 1, rocprim::plus<int64_t>(), s));
+    GCN_TRY(prims::exclusive_scan<int64_t>(flag.as<int64_t>(), pos.as<int64_t>(), (size_t)nnz + 1, s));
     int64_t nnz_hot = 0;
     GCN_HIP_TRY(hipMemcpyAsync(&nnz_hot, pos.as<int64_t>() + nnz, 8, hipMemcpyDeviceToHost, s));
     GCN_HIP_TRY(hipStreamSynchronize(s));
@@ -946,14 +865,9 @@ static int build_transpose(gcn_csr* a, const uint64_t* keys, uint64_t* scratch_k
     GCN_TRY(device_alloc_t(&a->At.val, (size_t)nnz));
     hipLaunchKernelGGL(k_swap_halves, dim3(blocks_for(nnz)), dim3(TPB), 0, s, nnz, keys, kin.as<uint64_t>());
     GCN_LAUNCH_CHECK();
-    size_t tmp_bytes = 0;
     unsigned end_bit = 32 + bits_for(n);                 // low half: rows of A, high half: its columns
-    GCN_HIP_TRY(rocprim::radix_sort_pairs(nullptr, tmp_bytes, kin.as<uint64_t>(), scratch_keys, a->A.val, a->At.val,
-                                          (size_t)nnz, 0u, end_bit, s));
-    TempBuf tmp;
-    GCN_TRY(tmp.alloc(tmp_bytes));
-    GCN_HIP_TRY(rocprim::radix_sort_pairs(tmp.p, tmp_bytes, kin.as<uint64_t>(), scratch_keys, a->A.val, a->At.val,
-                                          (size_t)nnz, 0u, end_bit, s));
+    GCN_TRY((prims::sort_pairs<uint64_t, float>(kin.as<uint64_t>(), scratch_keys, a->A.val, a->At.val, (size_t)nnz,
+                                                end_bit, s)));
     a->At.nrows = n;
     a->At.ncols = a->n;
     GCN_TRY(compress_keys(a->At, n, nnz, scratch_keys, s));
@@ -981,33 +895,24 @@ static int create_impl(gcn_csr* a, int64_t n, int64_t m, const int32_t* src, con
     GCN_HIP_TRY(hipStreamSynchronize(s));
     if (hbad) return fail(GCN_ERR_RANGE, "gcn_csr_create: a vertex id is outside [0, %lld)", (long long)n);
 
-    TempBuf k0, k1, cnt;
+    TempBuf k0, k1;
     GCN_TRY(k0.alloc((size_t)cap * 8));
     GCN_TRY(k1.alloc((size_t)cap * 8));
-    GCN_TRY(cnt.alloc(sizeof(size_t)));
     int64_t nnz = 0;
     if (cap > 0) {
         hipLaunchKernelGGL(k_make_keys, dim3(blocks_for(m + (loops ? n : 0))), dim3(TPB), 0, s, m, n, src, dst,
                            (int)sym, (int)loops, k0.as<uint64_t>());
         GCN_LAUNCH_CHECK();
         GCN_TRY(sort_keys(k0.as<uint64_t>(), k1.as<uint64_t>(), cap, n, s));
-        size_t tmp_bytes = 0;
-        GCN_HIP_TRY(rocprim::unique(nullptr, tmp_bytes, k1.as<uint64_t>(), k0.as<uint64_t>(), cnt.as<size_t>(),
-                                    (size_t)cap, rocprim::equal_to<uint64_t>(), s));
-        TempBuf tmp;
-        GCN_TRY(tmp.alloc(tmp_bytes));
-        GCN_HIP_TRY(rocprim::unique(tmp.p, tmp_bytes, k1.as<uint64_t>(), k0.as<uint64_t>(), cnt.as<size_t>(),
-                                    (size_t)cap, rocprim::equal_to<uint64_t>(), s));
-        size_t hcnt = 0;
+        int64_t hcnt = 0;
         uint64_t last = 0;
-        GCN_HIP_TRY(hipMemcpyAsync(&hcnt, cnt.p, sizeof(size_t), hipMemcpyDeviceToHost, s));
-        GCN_HIP_TRY(hipStreamSynchronize(s));
+        GCN_TRY(prims::unique_keys(k1.as<uint64_t>(), k0.as<uint64_t>(), cap, &hcnt, s));
         if (hcnt > 0) {
             GCN_HIP_TRY(hipMemcpyAsync(&last, k0.as<uint64_t>() + (hcnt - 1), 8, hipMemcpyDeviceToHost, s));
             GCN_HIP_TRY(hipStreamSynchronize(s));
             if (last == INVALID_KEY) hcnt -= 1;
         }
-        nnz = (int64_t)hcnt;
+        nnz = hcnt;
     }
     const uint64_t* keys = k0.as<uint64_t>();   // sorted, distinct, nnz of them
     a->n = n;
