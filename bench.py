@@ -149,10 +149,20 @@ def main() -> int:
             g.gcn_spmm(a, 0, Xd, Z)
             g.gcn_spmm(a, 1, Xs, Zt)
 
+        # plain device copy of the dense operand (reads and writes n*f*4 bytes): the stream rate this GPU
+        # reaches, beside the 8 TB/s peak; with --copy-calibration it is also the known-size dispatch
+        # that scales the PMC byte counters
+        for _ in range(2):
+            Zt.copy_(Xd)
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        ev[0].record()
+        for _ in range(5):
+            Zt.copy_(Xd)
+        ev[1].record()
+        torch.cuda.synchronize()
+        copy_gbps = 2 * n * f * 4 / (ev[0].elapsed_time(ev[1]) / 5 * 1e-3) / 1e9
+        extra["stream_copy_GBps"] = round(copy_gbps, 1)
         if args.copy_calibration:
-            for _ in range(2):
-                Zt.copy_(Xd)          # plain copy kernel: reads and writes n*f*4 bytes each
-            torch.cuda.synchronize()
             extra["copy_calibration_bytes_each_way"] = n * f * 4
         for _ in range(args.warmup):
             step()
@@ -225,6 +235,13 @@ def main() -> int:
                            "avg_kernel_ms": round(avg_kernel_ms, 4),
                            "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, f))
                            if args.slice <= 1 and not args.directed and not args.no_permute else None}
+        extra["achieved_pct_of_stream_copy"] = round(100 * achieved / copy_gbps, 2)
+        if out["roofline"]["traffic"]:
+            # counter-measured bytes (stored from the committed rocprofv3 runs) over this run's kernel time
+            moved = out["roofline"]["traffic"] / (avg_kernel_ms * 1e-3) / 1e9
+            extra.update(measured_traffic_GBps=round(moved, 1),
+                         measured_traffic_pct_hbm_peak=round(100 * moved / HBM_PEAK_GBPS, 1),
+                         measured_traffic_pct_of_stream_copy=round(100 * moved / copy_gbps, 1))
 
         if not args.no_cpu:
             import oracle
