@@ -262,6 +262,23 @@ int gcn_config(int key, int value);
 int gcn_timing_read(int64_t* launches, double* total_ms);
 int gcn_timing_read_phases(int64_t* spans, double* total_ms);
 
+/* Building blocks of graph construction (section "Graph Neural Networks": the modified adjacency matrix
+ * is assembled from an edge list; gcn_csr_create sorts 64-bit keys row<<32|col, drops equal neighbours and
+ * takes prefix sums with exactly these routines).  Exported so that they can be checked on their own.  All
+ * pointers are DEVICE pointers, inputs are left unchanged, outputs must not overlap inputs (gcn_exclusive_scan_i64
+ * allows in == out); the calls allocate temporaries on the device and return after the stream has finished.
+ *
+ * gcn_radix_sort: stable sort of n keys of key_bytes (4 or 8: unsigned) by their bits [0, end_bit), ascending or
+ * descending (descending != 0); equal keys keep their input order.  payload_bytes 0, 4, 8 or 12: a payload record
+ * of that size moves with each key (payload pointers NULL when 0).  GCN_ERR_BADARG for other sizes.
+ * gcn_exclusive_scan_i64: out[i] = in[0] + ... + in[i-1] (out[0] = 0), 64-bit wrap-around arithmetic.
+ * gcn_unique_u64: keeps the first key of every run of equal neighbours, in order; *count (HOST pointer) receives
+ * how many were kept. */
+int gcn_radix_sort(int64_t n, int key_bytes, const void* keys_in, void* keys_out, int payload_bytes,
+                   const void* payload_in, void* payload_out, int end_bit, int descending, void* stream);
+int gcn_exclusive_scan_i64(int64_t n, const int64_t* in, int64_t* out, void* stream);
+int gcn_unique_u64(int64_t n, const uint64_t* keys_in, uint64_t* keys_out, int64_t* count, void* stream);
+
 /* Which schedule the most recent sparse product of this process took (for tests and reports; not
  * meaningful while several threads run products). */
 #define GCN_SCHED_ROWWISE 1

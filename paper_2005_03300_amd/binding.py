@@ -329,6 +329,43 @@ def gcn_timing_read_phases():
     return {k: (cnt[i], ms[i]) for i, k in enumerate(names)}
 
 
+def gcn_radix_sort(keys, payload=None, end_bit=None, descending=False):
+    """Stable radix sort of a 1-D tensor of 4- or 8-byte keys (their bit patterns as unsigned); payload: [n, w]
+    int32 tensor with w in 1..3, or None.  Returns (sorted_keys, moved_payload or None)."""
+    import torch
+    keys = _dev(keys).contiguous()
+    kb = keys.element_size()
+    n = keys.numel()
+    out = torch.empty_like(keys)
+    pb, pout = 0, None
+    if payload is not None:
+        payload = _dev(payload, torch.int32).contiguous()
+        assert payload.dim() == 2 and payload.shape[0] == n
+        pb = 4 * payload.shape[1]
+        pout = torch.empty_like(payload)
+    _check(lib().gcn_radix_sort(C.c_int64(n), kb, _ptr(keys), _ptr(out), pb, _ptr(payload), _ptr(pout),
+                                8 * kb if end_bit is None else int(end_bit), int(bool(descending)), _stream()))
+    return out, pout
+
+
+def gcn_exclusive_scan_i64(x, out=None):
+    import torch
+    x = _dev(x, torch.int64).contiguous()
+    out = torch.empty_like(x) if out is None else _dev(out, torch.int64)
+    _check(lib().gcn_exclusive_scan_i64(C.c_int64(x.numel()), _ptr(x), _ptr(out), _stream()))
+    return out
+
+
+def gcn_unique_u64(keys):
+    """First key of every run of equal neighbours of an int64 tensor (bit patterns); returns the kept prefix."""
+    import torch
+    keys = _dev(keys, torch.int64).contiguous()
+    out = torch.empty_like(keys)
+    cnt = C.c_int64(0)
+    _check(lib().gcn_unique_u64(C.c_int64(keys.numel()), _ptr(keys), _ptr(out), C.byref(cnt), _stream()))
+    return out[:cnt.value]
+
+
 def gcn_last_spmm_schedule() -> int:
     return int(lib().gcn_last_spmm_schedule())
 

@@ -999,6 +999,27 @@ static int from_csr_impl(gcn_csr* a, int64_t n, int64_t ncols, const int64_t* ro
 
 using namespace gcn;
 
+namespace {
+struct Pay4 { uint32_t a; };
+struct Pay8 { uint32_t a, b; };
+struct Pay12 { uint32_t a, b, c; };
+
+template <typename K>
+int radix_sort_by_payload(int64_t n, const void* kin, void* kout, int payload_bytes, const void* pin, void* pout,
+                          unsigned end_bit, bool desc, hipStream_t s) {
+    using namespace gcn::prims;
+    const K* ki = (const K*)kin;
+    K* ko = (K*)kout;
+    switch (payload_bytes) {
+        case 0: return radix_sort<K, NoValue>(ki, ko, (const NoValue*)nullptr, (NoValue*)nullptr, (size_t)n, end_bit, desc, s);
+        case 4: return radix_sort<K, Pay4>(ki, ko, (const Pay4*)pin, (Pay4*)pout, (size_t)n, end_bit, desc, s);
+        case 8: return radix_sort<K, Pay8>(ki, ko, (const Pay8*)pin, (Pay8*)pout, (size_t)n, end_bit, desc, s);
+        case 12: return radix_sort<K, Pay12>(ki, ko, (const Pay12*)pin, (Pay12*)pout, (size_t)n, end_bit, desc, s);
+        default: return gcn::fail(GCN_ERR_BADARG, "gcn_radix_sort: payload_bytes must be 0, 4, 8 or 12");
+    }
+}
+}  // namespace
+
 extern "C" {
 
 int gcn_csr_create(gcn_csr** out, int64_t n, int64_t n_edges, const int32_t* src, const int32_t* dst,
@@ -1056,6 +1077,38 @@ int gcn_csr_create_from_csr_rect(gcn_csr** out, int64_t n_rows, int64_t n_cols, 
     }
     *out = a;
     return GCN_OK;
+}
+
+int gcn_radix_sort(int64_t n, int key_bytes, const void* keys_in, void* keys_out, int payload_bytes,
+                   const void* payload_in, void* payload_out, int end_bit, int descending, void* stream) {
+    using gcn::fail;
+    if (n < 0 || end_bit < 0) return fail(GCN_ERR_BADARG, "gcn_radix_sort: negative size");
+    if (n == 0) return GCN_OK;
+    if (!keys_in || !keys_out || keys_in == keys_out) return fail(GCN_ERR_BADARG, "gcn_radix_sort: keys NULL or in place");
+    if (payload_bytes != 0 && (!payload_in || !payload_out || payload_in == payload_out))
+        return fail(GCN_ERR_BADARG, "gcn_radix_sort: payload NULL or in place");
+    if (key_bytes == 8)
+        return radix_sort_by_payload<uint64_t>(n, keys_in, keys_out, payload_bytes, payload_in, payload_out,
+                                               (unsigned)end_bit, descending != 0, (hipStream_t)stream);
+    if (key_bytes == 4)
+        return radix_sort_by_payload<uint32_t>(n, keys_in, keys_out, payload_bytes, payload_in, payload_out,
+                                               (unsigned)end_bit, descending != 0, (hipStream_t)stream);
+    return fail(GCN_ERR_BADARG, "gcn_radix_sort: key_bytes must be 4 or 8");
+}
+
+int gcn_exclusive_scan_i64(int64_t n, const int64_t* in, int64_t* out, void* stream) {
+    if (n < 0) return gcn::fail(GCN_ERR_BADARG, "gcn_exclusive_scan_i64: negative size");
+    if (n == 0) return GCN_OK;
+    if (!in || !out) return gcn::fail(GCN_ERR_BADARG, "gcn_exclusive_scan_i64: NULL pointer");
+    return gcn::prims::exclusive_scan<int64_t>(in, out, (size_t)n, (hipStream_t)stream);
+}
+
+int gcn_unique_u64(int64_t n, const uint64_t* keys_in, uint64_t* keys_out, int64_t* count, void* stream) {
+    if (n < 0 || !count) return gcn::fail(GCN_ERR_BADARG, "gcn_unique_u64: negative size or NULL count");
+    *count = 0;
+    if (n == 0) return GCN_OK;
+    if (!keys_in || !keys_out || keys_in == keys_out) return gcn::fail(GCN_ERR_BADARG, "gcn_unique_u64: keys NULL or in place");
+    return gcn::prims::unique_keys(keys_in, keys_out, n, count, (hipStream_t)stream);
 }
 
 }  // extern "C"
