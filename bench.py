@@ -79,6 +79,8 @@ def main() -> int:
     ap.add_argument("--pattern", action="store_true",
                     help="SpMM mode: also time the value-free product (row pre-scaling + gcn_spmm_pattern) and report "
                          "it under extra")
+    ap.add_argument("--graph", action="store_true",
+                    help="epoch configs: also time the epoch replayed from a HIP graph (reported in extra)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain device copy of the dense operand (known size) for scaling PMC byte counters")
     args = ap.parse_args()
@@ -302,6 +304,19 @@ def main() -> int:
         torch.cuda.synchronize()
         dt = min(dt, time.perf_counter() - t0)
         ms_step = dt / args.steps * 1e3
+        if args.graph:
+            # the same epoch captured once in a HIP graph and replayed: what a launch-bound caller gains
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                step()
+            for _ in range(max(args.warmup, 1)):
+                graph.replay()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(args.steps):
+                graph.replay()
+            torch.cuda.synchronize()
+            extra["hip_graph_replay_ms_per_epoch"] = round((time.perf_counter() - t0) / args.steps * 1e3, 4)
         extra["phase_ms_per_epoch"] = {"spmm": round(phases["spmm"][1] / args.steps, 4),
                                        "gemm": round(phases["gemm"][1] / args.steps, 4),
                                        "loss_elementwise_update": round(phases["other"][1] / args.steps, 4)}

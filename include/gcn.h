@@ -214,6 +214,10 @@ int gcn_layer_backward(gcn_csr* a, int32_t f_in, int32_t f_out, const float* Hin
  * W, Y: HOST arrays of L_w device pointers (W[l] is dims[l] x dims[l+1]; Y[l] receives dL/dW[l]).
  * loss: device float.  workspace: device, 256-byte aligned, at least gcn_epoch_workspace_bytes();
  * holds every H^l, Z^{L_w}, G^l and the scratch matrices, O(n * sum f).  `order` applies to every layer.
+ * The first call with a given matrix, width set and configuration may build schedules and grow the
+ * library's scratch (device allocations, synchronisation).  Later calls with the same arguments only
+ * enqueue kernels and device-to-device copies on `stream`, so they can be captured in a HIP graph and
+ * replayed; all reductions run in a fixed order, so repeated epochs give bit-identical results.
  * ----------------------------------------------------------------------------------------- */
 int gcn_epoch(gcn_csr* a, int32_t L_w, const int32_t* dims, const float* H0, const int32_t* labels,
               float* const* W, float* const* Y, float lr, float* loss, void* workspace,

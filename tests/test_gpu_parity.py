@@ -900,6 +900,61 @@ def test_epoch_with_forced_schedules(algo, pattern):
         hub_defaults(g)
 
 
+@pytest.mark.parametrize("name,cfg,shrink,algo", [("c1", 1, 1, 0), ("c3s", 3, 32, 0), ("c4s", 4, 256, 3),
+                                                  ("c4s", 4, 256, 4)])
+def test_epoch_replays_from_a_hip_graph(name, cfg, shrink, algo):
+    """Once the schedules and the library's scratch exist, gcn_epoch only launches kernels and device copies on
+    the caller's stream (no allocation, no synchronisation, no memset), so a caller can capture it in a HIP
+    graph.  Every replay, with eager work and synchronisations in between, must give the eager call's results
+    bit for bit (all reductions run in a fixed order)."""
+    g = G()
+    g.gcn_config(g.CFG_SPMM_ALGO, algo)
+    g.gcn_config(g.CFG_SWEEP_HEAVY, 64)
+    hub_settings(g)
+    try:
+        w = synth.scaled(cfg, shrink)
+        a = gpu_csr(name)
+        A = oracle_csr(name)
+        H0, y, Ws = synth.make_model_inputs(dataclass_with_n(w, A.n))
+        dims = list(w.dims)
+        H0d, yd = dev(H0), dev(y)
+        Wd = [dev(x) for x in Ws]
+        Yd = [torch.empty_like(x) for x in Wd]
+        ws = torch.empty(g.gcn_epoch_workspace_bytes(A.n, dims, 0), dtype=torch.uint8, device="cuda")
+        loss = torch.zeros(1, device="cuda")
+        for _ in range(2):                                   # eager: builds whatever is built on first use
+            g.gcn_epoch(a, dims, H0d, yd, Wd, Yd, 0.0, loss, ws, 0)
+        torch.cuda.synchronize()
+        if algo:
+            assert g.gcn_last_spmm_schedule() == (g.SCHED_SWEEP if algo == 3 else g.SCHED_HUB)
+        want_loss, want_Y = loss.clone(), [x.clone() for x in Yd]
+        Zl, _ = g.gcn_epoch_view(A.n, dims, 0, ws, len(dims) - 1)
+        want_Z = Zl.clone()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            g.gcn_epoch(a, dims, H0d, yd, Wd, Yd, 0.0, loss, ws, 0)
+        other = torch.rand(A.n, 16, device="cuda")
+        out = torch.empty_like(other)
+        for rep in range(3):
+            loss.zero_()
+            ws.zero_()
+            for x in Yd:
+                x.fill_(float("nan"))
+            g.gcn_spmm(a, rep % 2, other, out)               # the program's own eager work between replays
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(loss, want_loss), (rep, loss.item(), want_loss.item())
+            for l in range(len(Yd)):
+                assert torch.equal(Yd[l], want_Y[l]), (rep, l)
+            assert torch.equal(g.gcn_epoch_view(A.n, dims, 0, ws, len(dims) - 1)[0], want_Z), rep
+        a.close()
+    finally:
+        g.gcn_config(g.CFG_SPMM_ALGO, 0)
+        g.gcn_config(g.CFG_SWEEP_HEAVY, 1024)
+        hub_defaults(g)
+
+
 def test_spmm_rectangular_block_row_through_sweep_and_hub():
     """One process's block row (rectangular, rows != columns) through the forced sweep and hub schedules."""
     g = G()
