@@ -260,6 +260,16 @@ def main() -> int:
             out["cpu_baseline"] = {"value": round(b_alg / t_o / 1e9, 3), "unit": "GB/s", "cores": oracle.threads(),
                                    "kind": "oracle", "sample": f"one full Z = A X ({zrows} x {n}, nnz={nnz}, f={f}), 1 rep",
                                    "ms": round(t_o * 1e3, 1), "oracle_csr_build_s": round(t_ob, 2)}
+            # the same product on one core, on a bounded sample of the rows (first rows of the relabelled graph)
+            all_threads = oracle.threads()
+            sample_rows = np.arange(min(zrows, max(zrows // 8, 1)), dtype=np.int64)
+            oracle.set_threads(1)
+            t0 = time.time()
+            oracle.spmm_rows(A, X, sample_rows)
+            t_1 = time.time() - t0
+            oracle.set_threads(all_threads)
+            extra["oracle_single_thread"] = {"rows": int(sample_rows.size), "ms": round(t_1 * 1e3, 1),
+                                             "ms_scaled_to_all_rows": round(t_1 * 1e3 * zrows / sample_rows.size, 1)}
             extra.update(max_abs_err_vs_oracle=err, rms_of_oracle=scale, nnz_matches_oracle=bool(A.nnz == nnz))
     else:
         H0, y, Ws = synth.make_model_inputs(w, args.seed)

@@ -73,6 +73,12 @@ def threads() -> int:
     return int(_lib("f32").orc_threads())
 
 
+def set_threads(count: int) -> None:
+    """Threads used by the loops from now on (for timing on one core); results do not depend on it."""
+    for kind in ("f32", "f64"):
+        _lib(kind).orc_set_threads(int(count))
+
+
 # ---------------------------------------------------------------------------------------------
 # graph
 # ---------------------------------------------------------------------------------------------

@@ -34,6 +34,16 @@ int orc_threads(void) {
 #endif
 }
 
+/* Number of threads of the loops below from now on (timing the oracle on one core); no effect on results:
+ * every output element is computed by one thread in a fixed order. */
+void orc_set_threads(int count) {
+#ifdef _OPENMP
+    if (count >= 1) omp_set_num_threads(count);
+#else
+    (void)count;
+#endif
+}
+
 /* ------------------------------------------------------------------------------------------
  * Graph: section "Graph Neural Networks".  The adjacency matrix gets self-connections, and for
  * an undirected graph is scaled to D^-1/2 (A + I) D^-1/2 with D the diagonal of the degrees of
