@@ -32,11 +32,11 @@ HBM_PEAK_GBPS = 8000.0
 # FETCH_SIZE x 2.0, WRITE_SIZE x 1.0); from profiles/spmm_split_rmat20_f128.txt.  Keyed by
 # (workload, f); workloads without a committed counter profile report null.
 MEASURED_TRAFFIC_BYTES = {
-    ("rmat20_spmm_f128", 128): int((4.56939e6 * 1.9999 + 555976 * 1.0) * 1024),
+    ("rmat20_spmm_f128", 128): int((4.56897e6 * 1.9999 + 555976 * 1.0) * 1024),
     # whole product on the config 5 graph: 15 sweep launches + split, fix-up and block-reduce kernels of the
     # long rows (profiles/spmm_sweep_chunglu_protein_f16.txt); the event bracket covers the same kernels
-    ("chunglu_protein_gcn_128_16_16_256", 16): int(((15 * 2.25976e6 + 7.38593e6 + 159130 + 517546) * 1.9999
-                                                    + (15 * 36439.8 + 950063 + 45046.2 + 7828.05) * 1.0) * 1024),
+    ("chunglu_protein_gcn_128_16_16_256", 16): int(((15 * 2.26363e6 + 7.37308e6 + 159128 + 515303) * 1.9999
+                                                    + (15 * 36439.8 + 950387 + 45046.2 + 7828.04) * 1.0) * 1024),
 }
 
 
