@@ -1064,6 +1064,40 @@ def test_spmm_full_size_config2_sampled_rows():
     a.close()
 
 
+def test_epoch_full_size_config3_against_the_oracle():
+    """Config 3 at full size (233 K vertices, 115 M entries, 602-16-16-41) exactly as the benchmark runs it
+    (automatic schedules: column-blocked nonzero-split, value-free form): construction bit-exact, then loss and
+    every weight gradient of one epoch against the oracle's epoch."""
+    g = G()
+    w = synth.CONFIGS[3]
+    n, src, dst = synth.make_graph(w)
+    A = oracle.build_csr(n, src, dst)
+    a = g.gcn_csr_create(n, dev(src), dev(dst), flags_all())
+    del src, dst
+    assert a.nnz == A.nnz
+    rowptr, colidx, val, deg = a.arrays(True)                 # the transposed copy: the forward products read it
+    assert torch.equal(rowptr.cpu(), torch.from_numpy(A.rowptr))
+    assert torch.equal(colidx.cpu(), torch.from_numpy(A.colidx))
+    assert torch.equal(val.cpu().view(torch.int32), torch.from_numpy(A.val.view(np.int32)))
+    del rowptr, colidx, val, deg
+    H0, y, Ws = synth.make_model_inputs(w)
+    dims = list(w.dims)
+    Wd = [dev(x) for x in Ws]
+    Yd = [torch.empty_like(x) for x in Wd]
+    ws = torch.empty(g.gcn_epoch_workspace_bytes(n, dims, 0), dtype=torch.uint8, device="cuda")
+    loss = torch.zeros(1, device="cuda")
+    g.gcn_epoch(a, dims, dev(H0), dev(y), Wd, Yd, 0.0, loss, ws, 0)
+    torch.cuda.synchronize()
+    assert g.gcn_last_spmm_schedule() == g.SCHED_BLOCKED
+    ref = oracle.epoch(A, A, H0, y, Ws, 0.0)
+    assert abs(loss.item() - ref["loss"]) <= 1e-4 * abs(ref["loss"])
+    for l in range(len(dims) - 1):
+        assert rel_fro(host(Yd[l]), ref["Y"][l]) <= 2e-4, (l, rel_fro(host(Yd[l]), ref["Y"][l]))
+    Zl, _ = g.gcn_epoch_view(n, dims, 0, ws, len(dims) - 1)
+    assert rel_fro(host(Zl), ref["Z"][len(dims) - 2]) <= 1e-4
+    a.close()
+
+
 def test_full_size_config4_hub_schedule_properties():
     """Config 4 at full size (14 M vertices, 246 M entries) in the configuration the benchmark times: the
     automatic choice is the hub schedule.  The oracle needs minutes here, so: the product equals the one of
