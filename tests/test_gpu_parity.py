@@ -1098,20 +1098,51 @@ def test_epoch_full_size_config3_against_the_oracle():
     a.close()
 
 
+def check_sampled_rows_against_the_definition(g, a, n, src, dst, X, Z, trans, seed):
+    """At sizes where the oracle's own construction and full product take minutes: for sampled rows (the
+    longest ones and random ones) the stored row must equal the row that the definition gives straight from
+    the raw pairs (neighbours in either direction, one self loop, ascending, 1/sqrt(d_i d_j) in the stated
+    rounding), and the product's row must equal the oracle's row-by-row product over the exported arrays."""
+    rowptr, colidx, val, deg = [host(x) for x in a.arrays(bool(trans))]
+    rs = np.random.default_rng(seed)
+    rows = np.unique(np.concatenate([np.argsort(deg)[-40:], rs.integers(0, n, 400), [0, n - 1]])).astype(np.int64)
+    pick = np.zeros(n, bool)
+    pick[rows] = True
+    m1, m2 = pick[src], pick[dst]
+    u = np.concatenate([src[m1], dst[m2]]).astype(np.int64)          # (u, v): u sampled, v its neighbour
+    v = np.concatenate([dst[m1], src[m2]]).astype(np.int64)
+    keep = u != v
+    u, v = u[keep], v[keep]
+    order = np.lexsort((v, u))
+    u, v = u[order], v[order]
+    lo, hi = np.searchsorted(u, rows, "left"), np.searchsorted(u, rows, "right")
+    for i, s, e in zip(rows.tolist(), lo.tolist(), hi.tolist()):
+        cols = np.unique(np.concatenate([v[s:e], [i]]))
+        got = colidx[rowptr[i]:rowptr[i + 1]]
+        assert deg[i] == len(cols) and np.array_equal(got, cols.astype(np.int32)), i
+        want_val = (1.0 / np.sqrt(np.float64(deg[i]) * deg[cols].astype(np.float64))).astype(np.float32)
+        assert np.array_equal(val[rowptr[i]:rowptr[i + 1]].view(np.int32), want_val.view(np.int32)), i
+    A = oracle.Csr(n=n, rowptr=rowptr, colidx=colidx, val=val, deg=deg)
+    want = oracle.spmm_rows(A, host(X), rows)
+    assert_close(host(Z[torch.from_numpy(rows).cuda()]), want, f"sampled rows, trans={trans}")
+
+
 def test_full_size_config4_hub_schedule_properties():
     """Config 4 at full size (14 M vertices, 246 M entries) in the configuration the benchmark times: the
-    automatic choice is the hub schedule.  The oracle needs minutes here, so: the product equals the one of
-    the plain kernel (an independent schedule), and sqrt(d) is reproduced by the normalised matrix."""
+    automatic choice is the hub schedule.  The oracle's construction and full product need minutes here, so:
+    sampled rows of the matrix against the definition and of the product against the oracle's row product,
+    the whole product against the plain kernel (an independent schedule), and sqrt(d) is reproduced by the
+    normalised matrix."""
     g = G()
     n, src, dst = synth.make_graph(synth.CONFIGS[4])
     a = g.gcn_csr_create(n, dev(src), dev(dst), flags_all())
-    del src, dst
     X = torch.rand(n, 16, device="cuda") * 2 - 1
     Z = torch.full((n, 16), float("nan"), device="cuda")
     Z2 = torch.empty_like(Z)
     for trans in (0, 1):
         g.gcn_spmm(a, trans, X, Z)
         assert g.gcn_last_spmm_schedule() == g.SCHED_HUB
+        check_sampled_rows_against_the_definition(g, a, n, src, dst, X, Z, trans, 40 + trans)
         g.gcn_config(g.CFG_SPMM_ALGO, 2)
         try:
             g.gcn_spmm(a, trans, X, Z2)
@@ -1133,13 +1164,13 @@ def test_quarter_size_config5_column_sweep_properties():
     g = G()
     n, src, dst = synth.make_graph(synth.scaled(5, 4))
     a = g.gcn_csr_create(n, dev(src), dev(dst), flags_all())
-    del src, dst
     X = torch.rand(n, 16, device="cuda") * 2 - 1
     Z = torch.full((n, 16), float("nan"), device="cuda")
     Z2 = torch.empty_like(Z)
     for trans in (0, 1):
         g.gcn_spmm(a, trans, X, Z)
         assert g.gcn_last_spmm_schedule() == g.SCHED_SWEEP
+        check_sampled_rows_against_the_definition(g, a, n, src, dst, X, Z, trans, 50 + trans)
         g.gcn_config(g.CFG_SPMM_ALGO, 2)
         try:
             g.gcn_spmm(a, trans, X, Z2)
