@@ -51,6 +51,14 @@ def spmm_alg_bytes(n: int, nnz: int, f: int) -> int:
     return 8 * nnz + 8 * (n + 1) + 4 * n * f + 4 * n * f
 
 
+_T0 = time.time()
+
+
+def progress(msg: str) -> None:
+    """One line per finished stage on stderr (stdout carries only the JSON line)."""
+    print(f"[bench {time.time() - _T0:7.1f}s] {msg}", file=sys.stderr, flush=True)
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -110,6 +118,7 @@ def main() -> int:
     t0 = time.time()
     n, src, dst = synth.make_graph(w, args.seed)
     t_gen = time.time() - t0
+    progress(f"generated {w.name}: n={n}, {src.shape[0]} raw pairs")
     t0 = time.time()
     src_d, dst_d = dev(src), dev(dst)
     flags = (g.ADD_SELF_LOOPS | g.NORM_ROW | g.BUILD_TRANSPOSE) if args.directed else \
@@ -119,6 +128,7 @@ def main() -> int:
     t_build = time.time() - t0
     del src_d, dst_d
     nnz = a.nnz
+    progress(f"compressed rows built on the GPU: nnz={nnz}")
     g.gcn_config(g.CFG_SPMM_ALGO, args.algo)
 
     out = {"n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "higher_is_better": True, "scaling": "weak",
@@ -211,6 +221,7 @@ def main() -> int:
                          pattern_bytes_alg_per_spmm=4 * nnz + 8 * (n + 1) + 4 * n + 8 * n * f,
                          pattern_max_abs_diff_vs_valued=float((Zt - g.gcn_spmm(a, 1, Xd, torch.empty_like(Zt))).abs().max()))
 
+        progress("SpMM timed")
         b_alg = spmm_alg_bytes(n, nnz, f) if args.slice <= 1 else 8 * nnz + 8 * (zrows + 1) + 4 * n * f + 4 * zrows * f
         ms_step = dt / args.steps * 1e3
         value = 2 * b_alg / (ms_step * 1e-3) / 1e9
@@ -252,9 +263,11 @@ def main() -> int:
             if args.slice > 1:
                 A = oracle.slice_rows(A, 0, zrows)
             t_ob = time.time() - t0
+            progress("oracle: compressed rows built")
             t0 = time.time()
             Zo = oracle.spmm(A, X)
             t_o = time.time() - t0
+            progress("oracle: product done")
             err = float((Z.cpu() - torch.from_numpy(Zo)).abs().max())
             scale = float(np.sqrt(np.mean(Zo.astype(np.float64) ** 2)))
             out["cpu_baseline"] = {"value": round(b_alg / t_o / 1e9, 3), "unit": "GB/s", "cores": oracle.threads(),
@@ -314,6 +327,7 @@ def main() -> int:
         torch.cuda.synchronize()
         dt = min(dt, time.perf_counter() - t0)
         ms_step = dt / args.steps * 1e3
+        progress("epochs timed")
         if args.graph:
             # the same epoch captured once in a HIP graph and replayed: what a launch-bound caller gains
             graph = torch.cuda.CUDAGraph()
@@ -358,6 +372,7 @@ def main() -> int:
             import oracle
             # bounded sample: the oracle's first-layer backward product S = A G at the hidden width
             A = oracle.build_csr(n, src, dst)
+            progress("oracle: compressed rows built")
             fw = widths[0]
             Xs = synth.normal_features(n, fw, args.seed + 1)
             t0 = time.time()
