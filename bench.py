@@ -29,10 +29,13 @@ HBM_PEAK_GBPS = 8000.0
 
 # HBM-side bytes per SpMM launch measured with rocprofv3 --pmc (FETCH_SIZE, then WRITE_SIZE, in KiB
 # per dispatch, each scaled by what the same counter reads for a plain device copy of 512 MiB:
-# FETCH_SIZE x 2.0, WRITE_SIZE x 1.0); from profiles/spmm_split_rmat20_f128.txt.  Keyed by
+# FETCH_SIZE x 2.0, WRITE_SIZE x 1.0); from the profiles/spmm_*.txt summaries.  Keyed by
 # (workload, f); workloads without a committed counter profile report null.
 MEASURED_TRAFFIC_BYTES = {
     ("rmat20_spmm_f128", 128): int((4.56897e6 * 1.9999 + 555976 * 1.0) * 1024),
+    # config 4 graph: the paired launch of the hub schedule, which is what the event bracket covers
+    # (profiles/spmm_hub_rmat_amazon_f16.txt)
+    ("rmat_amazon_gcn_300_16_16_24", 16): int((8.49107e6 * 1.9999 + 1.6237e6 * 1.0) * 1024),
     # whole product on the config 5 graph: 15 sweep launches + split, fix-up and block-reduce kernels of the
     # long rows (profiles/spmm_sweep_chunglu_protein_f16.txt); the event bracket covers the same kernels
     ("chunglu_protein_gcn_128_16_16_256", 16): int(((15 * 2.26363e6 + 7.37308e6 + 159128 + 515303) * 1.9999
