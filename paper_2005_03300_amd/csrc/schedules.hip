@@ -49,7 +49,7 @@ __global__ void k_block_flags(int64_t nnz, int64_t nsub, const uint64_t* __restr
 
 // From the flags and their exclusive prefix counts: sub_row, the first entry rp[q] of every partial
 // row q, and the sort key (row<<32 | q) that groups partial rows by the row they belong to.
-__global__ void k_block_rows(int64_t nnz, int64_t nsub, const uint32_t* __restrict__ flags,
+__global__ void k_block_rows(int64_t /*nnz*/, int64_t nsub, const uint32_t* __restrict__ flags,
                              const int32_t* __restrict__ pre, const uint64_t* __restrict__ keys,
                              int32_t* __restrict__ sub_row, int64_t* __restrict__ rp, uint64_t* __restrict__ rowq) {
     int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
