@@ -1,6 +1,5 @@
 """The C-ABI library loads without a GPU and exports every function include/gcn.h declares.
 No compute entry point is called here."""
-import ctypes
 import os
 
 import pytest
