@@ -12,7 +12,9 @@
  *   - Dense buffers are owned by the caller; the library neither frees nor keeps them after the
  *     work queued on `stream` has finished.  Only gcn_csr objects own device memory.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Compute calls only
- *     queue work on it and return; gcn_csr_create*, gcn_csr_info and gcn_csr_destroy synchronise.
+ *     queue work on it and return; gcn_csr_create*, gcn_csr_info and gcn_csr_destroy synchronise, and so
+ *     may the first sparse product of a given width on a matrix (it can build and cache another stored
+ *     order of the matrix, which allocates device memory) and any call that grows the library's scratch.
  *   - Every function returns GCN_OK (0) or a negative GCN_ERR_* code and never throws or aborts.
  *     gcn_last_error() returns a thread-local message for the last failure on this thread.
  *   - No call is safe to run concurrently with another call that uses the same gcn_csr.
