@@ -33,6 +33,8 @@ HBM_PEAK_GBPS = 8000.0
 # (workload, f); workloads without a committed counter profile report null.
 MEASURED_TRAFFIC_BYTES = {
     ("rmat20_spmm_f128", 128): int((4.56897e6 * 1.9999 + 555976 * 1.0) * 1024),
+    # config 3 graph: the nonzero-split kernel over the column-blocked copy (profiles/spmm_blocked_chunglu_reddit_f16.txt)
+    ("chunglu_reddit_gcn_602_16_16_41", 16): int((525976 * 1.9967 + 142071 * 1.0) * 1024),
     # config 4 graph: the paired launch of the hub schedule, which is what the event bracket covers
     # (profiles/spmm_hub_rmat_amazon_f16.txt)
     ("rmat_amazon_gcn_300_16_16_24", 16): int((8.49107e6 * 1.9999 + 1.6237e6 * 1.0) * 1024),
