@@ -313,16 +313,30 @@ def forward(At: Csr, H0: np.ndarray, Ws):
     return Zs, Hs
 
 
-def epoch(A: Csr, At: Csr, H0: np.ndarray, labels: np.ndarray, Ws, lr: float = 0.0):
+def epoch(A: Csr, At: Csr, H0: np.ndarray, labels: np.ndarray, Ws, lr: float = 0.0, sign_from=None):
     """One full-batch epoch: forward, loss, backward (Equations 1-3) and, if lr != 0, the
-    gradient step.  Returns dict(loss, Y=[...], W=[...], Z=[...], H=[...], G=[...])."""
+    gradient step.  Returns dict(loss, Y=[...], W=[...], Z=[...], H=[...], G=[...]).
+
+    ``sign_from`` (optional, one array per hidden layer, or None entries): sigma'(Z^l) of Equation 2
+    is then taken from the sign of ``sign_from[l]`` instead of this function's own Z^l.  sigma' is a
+    decision (z > 0 or not) that floating point takes; a caller that checks an fp32 implementation
+    passes that implementation's own pre-activations (or its H = ReLU(Z), which has the same sign
+    pattern) so that both sides take the decision on the same numbers, and checks separately that
+    the two sign patterns differ only where Z^l is zero to rounding.  The forward pass and the loss
+    never use it."""
     Zs, Hs = forward(At, H0, Ws)
     loss, G = softmax_nll(Zs[-1], labels)
     Ys = [None] * len(Ws)
     Gs = [None] * len(Ws)
     for l in range(len(Ws) - 1, -1, -1):
         Gs[l] = G
-        _, Ys[l], G, _ = layer_backward(A, Hs[l], Zs[l - 1] if l > 0 else None, Ws[l], G)
+        Zprev = None
+        if l > 0:
+            Zprev = Zs[l - 1]
+            if sign_from is not None and sign_from[l - 1] is not None:
+                Zprev = np.ascontiguousarray(sign_from[l - 1]).astype(Zprev.dtype)
+                assert Zprev.shape == Zs[l - 1].shape
+        _, Ys[l], G, _ = layer_backward(A, Hs[l], Zprev, Ws[l], G)
     newW = [sgd(W, Y, lr) if lr != 0.0 else W for W, Y in zip(Ws, Ys)]
     return dict(loss=loss, Y=Ys, W=newW, Z=Zs, H=Hs, G=Gs)
 

@@ -102,6 +102,26 @@ class Csr:
                                     _stream()))
         return rowptr, colidx, val, deg
 
+    def views(self, transposed: bool = False):
+        """(rowptr, colidx, val, deg) as torch tensors that ALIAS the library's own device arrays (no copy):
+        read-only for the caller, valid until close()."""
+        import torch
+        rp, ci, va, dg = C.c_void_p(), C.c_void_p(), C.c_void_p(), C.c_void_p()
+        _check(lib().gcn_csr_arrays(self._h, int(transposed), C.byref(rp), C.byref(ci), C.byref(va), C.byref(dg)))
+
+        class _Borrowed:
+            def __init__(self, ptr, count, typestr):
+                self.__cuda_array_interface__ = {"shape": (count,), "typestr": typestr, "data": (ptr, False),
+                                                 "version": 2, "strides": None}
+
+        def wrap(p, count, typestr, dtype):
+            if count == 0 or not p.value:
+                return torch.empty(0, dtype=dtype, device="cuda")
+            return torch.as_tensor(_Borrowed(p.value, count, typestr), device="cuda")
+        rows = self.n_cols if transposed else self.n_rows
+        return (wrap(rp, rows + 1, "<i8", torch.int64), wrap(ci, self.nnz, "<i4", torch.int32),
+                wrap(va, self.nnz, "<f4", torch.float32), wrap(dg, self.n, "<i4", torch.int32))
+
     def close(self):
         if self._h is not None and self._h.value:
             lib().gcn_csr_destroy(self._h)

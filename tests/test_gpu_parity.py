@@ -74,6 +74,16 @@ ALL_GRAPHS = ["c1", "c2s", "c3s", "c4s", "c5s", "star", "ring", "one", "tiny"]
 # a1 / a2: construction and transpose, bit-exact
 # ------------------------------------------------------------------------------------------------
 
+@pytest.mark.parametrize("name", ["c2s", "tiny"])
+def test_csr_array_pointers_alias_the_stored_matrix(name):
+    """gcn_csr_arrays hands out the library's own device arrays: same contents as gcn_csr_export, for A and A^T."""
+    a = gpu_csr(name, symmetrise=False, norm="none")
+    for trans in (False, True):
+        for got, want in zip(a.views(trans), a.arrays(trans)):
+            assert got.dtype == want.dtype and torch.equal(got, want)
+    a.close()
+
+
 @pytest.mark.parametrize("name", ALL_GRAPHS)
 def test_csr_build_bit_exact(name):
     a = gpu_csr(name)
@@ -765,6 +775,41 @@ def test_layer_forward_bias_and_in_place_relu():
 # whole epoch
 # ------------------------------------------------------------------------------------------------
 
+def oracle_epoch_same_signs(g, A, At, n, dims, order, ws, H0, y, Ws, lr=0.0):
+    """The oracle's epoch for comparison with a GPU epoch whose workspace is `ws`.  ReLU' is a decision that
+    floating point takes (z > 0 or not), so the oracle takes it on the GPU's own hidden activations (same
+    sign pattern as the GPU's pre-activations); separately, the two sign patterns may differ only where the
+    oracle's Z is zero to rounding (|Z| < 1e-5 rms(Z); the GPU's Z is within about 5e-7 rms of it).  Returns
+    (ref, number of such elements that were decided the other way)."""
+    signs, flips = [], 0
+    for l in range(1, len(dims) - 1):
+        Hl, _ = g.gcn_epoch_view(n, dims, order, ws, l)
+        signs.append(host(Hl))
+    ref = oracle.epoch(A, At, H0, y, Ws, lr, sign_from=signs)
+    for l, Hg in enumerate(signs):
+        Zr = ref["Z"][l]
+        differ = (Hg > 0) != (Zr > 0)
+        if differ.any():
+            rms = float(np.sqrt(np.mean(Zr.astype(np.float64) ** 2)))
+            assert float(np.abs(Zr[differ]).max()) < 1e-5 * rms, (l, int(differ.sum()), float(np.abs(Zr[differ]).max()), rms)
+            flips += int(differ.sum())
+    return ref, flips
+
+
+def assert_epoch_close(g, n, dims, order, ws, loss, Yd, ref, what=""):
+    """Loss, every weight gradient, the last layer's Z and every G^l of a GPU epoch against `ref`: 1e-4."""
+    e = abs(loss.item() - ref["loss"]) / abs(ref["loss"])
+    assert e <= 1e-4, (what, "loss", e)
+    for l in range(len(dims) - 1):
+        e = rel_fro(host(Yd[l]), ref["Y"][l])
+        assert e <= 1e-4, (what, "Y", l, e)
+        Zl, Gl = g.gcn_epoch_view(n, dims, order, ws, l + 1)      # hidden layers store H = ReLU(Z)
+        e = rel_fro(host(Zl), ref["Z"][l] if l + 2 == len(dims) else ref["H"][l + 1])
+        assert e <= 1e-4, (what, "Z/H", l, e)
+        e = rel_fro(host(Gl), ref["G"][l])
+        assert e <= 1e-4, (what, "G", l, e)
+
+
 def run_epoch(name, w, order, lr=0.0):
     g = G()
     a = gpu_csr(name)
@@ -777,7 +822,7 @@ def run_epoch(name, w, order, lr=0.0):
     loss = torch.zeros(1, device="cuda")
     g.gcn_epoch(a, dims, dev(H0), dev(y), Wd, Yd, lr, loss, ws, order)
     torch.cuda.synchronize()
-    ref = oracle.epoch(A, A, H0, y, Ws, lr)
+    ref, _ = oracle_epoch_same_signs(g, A, A, A.n, dims, order, ws, H0, y, Ws, lr)
     return g, a, A, dims, Wd, Yd, ws, loss, ref, (H0, y, Ws)
 
 
@@ -790,12 +835,7 @@ def dataclass_with_n(w, n):
 def test_epoch_config1_parity(order):
     w = synth.CONFIGS[1]
     g, a, A, dims, Wd, Yd, ws, loss, ref, _ = run_epoch("c1", w, order)
-    assert abs(loss.item() - ref["loss"]) <= 1e-4 * abs(ref["loss"])
-    for l in range(len(dims) - 1):
-        assert rel_fro(host(Yd[l]), ref["Y"][l]) <= 1e-4, l
-        Zl, Gl = g.gcn_epoch_view(A.n, dims, order, ws, l + 1)     # hidden layers store H = ReLU(Z)
-        assert rel_fro(host(Zl), ref["Z"][l] if l + 2 == len(dims) else ref["H"][l + 1]) <= 1e-4
-        assert rel_fro(host(Gl), ref["G"][l]) <= 1e-3       # isolated mask flips near Z = 0 are possible
+    assert_epoch_close(g, A.n, dims, order, ws, loss, Yd, ref, "config 1")
     a.close()
 
 
@@ -803,9 +843,7 @@ def test_epoch_config1_parity(order):
 def test_epoch_scaled_configs_parity(name, cfg, shrink):
     w = synth.scaled(cfg, shrink)
     g, a, A, dims, Wd, Yd, ws, loss, ref, _ = run_epoch(name, w, 0)
-    assert abs(loss.item() - ref["loss"]) <= 1e-4 * abs(ref["loss"])
-    for l in range(len(dims) - 1):
-        assert rel_fro(host(Yd[l]), ref["Y"][l]) <= 2e-4, (l, rel_fro(host(Yd[l]), ref["Y"][l]))
+    assert_epoch_close(g, A.n, dims, 0, ws, loss, Yd, ref, name)
     a.close()
 
 
@@ -819,11 +857,7 @@ def test_epoch_wide_hidden_and_two_weight_matrices(name, dims, classes, order):
     import dataclasses
     w = dataclasses.replace(synth.CONFIGS[1], dims=dims, n_classes=classes, features="normal")
     g, a, A, dl, Wd, Yd, ws, loss, ref, _ = run_epoch(name, w, order)
-    assert abs(loss.item() - ref["loss"]) <= 1e-4 * abs(ref["loss"])
-    for l in range(len(dl) - 1):
-        assert rel_fro(host(Yd[l]), ref["Y"][l]) <= 2e-4, (l, rel_fro(host(Yd[l]), ref["Y"][l]))
-    Zl, _ = g.gcn_epoch_view(A.n, dl, order, ws, len(dl) - 1)
-    assert rel_fro(host(Zl), ref["Z"][len(dl) - 2]) <= 1e-4
+    assert_epoch_close(g, A.n, dl, order, ws, loss, Yd, ref, name)
     a.close()
 
 
@@ -837,12 +871,7 @@ def test_epoch_value_free_spmm_on_and_off(mode, order):
     try:
         w = synth.CONFIGS[1]
         _, a, A, dims, Wd, Yd, ws, loss, ref, _ = run_epoch("c1", w, order)
-        assert abs(loss.item() - ref["loss"]) <= 1e-4 * abs(ref["loss"])
-        for l in range(len(dims) - 1):
-            assert rel_fro(host(Yd[l]), ref["Y"][l]) <= 1e-4, l
-            Zl, Gl = g.gcn_epoch_view(A.n, dims, order, ws, l + 1)
-            assert rel_fro(host(Zl), ref["Z"][l] if l + 2 == len(dims) else ref["H"][l + 1]) <= 1e-4
-            assert rel_fro(host(Gl), ref["G"][l]) <= 1e-3
+        assert_epoch_close(g, A.n, dims, order, ws, loss, Yd, ref, f"value-free mode {mode}")
         a.close()
     finally:
         g.gcn_config(g.CFG_PATTERN_SPMM, 2)
@@ -866,12 +895,8 @@ def test_epoch_with_first_layer_aggregated_once(name, cfg, shrink):
     loss = torch.zeros(1, device="cuda")
     g.gcn_epoch_preaggregated(a, dims, P0, dev(y), A.n, Wd, Yd, 0.0, loss, ws, 0)
     torch.cuda.synchronize()
-    ref = oracle.epoch(A, A, H0, y, Ws, 0.0)
-    assert abs(loss.item() - ref["loss"]) <= 1e-4 * abs(ref["loss"])
-    for l in range(len(dims) - 1):
-        assert rel_fro(host(Yd[l]), ref["Y"][l]) <= 2e-4, (l, rel_fro(host(Yd[l]), ref["Y"][l]))
-    Zl, Gl = g.gcn_epoch_view(A.n, dims, 0, ws, len(dims) - 1)
-    assert rel_fro(host(Zl), ref["Z"][len(dims) - 2]) <= 1e-4
+    ref, _ = oracle_epoch_same_signs(g, A, A, A.n, dims, 0, ws, H0, y, Ws)
+    assert_epoch_close(g, A.n, dims, 0, ws, loss, Yd, ref, f"{name}, first layer aggregated once")
     a.close()
 
 
@@ -889,9 +914,7 @@ def test_epoch_with_forced_schedules(algo, pattern):
         w = synth.scaled(4, 256)
         _, a, A, dims, Wd, Yd, ws, loss, ref, _ = run_epoch("c4s", w, 0)
         assert g.gcn_last_spmm_schedule() == (g.SCHED_SWEEP if algo == 3 else g.SCHED_HUB)
-        assert abs(loss.item() - ref["loss"]) <= 1e-4 * abs(ref["loss"])
-        for l in range(len(dims) - 1):
-            assert rel_fro(host(Yd[l]), ref["Y"][l]) <= 2e-4, (l, rel_fro(host(Yd[l]), ref["Y"][l]))
+        assert_epoch_close(g, A.n, dims, 0, ws, loss, Yd, ref, f"forced schedule {algo}, value-free {pattern}")
         a.close()
     finally:
         g.gcn_config(g.CFG_SPMM_ALGO, 0)
@@ -1011,19 +1034,28 @@ def test_training_loop_with_split_follows_the_oracle():
     ws = torch.empty(g.gcn_epoch_workspace_bytes(A.n, dims), dtype=torch.uint8, device="cuda")
     loss = torch.zeros(1, device="cuda")
     H0d, yd = dev(H0), dev(y)
-    lr, gpu_losses, ref_losses = 2.0, [], []
-    Wref = [x.copy() for x in Ws]
-    for _ in range(12):
+    lr, gpu_losses, free_losses = 2.0, [], []
+    Wfree = [x.copy() for x in Ws]                       # the oracle's own trajectory from the same start
+    for ep in range(12):
+        Wnow = [host(x).copy() for x in Wd]              # the fp32 weights this GPU epoch starts from
         g.gcn_epoch_masked(a, dims, H0d, yd, m, Wd, Yd, lr, loss, ws)
         gpu_losses.append(float(loss.item()))
-        out = oracle.epoch(A, A, H0, y, Wref, lr)
-        ref_losses.append(out["loss"])
-        Wref = out["W"]
+        # per epoch on identical inputs: the oracle's epoch from the same weights gives this loss, these
+        # gradients and these updated weights
+        ref, _ = oracle_epoch_same_signs(g, A, A, A.n, dims, 0, ws, H0, y, Wnow, lr)
+        assert_epoch_close(g, A.n, dims, 0, ws, loss, Yd, ref, f"epoch {ep}")
+        for l in range(len(Wd)):
+            assert_close(host(Wd[l]), ref["W"][l], f"W{l} after epoch {ep}")
+        out = oracle.epoch(A, A, H0, y, Wfree, lr)
+        free_losses.append(out["loss"])
+        Wfree = out["W"]
     assert gpu_losses[-1] < gpu_losses[0] - 1e-3      # labels are random: little to learn, but it must fall
     assert all(b < a for a, b in zip(gpu_losses, gpu_losses[1:]))
-    np.testing.assert_allclose(gpu_losses, ref_losses, rtol=2e-4)
+    # the free-running trajectories (each side feeding on its own weights) stay together as well
+    np.testing.assert_allclose(gpu_losses, free_losses, rtol=1e-4)
     for l in range(len(Wd)):
-        assert rel_fro(host(Wd[l]), Wref[l]) <= 1e-3
+        e = rel_fro(host(Wd[l]), Wfree[l])
+        assert e <= 1e-4, (l, e)
     a.close()
 
 
@@ -1089,13 +1121,16 @@ def test_epoch_full_size_config3_against_the_oracle():
     g.gcn_epoch(a, dims, dev(H0), dev(y), Wd, Yd, 0.0, loss, ws, 0)
     torch.cuda.synchronize()
     assert g.gcn_last_spmm_schedule() == g.SCHED_BLOCKED
-    ref = oracle.epoch(A, A, H0, y, Ws, 0.0)
-    assert abs(loss.item() - ref["loss"]) <= 1e-4 * abs(ref["loss"])
-    for l in range(len(dims) - 1):
-        assert rel_fro(host(Yd[l]), ref["Y"][l]) <= 2e-4, (l, rel_fro(host(Yd[l]), ref["Y"][l]))
-    Zl, _ = g.gcn_epoch_view(n, dims, 0, ws, len(dims) - 1)
-    assert rel_fro(host(Zl), ref["Z"][len(dims) - 2]) <= 1e-4
+    ref, flips = oracle_epoch_same_signs(g, A, A, n, dims, 0, ws, H0, y, Ws)
+    assert flips <= 16, flips            # of 7.5 M hidden pre-activations a handful are zero to rounding
+    assert_epoch_close(g, n, dims, 0, ws, loss, Yd, ref, "config 3 at full size")
     a.close()
+
+
+@functools.lru_cache(maxsize=2)
+def big_graph(cfg):
+    """The raw pairs of config 4 or 5 at full size (generated once for the tests that share them)."""
+    return synth.make_graph(synth.CONFIGS[cfg])
 
 
 def check_sampled_rows_against_the_definition(g, a, n, src, dst, X, Z, trans, seed):
@@ -1134,7 +1169,7 @@ def test_full_size_config4_hub_schedule_properties():
     the whole product against the plain kernel (an independent schedule), and sqrt(d) is reproduced by the
     normalised matrix."""
     g = G()
-    n, src, dst = synth.make_graph(synth.CONFIGS[4])
+    n, src, dst = big_graph(4)
     a = g.gcn_csr_create(n, dev(src), dev(dst), flags_all())
     X = torch.rand(n, 16, device="cuda") * 2 - 1
     Z = torch.full((n, 16), float("nan"), device="cuda")
@@ -1182,6 +1217,57 @@ def test_quarter_size_config5_column_sweep_properties():
     sq = torch.sqrt(deg.float())[:, None].repeat(1, 16).contiguous()
     g.gcn_spmm(a, 0, sq, Z)
     assert float(((Z - sq).abs() / sq).max()) < 1e-4
+    a.close()
+
+
+def test_full_size_config5_column_sweep_against_the_oracle_rows():
+    """Config 5 at full size (8.7 M vertices, 1.32 G entries), the graph and launch configuration the benchmark
+    times: sampled rows of the stored matrix against the definition from the raw pairs, sampled rows of both
+    products against the oracle's row product, the whole product against an independent schedule."""
+    g = G()
+    n, src, dst = big_graph(5)
+    a = g.gcn_csr_create(n, dev(src), dev(dst), flags_all())
+    X = torch.rand(n, 16, device="cuda") * 2 - 1
+    Z = torch.full((n, 16), float("nan"), device="cuda")
+    Z2 = torch.empty_like(Z)
+    for trans in (0, 1):
+        g.gcn_spmm(a, trans, X, Z)
+        assert g.gcn_last_spmm_schedule() == g.SCHED_SWEEP
+        check_sampled_rows_against_the_definition(g, a, n, src, dst, X, Z, trans, 60 + trans)
+        g.gcn_config(g.CFG_SPMM_ALGO, 2)
+        try:
+            g.gcn_spmm(a, trans, X, Z2)
+        finally:
+            g.gcn_config(g.CFG_SPMM_ALGO, 0)
+        rms = float(Z2.double().pow(2).mean().sqrt())
+        assert bool(torch.isfinite(Z).all()) and float((Z - Z2).abs().max()) <= 1e-5 * rms
+    a.close()
+
+
+@pytest.mark.parametrize("cfg", [4, 5])
+def test_epoch_full_size_configs_4_and_5_against_the_oracle(cfg):
+    """One epoch of configs 4 and 5 at full size with the automatic schedules (hub / column sweep, fused or
+    SpMM-first last layer, value-free form where chosen) against the oracle's epoch.  The oracle's own graph
+    construction would take many minutes at these sizes, so it runs on the stored arrays exported from the
+    library, which the tests above check against the definition row by row; its products are the plain loops."""
+    g = G()
+    w = synth.CONFIGS[cfg]
+    n, src, dst = big_graph(cfg)
+    a = g.gcn_csr_create(n, dev(src), dev(dst), flags_all())
+    rowptr, colidx, val, deg = [host(x) for x in a.views(False)]
+    A = oracle.Csr(n=n, rowptr=rowptr, colidx=colidx, val=val, deg=deg)
+    H0, y, Ws = synth.make_model_inputs(w)
+    dims = list(w.dims)
+    Wd = [dev(x) for x in Ws]
+    Yd = [torch.empty_like(x) for x in Wd]
+    ws = torch.empty(g.gcn_epoch_workspace_bytes(n, dims, 0), dtype=torch.uint8, device="cuda")
+    loss = torch.zeros(1, device="cuda")
+    g.gcn_epoch(a, dims, dev(H0), dev(y), Wd, Yd, 0.0, loss, ws, 0)
+    torch.cuda.synchronize()
+    assert g.gcn_last_spmm_schedule() == (g.SCHED_HUB if cfg == 4 else g.SCHED_SWEEP)
+    ref, flips = oracle_epoch_same_signs(g, A, A, n, dims, 0, ws, H0, y, Ws)     # A == A^T (checked bit for bit elsewhere)
+    assert flips <= 64, flips
+    assert_epoch_close(g, n, dims, 0, ws, loss, Yd, ref, f"config {cfg} at full size")
     a.close()
 
 

@@ -473,6 +473,33 @@ def test_backward_recurrence_matches_dense_python():
     np.testing.assert_allclose(out["G"][0], G0, rtol=1e-12, atol=1e-15)
 
 
+def test_backward_with_imposed_sign_pattern_matches_dense_python():
+    """Equation 2 with sigma' taken from a sign pattern the caller imposes (what the GPU parity tests do with
+    the GPU's own pre-activations): the same dense recurrence with that pattern; the forward pass, the loss
+    and the last layer's gradient do not depend on it; the oracle's own Z as the pattern changes nothing."""
+    A, At, H0, y, Ws = tiny_problem(directed=True, dims=(4, 3, 3, 2))
+    base = oracle.epoch(A, At, H0, y, Ws)
+    same = oracle.epoch(A, At, H0, y, Ws, sign_from=[base["Z"][0], base["H"][2]])   # H = ReLU(Z): same signs
+    for l in range(3):
+        np.testing.assert_array_equal(same["Y"][l], base["Y"][l])
+    P = [synth.normal_features(A.n, 3, 77).astype(np.float64), None]                 # layer 1 imposed, layer 2 own
+    assert ((P[0] > 0) != (base["Z"][0] > 0)).sum() > 10
+    out = oracle.epoch(A, At, H0, y, Ws, sign_from=P)
+    assert out["loss"] == base["loss"]
+    for l in range(3):
+        np.testing.assert_array_equal(out["Z"][l], base["Z"][l])
+    np.testing.assert_array_equal(out["G"][2], base["G"][2])
+    np.testing.assert_array_equal(out["G"][1], base["G"][1])
+    np.testing.assert_array_equal(out["Y"][1], base["Y"][1])
+    D = np.array(py_dense(A))
+    S = np.array(py_matmul(D.tolist(), base["G"][1].tolist()))
+    G0 = np.array(py_matmul(S.tolist(), Ws[1].T.tolist())) * (P[0] > 0)
+    np.testing.assert_allclose(out["G"][0], G0, rtol=1e-12, atol=1e-15)
+    S0 = np.array(py_matmul(D.tolist(), G0.tolist()))
+    np.testing.assert_allclose(out["Y"][0], np.array(py_matmul(H0.T.tolist(), S0.tolist())), rtol=1e-12, atol=1e-15)
+    assert np.abs(out["Y"][0] - base["Y"][0]).max() > 1e-6                           # the pattern is really used
+
+
 def test_layer_backward_bias_gradient():
     A, At, H0, y, Ws = tiny_problem(False, dims=(4, 3))
     G = synth.normal_features(A.n, 3, 12).astype(np.float64)
