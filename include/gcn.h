@@ -134,6 +134,24 @@ int gcn_spmm(gcn_csr* a, int trans, int32_t f, const float* X, int64_t ldx, floa
              int epilogue, const float* Zprev, int64_t ldzprev, void* stream);
 
 /* -------------------------------------------------------------------------------------------
+ * gcn_spmm for callers that cannot allocate device memory: code under HIP graph capture from its
+ * first call on, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, result and
+ * errors as gcn_spmm, always through the nonzero-split kernel over the stored order (so the result is
+ * bit-identical to gcn_spmm with GCN_CFG_SPMM_ALGO = 2 and GCN_CFG_SPMM_BLOCKS = 1), but the partial rows of
+ * rows that cross wavefronts (f floats per 512 stored entries) live in a fixed array of
+ * GCN_SPMM_STATIC_SCRATCH_BYTES inside the library's device image instead of a buffer the handle grows.
+ * The call makes no hipMalloc / hipFree and no allocating library call; it only queues kernels on `stream`.
+ * GCN_ERR_WORKSPACE when ceil(nnz / 512) * f * 4 bytes exceed the array (e.g. more than 134 M stored entries
+ * at f = 16); BADARG when the matrix lives on another device than the current one.
+ * Every call on a GPU shares that GPU's array (each GPU holds its own copy until the process ends): calls that
+ * overlap in time on one GPU (different streams or threads) race on it.  Nothing in it has to start at
+ * zero -- every partial row is written by the product before it is read -- so consecutive calls need no clearing.
+ * ----------------------------------------------------------------------------------------- */
+#define GCN_SPMM_STATIC_SCRATCH_BYTES (16u << 20)
+int gcn_spmm_static(gcn_csr* a, int trans, int32_t f, const float* X, int64_t ldx, float* Z, int64_t ldz,
+                    int epilogue, const float* Zprev, int64_t ldzprev, void* stream);
+
+/* -------------------------------------------------------------------------------------------
  * Value-free SpMM for the symmetric normalisation of section "Graph Neural Networks":
  * D^-1/2 (A+I) D^-1/2 X = D^-1/2 ((A+I) (D^-1/2 X)), so the stored values need not be read.
  *   gcn_spmm_pattern:  Z[i,:] = epilogue(row_scale[i] * sum over stored entries k of row i of

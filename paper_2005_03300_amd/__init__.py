@@ -7,7 +7,7 @@ library has not been built (there is no CPU fallback).
 """
 from .binding import (  # noqa: F401
     GcnError, Csr, lib, library_path, exported_symbols,
-    gcn_csr_create, gcn_csr_create_from_csr, gcn_csr_create_from_csr_rect, gcn_spmm, gcn_spmm_pattern, gcn_scale_rows,
+    gcn_csr_create, gcn_csr_create_from_csr, gcn_csr_create_from_csr_rect, gcn_spmm, gcn_spmm_static, gcn_spmm_pattern, gcn_scale_rows,
     gcn_csr_inv_sqrt_degrees, gcn_gemm, gcn_relu, gcn_relu_mask,
     gcn_softmax_nll, gcn_softmax_nll_masked, gcn_layer_forward, gcn_layer_backward, gcn_epoch, gcn_epoch_masked, gcn_epoch_preaggregated,
     gcn_epoch_workspace_bytes,

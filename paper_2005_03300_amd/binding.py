@@ -179,6 +179,18 @@ def gcn_spmm(a: Csr, trans: int, X, Z, epilogue: int = EPI_NONE, Zprev=None):
     return Z
 
 
+def gcn_spmm_static(a: Csr, trans: int, X, Z, epilogue: int = EPI_NONE, Zprev=None):
+    import torch
+    _dev(X, torch.float32), _dev(Z, torch.float32)
+    f = X.shape[1]
+    xr, zr = (a.n_rows, a.n_cols) if trans else (a.n_cols, a.n_rows)
+    assert X.shape[0] == xr and tuple(Z.shape) == (zr, f)
+    _check(lib().gcn_spmm_static(a._h, int(trans), C.c_int32(f), _ptr(X), C.c_int64(_ld(X)), _ptr(Z),
+                                 C.c_int64(_ld(Z)), int(epilogue), _ptr(Zprev),
+                                 C.c_int64(_ld(Zprev) if Zprev is not None else 0), _stream()))
+    return Z
+
+
 def gcn_spmm_pattern(a: Csr, trans: int, X, Z, row_scale=None, epilogue: int = EPI_NONE, Zprev=None):
     import torch
     _dev(X, torch.float32), _dev(Z, torch.float32)

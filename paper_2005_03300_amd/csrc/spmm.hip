@@ -16,6 +16,7 @@
 // Column indices and values are read with coalesced 16-byte loads into LDS first and consumed
 // from there; the gathered rows of X are read with one 16-byte load per lane.
 #include <algorithm>
+#include <mutex>
 
 #include "common.h"
 
@@ -668,13 +669,15 @@ static int64_t choose_blocks(int64_t nrows, int64_t ncols, int64_t nnz, int32_t 
 // copy (then row_map gives the row each of its rows stands for) -- with or without column blocks.
 static int run_matrix(gcn_csr* a, Matrix& mm, const int32_t* row_map, int64_t nnz, int64_t nblocks, int32_t f,
                       const float* X, int64_t ldx, float* Z, int64_t ldz, int epilogue, const float* Zprev,
-                      int64_t ldzprev, const SpmmOpt& o, hipStream_t s) {
+                      int64_t ldzprev, const SpmmOpt& o, hipStream_t s, float* carry_given = nullptr) {
     if ((mm.nchunks + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK >= (1ll << 31))
         return fail(GCN_ERR_RANGE, "gcn_spmm: too many chunks for one launch");
-    GCN_TRY(grow(&a->carry, &a->carry_bytes, (size_t)mm.nchunks * (size_t)f * sizeof(float)));
+    // carry_given: a buffer of at least nchunks * f floats that the caller of this function provides
+    // (only without column blocks); otherwise the handle's own buffer, grown on demand
+    if (!carry_given) GCN_TRY(grow(&a->carry, &a->carry_bytes, (size_t)mm.nchunks * (size_t)f * sizeof(float)));
     SplitArgs args;
     args.nnz = nnz; args.nsub = mm.nsub; args.nchunks = mm.nchunks; args.f = f;
-    args.X = X; args.ldx = ldx; args.carry = a->carry;
+    args.X = X; args.ldx = ldx; args.carry = carry_given ? carry_given : a->carry;
     args.defer = nullptr;
     if (nblocks >= 2) {
         int64_t cpb = (mm.ncols + nblocks - 1) / nblocks;
@@ -932,37 +935,77 @@ int spmm_launch(gcn_csr* a, Matrix& m, int32_t f, const float* X, int64_t ldx, f
 
 using namespace gcn;
 
+static int check_spmm_args(const char* who, const gcn_csr* a, int trans, int32_t f, const float* X, int64_t ldx,
+                           const float* Z, int64_t ldz, int epilogue, const float* Zprev, int64_t ldzprev) {
+    if (!a || !X || !Z) return fail(GCN_ERR_BADARG, "%s: NULL argument", who);
+    if (f <= 0 || ldx < f || ldz < f) return fail(GCN_ERR_BADARG, "%s: need f > 0, ldx >= f, ldz >= f", who);
+    if (epilogue < GCN_EPI_NONE || epilogue > GCN_EPI_MASK) return fail(GCN_ERR_BADARG, "%s: unknown epilogue", who);
+    if (epilogue == GCN_EPI_MASK && (!Zprev || ldzprev < f)) return fail(GCN_ERR_BADARG, "%s: mask epilogue needs Zprev with ld >= f", who);
+    if (trans && !a->has_t) return fail(GCN_ERR_NOTRANSPOSE, "%s: trans=1 needs GCN_BUILD_TRANSPOSE", who);
+    // X and Z must not overlap: the product gathers rows of X while rows of Z are written
+    const int64_t xrows = trans ? a->n : a->ncols, zrows = trans ? a->ncols : a->n;
+    const char* xb = (const char*)X; const char* xe = xb + ((size_t)(xrows - 1) * ldx + f) * sizeof(float);
+    const char* zb = (const char*)Z; const char* ze = zb + ((size_t)(zrows - 1) * ldz + f) * sizeof(float);
+    if (xb < ze && zb < xe) return fail(GCN_ERR_BADARG, "%s: X and Z overlap", who);
+    return GCN_OK;
+}
+
 extern "C" int gcn_spmm(gcn_csr* a, int trans, int32_t f, const float* X, int64_t ldx, float* Z, int64_t ldz,
                         int epilogue, const float* Zprev, int64_t ldzprev, void* stream) {
-    if (!a || !X || !Z) return fail(GCN_ERR_BADARG, "gcn_spmm: NULL argument");
-    if (f <= 0 || ldx < f || ldz < f) return fail(GCN_ERR_BADARG, "gcn_spmm: need f > 0, ldx >= f, ldz >= f");
-    if (epilogue < GCN_EPI_NONE || epilogue > GCN_EPI_MASK) return fail(GCN_ERR_BADARG, "gcn_spmm: unknown epilogue");
-    if (epilogue == GCN_EPI_MASK && (!Zprev || ldzprev < f)) return fail(GCN_ERR_BADARG, "gcn_spmm: mask epilogue needs Zprev with ld >= f");
-    if (trans && !a->has_t) return fail(GCN_ERR_NOTRANSPOSE, "gcn_spmm: trans=1 needs GCN_BUILD_TRANSPOSE");
-    {   // X and Z must not overlap: the product gathers rows of X while rows of Z are written
-        const int64_t xrows = trans ? a->n : a->ncols, zrows = trans ? a->ncols : a->n;
-        const char* xb = (const char*)X; const char* xe = xb + ((size_t)(xrows - 1) * ldx + f) * sizeof(float);
-        const char* zb = (const char*)Z; const char* ze = zb + ((size_t)(zrows - 1) * ldz + f) * sizeof(float);
-        if (xb < ze && zb < xe) return fail(GCN_ERR_BADARG, "gcn_spmm: X and Z overlap");
-    }
+    GCN_TRY(check_spmm_args("gcn_spmm", a, trans, f, X, ldx, Z, ldz, epilogue, Zprev, ldzprev));
     return spmm_launch(a, trans ? a->At : a->A, f, X, ldx, Z, ldz, epilogue, Zprev, ldzprev, (hipStream_t)stream);
+}
+
+// ---- the product for callers that cannot allocate --------------------------------------------------------
+// The nonzero-split kernel needs one row of f floats per 512 stored entries for the pieces of rows that
+// cross wavefronts.  gcn_spmm keeps that buffer in the handle and grows it with hipMalloc; this entry point
+// keeps it in a fixed array in the library's device image instead, so that it never allocates.  Each GPU
+// has its own copy of the array at its own address; the address is looked up once per device.
+static constexpr size_t STATIC_SCRATCH_BYTES = GCN_SPMM_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+static constexpr int STATIC_MAX_DEVICES = 64;
+static std::mutex g_static_mu;
+static void* g_static_ptr[STATIC_MAX_DEVICES] = {};
+
+static int static_scratch(float** out) {
+    int dev = -1;
+    GCN_HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= STATIC_MAX_DEVICES) return fail(GCN_ERR_RANGE, "gcn_spmm_static: device index %d not supported", dev);
+    std::lock_guard<std::mutex> lk(g_static_mu);
+    if (!g_static_ptr[dev]) {
+        void* ptr = nullptr;
+        GCN_HIP_TRY(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));      // with `dev` current: this device's copy
+        if (!ptr) return fail(GCN_ERR_HIP, "gcn_spmm_static: no address for the scratch array on device %d", dev);
+        g_static_ptr[dev] = ptr;
+    }
+    *out = (float*)g_static_ptr[dev];
+    return GCN_OK;
+}
+
+extern "C" int gcn_spmm_static(gcn_csr* a, int trans, int32_t f, const float* X, int64_t ldx, float* Z, int64_t ldz,
+                               int epilogue, const float* Zprev, int64_t ldzprev, void* stream) {
+    GCN_TRY(check_spmm_args("gcn_spmm_static", a, trans, f, X, ldx, Z, ldz, epilogue, Zprev, ldzprev));
+    int dev = -1;
+    GCN_HIP_TRY(hipGetDevice(&dev));
+    if (dev != a->device) return fail(GCN_ERR_BADARG, "gcn_spmm_static: the matrix lives on device %d, current device is %d", a->device, dev);
+    Matrix& m = trans ? a->At : a->A;
+    const size_t need = (size_t)m.nchunks * (size_t)f * sizeof(float);
+    if (need > STATIC_SCRATCH_BYTES)
+        return fail(GCN_ERR_WORKSPACE, "gcn_spmm_static: needs %zu bytes of scratch (%lld stored entries / 512, rounded up, x %d floats), the fixed "
+                    "array holds %zu; use gcn_spmm", need, (long long)a->nnz, (int)f, STATIC_SCRATCH_BYTES);
+    hipStream_t s = (hipStream_t)stream;
+    if (a->nnz == 0 || m.n_ne < m.nrows) GCN_TRY(zero_empty_rows(m, f, Z, ldz, s));
+    if (a->nnz == 0) return GCN_OK;
+    float* carry = nullptr;
+    GCN_TRY(static_scratch(&carry));
+    g_last_schedule = GCN_SCHED_SPLIT;
+    return run_matrix(a, m, nullptr, a->nnz, 1, f, X, ldx, Z, ldz, epilogue, Zprev, ldzprev, SpmmOpt(), s, carry);
 }
 
 extern "C" int gcn_spmm_pattern(gcn_csr* a, int trans, int32_t f, const float* X, int64_t ldx, float* Z, int64_t ldz,
                                 const float* row_scale, int epilogue, const float* Zprev, int64_t ldzprev,
                                 void* stream) {
-    if (!a || !X || !Z) return fail(GCN_ERR_BADARG, "gcn_spmm_pattern: NULL argument");
-    if (f <= 0 || ldx < f || ldz < f) return fail(GCN_ERR_BADARG, "gcn_spmm_pattern: need f > 0, ldx >= f, ldz >= f");
-    if (epilogue < GCN_EPI_NONE || epilogue > GCN_EPI_MASK) return fail(GCN_ERR_BADARG, "gcn_spmm_pattern: unknown epilogue");
-    if (epilogue == GCN_EPI_MASK && (!Zprev || ldzprev < f))
-        return fail(GCN_ERR_BADARG, "gcn_spmm_pattern: mask epilogue needs Zprev with ld >= f");
-    if (trans && !a->has_t) return fail(GCN_ERR_NOTRANSPOSE, "gcn_spmm_pattern: trans=1 needs GCN_BUILD_TRANSPOSE");
-    {
-        const int64_t xrows = trans ? a->n : a->ncols, zrows = trans ? a->ncols : a->n;
-        const char* xb = (const char*)X; const char* xe = xb + ((size_t)(xrows - 1) * ldx + f) * sizeof(float);
-        const char* zb = (const char*)Z; const char* ze = zb + ((size_t)(zrows - 1) * ldz + f) * sizeof(float);
-        if (xb < ze && zb < xe) return fail(GCN_ERR_BADARG, "gcn_spmm_pattern: X and Z overlap");
-    }
+    GCN_TRY(check_spmm_args("gcn_spmm_pattern", a, trans, f, X, ldx, Z, ldz, epilogue, Zprev, ldzprev));
     SpmmOpt o;
     o.pattern = true;
     o.row_scale = row_scale;
