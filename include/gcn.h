@@ -12,12 +12,22 @@
  *   - Dense buffers are owned by the caller; the library neither frees nor keeps them after the
  *     work queued on `stream` has finished.  Only gcn_csr objects own device memory.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Compute calls only
- *     queue work on it and return; gcn_csr_create*, gcn_csr_info and gcn_csr_destroy synchronise, and so
- *     may the first sparse product of a given width on a matrix (it can build and cache another stored
- *     order of the matrix, which allocates device memory) and any call that grows the library's scratch.
+ *     queue work on it and return; gcn_csr_create*, gcn_csr_info, gcn_csr_destroy and the prepare calls
+ *     synchronise.  A sparse product whose width was not prepared (gcn_spmm_prepare, gcn_epoch_prepare) and
+ *     was not used before may build and keep another stored order of the matrix and grow the handle's
+ *     buffers: it then allocates device memory and waits for the stream once.  After a prepare call for the
+ *     widths in use, the products and the epoch calls only queue kernels and device-to-device copies: they
+ *     can be captured in a HIP graph from their first call on.  Nothing the library has handed to a kernel is
+ *     freed before gcn_csr_destroy (a larger buffer replaces a smaller one, which is kept), so graphs captured
+ *     earlier stay valid.
+ *   - Library-owned scratch exists only for the stand-alone gcn_gemm (ta = 1), gcn_softmax_nll* and the bias
+ *     gradient of gcn_layer_backward: one buffer per (device, stream), grown on demand by the first call that
+ *     needs more (an allocation), never shared between streams; gcn_scratch_release frees all of them.  The
+ *     epoch calls keep these partial sums in the caller's workspace instead.
  *   - Every function returns GCN_OK (0) or a negative GCN_ERR_* code and never throws or aborts.
  *     gcn_last_error() returns a thread-local message for the last failure on this thread.
- *   - No call is safe to run concurrently with another call that uses the same gcn_csr.
+ *   - No call is safe to run concurrently with another call that uses the same gcn_csr.  Calls on different
+ *     matrices, or calls without a matrix on different streams, may run concurrently from different threads.
  */
 #ifndef GCN_H
 #define GCN_H
@@ -58,7 +68,7 @@ extern "C" {
 #define GCN_ACT_NONE 0
 #define GCN_ACT_RELU 1
 
-/* gcn_config keys */
+/* gcn_config / gcn_csr_config keys */
 #define GCN_CFG_SPMM_ALGO 1 /* 0 = automatic, 1 = one thread per output element, 2 = nonzero-split, 3 = column sweep, 4 = hub schedule (long rows x hot columns over a packed buffer, the rest as 2) */
 #define GCN_CFG_TIMING 2    /* 1 = bracket the dominant kernels with HIP events (see gcn_timing_read) */
 #define GCN_CFG_SPMM_BLOCKS 3 /* column blocks of the SpMM: 0 = automatic, 1 = never block, k >= 2 = k blocks */
@@ -81,7 +91,8 @@ typedef struct gcn_csr gcn_csr; /* opaque: A (and A^T) in compressed rows, degre
  * duplicates collapse to one entry.  The result has columns ascending in every row; rowptr is
  * int64, colidx int32, val fp32, deg int32 = entries per row of A.  With GCN_NORM_SYM,
  * val(i,j) = (float)(1.0 / sqrt((double)deg_i * (double)deg_j)); with GCN_NORM_ROW, (float)(1.0 / (double)deg_i).
- * The rows of a graph without self loops can be empty; normalising those is the caller's error.
+ * The rows of a graph without self loops can be empty; with GCN_NORM_SYM an entry that touches a vertex whose
+ * row is empty gets the value 0 (D^-1/2 as a pseudo-inverse), and gcn_csr_inv_sqrt_degrees gives 0 for it.
  * Errors: BADARG (NULL out, n <= 0, n_edges < 0, NULL arrays with n_edges > 0), RANGE (n >= 2^31
  * or an id outside [0,n)), OOM, HIP.  On error *out is NULL.
  * ----------------------------------------------------------------------------------------- */
@@ -132,6 +143,16 @@ int gcn_csr_export(const gcn_csr* a, int transposed, int64_t* rowptr, int32_t* c
  * ----------------------------------------------------------------------------------------- */
 int gcn_spmm(gcn_csr* a, int trans, int32_t f, const float* X, int64_t ldx, float* Z, int64_t ldz,
              int epilogue, const float* Zprev, int64_t ldzprev, void* stream);
+
+/* Builds, for operands of width f (16-byte aligned, leading dimensions multiples of 4 when f is), whatever
+ * gcn_spmm / gcn_spmm_pattern would build or grow on their first call at that width -- the stored order the
+ * schedule needs and the handle's buffers -- without running a product.  Synchronises `stream`.  Copies for
+ * several widths are kept side by side, so a model whose products alternate between widths never rebuilds.
+ * gcn_spmm_describe writes the schedule such a product takes and its launch shape as text into `out`
+ * (host, out_bytes including the terminator; truncated if too small), building it like gcn_spmm_prepare if
+ * needed; reports and tests use it to tie a measurement to the schedule it was taken on. */
+int gcn_spmm_prepare(gcn_csr* a, int trans, int32_t f, void* stream);
+int gcn_spmm_describe(gcn_csr* a, int trans, int32_t f, char* out, size_t out_bytes, void* stream);
 
 /* -------------------------------------------------------------------------------------------
  * gcn_spmm for callers that cannot allocate device memory: code under HIP graph capture from its
@@ -233,11 +254,12 @@ int gcn_layer_backward(gcn_csr* a, int32_t f_in, int32_t f_out, const float* Hin
  * dims: HOST int32[L_w+1] = f^0..f^{L_w}.  H0: device n x dims[0] dense.  labels: device int32[n].
  * W, Y: HOST arrays of L_w device pointers (W[l] is dims[l] x dims[l+1]; Y[l] receives dL/dW[l]).
  * loss: device float.  workspace: device, 256-byte aligned, at least gcn_epoch_workspace_bytes();
- * holds every H^l, Z^{L_w}, G^l and the scratch matrices, O(n * sum f).  `order` applies to every layer.
- * The first call with a given matrix, width set and configuration may build schedules and grow the
- * library's scratch (device allocations, synchronisation).  Later calls with the same arguments only
- * enqueue kernels and device-to-device copies on `stream`, so they can be captured in a HIP graph and
- * replayed; all reductions run in a fixed order, so repeated epochs give bit-identical results.
+ * holds every H^l, Z^{L_w}, G^l, the scratch matrices and the partial sums of the reductions over n,
+ * O(n * sum f).  `order` applies to every layer.
+ * The first call with a given matrix, width set and configuration may build schedules and grow the handle's
+ * buffers (device allocations, one wait for the stream) unless gcn_epoch_prepare ran before.  Otherwise the
+ * call only enqueues kernels and device-to-device copies on `stream`, so it can be captured in a HIP graph
+ * and replayed; all reductions run in a fixed order, so repeated epochs give bit-identical results.
  * ----------------------------------------------------------------------------------------- */
 int gcn_epoch(gcn_csr* a, int32_t L_w, const int32_t* dims, const float* H0, const int32_t* labels,
               float* const* W, float* const* Y, float lr, float* loss, void* workspace,
@@ -245,6 +267,10 @@ int gcn_epoch(gcn_csr* a, int32_t L_w, const int32_t* dims, const float* H0, con
 
 /* gcn_epoch with a training split: labels < 0 mark vertices outside it, n_labelled counts the others
  * (see gcn_softmax_nll_masked).  Calling it in a loop with lr != 0 is full-batch gradient descent. */
+/* gcn_spmm_prepare for every sparse product of an epoch with these arguments (both stored matrices, the widths
+ * the association order gives).  After it, gcn_epoch* with the same matrix, dims and order only queues work. */
+int gcn_epoch_prepare(gcn_csr* a, int32_t L_w, const int32_t* dims, int order, void* stream);
+
 int gcn_epoch_masked(gcn_csr* a, int32_t L_w, const int32_t* dims, const float* H0, const int32_t* labels,
                      int64_t n_labelled, float* const* W, float* const* Y, float lr, float* loss, void* workspace,
                      size_t workspace_bytes, int order, void* stream);
@@ -266,8 +292,14 @@ size_t gcn_epoch_workspace_bytes(int64_t n, int32_t L_w, const int32_t* dims, in
 int gcn_epoch_view(int64_t n, int32_t L_w, const int32_t* dims, int order, void* workspace, int32_t l,
                    float** Z, float** G);
 
-/* Library-wide settings (GCN_CFG_*).  Returns BADARG for an unknown key or value. */
+/* Process-wide settings (GCN_CFG_*), followed by every matrix that has no settings of its own.  Returns BADARG
+ * for an unknown key or value.  gcn_csr_config gives one matrix its own settings: the first call copies the
+ * process-wide ones into the matrix, which from then on ignores gcn_config (GCN_CFG_TIMING stays process-wide). */
 int gcn_config(int key, int value);
+int gcn_csr_config(gcn_csr* a, int key, int value);
+
+/* Frees the library-owned per-stream scratch (after waiting for the device); later calls allocate it again. */
+int gcn_scratch_release(void);
 
 /* With GCN_CFG_TIMING = 1 the SpMM main kernel is bracketed by HIP events on its own stream.
  * gcn_timing_read synchronises with the recorded events, returns the number of bracketed
@@ -311,6 +343,10 @@ int gcn_unique_u64(int64_t n, const uint64_t* keys_in, uint64_t* keys_out, int64
 #define GCN_SCHED_HUB 4      /* hub schedule */
 #define GCN_SCHED_BLOCKED 5  /* nonzero-split over the column-blocked copy */
 int gcn_last_spmm_schedule(void);
+int gcn_csr_last_spmm_schedule(const gcn_csr* a);   /* the same per matrix (0 before its first product) */
+/* Number of stored orders of matrices (column-blocked, sweep, hub copies) this process has built so far: a
+ * caller can check that a steady-state loop builds nothing. */
+int64_t gcn_build_count(void);
 
 const char* gcn_last_error(void);
 const char* gcn_version(void);

@@ -102,7 +102,12 @@ void orc_degrees(int64_t n, const int64_t* rowptr, int32_t* deg) {
 void orc_values_sym(int64_t n, const int64_t* ptr, const int32_t* minor, const int32_t* deg, float* val) {
     for (int64_t i = 0; i < n; ++i)
         for (int64_t k = ptr[i]; k < ptr[i + 1]; ++k)
-            val[k] = (float)(1.0 / sqrt((double)deg[i] * (double)deg[minor[k]]));
+        {
+            /* D^-1/2 is taken as the pseudo-inverse: a vertex whose row has no entry (possible only without
+             * self-connections, for a vertex with no outgoing edge) scales by 0, not by 1/0. */
+            const double dd = (double)deg[i] * (double)deg[minor[k]];
+            val[k] = dd > 0.0 ? (float)(1.0 / sqrt(dd)) : 0.0f;
+        }
 }
 
 /* Row normalisation D^-1 (A+I) for directed graphs: entry (i,j) = 1/d_i with d the degrees of the

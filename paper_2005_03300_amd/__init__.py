@@ -11,7 +11,8 @@ from .binding import (  # noqa: F401
     gcn_csr_inv_sqrt_degrees, gcn_gemm, gcn_relu, gcn_relu_mask,
     gcn_softmax_nll, gcn_softmax_nll_masked, gcn_layer_forward, gcn_layer_backward, gcn_epoch, gcn_epoch_masked, gcn_epoch_preaggregated,
     gcn_epoch_workspace_bytes,
-    gcn_epoch_view, gcn_config, gcn_timing_read, gcn_timing_read_phases, gcn_version, gcn_last_spmm_schedule, gcn_radix_sort, gcn_exclusive_scan_i64, gcn_unique_u64,
+    gcn_epoch_view, gcn_config, gcn_csr_config, gcn_spmm_prepare, gcn_spmm_describe, gcn_epoch_prepare, gcn_scratch_release,
+    gcn_build_count, gcn_csr_last_spmm_schedule, gcn_timing_read, gcn_timing_read_phases, gcn_version, gcn_last_spmm_schedule, gcn_radix_sort, gcn_exclusive_scan_i64, gcn_unique_u64,
     SCHED_ROWWISE, SCHED_SPLIT, SCHED_SWEEP, SCHED_HUB, SCHED_BLOCKED,
     SYMMETRISE, ADD_SELF_LOOPS, NORM_SYM, BUILD_TRANSPOSE, NORM_ROW,
     EPI_NONE, EPI_RELU, EPI_MASK, ORDER_AUTO, ORDER_GEMM_FIRST, ORDER_SPMM_FIRST, ACT_NONE, ACT_RELU,

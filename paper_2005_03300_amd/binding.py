@@ -48,6 +48,7 @@ def lib():
         L.gcn_last_error.restype = C.c_char_p
         L.gcn_version.restype = C.c_char_p
         L.gcn_epoch_workspace_bytes.restype = C.c_size_t
+        L.gcn_build_count.restype = C.c_int64
         _lib = L
     return _lib
 
@@ -344,6 +345,36 @@ def gcn_epoch_view(n: int, dims, order: int, workspace, layer: int):
 
 def gcn_config(key: int, value: int):
     _check(lib().gcn_config(int(key), int(value)))
+
+
+def gcn_csr_config(a: Csr, key: int, value: int):
+    _check(lib().gcn_csr_config(a._h, int(key), int(value)))
+
+
+def gcn_spmm_prepare(a: Csr, trans: int, f: int):
+    _check(lib().gcn_spmm_prepare(a._h, int(trans), C.c_int32(f), _stream()))
+
+
+def gcn_spmm_describe(a: Csr, trans: int, f: int) -> str:
+    buf = C.create_string_buffer(1024)
+    _check(lib().gcn_spmm_describe(a._h, int(trans), C.c_int32(f), buf, C.c_size_t(1024), _stream()))
+    return buf.value.decode()
+
+
+def gcn_epoch_prepare(a: Csr, dims, order: int = ORDER_AUTO):
+    _check(lib().gcn_epoch_prepare(a._h, C.c_int32(len(dims) - 1), _dims_array(dims), int(order), _stream()))
+
+
+def gcn_scratch_release():
+    _check(lib().gcn_scratch_release())
+
+
+def gcn_build_count() -> int:
+    return int(lib().gcn_build_count())
+
+
+def gcn_csr_last_spmm_schedule(a: Csr) -> int:
+    return int(lib().gcn_csr_last_spmm_schedule(a._h))
 
 
 def gcn_timing_read():

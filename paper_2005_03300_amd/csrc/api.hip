@@ -2,6 +2,7 @@
 #include <stdarg.h>
 #include <string.h>
 
+#include <atomic>
 #include <mutex>
 #include <vector>
 
@@ -43,26 +44,80 @@ void device_free(void* p) {
     if (p) (void)hipFree(p);
 }
 
+// ---- per-stream scratch ------------------------------------------------------------------------
+struct Arena { int device; hipStream_t stream; void* p; size_t bytes; };
 static std::mutex g_scratch_mu;
-static void* g_scratch = nullptr;
-static size_t g_scratch_bytes = 0;
+static std::vector<Arena> g_arenas;
+static std::vector<void*> g_scratch_retired;
 
-int scratch_get(void** p, size_t bytes) {
-    std::lock_guard<std::mutex> lk(g_scratch_mu);
-    if (bytes > g_scratch_bytes) {
-        // Work queued earlier may still read the old buffer: wait before freeing it.
-        if (g_scratch) {
-            GCN_HIP_TRY(hipDeviceSynchronize());
-            device_free(g_scratch);
-            g_scratch = nullptr;
-            g_scratch_bytes = 0;
-        }
-        size_t want = bytes + bytes / 4;
-        GCN_TRY(device_alloc(&g_scratch, want));
-        g_scratch_bytes = want;
+static thread_local void* g_scope_p = nullptr;
+static thread_local size_t g_scope_bytes = 0;
+
+ScratchScope::ScratchScope(void* p, size_t bytes) : prev_p(g_scope_p), prev_bytes(g_scope_bytes) {
+    g_scope_p = p;
+    g_scope_bytes = bytes;
+}
+ScratchScope::~ScratchScope() {
+    g_scope_p = prev_p;
+    g_scope_bytes = prev_bytes;
+}
+
+int scratch_get(void** p, size_t bytes, hipStream_t s) {
+    if (g_scope_p) {
+        if (bytes > g_scope_bytes)
+            return fail(GCN_ERR_WORKSPACE, "workspace scratch region has %zu bytes, %zu needed", g_scope_bytes, bytes);
+        *p = g_scope_p;
+        return GCN_OK;
     }
-    *p = g_scratch;
+    int dev = 0;
+    GCN_HIP_TRY(hipGetDevice(&dev));
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    Arena* ar = nullptr;
+    for (auto& x : g_arenas)
+        if (x.device == dev && x.stream == s) { ar = &x; break; }
+    if (!ar) {
+        g_arenas.push_back({dev, s, nullptr, 0});
+        ar = &g_arenas.back();
+    }
+    if (bytes > ar->bytes) {
+        // Work queued (or captured in a graph) earlier may still use the old buffer: keep it.
+        void* fresh = nullptr;
+        const size_t want = bytes + bytes / 4;
+        GCN_TRY(device_alloc(&fresh, want));
+        if (ar->p) g_scratch_retired.push_back(ar->p);
+        ar->p = fresh;
+        ar->bytes = want;
+    }
+    *p = ar->p;
     return GCN_OK;
+}
+
+int grow_retire(gcn_csr* a, float** buf, size_t* have, size_t need) {
+    if (need <= *have) return GCN_OK;
+    void* fresh = nullptr;
+    GCN_TRY(device_alloc(&fresh, need));
+    if (*buf) a->retired.push_back(*buf);
+    *buf = (float*)fresh;
+    *have = need;
+    return GCN_OK;
+}
+
+const DeviceInfo& device_info() {
+    static std::mutex mu;
+    static DeviceInfo info[64];
+    static bool known[64] = {};
+    int dev = 0;
+    (void)hipGetDevice(&dev);
+    if (dev < 0 || dev >= 64) dev = 0;
+    std::lock_guard<std::mutex> lk(mu);
+    if (!known[dev]) {
+        int cus = 0, l2 = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
+        if (hipDeviceGetAttribute(&l2, hipDeviceAttributeL2CacheSize, dev) != hipSuccess || l2 <= 0) l2 = 4 << 20;
+        info[dev] = {cus, (int64_t)l2};
+        known[dev] = true;
+    }
+    return info[dev];
 }
 
 Config& config() {
@@ -71,6 +126,9 @@ Config& config() {
 }
 
 int g_last_schedule = 0;
+
+static std::atomic<int64_t> g_builds{0};
+void count_build() { g_builds.fetch_add(1); }
 
 // ---- event timing ---------------------------------------------------------------------------
 struct TimedSpan { hipEvent_t a, b; int phase; };
@@ -151,6 +209,9 @@ void free_matrix(Matrix& m) {
     free_blocked(m.blk);
     free_sweep(m.swp);
     free_hub(m.hub);
+    for (auto& b : m.blk_parked) free_blocked(b);
+    for (auto& w : m.swp_parked) free_sweep(w);
+    for (auto& h : m.hub_parked) free_hub(h);
     m = Matrix();
 }
 
@@ -165,51 +226,63 @@ const char* gcn_version(void) { return "gcn-hip 0.1 (gfx950)"; }
 
 int gcn_last_spmm_schedule(void) { return gcn::g_last_schedule; }
 
-int gcn_config(int key, int value) {
+static int set_config(Config& c, int key, int value) {
     switch (key) {
         case GCN_CFG_SPMM_ALGO:
             if (value < 0 || value > 4) return fail(GCN_ERR_BADARG, "GCN_CFG_SPMM_ALGO must be 0, 1, 2, 3 or 4");
-            config().spmm_algo = value;
+            c.spmm_algo = value;
             return GCN_OK;
         case GCN_CFG_SPMM_BLOCKS:
             if (value < 0 || value > (1 << 24)) return fail(GCN_ERR_BADARG, "GCN_CFG_SPMM_BLOCKS must be in [0, 2^24]");
-            config().spmm_blocks = value;
+            c.spmm_blocks = value;
             return GCN_OK;
         case GCN_CFG_SPLIT_LDS_KB:
             if (value < 18 || value > 64) return fail(GCN_ERR_BADARG, "GCN_CFG_SPLIT_LDS_KB must be in [18, 64]");
-            config().split_lds_kb = value;
+            c.split_lds_kb = value;
             return GCN_OK;
         case GCN_CFG_SWEEP_WAVES:
             if (value < 1 || value > 18) return fail(GCN_ERR_BADARG, "GCN_CFG_SWEEP_WAVES must be in [1, 18]");
-            config().sweep_waves = value;
+            c.sweep_waves = value;
             return GCN_OK;
         case GCN_CFG_SWEEP_HEAVY:
             if (value < 1) return fail(GCN_ERR_BADARG, "GCN_CFG_SWEEP_HEAVY must be at least 1");
-            config().sweep_heavy = value;
+            c.sweep_heavy = value;
             return GCN_OK;
         case GCN_CFG_HUB_MB:
             if (value < 1 || value > 4096) return fail(GCN_ERR_BADARG, "GCN_CFG_HUB_MB must be in [1, 4096]");
-            config().hub_mb = value;
+            c.hub_mb = value;
             return GCN_OK;
         case GCN_CFG_HUB_BLOCK_COLS:
             if (value < 0 || (value % 64) != 0) return fail(GCN_ERR_BADARG, "GCN_CFG_HUB_BLOCK_COLS must be 0 or a multiple of 64");
-            config().hub_block_cols = value;
+            c.hub_block_cols = value;
             return GCN_OK;
         case GCN_CFG_HUB_DMIN:
             if (value < 1) return fail(GCN_ERR_BADARG, "GCN_CFG_HUB_DMIN must be at least 1");
-            config().hub_dmin = value;
+            c.hub_dmin = value;
             return GCN_OK;
         case GCN_CFG_PATTERN_SPMM:
             if (value < 0 || value > 2) return fail(GCN_ERR_BADARG, "GCN_CFG_PATTERN_SPMM must be 0, 1 or 2");
-            config().pattern_spmm = value;
+            c.pattern_spmm = value;
             return GCN_OK;
         case GCN_CFG_TIMING:
             if (value != 0 && value != 1) return fail(GCN_ERR_BADARG, "GCN_CFG_TIMING must be 0 or 1");
-            config().timing = value;
+            c.timing = value;
             return GCN_OK;
         default:
             return fail(GCN_ERR_BADARG, "unknown config key %d", key);
     }
+}
+
+int gcn_config(int key, int value) { return set_config(config(), key, value); }
+
+int gcn_csr_config(gcn_csr* a, int key, int value) {
+    if (!a) return fail(GCN_ERR_BADARG, "gcn_csr_config: NULL matrix");
+    if (key == GCN_CFG_TIMING) return fail(GCN_ERR_BADARG, "gcn_csr_config: GCN_CFG_TIMING is process-wide (gcn_config)");
+    if (!a->own_cfg) {               // from now on this matrix no longer follows gcn_config
+        a->cfg = config();
+        a->own_cfg = true;
+    }
+    return set_config(a->cfg, key, value);
 }
 
 int gcn_timing_read_phases(int64_t* spans, double* total_ms) {
@@ -254,9 +327,24 @@ int gcn_csr_destroy(gcn_csr* a) {
     device_free(a->inv_sqrt_deg);
     device_free(a->carry);
     device_free(a->partial);
+    for (void* p : a->retired) device_free(p);
     delete a;
     return GCN_OK;
 }
+
+int gcn_scratch_release(void) {
+    GCN_HIP_TRY(hipDeviceSynchronize());
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    for (auto& x : g_arenas) device_free(x.p);
+    for (void* p : g_scratch_retired) device_free(p);
+    g_arenas.clear();
+    g_scratch_retired.clear();
+    return GCN_OK;
+}
+
+int64_t gcn_build_count(void) { return g_builds.load(); }
+
+int gcn_csr_last_spmm_schedule(const gcn_csr* a) { return a ? a->last_schedule : 0; }
 
 int gcn_csr_info(const gcn_csr* a, int64_t* n, int64_t* nnz, int32_t* max_degree) {
     if (!a) return fail(GCN_ERR_BADARG, "gcn_csr_info: NULL matrix");

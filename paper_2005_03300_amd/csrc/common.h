@@ -5,6 +5,9 @@
 #include <stdint.h>
 #include <stdio.h>
 
+#include <string>
+#include <vector>
+
 #include "gcn.h"
 
 namespace gcn {
@@ -125,9 +128,30 @@ struct Matrix {
     int64_t n_fix = -1;          // -1: no list (every chunk is examined)
     int64_t nsub = 0, nchunks = 0;
     int32_t max_degree = 0;
-    Blocked blk;                 // built on first use for one block width
-    Sweep swp;                   // built on first use for one block width / task height
-    Hub hub;                     // built on first use for one packed-buffer size / block width
+    // Other stored orders of the matrix, built on first use (or by a prepare call) and kept until the
+    // matrix is destroyed.  blk / swp / hub are the copies the latest product used; a product that needs
+    // another key (block width; lane groups, task height and long-row threshold; hub settings) parks the
+    // current copy in the list beside it and takes the matching one from there, or builds it.  Nothing is
+    // freed before destroy, so kernels already queued (or captured in a HIP graph) keep valid pointers.
+    Blocked blk;
+    Sweep swp;
+    Hub hub;
+    std::vector<Blocked> blk_parked;
+    std::vector<Sweep> swp_parked;
+    std::vector<Hub> hub_parked;
+};
+
+struct Config {
+    int spmm_algo = 0;
+    int spmm_blocks = 0;
+    int sweep_heavy = 1024;
+    int split_lds_kb = 28;       // nonzero-split kernels for rows of up to 64 bytes: LDS per workgroup incl. padding (18: none)
+    int sweep_waves = 9;
+    int hub_mb = 32;             // hub schedule: size of the packed buffer of hot rows of X, MB
+    int hub_block_cols = 0;      // hub schedule: columns per block (0: about 2 MB of the gathered panel)
+    int hub_dmin = 64;           // hub schedule: rows with at least this many entries are long rows
+    int pattern_spmm = 2;        // epoch: value-free SpMM for symmetric normalisation (0 never, 1 always, 2 by row length)
+    int timing = 0;
 };
 
 }  // namespace gcn
@@ -146,6 +170,10 @@ struct gcn_csr {
     size_t carry2_bytes = 0;
     float* partial = nullptr;    // P of the column-blocked SpMM
     size_t partial_bytes = 0;
+    std::vector<void*> retired;  // buffers replaced by larger ones: kept until destroy (queued or captured work may use them)
+    bool own_cfg = false;        // set by gcn_csr_config: this matrix has settings of its own
+    gcn::Config cfg;             // valid when own_cfg
+    int last_schedule = 0;       // GCN_SCHED_* of the latest product on this matrix
 };
 
 namespace gcn {
@@ -155,25 +183,33 @@ template <typename T>
 int device_alloc_t(T** p, size_t count) { return device_alloc((void**)p, count * sizeof(T)); }
 void device_free(void* p);
 
-// library-owned scratch that grows on demand (used by the split-K weight-gradient product and
-// the loss reduction); one per process, calls on different streams must not overlap.
-int scratch_get(void** p, size_t bytes);
-
-struct Config {
-    int spmm_algo = 0;
-    int spmm_blocks = 0;
-    int sweep_heavy = 1024;
-    int split_lds_kb = 28;       // nonzero-split kernels for rows of up to 64 bytes: LDS per workgroup incl. padding (18: none)
-    int sweep_waves = 9;
-    int hub_mb = 32;             // hub schedule: size of the packed buffer of hot rows of X, MB
-    int hub_block_cols = 0;      // hub schedule: columns per block (0: about 2 MB of the gathered panel)
-    int hub_dmin = 64;           // hub schedule: rows with at least this many entries are long rows
-    int pattern_spmm = 2;        // epoch: value-free SpMM for symmetric normalisation (0 never, 1 always, 2 by row length)
-    int timing = 0;
+// Library-owned scratch for the split-K partial sums of the weight-gradient product, the column sums and the
+// loss: one buffer per (device, stream), so calls on different streams never share it.  It grows on demand; the
+// buffer it replaces is kept (work queued or captured earlier may still use it) until gcn_scratch_release.
+int scratch_get(void** p, size_t bytes, hipStream_t s);
+// While one of these is alive on a thread, scratch_get on that thread hands out the given caller-owned
+// buffer instead (GCN_ERR_WORKSPACE if it is too small): the epoch calls keep their partial sums in the
+// caller's workspace.
+struct ScratchScope {
+    ScratchScope(void* p, size_t bytes);
+    ~ScratchScope();
+    void* prev_p;
+    size_t prev_bytes;
 };
-Config& config();
+// bytes of that scratch the split-K product (ta = 1) and the column sums take for the given shape
+size_t gemm_tn_scratch_bytes(int64_t M, int64_t N, int64_t K);
+size_t colsum_scratch_bytes(int64_t rows, int32_t cols);
+size_t loss_scratch_bytes();
+
+// Compute units and L2 size (one XCD's) of the current device, read once per device from the runtime.
+struct DeviceInfo { int cus; int64_t l2_bytes; };
+const DeviceInfo& device_info();
+
+Config& config();                               // the process-wide settings (gcn_config)
+inline const Config& cfg_of(const gcn_csr* a) { return a->own_cfg ? a->cfg : config(); }
 // schedule taken by the most recent sparse product of this process (GCN_SCHED_*), for tests and reports
 extern int g_last_schedule;
+void count_build();
 
 // event bracketing of the dominant kernel (GCN_CFG_TIMING)
 void timing_begin(hipStream_t s, int phase = GCN_PHASE_SPMM_KERNEL);
@@ -190,6 +226,9 @@ int build_schedule(Matrix& m, int64_t n, int64_t nnz, hipStream_t s);
 int build_fix_list(const uint32_t* flags, const int32_t* sub_row, const int64_t* rp, int64_t nchunks, int32_t** list,
                    int64_t* count, hipStream_t s);
 int build_blocked(Matrix& m, int64_t nnz, int64_t cols_per_block, hipStream_t s);
+// make m.blk / m.swp the copy with the given key: the current one, a parked one, or a newly built one
+int want_blocked(Matrix& m, int64_t nnz, int64_t cols_per_block, hipStream_t s);
+int want_sweep(Matrix& m, int64_t nnz, int32_t groups, int32_t rb, int32_t heavy_threshold, hipStream_t s);
 void free_blocked(Blocked& b);
 int build_sweep(Matrix& m, int64_t nnz, int32_t groups, int32_t rb, int32_t heavy_threshold, hipStream_t s);
 void free_sweep(Sweep& w);
@@ -205,12 +244,20 @@ struct SpmmOpt {
     // internal to the hub schedule:
     const uint8_t* defer = nullptr;   // rows whose sum is stored raw (no scale, no epilogue)
     bool accumulate = false;          // column-blocked reduce adds to what Z already holds
+    // prepare / describe:
+    bool dry = false;                 // build the stored order and size the buffers, launch nothing
+    std::string* describe = nullptr;  // receives the schedule and its launch shape as text
 };
 int scale_rows_launch(int64_t rows, int32_t cols, const float* X, int64_t ldx, const float* scale, float* Y, int64_t ldy,
                       hipStream_t s);
 int inv_sqrt_deg_launch(int64_t n, const int32_t* deg, float* out, hipStream_t s);
 int spmm_launch(gcn_csr* a, Matrix& m, int32_t f, const float* X, int64_t ldx, float* Z, int64_t ldz,
                 int epilogue, const float* Zprev, int64_t ldzprev, hipStream_t s, const SpmmOpt& o = SpmmOpt());
+// builds the stored order and sizes the handle's buffers that spmm_launch would need for width f (16-byte
+// aligned operands with leading dimensions that are multiples of 4 assumed), without running the product
+int spmm_prepare(gcn_csr* a, Matrix& m, int32_t f, hipStream_t s);
+// grows one of the handle's buffers; the replaced buffer is retired, not freed
+int grow_retire(gcn_csr* a, float** buf, size_t* have, size_t need);
 
 int gemm_launch(int ta, int tb, int64_t M, int64_t N, int64_t K, const float* A, int64_t lda, const float* B,
                 int64_t ldb, float* C, int64_t ldc, const float* bias, int epilogue, const float* Zprev,

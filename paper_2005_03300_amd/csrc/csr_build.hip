@@ -83,7 +83,12 @@ __global__ void k_values(int64_t nnz, const uint64_t* __restrict__ keys, const i
     uint64_t key = keys[k];
     double di = (double)deg[key >> 32], dj = (double)deg[key & 0xffffffffu];
     if (norm == 2) val[k] = (float)__ddiv_rn(1.0, di);
-    else val[k] = (float)__ddiv_rn(1.0, __dsqrt_rn(__dmul_rn(di, dj)));
+    else {
+        // a vertex whose row is empty (no self loops, no outgoing edge) scales by 0: D^-1/2 as a pseudo-inverse,
+        // the same convention as the per-vertex factors of the value-free product
+        const double dd = __dmul_rn(di, dj);
+        val[k] = dd > 0.0 ? (float)__ddiv_rn(1.0, __dsqrt_rn(dd)) : 0.f;
+    }
 }
 
 __global__ void k_swap_halves(int64_t nnz, const uint64_t* __restrict__ keys, uint64_t* __restrict__ out) {

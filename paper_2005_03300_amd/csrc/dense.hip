@@ -130,6 +130,43 @@ int gemm_mfma_launch(int ta, int tb, int64_t M, int64_t N, int64_t K, const floa
                      int64_t ldb, float* C, int64_t ldc, const float* bias, int epilogue, const float* Zprev,
                      int64_t ldzprev, hipStream_t s, bool* handled);
 
+// split of the long dimension of the plain (non-MFMA) A^T B kernel
+static void naive_tn_split(int64_t K, int64_t* parts_out, int64_t* kpb_out) {
+    int64_t parts = (K + 1023) / 1024;
+    if (parts > 1024) parts = 1024;
+    if (parts < 1) parts = 1;
+    const int64_t kpb = (K + parts - 1) / parts;
+    parts = (K + kpb - 1) / kpb;
+    if (parts < 1) parts = 1;
+    *parts_out = parts;
+    *kpb_out = kpb;
+}
+
+size_t gemm_mfma_tn_scratch_bytes(int64_t M, int64_t N, int64_t K);
+
+size_t gemm_tn_scratch_bytes(int64_t M, int64_t N, int64_t K) {
+    int64_t parts = 0, kpb = 0;
+    naive_tn_split(K, &parts, &kpb);
+    const size_t plain = (size_t)parts * M * N * sizeof(float);
+    const size_t mfma = gemm_mfma_tn_scratch_bytes(M, N, K);
+    return plain > mfma ? plain : mfma;              // whichever kernel the operands' alignment selects
+}
+
+static void colsum_split(int64_t rows, int64_t* parts_out, int64_t* rpb_out) {
+    int64_t parts = (rows + 4095) / 4096;
+    if (parts > 512) parts = 512;
+    if (parts < 1) parts = 1;
+    const int64_t rpb = (rows + parts - 1) / parts;
+    *parts_out = (rows + rpb - 1) / rpb;
+    *rpb_out = rpb;
+}
+
+size_t colsum_scratch_bytes(int64_t rows, int32_t cols) {
+    int64_t parts = 0, rpb = 0;
+    colsum_split(rows, &parts, &rpb);
+    return (size_t)parts * cols * sizeof(float);
+}
+
 int gemm_launch(int ta, int tb, int64_t M, int64_t N, int64_t K, const float* A, int64_t lda, const float* B,
                 int64_t ldb, float* C, int64_t ldc, const float* bias, int epilogue, const float* Zprev,
                 int64_t ldzprev, hipStream_t s) {
@@ -148,14 +185,10 @@ int gemm_launch(int ta, int tb, int64_t M, int64_t N, int64_t K, const float* A,
         return GCN_OK;
     }
     // ta: split K
-    int64_t parts = (K + 1023) / 1024;
-    if (parts > 1024) parts = 1024;
-    if (parts < 1) parts = 1;
-    const int64_t kpb = (K + parts - 1) / parts;
-    parts = (K + kpb - 1) / kpb;
-    if (parts < 1) parts = 1;
+    int64_t parts = 0, kpb = 0;
+    naive_tn_split(K, &parts, &kpb);
     void* scratch = nullptr;
-    GCN_TRY(scratch_get(&scratch, (size_t)parts * M * N * sizeof(float)));
+    GCN_TRY(scratch_get(&scratch, (size_t)parts * M * N * sizeof(float), s));
     hipLaunchKernelGGL(k_gemm_tn_partial, dim3((unsigned)parts), dim3(256), 0, s, M, N, K, kpb, A, lda, B, ldb, (float*)scratch);
     GCN_LAUNCH_CHECK();
     const int64_t count = M * N;
@@ -169,13 +202,10 @@ int gemm_launch(int ta, int tb, int64_t M, int64_t N, int64_t K, const float* A,
 }
 
 int colsum_launch(int64_t rows, int32_t cols, const float* G, int64_t ldg, float* out, hipStream_t s) {
-    int64_t parts = (rows + 4095) / 4096;
-    if (parts > 512) parts = 512;
-    if (parts < 1) parts = 1;
-    const int64_t rpb = (rows + parts - 1) / parts;
-    parts = (rows + rpb - 1) / rpb;
+    int64_t parts = 0, rpb = 0;
+    colsum_split(rows, &parts, &rpb);
     void* scratch = nullptr;
-    GCN_TRY(scratch_get(&scratch, (size_t)parts * cols * sizeof(float)));
+    GCN_TRY(scratch_get(&scratch, (size_t)parts * cols * sizeof(float), s));
     hipLaunchKernelGGL(k_colsum_partial, dim3((unsigned)parts), dim3(64), 0, s, rows, cols, rpb, G, ldg, (float*)scratch);
     GCN_LAUNCH_CHECK();
     hipLaunchKernelGGL(k_reduce_partials<GCN_EPI_NONE>, dim3(nblocks(cols)), dim3(256), 0, s, (int64_t)cols, (int64_t)cols,

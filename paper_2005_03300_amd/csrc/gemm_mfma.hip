@@ -339,6 +339,63 @@ static void launch_tn(const TnArgs& args, int blocks, hipStream_t s) {
     hipLaunchKernelGGL((k_gemm_tn<MG, NT, NARROW>), dim3(blocks), dim3(64 * args.waves), 0, s, args);
 }
 
+// Launch geometry of the MFMA A^T B product (K long): which operand goes on the 64-column groups, wavefronts
+// per workgroup, split of K, partial buffers.  Returns false when the shape is left to the plain kernel.
+struct TnShape {
+    bool swap, narrow;
+    int64_t Mw, Nw, blocks, kpb;
+    int NTn, W, MG, fold;
+    size_t scratch_bytes;
+};
+
+static bool tn_shape(int64_t M, int64_t N, int64_t K, TnShape* g) {
+    if (K < 1024) return false;
+    // Put the wider of (M, N) on the 64-column groups: if N > M compute C^T = B^T A and let the
+    // reduction write it back transposed.
+    g->swap = N > M;
+    g->Mw = g->swap ? N : M;
+    g->Nw = g->swap ? M : N;
+    if (g->Nw > 32 || g->Mw > 1024) return false;        // narrow side up to 32, wide side up to 1024
+    g->NTn = (int)((g->Nw + 15) / 16);
+    g->narrow = g->Mw <= 32;
+    const int groups = (int)((g->Mw + 63) / 64);
+    // wavefronts per workgroup: one per column group up to 8, else the count in 4..8 that leaves the
+    // fewest idle slots (300 columns: 5 groups on 5 wavefronts instead of 2+1+1+1 on 4)
+    int W = 4;
+    if (!g->narrow) {
+        if (groups <= 8) W = groups < 2 ? 2 : groups;
+        else {
+            int best = 1 << 30;
+            for (int w = 4; w <= 8; ++w) {
+                const int idle = (groups + w - 1) / w * w - groups;
+                if (idle < best) { best = idle; W = w; }
+            }
+        }
+    }
+    g->W = W;
+    g->MG = g->narrow ? (int)((g->Mw + 15) / 16) : (groups + W - 1) / W;   // tiles (narrow) or column groups per wavefront
+    int64_t blocks = K / 256;                             // at least 256 rows per workgroup
+    // measured: more, shorter workgroups pay when a workgroup has five or more wavefronts (300 columns:
+    // 4.13 ms with 2048 workgroups, 3.84 ms with 8192), fewer otherwise (256 columns: 2.69 vs 2.84 ms)
+    // and when it has two or three, so that enough wavefronts exist (128 columns: 1.74 vs 1.47 ms)
+    const int64_t max_blocks = g->narrow ? 2048 : (W >= 5 ? 8192 : (W <= 3 ? 16384 / W : 2048));
+    if (blocks > max_blocks) blocks = max_blocks;
+    if (blocks < 1) blocks = 1;
+    int64_t kpb = (K + blocks - 1) / blocks;
+    kpb = (kpb + 63) & ~63ll;
+    blocks = (K + kpb - 1) / kpb;
+    g->blocks = blocks;
+    g->kpb = kpb;
+    g->fold = blocks > 64 ? 32 : 0;                       // two-stage reduction when there are many partials
+    g->scratch_bytes = (size_t)(blocks + g->fold) * g->Mw * g->Nw * sizeof(float);
+    return true;
+}
+
+size_t gemm_mfma_tn_scratch_bytes(int64_t M, int64_t N, int64_t K) {
+    TnShape g;
+    return tn_shape(M, N, K, &g) ? g.scratch_bytes : 0;
+}
+
 int gemm_mfma_launch(int ta, int tb, int64_t M, int64_t N, int64_t K, const float* A, int64_t lda, const float* B,
                      int64_t ldb, float* C, int64_t ldc, const float* bias, int epilogue, const float* Zprev,
                      int64_t ldzprev, hipStream_t s, bool* handled) {
@@ -378,45 +435,18 @@ int gemm_mfma_launch(int ta, int tb, int64_t M, int64_t N, int64_t K, const floa
         *handled = true;
         return GCN_OK;
     }
-    // ta: C = A^T B with K long.  Put the wider of (M, N) on the 64-column groups: if N > M compute
-    // C^T = B^T A and let the reduction write it back transposed.
-    if (tb || K < 1024) return GCN_OK;
-    const bool swap = N > M;
+    // ta: C = A^T B with K long
+    if (tb) return GCN_OK;
+    TnShape g;
+    if (!tn_shape(M, N, K, &g)) return GCN_OK;
+    const bool swap = g.swap, narrow = g.narrow;
     const float* Aw = swap ? B : A;
     const float* Bw = swap ? A : B;
     const int64_t ldaw = swap ? ldb : lda, ldbw = swap ? lda : ldb;
-    const int64_t Mw = swap ? N : M, Nw = swap ? M : N;
-    if (Nw > 32 || Mw > 1024) return GCN_OK;             // narrow side up to 32, wide side up to 1024
-    const int NTn = (int)((Nw + 15) / 16);
-    const bool narrow = Mw <= 32;
-    const int groups = (int)((Mw + 63) / 64);
-    // wavefronts per workgroup: one per column group up to 8, else the count in 4..8 that leaves the
-    // fewest idle slots (300 columns: 5 groups on 5 wavefronts instead of 2+1+1+1 on 4)
-    int W = 4;
-    if (!narrow) {
-        if (groups <= 8) W = groups < 2 ? 2 : groups;
-        else {
-            int best = 1 << 30;
-            for (int w = 4; w <= 8; ++w) {
-                const int idle = (groups + w - 1) / w * w - groups;
-                if (idle < best) { best = idle; W = w; }
-            }
-        }
-    }
-    const int MG = narrow ? (int)((Mw + 15) / 16) : (groups + W - 1) / W;   // tiles (narrow) or column groups per wavefront
-    int64_t blocks = K / 256;                             // at least 256 rows per workgroup
-    // measured: more, shorter workgroups pay when a workgroup has five or more wavefronts (300 columns:
-    // 4.13 ms with 2048 workgroups, 3.84 ms with 8192), fewer otherwise (256 columns: 2.69 vs 2.84 ms)
-    // and when it has two or three, so that enough wavefronts exist (128 columns: 1.74 vs 1.47 ms)
-    const int64_t max_blocks = narrow ? 2048 : (W >= 5 ? 8192 : (W <= 3 ? 16384 / W : 2048));
-    if (blocks > max_blocks) blocks = max_blocks;
-    if (blocks < 1) blocks = 1;
-    int64_t kpb = (K + blocks - 1) / blocks;
-    kpb = (kpb + 63) & ~63ll;
-    blocks = (K + kpb - 1) / kpb;
-    const int fold = blocks > 64 ? 32 : 0;               // two-stage reduction when there are many partials
+    const int64_t Mw = g.Mw, Nw = g.Nw, blocks = g.blocks, kpb = g.kpb;
+    const int NTn = g.NTn, W = g.W, MG = g.MG, fold = g.fold;
     void* scratch = nullptr;
-    GCN_TRY(scratch_get(&scratch, (size_t)(blocks + fold) * Mw * Nw * sizeof(float)));
+    GCN_TRY(scratch_get(&scratch, g.scratch_bytes, s));
     TnArgs args;
     args.K = K; args.M = (int32_t)Mw; args.N = (int32_t)Nw;
     args.A = Aw; args.lda = ldaw; args.B = Bw; args.ldb = ldbw;

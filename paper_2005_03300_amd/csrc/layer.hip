@@ -18,7 +18,7 @@ static int resolve_order(int order, int32_t f_in, int32_t f_out) {
 // (section "Graph Neural Networks"): the product can skip the stored values, which halves the
 // index/value stream.  It pays when rows are long (the pre-scaling pass over X is amortised).
 static bool use_pattern(const gcn_csr* a) {
-    const int mode = config().pattern_spmm;
+    const int mode = cfg_of(a).pattern_spmm;
     if (!a->inv_sqrt_deg || mode == 0) return false;
     return mode == 1 || a->nnz / (a->n > 0 ? a->n : 1) >= 64;
 }
@@ -37,8 +37,6 @@ static int norm_spmm(gcn_csr* a, Matrix& m, int32_t f, const float* X, int64_t l
     return spmm_launch(a, m, f, xs, f, Z, ldz, epilogue, Zprev, ldzprev, s, o);
 }
 
-// `xs`: scratch for the value-free product (n x the SpMM width) or NULL; `t_scratch` says that T is
-// a pure temporary which may be overwritten by its scaled copy.
 static int timed_gemm(int ta, int tb, int64_t M, int64_t N, int64_t K, const float* A, int64_t lda, const float* B,
                       int64_t ldb, float* C, int64_t ldc, const float* bias, int epilogue, const float* Zprev,
                       int64_t ldzprev, hipStream_t s) {
@@ -46,6 +44,8 @@ static int timed_gemm(int ta, int tb, int64_t M, int64_t N, int64_t K, const flo
     return gemm_launch(ta, tb, M, N, K, A, lda, B, ldb, C, ldc, bias, epilogue, Zprev, ldzprev, s);
 }
 
+// `xs`: scratch for the value-free product (n x the SpMM width) or NULL; `t_scratch` says that T is
+// a pure temporary which may be overwritten by its scaled copy.
 static int layer_forward_impl(gcn_csr* a, int32_t f_in, int32_t f_out, const float* Hin, int64_t ldh, const float* W,
                               const float* bias, float* Z, float* Hout, float* T, int order, int act, hipStream_t s,
                               float* xs = nullptr, bool t_scratch = false, bool t_given = false) {
@@ -107,6 +107,7 @@ static int layer_backward_impl(gcn_csr* a, int32_t f_in, int32_t f_out, const fl
 struct EpochLayout {
     std::vector<size_t> Z, H, T, G;   // byte offsets per layer index 0..L_w-1 (layer l = index + 1)
     size_t S = 0, XS = 0, total = 0;  // XS: pre-scaled SpMM operand of the value-free product
+    size_t scratch = 0, scratch_bytes = 0;   // split-K partials of the weight gradients, loss partials
     std::vector<int> order;
 };
 
@@ -131,6 +132,15 @@ static EpochLayout epoch_layout(int64_t n, int32_t L, const int32_t* dims, int o
     }
     lay.S = take(smax);
     lay.XS = take(smax);
+    // the partial sums of the reductions over n live in the caller's workspace too, so that an epoch never
+    // touches library-owned scratch (which is per stream and would have to exist before a graph capture)
+    size_t sc = loss_scratch_bytes();
+    for (int l = 0; l < L; ++l) {
+        const size_t need = gemm_tn_scratch_bytes(dims[l], dims[l + 1], n);
+        if (need > sc) sc = need;
+    }
+    lay.scratch_bytes = sc;
+    lay.scratch = take((sc + sizeof(float) - 1) / sizeof(float));
     lay.total = off;
     return lay;
 }
@@ -214,6 +224,7 @@ static int epoch_impl(gcn_csr* a, int32_t L_w, const int32_t* dims, const float*
     hipStream_t s = (hipStream_t)stream;
     char* ws = (char*)workspace;
     auto at = [&](size_t off) { return (float*)(ws + off); };
+    ScratchScope scratch_scope(ws + lay.scratch, lay.scratch_bytes);
     // With P0 = A^T H0 given, layer 1 runs in SpMM-first order on it: Z^1 = P0 W^1, Y^1 = P0^T G^1, and
     // neither direction needs a sparse product.
     auto layer_order = [&](int l) { return (l == 0 && P0) ? (int)GCN_ORDER_SPMM_FIRST : lay.order[l]; };
@@ -241,6 +252,23 @@ static int epoch_impl(gcn_csr* a, int32_t L_w, const int32_t* dims, const float*
     PhaseTimer pt(s, GCN_PHASE_OTHER);
     if (lr != 0.f)
         for (int l = 0; l < L_w; ++l) GCN_TRY(axpy_launch((int64_t)dims[l] * dims[l + 1], W[l], Y[l], lr, s));
+    return GCN_OK;
+}
+
+int gcn_epoch_prepare(gcn_csr* a, int32_t L_w, const int32_t* dims, int order, void* stream) {
+    if (!a) return fail(GCN_ERR_BADARG, "gcn_epoch_prepare: NULL matrix");
+    GCN_TRY(check_dims(a->n, L_w, dims));
+    if (order < GCN_ORDER_AUTO || order > GCN_ORDER_SPMM_FIRST) return fail(GCN_ERR_BADARG, "gcn_epoch_prepare: unknown order");
+    if (!a->has_t) return fail(GCN_ERR_NOTRANSPOSE, "gcn_epoch_prepare needs GCN_BUILD_TRANSPOSE");
+    if (a->n != a->ncols) return fail(GCN_ERR_BADARG, "gcn_epoch_prepare needs a square matrix");
+    hipStream_t s = (hipStream_t)stream;
+    for (int l = 0; l < L_w; ++l) {
+        const int ord = resolve_order(order, dims[l], dims[l + 1]);
+        const int32_t fw = ord == GCN_ORDER_GEMM_FIRST ? dims[l + 1] : dims[l];     // width of this layer's sparse products
+        GCN_TRY(spmm_prepare(a, a->At, fw, s));                                      // forward: A^T
+        if (ord == GCN_ORDER_GEMM_FIRST || l > 0) GCN_TRY(spmm_prepare(a, a->A, fw, s));   // backward: A
+    }
+    GCN_HIP_TRY(hipStreamSynchronize(s));
     return GCN_OK;
 }
 

@@ -145,6 +145,8 @@ static void dispatch_rows(int lanes, int64_t n, int32_t C, const float* Z, int64
     }
 }
 
+size_t loss_scratch_bytes() { return (size_t)LOSS_BLOCKS_MAX * sizeof(double); }
+
 }  // namespace gcn
 
 using namespace gcn;
@@ -152,7 +154,7 @@ using namespace gcn;
 static int softmax_nll_impl(int64_t n, int32_t C, const float* Z, int64_t ldz, const int32_t* labels, int64_t n_labelled,
                             float* loss, float* G, int64_t ldg, hipStream_t s) {
     void* scratch = nullptr;
-    GCN_TRY(scratch_get(&scratch, (size_t)LOSS_BLOCKS_MAX * sizeof(double)));
+    GCN_TRY(scratch_get(&scratch, loss_scratch_bytes(), s));
     double* part = (double*)scratch;
     int64_t blocks = 0;
     const float inv_m = 1.0f / (float)n_labelled;

@@ -80,6 +80,7 @@ __global__ void k_set_i64(int64_t* p, int64_t v) { *p = v; }
 void free_blocked(Blocked& b);
 
 int build_blocked(Matrix& m, int64_t nnz, int64_t cpb, hipStream_t s) {
+    count_build();
     free_blocked(m.blk);
     Blocked& b = m.blk;
     if (nnz <= 0 || cpb <= 0) return fail(GCN_ERR_BADARG, "build_blocked: empty matrix or bad block width");
@@ -283,6 +284,7 @@ __global__ void k_heavy_len(int64_t nh, const int32_t* __restrict__ rows, const 
 }
 
 int build_sweep(Matrix& m, int64_t nnz, int32_t groups, int32_t rb, int32_t heavy_th, hipStream_t s) {
+    count_build();
     free_sweep(m.swp);
     Sweep& w = m.swp;
     if (nnz <= 0 || rb <= 0 || rb > 256 || (groups != 8 && groups != 16))
@@ -475,6 +477,7 @@ __global__ void k_hub_hot_rowptr(int64_t nh, int64_t nnz_hot, const int32_t* __r
 void free_hub(Hub& h);
 
 int build_hub(Matrix& m, int64_t nnz, int64_t H, int64_t cpb, int32_t dmin, hipStream_t s) {
+    count_build();
     free_hub(m.hub);
     Hub& h = m.hub;
     h.state = -1;                                            // until everything below has succeeded

@@ -17,6 +17,7 @@
 // from there; the gathered rows of X are read with one 16-byte load per lane.
 #include <algorithm>
 #include <mutex>
+#include <string>
 
 #include "common.h"
 
@@ -49,6 +50,7 @@ struct SplitArgs {
     const float* Zprev;
     int64_t ldzprev;
     float* carry;             // [nchunks][f]
+    int lds_kb;               // host side: LDS per workgroup of the narrow kernel, padding included (settings)
 };
 
 // The index/value stream is read exactly once per product: load it with the non-temporal hint so
@@ -379,10 +381,10 @@ __global__ void k_spmm_rowwise(int64_t n, const int64_t* __restrict__ rowptr, co
 // workgroup 0.66 / 0.57 ms valued / value-free, 28 KB 0.58 / 0.55 ms, 32 KB 0.61 / 0.58 ms; plain kernel
 // on config 4 4.40 -> 4.10 ms; long rows of config 5 -0.1 ms).  The 8-group kernels (config 2: 1.44 ->
 // 1.59 ms at half occupancy) and the paired launch (config 4: 3.15 -> 3.34 ms) want it all.
-static size_t occupancy_pad(int lpr) {
+static size_t occupancy_pad(int lpr, int lds_kb) {
     if (lpr != 4) return 0;
     const size_t own = 2 * sizeof(int32_t) * WAVES_PER_BLOCK * LDS_PER_WAVE;     // s_col + s_val
-    const size_t want = (size_t)config().split_lds_kb * 1024;
+    const size_t want = (size_t)lds_kb * 1024;
     return want > own ? want - own : 0;
 }
 
@@ -395,9 +397,9 @@ static int launch_split(const SplitArgs& args, int epilogue, hipStream_t s) {
     const dim3 fgrid((unsigned)((fix_threads + 255) / 256), ytiles);
     timing_begin(s);
     switch (epilogue) {
-        case GCN_EPI_NONE: hipLaunchKernelGGL((k_spmm_split<LPR, VEC, GCN_EPI_NONE>), grid, dim3(64 * WAVES_PER_BLOCK), occupancy_pad(LPR), s, args); break;
-        case GCN_EPI_RELU: hipLaunchKernelGGL((k_spmm_split<LPR, VEC, GCN_EPI_RELU>), grid, dim3(64 * WAVES_PER_BLOCK), occupancy_pad(LPR), s, args); break;
-        default: hipLaunchKernelGGL((k_spmm_split<LPR, VEC, GCN_EPI_MASK>), grid, dim3(64 * WAVES_PER_BLOCK), occupancy_pad(LPR), s, args); break;
+        case GCN_EPI_NONE: hipLaunchKernelGGL((k_spmm_split<LPR, VEC, GCN_EPI_NONE>), grid, dim3(64 * WAVES_PER_BLOCK), occupancy_pad(LPR, args.lds_kb), s, args); break;
+        case GCN_EPI_RELU: hipLaunchKernelGGL((k_spmm_split<LPR, VEC, GCN_EPI_RELU>), grid, dim3(64 * WAVES_PER_BLOCK), occupancy_pad(LPR, args.lds_kb), s, args); break;
+        default: hipLaunchKernelGGL((k_spmm_split<LPR, VEC, GCN_EPI_MASK>), grid, dim3(64 * WAVES_PER_BLOCK), occupancy_pad(LPR, args.lds_kb), s, args); break;
     }
     timing_end(s);
     GCN_LAUNCH_CHECK();
@@ -575,15 +577,13 @@ __global__ __launch_bounds__(64) void k_spmm_sweep(SweepArgs a, int64_t first_ta
     }
 }
 
-static constexpr int SWEEP_CUS = 256;
-
 template <int LPR>
-static int launch_sweep(const SweepArgs& args, int64_t ntasks, int epilogue, hipStream_t s) {
+static int launch_sweep(const SweepArgs& args, int64_t ntasks, int sweep_waves, int epilogue, hipStream_t s) {
     constexpr int W = LPR * 4;
     const size_t lds = (size_t)args.rb * W * sizeof(float);
     const unsigned ytiles = (unsigned)((args.f + W - 1) / W);
     // tasks that are resident at once; the launches get equal shares so that the last one is not a stub
-    const int64_t cap = (int64_t)SWEEP_CUS * config().sweep_waves;
+    const int64_t cap = (int64_t)device_info().cus * sweep_waves;
     const int64_t nlaunch = (ntasks + cap - 1) / cap;
     const int64_t gen = (ntasks + nlaunch - 1) / nlaunch;
     timing_begin(s);
@@ -634,32 +634,21 @@ static int run_split(const SplitArgs& args, int epilogue, hipStream_t s, bool l2
     return launch_split<64, 1>(args, epilogue, s);
 }
 
-static int grow(float** buf, size_t* have, size_t need) {
-    if (need <= *have) return GCN_OK;
-    if (*buf) {
-        GCN_HIP_TRY(hipDeviceSynchronize());             // queued work may still use the old buffer
-        device_free(*buf);
-        *buf = nullptr;
-        *have = 0;
-    }
-    GCN_TRY(device_alloc((void**)buf, need));
-    *have = need;
-    return GCN_OK;
-}
-
 // How many column blocks to cut X into so that one block of the gathered panel stays in one L2
-// (4 MB per XCD).  Blocking costs one partial row per non-empty (block,row) pair, so it only pays
-// when rows are long compared with the number of blocks: at least `per_block` entries per partial
-// row.  When 2 MB blocks would make the partial rows shorter than that, blocks of up to 8 MB are
-// still worth it (measured on the long rows of config 5: 5.6 MB blocks beat 2 MB ones); beyond
-// that 1 (no blocking).
-static int64_t choose_blocks(int64_t nrows, int64_t ncols, int64_t nnz, int32_t f, int64_t per_block) {
-    const int forced = config().spmm_blocks;
+// (4 MB per XCD on this GPU; the size is read from the device).  Blocking costs one partial row per
+// non-empty (block,row) pair, so it only pays when rows are long compared with the number of blocks: at
+// least `per_block` entries per partial row.  When half-L2 blocks would make the partial rows shorter than
+// that, blocks of up to twice the L2 are still worth it (measured on the long rows of config 5: 5.6 MB
+// blocks beat 2 MB ones); beyond that 1 (no blocking).
+static int64_t choose_blocks(const Config& cfg, int64_t nrows, int64_t ncols, int64_t nnz, int32_t f, int64_t per_block) {
+    const int forced = cfg.spmm_blocks;
     if (forced >= 1) return forced;
+    const int64_t l2 = device_info().l2_bytes;
     const int64_t panel = f < 32 ? f : 32;
     const int64_t xbytes = ncols * panel * 4;
-    if (xbytes <= (7ll << 19)) return 1;                  // 3.5 MB: already L2-resident
-    const int64_t want = (xbytes + (2ll << 20) - 1) / (2ll << 20);
+    if (xbytes <= l2 / 8 * 7) return 1;                    // already L2-resident
+    const int64_t block = l2 / 2;
+    const int64_t want = (xbytes + block - 1) / block;
     const int64_t cap = (nnz / (nrows > 0 ? nrows : 1)) / per_block;
     if (want <= cap) return want;
     return (cap >= 2 && 4 * cap >= want) ? cap : 1;
@@ -674,17 +663,25 @@ static int run_matrix(gcn_csr* a, Matrix& mm, const int32_t* row_map, int64_t nn
         return fail(GCN_ERR_RANGE, "gcn_spmm: too many chunks for one launch");
     // carry_given: a buffer of at least nchunks * f floats that the caller of this function provides
     // (only without column blocks); otherwise the handle's own buffer, grown on demand
-    if (!carry_given) GCN_TRY(grow(&a->carry, &a->carry_bytes, (size_t)mm.nchunks * (size_t)f * sizeof(float)));
+    if (!carry_given) GCN_TRY(grow_retire(a, &a->carry, &a->carry_bytes, (size_t)mm.nchunks * (size_t)f * sizeof(float)));
     SplitArgs args;
+    args.lds_kb = cfg_of(a).split_lds_kb;
     args.nnz = nnz; args.nsub = mm.nsub; args.nchunks = mm.nchunks; args.f = f;
     args.X = X; args.ldx = ldx; args.carry = carry_given ? carry_given : a->carry;
     args.defer = nullptr;
     if (nblocks >= 2) {
         int64_t cpb = (mm.ncols + nblocks - 1) / nblocks;
         cpb = (cpb + 1023) & ~1023ll;
-        if (mm.blk.cols_per_block != cpb) GCN_TRY(build_blocked(mm, nnz, cpb, s));
+        GCN_TRY(want_blocked(mm, nnz, cpb, s));
         const Blocked& b = mm.blk;
-        GCN_TRY(grow(&a->partial, &a->partial_bytes, (size_t)b.nrows * (size_t)f * sizeof(float)));
+        GCN_TRY(grow_retire(a, &a->partial, &a->partial_bytes, (size_t)b.nrows * (size_t)f * sizeof(float)));
+        if (o.describe) {
+            char t[160];
+            snprintf(t, sizeof t, "blocked(blocks=%d,cols_per_block=%lld,partial_rows=%lld,chunks=%lld)", (int)b.nblocks,
+                     (long long)b.cols_per_block, (long long)b.nrows, (long long)mm.nchunks);
+            *o.describe += t;
+        }
+        if (o.dry) return GCN_OK;
         args.colidx = b.colidx; args.val = o.pattern ? nullptr : b.val; args.flags = b.flags; args.sub_row = b.sub_row;
         args.ne_rows = nullptr; args.rp = b.rp; args.row_scale = nullptr;     // the scale belongs to the reduced row
         args.fix_list = b.fix_list; args.n_fix = b.n_fix;
@@ -695,6 +692,12 @@ static int run_matrix(gcn_csr* a, Matrix& mm, const int32_t* row_map, int64_t nn
         if (vec4) return launch_block_reduce<4>(mm.nrows, f, b, row_map, o.row_scale, o.accumulate ? 1 : 0, a->partial, Z, ldz, epilogue, Zprev, ldzprev, s);
         return launch_block_reduce<1>(mm.nrows, f, b, row_map, o.row_scale, o.accumulate ? 1 : 0, a->partial, Z, ldz, epilogue, Zprev, ldzprev, s);
     }
+    if (o.describe) {
+        char t[96];
+        snprintf(t, sizeof t, "split(chunks=%lld)", (long long)mm.nchunks);
+        *o.describe += t;
+    }
+    if (o.dry) return GCN_OK;
     args.colidx = mm.colidx; args.val = o.pattern ? nullptr : mm.val; args.flags = mm.flags; args.sub_row = mm.sub_row;
     args.row_scale = o.row_scale;
     args.defer = o.defer;
@@ -732,10 +735,10 @@ __global__ __launch_bounds__(256) void k_pack_rows(int64_t H, int32_t lanes, con
 
 // Packed-buffer size and block width of the hub copy for operands of width f: blocks of about 2 MB
 // of the gathered panel, as many hot columns as fit `budget` bytes (a multiple of the block width).
-static void hub_shape(int64_t ncols, int32_t f, int64_t* H, int64_t* cpb) {
+static void hub_shape(const Config& cfg, int64_t ncols, int32_t f, int64_t* H, int64_t* cpb) {
     const int64_t panel = f < 32 ? f : 32;
-    *cpb = config().hub_block_cols > 0 ? config().hub_block_cols : (2ll << 20) / (panel * 4);
-    const int64_t budget = (int64_t)config().hub_mb << 20;
+    *cpb = cfg.hub_block_cols > 0 ? cfg.hub_block_cols : (device_info().l2_bytes / 2) / (panel * 4);
+    const int64_t budget = (int64_t)cfg.hub_mb << 20;
     int64_t h = budget / ((int64_t)f * 4);
     if (h > ncols) h = ncols;
     *H = h / *cpb * *cpb;
@@ -784,25 +787,22 @@ static int launch_pair(const SplitArgs& ra_args, const SplitArgs& rb_args, int e
 static int run_hub(gcn_csr* a, Matrix& m, int32_t f, const float* X, int64_t ldx, float* Z, int64_t ldz, int epilogue,
                    const float* Zprev, int64_t ldzprev, const SpmmOpt& o, hipStream_t s) {
     Hub& h = m.hub;
-    const size_t need = (size_t)h.H * (size_t)f * sizeof(float);
-    if (need > h.xhot_bytes) {
-        if (h.xhot) {
-            GCN_HIP_TRY(hipDeviceSynchronize());
-            device_free(h.xhot);
-            h.xhot = nullptr;
-            h.xhot_bytes = 0;
-        }
-        GCN_TRY(device_alloc((void**)&h.xhot, need));
-        h.xhot_bytes = need;
-    }
+    GCN_TRY(grow_retire(a, &h.xhot, &h.xhot_bytes, (size_t)h.H * (size_t)f * sizeof(float)));
     Matrix& rest = *h.rest;
     Matrix& hot = *h.hot;
     const Blocked& b = hot.blk;
     if ((rest.nchunks + hot.nchunks) / WAVES_PER_BLOCK + 16 >= (1ll << 31))
         return fail(GCN_ERR_RANGE, "gcn_spmm: too many chunks for one launch");
-    GCN_TRY(grow(&a->carry, &a->carry_bytes, (size_t)rest.nchunks * (size_t)f * sizeof(float)));
-    GCN_TRY(grow(&a->carry2, &a->carry2_bytes, (size_t)hot.nchunks * (size_t)f * sizeof(float)));
-    GCN_TRY(grow(&a->partial, &a->partial_bytes, (size_t)b.nrows * (size_t)f * sizeof(float)));
+    GCN_TRY(grow_retire(a, &a->carry, &a->carry_bytes, (size_t)rest.nchunks * (size_t)f * sizeof(float)));
+    GCN_TRY(grow_retire(a, &a->carry2, &a->carry2_bytes, (size_t)hot.nchunks * (size_t)f * sizeof(float)));
+    GCN_TRY(grow_retire(a, &a->partial, &a->partial_bytes, (size_t)b.nrows * (size_t)f * sizeof(float)));
+    if (o.describe) {
+        char t[200];
+        snprintf(t, sizeof t, "hub(hot_cols=%lld,cols_per_block=%lld,long_row>=%d,nnz_hot=%lld,nnz_rest=%lld,partial_rows=%lld)",
+                 (long long)h.H, (long long)h.cpb, (int)h.dmin, (long long)h.nnz_hot, (long long)h.nnz_rest, (long long)b.nrows);
+        *o.describe += t;
+    }
+    if (o.dry) return GCN_OK;
     const int lanes = f / 4;
     hipLaunchKernelGGL(k_pack_rows, dim3((unsigned)((h.H * lanes + 255) / 256)), dim3(256), 0, s, h.H, lanes, X, ldx,
                        h.hot_col, h.xhot);
@@ -810,6 +810,7 @@ static int run_hub(gcn_csr* a, Matrix& m, int32_t f, const float* X, int64_t ldx
     if (rest.n_ne < rest.nrows) GCN_TRY(zero_empty_rows(rest, f, Z, ldz, s));
 
     SplitArgs ar;                                  // A_rest over X, into Z
+    ar.lds_kb = cfg_of(a).split_lds_kb;
     ar.colidx = rest.colidx; ar.val = o.pattern ? nullptr : rest.val; ar.flags = rest.flags; ar.sub_row = rest.sub_row;
     ar.row_scale = o.row_scale; ar.defer = h.defer;
     ar.ne_rows = rest.ne_rows; ar.rp = rest.ne_rowptr ? rest.ne_rowptr : rest.rowptr;
@@ -817,6 +818,7 @@ static int run_hub(gcn_csr* a, Matrix& m, int32_t f, const float* X, int64_t ldx
     ar.nnz = h.nnz_rest; ar.nsub = rest.nsub; ar.nchunks = rest.nchunks; ar.f = f;
     ar.X = X; ar.ldx = ldx; ar.Z = Z; ar.ldz = ldz; ar.Zprev = Zprev; ar.ldzprev = ldzprev; ar.carry = a->carry;
     SplitArgs ah;                                  // A_hot over the packed rows, into the partial rows
+    ah.lds_kb = ar.lds_kb;
     ah.colidx = b.colidx; ah.val = o.pattern ? nullptr : b.val; ah.flags = b.flags; ah.sub_row = b.sub_row;
     ah.row_scale = nullptr; ah.defer = nullptr; ah.ne_rows = nullptr; ah.rp = b.rp;
     ah.fix_list = b.fix_list; ah.n_fix = b.n_fix;
@@ -828,19 +830,89 @@ static int run_hub(gcn_csr* a, Matrix& m, int32_t f, const float* X, int64_t ldx
                                   ldzprev, s);
 }
 
+// ---- stored orders kept per key ------------------------------------------------------------------------
+int want_blocked(Matrix& m, int64_t nnz, int64_t cpb, hipStream_t s) {
+    if (m.blk.cols_per_block == cpb) return GCN_OK;
+    if (m.blk.cols_per_block != 0) {
+        m.blk_parked.push_back(m.blk);
+        m.blk = Blocked();
+    }
+    for (size_t i = 0; i < m.blk_parked.size(); ++i)
+        if (m.blk_parked[i].cols_per_block == cpb) {
+            m.blk = m.blk_parked[i];
+            m.blk_parked.erase(m.blk_parked.begin() + (long)i);
+            return GCN_OK;
+        }
+    return build_blocked(m, nnz, cpb, s);
+}
+
+int want_sweep(Matrix& m, int64_t nnz, int32_t groups, int32_t rb, int32_t th, hipStream_t s) {
+    auto is = [&](const Sweep& w) { return w.groups == groups && w.rb == rb && w.heavy_threshold == th; };
+    if (is(m.swp)) return GCN_OK;
+    if (m.swp.groups != 0) {
+        m.swp_parked.push_back(m.swp);
+        m.swp = Sweep();
+    }
+    for (size_t i = 0; i < m.swp_parked.size(); ++i)
+        if (is(m.swp_parked[i])) {
+            m.swp = m.swp_parked[i];
+            m.swp_parked.erase(m.swp_parked.begin() + (long)i);
+            return GCN_OK;
+        }
+    return build_sweep(m, nnz, groups, rb, th, s);
+}
+
+// The hub copy for the current settings: the one in use, a parked one, or a new attempt (state 1 built,
+// -1 rejected for these settings).  A change of operand width reuses the copy.
+static int want_hub(Matrix& m, const Config& cfg, int64_t nnz, int64_t H, int64_t cpb, bool forced, hipStream_t s) {
+    auto is = [&](const Hub& h) {
+        return h.state != 0 && h.dmin == cfg.hub_dmin && h.cfg_mb == cfg.hub_mb && h.cfg_block_cols == cfg.hub_block_cols;
+    };
+    if (is(m.hub)) return GCN_OK;
+    if (m.hub.state != 0) {
+        m.hub_parked.push_back(m.hub);
+        m.hub = Hub();
+    }
+    for (size_t i = 0; i < m.hub_parked.size(); ++i)
+        if (is(m.hub_parked[i])) {
+            m.hub = m.hub_parked[i];
+            m.hub_parked.erase(m.hub_parked.begin() + (long)i);
+            return GCN_OK;
+        }
+    const int rc = build_hub(m, nnz, H, cpb, cfg.hub_dmin, s);
+    if (rc != GCN_OK) {
+        // the copy is an optimisation: without it (for instance out of memory) the plain kernel runs
+        if (forced) return rc;
+        free_hub(m.hub);
+        m.hub.state = -1;
+    }
+    m.hub.dmin = cfg.hub_dmin;
+    m.hub.cfg_mb = cfg.hub_mb;
+    m.hub.cfg_block_cols = cfg.hub_block_cols;
+    return GCN_OK;
+}
+
+static void took(gcn_csr* a, int sched) {
+    g_last_schedule = sched;
+    a->last_schedule = sched;
+}
+
 int spmm_launch(gcn_csr* a, Matrix& m, int32_t f, const float* X, int64_t ldx, float* Z, int64_t ldz,
                 int epilogue, const float* Zprev, int64_t ldzprev, hipStream_t s, const SpmmOpt& o) {
     const int64_t n = m.nrows, ncols = m.ncols, nnz = a->nnz;
+    const Config& cfg = cfg_of(a);
     if (nnz == 0) {
+        if (o.describe) *o.describe += "empty";
+        if (o.dry) return GCN_OK;
         const int64_t work = n * f;
         hipLaunchKernelGGL(k_zero_empty_rows, dim3((unsigned)((work + 255) / 256)), dim3(256), 0, s, n, m.rowptr, f, Z, ldz);
         GCN_LAUNCH_CHECK();
         return GCN_OK;
     }
-    int algo = config().spmm_algo;
+    int algo = cfg.spmm_algo;
     const bool vec4_all = (f % 4 == 0) && (ldx % 4 == 0) && (ldz % 4 == 0) && aligned16(X) && aligned16(Z) &&
                           (epilogue != GCN_EPI_MASK || ((ldzprev % 4 == 0) && aligned16(Zprev)));
-    const int64_t nblocks = choose_blocks(n, ncols, nnz, f, 24);
+    const int64_t nblocks = choose_blocks(cfg, n, ncols, nnz, f, 24);
     if (algo == 0) {
         // Column sweep when X is far beyond the caches, rows are long enough to give every task a
         // real walk over the columns, and too short for partial-row blocking; else nonzero-split.
@@ -853,66 +925,64 @@ int spmm_launch(gcn_csr* a, Matrix& m, int32_t f, const float* X, int64_t ldx, f
         algo = (huge && vec4_all && nblocks < 2 && narrow_steps) ? 3 : 2;
     }
     if (algo == 3 && !vec4_all) algo = 2;
-    if ((algo == 2 && config().spmm_algo == 0) || algo == 4) {
+    if ((algo == 2 && cfg.spmm_algo == 0) || algo == 4) {
         // Hub schedule: for operands beyond the L2s when most entries sit in long rows and hot columns
         // (decided from the matrix itself when the copy is built; a rejected shape is remembered).
         const bool forced = algo == 4;
         algo = 2;
         const int64_t panel = f < 32 ? f : 32;
         int64_t H = 0, cpb = 0;
-        hub_shape(ncols, f, &H, &cpb);
+        hub_shape(cfg, ncols, f, &H, &cpb);
         // Measured: it pays when a gathered row is narrower than a 128-byte line (packing then also puts
         // two hot rows into one line: config 4, width 16, 4.33 -> 3.15 ms) and not at 128 bytes per row
         // (config 2: 1.44 -> 1.48 ms), so the automatic choice is limited to panels below 32 floats.
         const bool eligible = vec4_all && nblocks < 2 && H >= 2 * cpb && nnz >= (forced ? 1 : (4ll << 20)) &&
                               (forced || (panel < 32 && ncols * panel * 4 > (32ll << 20)));
         if (eligible) {
-            // built once per matrix for the width of the first product that qualifies; later widths reuse it
-            const int32_t dmin = config().hub_dmin;
-            if (m.hub.state == 0 || m.hub.dmin != dmin || m.hub.cfg_mb != config().hub_mb ||
-                m.hub.cfg_block_cols != config().hub_block_cols) {
-                const int rc = build_hub(m, nnz, H, cpb, dmin, s);
-                if (rc != GCN_OK) {
-                    // the copy is an optimisation: without it (for instance out of memory) the plain kernel runs
-                    if (forced) return rc;
-                    free_hub(m.hub);
-                    m.hub.state = -1;
-                    m.hub.dmin = dmin;
-                }
-                m.hub.cfg_mb = config().hub_mb;
-                m.hub.cfg_block_cols = config().hub_block_cols;
-            }
+            // built once per matrix and settings for the width of the first product that qualifies
+            GCN_TRY(want_hub(m, cfg, nnz, H, cpb, forced, s));
             if (m.hub.state == 1) {
-                g_last_schedule = GCN_SCHED_HUB;
+                took(a, GCN_SCHED_HUB);
                 return run_hub(a, m, f, X, ldx, Z, ldz, epilogue, Zprev, ldzprev, o, s);
             }
         }
     }
     if (algo == 3) {
-        g_last_schedule = GCN_SCHED_SWEEP;
+        took(a, GCN_SCHED_SWEEP);
         const int LPRs = f <= 16 ? 4 : 8;
         const int W = LPRs * 4;
         const int32_t rb = 4096 / W;                       // 16 KB of accumulators per wavefront
-        const int32_t th = config().sweep_heavy;
-        if (m.swp.groups != 64 / LPRs || m.swp.rb != rb || m.swp.heavy_threshold != th)
-            GCN_TRY(build_sweep(m, nnz, 64 / LPRs, rb, th, s));
+        GCN_TRY(want_sweep(m, nnz, 64 / LPRs, rb, cfg.sweep_heavy, s));
         const Sweep& w = m.swp;
-        SweepArgs sa;
-        sa.colidx = w.colidx; sa.val = o.pattern ? nullptr : w.val; sa.row_scale = o.row_scale; sa.lrow = w.lrow; sa.task_base = w.task_base; sa.task_len = w.task_len; sa.task_order = w.task_order;
-        sa.n = n; sa.f = f; sa.rb = rb; sa.X = X; sa.ldx = ldx; sa.Z = Z; sa.ldz = ldz; sa.Zprev = Zprev; sa.ldzprev = ldzprev;
-        if (LPRs == 4) GCN_TRY(launch_sweep<4>(sa, w.ntasks, epilogue, s));
-        else GCN_TRY(launch_sweep<8>(sa, w.ntasks, epilogue, s));
+        if (o.describe) {
+            const int64_t cap = (int64_t)device_info().cus * cfg.sweep_waves;
+            char t[200];
+            snprintf(t, sizeof t, "sweep(entries_per_step=%d,rows_per_task=%d,long_row>%d,tasks=%lld,launches=%lld,stored=%lld)",
+                     64 / LPRs, (int)rb, (int)cfg.sweep_heavy, (long long)w.ntasks,
+                     (long long)(((w.ntasks + cap - 1) / cap) * ((f + W - 1) / W)), (long long)w.padded);
+            *o.describe += t;
+        }
+        if (!o.dry) {
+            SweepArgs sa;
+            sa.colidx = w.colidx; sa.val = o.pattern ? nullptr : w.val; sa.row_scale = o.row_scale; sa.lrow = w.lrow; sa.task_base = w.task_base; sa.task_len = w.task_len; sa.task_order = w.task_order;
+            sa.n = n; sa.f = f; sa.rb = rb; sa.X = X; sa.ldx = ldx; sa.Z = Z; sa.ldz = ldz; sa.Zprev = Zprev; sa.ldzprev = ldzprev;
+            if (LPRs == 4) GCN_TRY(launch_sweep<4>(sa, w.ntasks, cfg.sweep_waves, epilogue, s));
+            else GCN_TRY(launch_sweep<8>(sa, w.ntasks, cfg.sweep_waves, epilogue, s));
+        }
         if (w.heavy) {
             // long rows: nonzero-split kernel over the row subset; their rows are long enough for the
             // column-blocked form to pay even with many blocks
             Matrix& h = *w.heavy;
-            const int64_t hb = choose_blocks(h.nrows, ncols, w.nnz_heavy, f, 30);
+            const int64_t hb = choose_blocks(cfg, h.nrows, ncols, w.nnz_heavy, f, 30);
+            if (o.describe) *o.describe += "+long_rows:";
             GCN_TRY(run_matrix(a, h, h.ne_rows, w.nnz_heavy, hb, f, X, ldx, Z, ldz, epilogue, Zprev, ldzprev, o, s));
         }
         return GCN_OK;
     }
     if (algo == 1) {
-        g_last_schedule = GCN_SCHED_ROWWISE;
+        took(a, GCN_SCHED_ROWWISE);
+        if (o.describe) *o.describe += "rowwise";
+        if (o.dry) return GCN_OK;
         const int64_t work = n * f;
         const dim3 grid((unsigned)((work + 255) / 256));
         if (work / 256 >= (1ll << 31)) return fail(GCN_ERR_RANGE, "gcn_spmm: n*f too large for the row-wise kernel");
@@ -926,14 +996,22 @@ int spmm_launch(gcn_csr* a, Matrix& m, int32_t f, const float* X, int64_t ldx, f
         GCN_LAUNCH_CHECK();
         return GCN_OK;
     }
-    g_last_schedule = nblocks >= 2 ? GCN_SCHED_BLOCKED : GCN_SCHED_SPLIT;
-    if (nblocks < 2 && m.n_ne < n) GCN_TRY(zero_empty_rows(m, f, Z, ldz, s));
+    took(a, nblocks >= 2 ? GCN_SCHED_BLOCKED : GCN_SCHED_SPLIT);
+    if (!o.dry && nblocks < 2 && m.n_ne < n) GCN_TRY(zero_empty_rows(m, f, Z, ldz, s));
     return run_matrix(a, m, nullptr, nnz, nblocks, f, X, ldx, Z, ldz, epilogue, Zprev, ldzprev, o, s);
+}
+
+int spmm_prepare(gcn_csr* a, Matrix& m, int32_t f, hipStream_t s) {
+    SpmmOpt o;
+    o.dry = true;
+    return spmm_launch(a, m, f, nullptr, f, nullptr, f, GCN_EPI_NONE, nullptr, 0, s, o);
 }
 
 }  // namespace gcn
 
 using namespace gcn;
+
+static inline hipStream_t s_of(void* stream) { return (hipStream_t)stream; }
 
 static int check_spmm_args(const char* who, const gcn_csr* a, int trans, int32_t f, const float* X, int64_t ldx,
                            const float* Z, int64_t ldz, int epilogue, const float* Zprev, int64_t ldzprev) {
@@ -953,7 +1031,26 @@ static int check_spmm_args(const char* who, const gcn_csr* a, int trans, int32_t
 extern "C" int gcn_spmm(gcn_csr* a, int trans, int32_t f, const float* X, int64_t ldx, float* Z, int64_t ldz,
                         int epilogue, const float* Zprev, int64_t ldzprev, void* stream) {
     GCN_TRY(check_spmm_args("gcn_spmm", a, trans, f, X, ldx, Z, ldz, epilogue, Zprev, ldzprev));
+    PhaseTimer whole(s_of(stream), GCN_PHASE_SPMM);           // the whole product: every kernel it queues
     return spmm_launch(a, trans ? a->At : a->A, f, X, ldx, Z, ldz, epilogue, Zprev, ldzprev, (hipStream_t)stream);
+}
+
+extern "C" int gcn_spmm_prepare(gcn_csr* a, int trans, int32_t f, void* stream) {
+    if (!a || f <= 0) return fail(GCN_ERR_BADARG, "gcn_spmm_prepare: NULL matrix or f <= 0");
+    if (trans && !a->has_t) return fail(GCN_ERR_NOTRANSPOSE, "gcn_spmm_prepare: trans=1 needs GCN_BUILD_TRANSPOSE");
+    return spmm_prepare(a, trans ? a->At : a->A, f, (hipStream_t)stream);
+}
+
+extern "C" int gcn_spmm_describe(gcn_csr* a, int trans, int32_t f, char* out, size_t out_bytes, void* stream) {
+    if (!a || f <= 0 || !out || out_bytes == 0) return fail(GCN_ERR_BADARG, "gcn_spmm_describe: bad argument");
+    if (trans && !a->has_t) return fail(GCN_ERR_NOTRANSPOSE, "gcn_spmm_describe: trans=1 needs GCN_BUILD_TRANSPOSE");
+    std::string text;
+    SpmmOpt o;
+    o.dry = true;
+    o.describe = &text;
+    GCN_TRY(spmm_launch(a, trans ? a->At : a->A, f, nullptr, f, nullptr, f, GCN_EPI_NONE, nullptr, 0, (hipStream_t)stream, o));
+    snprintf(out, out_bytes, "%s", text.c_str());
+    return GCN_OK;
 }
 
 // ---- the product for callers that cannot allocate --------------------------------------------------------
@@ -998,7 +1095,7 @@ extern "C" int gcn_spmm_static(gcn_csr* a, int trans, int32_t f, const float* X,
     if (a->nnz == 0) return GCN_OK;
     float* carry = nullptr;
     GCN_TRY(static_scratch(&carry));
-    g_last_schedule = GCN_SCHED_SPLIT;
+    took(a, GCN_SCHED_SPLIT);
     return run_matrix(a, m, nullptr, a->nnz, 1, f, X, ldx, Z, ldz, epilogue, Zprev, ldzprev, SpmmOpt(), s, carry);
 }
 
@@ -1009,5 +1106,6 @@ extern "C" int gcn_spmm_pattern(gcn_csr* a, int trans, int32_t f, const float* X
     SpmmOpt o;
     o.pattern = true;
     o.row_scale = row_scale;
+    PhaseTimer whole(s_of(stream), GCN_PHASE_SPMM);
     return spmm_launch(a, trans ? a->At : a->A, f, X, ldx, Z, ldz, epilogue, Zprev, ldzprev, (hipStream_t)stream, o);
 }

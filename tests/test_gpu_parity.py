@@ -106,8 +106,6 @@ def test_csr_build_bit_exact(name):
 @pytest.mark.parametrize("self_loops", [True, False])
 @pytest.mark.parametrize("norm", ["sym", "none"])
 def test_directed_build_and_transpose_bit_exact(name, self_loops, norm):
-    if norm == "sym" and not self_loops:
-        pytest.skip("rows can be empty without self loops; 1/sqrt(0) is not a use case")
     a = gpu_csr(name, symmetrise=False, self_loops=self_loops, norm=norm)
     ref = oracle_csr(name, False, self_loops, norm, False)
     ref_t = oracle_csr(name, False, self_loops, norm, True)
@@ -1056,6 +1054,136 @@ def test_training_loop_with_split_follows_the_oracle():
     for l in range(len(Wd)):
         e = rel_fro(host(Wd[l]), Wfree[l])
         assert e <= 1e-4, (l, e)
+    a.close()
+
+
+# ------------------------------------------------------------------------------------------------
+# prepare calls, stored orders kept per width, per-matrix settings
+# ------------------------------------------------------------------------------------------------
+
+def test_mixed_widths_build_each_stored_order_once():
+    """A model whose sparse products alternate between widths (64 -> 32 -> 16 -> 8 through the column sweep, whose
+    stored order differs between operands of up to 16 floats and wider ones) keeps one stored order per kind:
+    gcn_epoch_prepare alone builds everything, the epochs after it build nothing."""
+    import dataclasses
+    g = G()
+    w = dataclasses.replace(synth.scaled(4, 256), dims=(64, 32, 16, 8), n_classes=8)
+    a = gpu_csr("c4s")
+    A = oracle_csr("c4s")
+    g.gcn_csr_config(a, g.CFG_SPMM_ALGO, 3)
+    g.gcn_csr_config(a, g.CFG_SWEEP_HEAVY, 64)
+    H0, y, Ws = synth.make_model_inputs(dataclass_with_n(w, A.n))
+    dims = list(w.dims)
+    Wd = [dev(x) for x in Ws]
+    Yd = [torch.empty_like(x) for x in Wd]
+    ws = torch.empty(g.gcn_epoch_workspace_bytes(A.n, dims, 0), dtype=torch.uint8, device="cuda")
+    loss = torch.zeros(1, device="cuda")
+    b0 = g.gcn_build_count()
+    g.gcn_epoch_prepare(a, dims, 0)
+    b1 = g.gcn_build_count()
+    assert b1 >= b0 + 4                                        # two kinds of sweep copy for each of A and A^T
+    assert "entries_per_step=8" in g.gcn_spmm_describe(a, 1, 32) and "entries_per_step=16" in g.gcn_spmm_describe(a, 1, 16)
+    for _ in range(2):
+        g.gcn_epoch(a, dims, dev(H0), dev(y), Wd, Yd, 0.0, loss, ws, 0)
+        torch.cuda.synchronize()
+        assert g.gcn_csr_last_spmm_schedule(a) == g.SCHED_SWEEP
+        assert g.gcn_build_count() == b1                       # nothing is built or rebuilt after prepare
+    ref, _ = oracle_epoch_same_signs(g, A, A, A.n, dims, 0, ws, H0, y, Ws)
+    assert_epoch_close(g, A.n, dims, 0, ws, loss, Yd, ref, "mixed widths")
+    a.close()
+
+
+def test_first_epoch_after_prepare_is_captured_in_a_hip_graph():
+    """After gcn_epoch_prepare the very first epoch only queues work: it is captured in a HIP graph without an
+    eager warm-up, on a stream of its own, and every replay equals an eager epoch bit for bit."""
+    g = G()
+    w = synth.scaled(3, 32)
+    a = gpu_csr("c3s")
+    A = oracle_csr("c3s")
+    H0, y, Ws = synth.make_model_inputs(dataclass_with_n(w, A.n))
+    dims = list(w.dims)
+    H0d, yd = dev(H0), dev(y)
+    Wd = [dev(x) for x in Ws]
+    Yd = [torch.empty_like(x) for x in Wd]
+    ws = torch.empty(g.gcn_epoch_workspace_bytes(A.n, dims, 0), dtype=torch.uint8, device="cuda")
+    loss = torch.zeros(1, device="cuda")
+    g.gcn_epoch_prepare(a, dims, 0)
+    builds = g.gcn_build_count()
+    side = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        g.gcn_epoch(a, dims, H0d, yd, Wd, Yd, 0.0, loss, ws, 0)
+    assert g.gcn_build_count() == builds
+    got = []
+    for rep in range(3):
+        loss.zero_()
+        ws.zero_()
+        for x in Yd:
+            x.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got.append((loss.clone(), [x.clone() for x in Yd]))
+    g.gcn_epoch(a, dims, H0d, yd, Wd, Yd, 0.0, loss, ws, 0)                  # eager, default stream
+    torch.cuda.synchronize()
+    for l0, Y0 in got:
+        assert torch.equal(l0, loss)
+        for l in range(len(Yd)):
+            assert torch.equal(Y0[l], Yd[l]), l
+    ref, _ = oracle_epoch_same_signs(g, A, A, A.n, dims, 0, ws, H0, y, Ws)
+    assert_epoch_close(g, A.n, dims, 0, ws, loss, Yd, ref, "captured first epoch")
+    a.close()
+
+
+def test_two_matrices_with_settings_of_their_own():
+    """gcn_csr_config: one matrix runs the per-element kernel, the other the nonzero-split kernel, in the same
+    process and interleaved; each reports its own schedule; the description names what ran."""
+    g = G()
+    a1, a2 = gpu_csr("c2s"), gpu_csr("c2s")
+    A = oracle_csr("c2s")
+    g.gcn_csr_config(a1, g.CFG_SPMM_ALGO, 1)
+    g.gcn_csr_config(a2, g.CFG_SPMM_ALGO, 2)
+    g.gcn_csr_config(a2, g.CFG_SPMM_BLOCKS, 1)
+    X = synth.normal_features(A.n, 16, 3)
+    want = oracle.spmm(A, X)
+    Z1, Z2 = torch.empty(A.n, 16, device="cuda"), torch.empty(A.n, 16, device="cuda")
+    for _ in range(2):
+        g.gcn_spmm(a1, 0, dev(X), Z1)
+        g.gcn_spmm(a2, 0, dev(X), Z2)
+    assert g.gcn_csr_last_spmm_schedule(a1) == g.SCHED_ROWWISE and g.gcn_csr_last_spmm_schedule(a2) == g.SCHED_SPLIT
+    assert_close(host(Z1), want, "per-element kernel")
+    assert_close(host(Z2), want, "nonzero-split kernel")
+    assert g.gcn_spmm_describe(a1, 0, 16) == "rowwise" and g.gcn_spmm_describe(a2, 0, 16).startswith("split(chunks=")
+    with pytest.raises(g.GcnError):
+        g.gcn_csr_config(a1, g.CFG_TIMING, 1)
+    a1.close()
+    a2.close()
+
+
+def test_symmetric_normalisation_with_an_empty_row_is_finite_and_consistent():
+    """Directed graph without self loops: vertices with incoming edges only have empty rows.  Stored values that
+    touch them are 0 on both sides (bit-exact build), the valued and the value-free product agree, nothing is inf."""
+    g = G()
+    n, src, dst = graph("c2s")
+    a = g.gcn_csr_create(n, dev(src), dev(dst), g.NORM_SYM | g.BUILD_TRANSPOSE)
+    ref = oracle.build_csr(n, src, dst, symmetrise=False, self_loops=False, norm="sym")
+    assert int((ref.deg == 0).sum()) > 0 and int((ref.val == 0).sum()) > 0
+    rowptr, colidx, val, deg = [host(t) for t in a.arrays(False)]
+    np.testing.assert_array_equal(colidx, ref.colidx)
+    np.testing.assert_array_equal(val.view(np.uint32), ref.val.view(np.uint32))
+    X = synth.normal_features(n, 16, 9)
+    Z = torch.empty(n, 16, device="cuda")
+    g.gcn_spmm(a, 0, dev(X), Z)
+    assert_close(host(Z), oracle.spmm(ref, X), "valued product")
+    sc = torch.empty(n, device="cuda")
+    g.gcn_csr_inv_sqrt_degrees(a, sc)
+    np.testing.assert_array_equal(host(sc), oracle.inv_sqrt_degrees(ref))
+    Xs = torch.empty(n, 16, device="cuda")
+    g.gcn_scale_rows(dev(X), sc, Xs)
+    Zp = torch.empty(n, 16, device="cuda")
+    g.gcn_spmm_pattern(a, 0, Xs, Zp, sc)
+    assert_close(host(Zp), oracle.spmm(ref, X), "value-free product")
     a.close()
 
 

@@ -26,8 +26,8 @@ def test_host_only_calls():
     assert e.value.code == -1 and "unknown config key" in str(e.value)
     g.gcn_config(g.CFG_SPMM_ALGO, 2)
     g.gcn_config(g.CFG_SPMM_ALGO, 0)
-    # workspace sizing is pure host arithmetic: sum over layers of H (last layer: Z), T, G plus the shared S
-    # and the scaled-operand buffer of the same size
+    # workspace sizing is pure host arithmetic: sum over layers of H (last layer: Z), T, G plus the shared S,
+    # the scaled-operand buffer of the same size and the region for partial sums
     n, dims = 1000, [64, 16, 8]
     want = 0
     r = lambda e: (e * 4 + 255) // 256 * 256
@@ -35,6 +35,7 @@ def test_host_only_calls():
         fo = dims[l + 1]
         want += r(n * fo) + r(n * fo) + r(n * fo)          # H (or last Z), T, G
     want += 2 * r(n * 16)
+    want += 2048 * 8            # partial sums of the reductions over n: here the loss's 2048 doubles are the largest
     assert g.gcn_epoch_workspace_bytes(n, dims, g.ORDER_GEMM_FIRST) == want
     assert g.gcn_epoch_workspace_bytes(n, [64, 0, 8], 0) == 0
 

@@ -140,6 +140,22 @@ def test_normalisation_closed_forms():
     assert np.all(np.diag(D)[1:] == np.float32(0.5))
 
 
+def test_symmetric_normalisation_of_a_vertex_without_entries_is_zero():
+    """Directed graph without self-connections: vertex 2 has incoming edges only, so its row is empty and
+    D^-1/2 (a pseudo-inverse there) scales by 0: the stored values that touch it are 0, as are the
+    per-vertex factors of the value-free product, and the two forms of the product agree."""
+    src = np.array([0, 0, 1], np.int32)
+    dst = np.array([1, 2, 2], np.int32)
+    A = oracle.build_csr(3, src, dst, symmetrise=False, self_loops=False, norm="sym")
+    assert A.deg.tolist() == [2, 1, 0] and A.colidx.tolist() == [1, 2, 2]
+    assert A.val.tolist() == [np.float32(1 / math.sqrt(2.0)), 0.0, 0.0]
+    s = oracle.inv_sqrt_degrees(A)
+    assert s.tolist() == [np.float32(1 / math.sqrt(2.0)), 1.0, 0.0]
+    X = synth.normal_features(3, 4, 5).astype(np.float64)
+    np.testing.assert_allclose(oracle.spmm_pattern(A, oracle.scale_rows(X, s), s), oracle.spmm(A, X), rtol=1e-7)
+    assert np.all(np.isfinite(oracle.spmm(A, X)))
+
+
 def test_normalised_matrix_has_sqrt_degree_eigenvector():
     # D^-1/2 (A+I) D^-1/2 sqrt(d) = D^-1/2 (A+I) 1 = D^-1/2 d = sqrt(d)
     n, src, dst = small_graph(300, 2000, 11)
