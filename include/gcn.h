@@ -80,6 +80,8 @@ extern "C" {
 #define GCN_CFG_HUB_BLOCK_COLS 9 /* hub schedule: columns per block of the packed buffer (0, default: about 2 MB of the gathered panel; a multiple of 64) */
 #define GCN_CFG_SPLIT_LDS_KB 10 /* nonzero-split kernel for operands of up to 16 floats: LDS per workgroup in KB, padding included (18..64, default 28; 18 = no padding).  Padding lowers the number of resident wavefronts, which keep 64 gathers in flight each */
 
+#define GCN_CFG_FUSED_LAST_LAYER 11 /* gcn_epoch*: when the last layer runs SpMM-first at f_in = 16 with at most 256 classes, one kernel per 16-row strip of A^T H computes the logits, the loss, G^L, the weight gradient and G^L W^T, and the n x C matrices Z^L and G^L are not written to memory.  1 (default): fused, gcn_epoch_view of the last layer then points at memory the epoch did not write; 2: fused and Z^L, G^L stored for inspection; 0: separate kernels (stored) */
+
 typedef struct gcn_csr gcn_csr; /* opaque: A (and A^T) in compressed rows, degrees, schedules */
 
 /* -------------------------------------------------------------------------------------------
@@ -288,7 +290,9 @@ size_t gcn_epoch_workspace_bytes(int64_t n, int32_t L_w, const int32_t* dims, in
 
 /* After gcn_epoch: device pointers into the workspace for layer l in [1, L_w], both n x dims[l]
  * dense, for parity checks: G = G^l; Z = Z^l for the last layer and H^l = ReLU(Z^l) for the hidden
- * layers (their Z is never stored: sigma'(Z) = [H > 0]).  BADARG if l or the workspace is bad. */
+ * layers (their Z is never stored: sigma'(Z) = [H > 0]).  For the last layer see GCN_CFG_FUSED_LAST_LAYER: with the
+ * fused last layer (the default where it applies) Z^L and G^L are stored only on request.  BADARG if l or the
+ * workspace is bad. */
 int gcn_epoch_view(int64_t n, int32_t L_w, const int32_t* dims, int order, void* workspace, int32_t l,
                    float** Z, float** G);
 

@@ -16,5 +16,5 @@ from .binding import (  # noqa: F401
     SCHED_ROWWISE, SCHED_SPLIT, SCHED_SWEEP, SCHED_HUB, SCHED_BLOCKED,
     SYMMETRISE, ADD_SELF_LOOPS, NORM_SYM, BUILD_TRANSPOSE, NORM_ROW,
     EPI_NONE, EPI_RELU, EPI_MASK, ORDER_AUTO, ORDER_GEMM_FIRST, ORDER_SPMM_FIRST, ACT_NONE, ACT_RELU,
-    CFG_SPMM_ALGO, CFG_TIMING, CFG_SPMM_BLOCKS, CFG_SWEEP_HEAVY, CFG_SWEEP_WAVES, CFG_PATTERN_SPMM, CFG_HUB_MB, CFG_HUB_DMIN, CFG_HUB_BLOCK_COLS, CFG_SPLIT_LDS_KB,
+    CFG_SPMM_ALGO, CFG_TIMING, CFG_SPMM_BLOCKS, CFG_SWEEP_HEAVY, CFG_SWEEP_WAVES, CFG_PATTERN_SPMM, CFG_HUB_MB, CFG_HUB_DMIN, CFG_HUB_BLOCK_COLS, CFG_SPLIT_LDS_KB, CFG_FUSED_LAST_LAYER,
 )

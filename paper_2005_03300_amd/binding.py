@@ -13,7 +13,7 @@ SYMMETRISE, ADD_SELF_LOOPS, NORM_SYM, BUILD_TRANSPOSE, NORM_ROW = 1, 2, 4, 8, 16
 EPI_NONE, EPI_RELU, EPI_MASK = 0, 1, 2
 ORDER_AUTO, ORDER_GEMM_FIRST, ORDER_SPMM_FIRST = 0, 1, 2
 ACT_NONE, ACT_RELU = 0, 1
-CFG_SPMM_ALGO, CFG_TIMING, CFG_SPMM_BLOCKS, CFG_SWEEP_HEAVY, CFG_SWEEP_WAVES, CFG_PATTERN_SPMM, CFG_HUB_MB, CFG_HUB_DMIN, CFG_HUB_BLOCK_COLS, CFG_SPLIT_LDS_KB = 1, 2, 3, 4, 5, 6, 7, 8, 9, 10
+CFG_SPMM_ALGO, CFG_TIMING, CFG_SPMM_BLOCKS, CFG_SWEEP_HEAVY, CFG_SWEEP_WAVES, CFG_PATTERN_SPMM, CFG_HUB_MB, CFG_HUB_DMIN, CFG_HUB_BLOCK_COLS, CFG_SPLIT_LDS_KB, CFG_FUSED_LAST_LAYER = 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11
 
 _lib = None
 

@@ -10,7 +10,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libgcn_hip.so")
-SOURCES = ["api.hip", "csr_build.hip", "schedules.hip", "spmm.hip", "dense.hip", "gemm_mfma.hip", "loss.hip", "layer.hip"]
+SOURCES = ["api.hip", "csr_build.hip", "schedules.hip", "spmm.hip", "dense.hip", "gemm_mfma.hip", "loss.hip", "layer.hip", "fused_last.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-mcode-object-version=5", "-std=c++17", "-I", os.path.join(ROOT, "include"), "-I", CSRC,
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-result",
          "-Wno-unused-command-line-argument"]

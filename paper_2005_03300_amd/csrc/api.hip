@@ -264,6 +264,10 @@ static int set_config(Config& c, int key, int value) {
             if (value < 0 || value > 2) return fail(GCN_ERR_BADARG, "GCN_CFG_PATTERN_SPMM must be 0, 1 or 2");
             c.pattern_spmm = value;
             return GCN_OK;
+        case GCN_CFG_FUSED_LAST_LAYER:
+            if (value < 0 || value > 2) return fail(GCN_ERR_BADARG, "GCN_CFG_FUSED_LAST_LAYER must be 0, 1 or 2");
+            c.fused_last = value;
+            return GCN_OK;
         case GCN_CFG_TIMING:
             if (value != 0 && value != 1) return fail(GCN_ERR_BADARG, "GCN_CFG_TIMING must be 0 or 1");
             c.timing = value;

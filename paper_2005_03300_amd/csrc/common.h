@@ -151,6 +151,7 @@ struct Config {
     int hub_block_cols = 0;      // hub schedule: columns per block (0: about 2 MB of the gathered panel)
     int hub_dmin = 64;           // hub schedule: rows with at least this many entries are long rows
     int pattern_spmm = 2;        // epoch: value-free SpMM for symmetric normalisation (0 never, 1 always, 2 by row length)
+    int fused_last = 1;          // epoch: fused last layer (0 off, 1 on without storing Z^L and G^L, 2 on and stored)
     int timing = 0;
 };
 
@@ -262,6 +263,11 @@ int grow_retire(gcn_csr* a, float** buf, size_t* have, size_t need);
 int gemm_launch(int ta, int tb, int64_t M, int64_t N, int64_t K, const float* A, int64_t lda, const float* B,
                 int64_t ldb, float* C, int64_t ldc, const float* bias, int epilogue, const float* Zprev,
                 int64_t ldzprev, hipStream_t s);
+// the fused last layer of the epoch (f_in = 16, up to 256 classes)
+bool fused_last_supported(int32_t f_in, int32_t C);
+size_t fused_last_scratch_bytes(int64_t n, int32_t C);
+int fused_last_launch(int64_t n, int32_t C, const float* T, const float* W, const int32_t* labels, int64_t n_labelled,
+                      float* loss, float* Y, float* S, float* Zout, float* Gout, void* scratch, hipStream_t s);
 int colsum_launch(int64_t rows, int32_t cols, const float* G, int64_t ldg, float* out, hipStream_t s);
 int axpy_launch(int64_t count, float* W, const float* Y, float lr, hipStream_t s);
 int relu_launch(int64_t rows, int32_t cols, const float* Z, int64_t ldz, float* H, int64_t ldh, hipStream_t s);

@@ -1,0 +1,296 @@
+// The last layer of the epoch in SpMM-first order, fused.  With T = A^T H^{L-1} (n x 16) at hand, everything
+// that follows is local to a row of T: the logits Z^L = T W^L ("Forward Propagation"), the row-wise
+// log-softmax and its loss (section "Block Two-Dimensional (2D) Algorithms" names the activation), Equation 1
+// G^L = (softmax(Z^L) - onehot(y)) / m, the weight gradient Y^L = T^T G^L (Equation 3 in this association
+// order) and the operand S = G^L (W^L)^T of Equation 2's sparse product.  One kernel does all of it per
+// 16-row strip, so the n x C matrices Z^L and G^L are never written to memory (unless the caller wants to
+// look at them): per row it reads 64 bytes of T and a label and writes 64 bytes of S.
+//
+// Matrix instruction: v_mfma_f32_16x16x4_f32 (full fp32).  Lane l supplies A[i = l%16][k = l/16] and
+// B[k = l/16][j = l%16] and holds D[i = 4*(l/16) + v][j = l%16] in element v.  Let r = l%16, g = l/16.
+// The three products are arranged so that each result is already the next one's operand:
+//   1. Z^T tiles:  A = W[k = feature][c = 16t + r], B = T[row r][k = feature]   -> the lane holds
+//      Z[row r][c = 16t + 4g + v]: a quarter of the row's logits; the softmax joins the four g by shuffles.
+//      (The k index of instruction e is 4g' + e for lane group g', so B is element e of the lane's
+//      16-byte load of T[row r][4g .. 4g+3].)
+//   2. S^T = W G^T:  A = W[feature r][c = 16t + 4g + v], B = the lane's own G[row r][16t + 4g + v]
+//      -> the lane holds S[row r][4g + v], stored with one 16-byte store.
+//   3. Y tiles += T^T G over the 16 rows of the strip: here the row index is the contraction index, which
+//      both operand layouts keep in l/16, so G goes through a 16 x 16 transposition in LDS, tile by tile.
+// Y accumulates in registers over all strips of a wavefront; the wavefronts of a workgroup are added in a fixed
+// order in LDS, the workgroups by two small kernels in a fixed order: bit-reproducible.
+#include "common.h"
+
+namespace gcn {
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+static constexpr int FUSED_BLOCKS_MAX = 2048;
+static constexpr int FUSED_FOLD = 32;
+
+struct FusedArgs {
+    int64_t n;
+    int32_t C;                // classes
+    const float* T;           // n x 16, contiguous rows, 16-byte aligned
+    const float* W;           // 16 x C row-major
+    const int32_t* labels;    // n; negative: outside the training split
+    float inv_m;              // 1 / labelled vertices
+    float* S;                 // n x 16 = G W^T, or NULL when no earlier layer needs it
+    float* Zout;              // n x C (ld C) or NULL
+    float* Gout;              // n x C (ld C) or NULL
+    float* ypart;             // [gridDim.x][16][16*NT]
+    double* lpart;            // [gridDim.x]
+};
+
+// FULL: C == 16 NT, no padding columns (their tests are compiled out)
+template <int NT, bool FULL>
+__global__ __launch_bounds__(256) void k_fused_last(FusedArgs a) {
+    constexpr int CP = 16 * NT;            // padded class count
+    constexpr int SW = CP + 4;             // row stride of Ws
+    constexpr int ST = 20;                 // row stride of Wt and of the per-wavefront tiles
+    extern __shared__ float lds[];
+    float* Ws = lds;                       // [16][SW]   W[feature][c]
+    float* Wt = Ws + 16 * SW;              // [CP][ST]   W[feature][c] stored as [c][feature]
+    float* tiles = Wt + CP * ST;           // per wavefront: Ts[16][ST], Gs[16][ST]
+    for (int idx = threadIdx.x; idx < 16 * CP; idx += 256) {
+        const int k = idx / CP, c = idx % CP;
+        const float v = c < a.C ? a.W[k * a.C + c] : 0.f;
+        Ws[k * SW + c] = v;
+        Wt[c * ST + k] = v;
+    }
+    __syncthreads();
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int r = lane & 15, g = lane >> 4;
+    float* Ts = tiles + wave * (2 * 16 * ST);
+    float* Gs = Ts + 16 * ST;
+    floatx4 yacc[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) yacc[t] = (floatx4){0.f, 0.f, 0.f, 0.f};
+    double lmine = 0.0;
+    const int64_t nstrips = (a.n + 15) / 16;
+    for (int64_t strip = (int64_t)blockIdx.x * 4 + wave; strip < nstrips; strip += (int64_t)gridDim.x * 4) {
+        const int64_t row = strip * 16 + r;
+        const bool valid = row < a.n;
+        float4 tv = make_float4(0.f, 0.f, 0.f, 0.f);
+        int32_t y = -1;
+        if (valid) {
+            tv = *reinterpret_cast<const float4*>(a.T + row * 16 + 4 * g);
+            y = a.labels[row];
+        }
+        // (The operands from W do not depend on the strip: the compiler keeps them in registers across the
+        // loop, 128 of them at 256 classes, which leaves one wavefront per SIMD; forcing two by re-reading them
+        // from LDS made the register allocator spill, so this is the faster form.)
+        const bool labelled = y >= 0;
+        const int yc = y < 0 ? 0 : (y >= a.C ? a.C - 1 : y);       // labels >= C are the caller's error; stay in bounds
+        *reinterpret_cast<float4*>(Ts + r * ST + 4 * g) = tv;
+        const float te[4] = {tv.x, tv.y, tv.z, tv.w};
+
+        // 1. logits: the lane gets Z[row r][16t + 4g + v]
+        floatx4 z[NT];
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            z[t] = (floatx4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                z[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(Ws[(4 * g + e) * SW + 16 * t + r], te[e], z[t], 0, 0, 0);
+        }
+        if (a.Zout && valid) {
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int c = 16 * t + 4 * g + v;
+                    if (FULL || c < a.C) a.Zout[row * a.C + c] = z[t][v];
+                }
+        }
+        // row-wise log-softmax over the C real columns (padding columns are left out)
+        float m = -INFINITY;
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+                if (FULL || 16 * t + 4 * g + v < a.C) m = fmaxf(m, z[t][v]);
+        m = fmaxf(m, __shfl_xor(m, 16, 64));
+        m = fmaxf(m, __shfl_xor(m, 32, 64));
+        // e = exp(z - max) is computed once per logit and reused: softmax = e / sum(e); the lane that holds
+        // column y keeps z_y for the loss
+        float ssum = 0.f, zy = 0.f;
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int c = 16 * t + 4 * g + v;
+                const float zv = z[t][v];
+                zy = c == yc ? zv : zy;
+                const float e = (FULL || c < a.C) ? __expf(zv - m) : 0.f;
+                ssum += e;
+                z[t][v] = e;
+            }
+        ssum += __shfl_xor(ssum, 16, 64);
+        ssum += __shfl_xor(ssum, 32, 64);
+        const float lse = m + logf(ssum);
+        if (labelled && yc >= 4 * g && ((yc - 4 * g) & 15) < 4) lmine += (double)lse - (double)zy;   // column y is this lane's
+        // Equation 1 for this loss
+        const float scale = labelled ? a.inv_m / ssum : 0.f;
+        const float minus = labelled ? a.inv_m : 0.f;
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int c = 16 * t + 4 * g + v;
+                z[t][v] = z[t][v] * scale - (c == yc ? minus : 0.f);
+            }
+        if (a.Gout && valid) {
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int c = 16 * t + 4 * g + v;
+                    if (FULL || c < a.C) a.Gout[row * a.C + c] = z[t][v];
+                }
+        }
+        // 2. S = G W^T: the lane gets S[row r][4g + v]
+        if (a.S) {
+            floatx4 sacc[4];                       // four independent chains, joined at the end
+#pragma unroll
+            for (int v = 0; v < 4; ++v) sacc[v] = (floatx4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+                    sacc[v] = __builtin_amdgcn_mfma_f32_16x16x4f32(Wt[(16 * t + 4 * g + v) * ST + r], z[t][v], sacc[v], 0, 0, 0);
+            }
+            const floatx4 sum = (sacc[0] + sacc[1]) + (sacc[2] + sacc[3]);
+            if (valid) *reinterpret_cast<float4*>(a.S + row * 16 + 4 * g) = make_float4(sum[0], sum[1], sum[2], sum[3]);
+        }
+        // 3. Y += T^T G, tile by tile through a transposition in this wavefront's LDS (its LDS operations
+        //    complete in program order; the barriers only keep the compiler from reordering them)
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            *reinterpret_cast<float4*>(Gs + r * ST + 4 * g) = make_float4(z[t][0], z[t][1], z[t][2], z[t][3]);
+            __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) {
+                const int rs = 4 * kk + g;         // the strip's row this lane contributes to instruction kk
+                yacc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(Ts[rs * ST + r], Gs[rs * ST + r], yacc[t], 0, 0, 0);
+            }
+            __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+        }
+    }
+
+    // the workgroup's Y: wavefronts added in order 0, 1, 2, 3 in LDS (the lane holds Y[4g + v][16t + r])
+    __syncthreads();
+    float* Yr = Ws;
+    for (int w = 0; w < 4; ++w) {
+        if (wave == w) {
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int idx = (4 * g + v) * SW + 16 * t + r;
+                    Yr[idx] = (w == 0 ? 0.f : Yr[idx]) + yacc[t][v];
+                }
+        }
+        __syncthreads();
+    }
+    float* yp = a.ypart + (size_t)blockIdx.x * 16 * CP;
+    for (int idx = threadIdx.x; idx < 16 * CP; idx += 256) yp[idx] = Yr[(idx / CP) * SW + idx % CP];
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) lmine += __shfl_xor(lmine, d, 64);
+    __shared__ double s_w[4];
+    if (lane == 0) s_w[wave] = lmine;
+    __syncthreads();
+    if (threadIdx.x == 0) a.lpart[blockIdx.x] = (s_w[0] + s_w[1]) + (s_w[2] + s_w[3]);
+}
+
+// folded[j][e] = sum over the workgroups b = j, j + FOLD, j + 2 FOLD, ... of part[b][e], in that order
+__global__ __launch_bounds__(256) void k_fused_fold(int count, int blocks, const float* __restrict__ part,
+                                                    float* __restrict__ folded) {
+    const int e = blockIdx.x * 256 + threadIdx.x;
+    const int j = blockIdx.y;
+    if (e >= count) return;
+    float acc = 0.f;
+    for (int b = j; b < blocks; b += FUSED_FOLD) acc += part[(size_t)b * count + e];
+    folded[(size_t)j * count + e] = acc;
+}
+
+// Y[k][c] = sum over j of folded[j][k][c] for the C real columns
+__global__ __launch_bounds__(256) void k_fused_y(int C, int CP, int parts, const float* __restrict__ folded,
+                                                 float* __restrict__ Y) {
+    const int e = blockIdx.x * 256 + threadIdx.x;
+    if (e >= 16 * C) return;
+    const int k = e / C, c = e % C;
+    float acc = 0.f;
+    for (int j = 0; j < parts; ++j) acc += folded[(size_t)j * 16 * CP + k * CP + c];
+    Y[k * C + c] = acc;
+}
+
+int loss_final_launch(int64_t parts, const double* part, double inv_n, float* loss, hipStream_t s);
+
+static int fused_nt(int32_t C) {
+    const int need = (C + 15) / 16;
+    const int have[6] = {1, 2, 3, 4, 8, 16};
+    for (int i = 0; i < 6; ++i)
+        if (have[i] >= need) return have[i];
+    return 0;
+}
+
+static int64_t fused_blocks(int64_t n) {
+    int64_t blocks = ((n + 15) / 16 + 3) / 4;
+    return blocks > FUSED_BLOCKS_MAX ? FUSED_BLOCKS_MAX : (blocks < 1 ? 1 : blocks);
+}
+
+bool fused_last_supported(int32_t f_in, int32_t C) { return f_in == 16 && C >= 1 && fused_nt(C) != 0; }
+
+size_t fused_last_scratch_bytes(int64_t n, int32_t C) {
+    const int NT = fused_nt(C);
+    if (!NT) return 0;
+    const size_t per = (size_t)16 * 16 * NT * sizeof(float);
+    return (size_t)(fused_blocks(n) + FUSED_FOLD) * per + (size_t)FUSED_BLOCKS_MAX * sizeof(double);
+}
+
+template <int NT>
+static void launch_fused(const FusedArgs& a, int64_t blocks, hipStream_t s) {
+    const size_t lds = (size_t)(16 * (16 * NT + 4) + 16 * NT * 20 + 4 * 2 * 16 * 20) * sizeof(float);
+    // (a variant with the padding tests compiled out for C == 16 NT made the register allocator spill: not used)
+    hipLaunchKernelGGL((k_fused_last<NT, false>), dim3((unsigned)blocks), dim3(256), lds, s, a);
+}
+
+// T: n x 16 contiguous; W: 16 x C; Y: 16 x C; S: n x 16 or NULL; Zout / Gout: n x C or NULL; scratch: at
+// least fused_last_scratch_bytes(n, C).
+int fused_last_launch(int64_t n, int32_t C, const float* T, const float* W, const int32_t* labels, int64_t n_labelled,
+                      float* loss, float* Y, float* S, float* Zout, float* Gout, void* scratch, hipStream_t s) {
+    const int NT = fused_nt(C);
+    if (!NT) return fail(GCN_ERR_BADARG, "fused last layer: more than 256 classes");
+    if (((uintptr_t)T & 15u) || (S && ((uintptr_t)S & 15u))) return fail(GCN_ERR_BADARG, "fused last layer: unaligned operand");
+    const int64_t blocks = fused_blocks(n);
+    const int count = 16 * 16 * NT;
+    FusedArgs a;
+    a.n = n; a.C = C; a.T = T; a.W = W; a.labels = labels; a.inv_m = 1.0f / (float)n_labelled;
+    a.S = S; a.Zout = Zout; a.Gout = Gout;
+    a.ypart = (float*)scratch;
+    float* folded = a.ypart + (size_t)blocks * count;
+    a.lpart = (double*)(folded + (size_t)FUSED_FOLD * count);
+    switch (NT) {
+        case 1: launch_fused<1>(a, blocks, s); break;
+        case 2: launch_fused<2>(a, blocks, s); break;
+        case 3: launch_fused<3>(a, blocks, s); break;
+        case 4: launch_fused<4>(a, blocks, s); break;
+        case 8: launch_fused<8>(a, blocks, s); break;
+        default: launch_fused<16>(a, blocks, s); break;
+    }
+    GCN_LAUNCH_CHECK();
+    const int parts = blocks < FUSED_FOLD ? (int)blocks : FUSED_FOLD;
+    hipLaunchKernelGGL(k_fused_fold, dim3((unsigned)((count + 255) / 256), (unsigned)parts), dim3(256), 0, s, count,
+                       (int)blocks, (const float*)a.ypart, folded);
+    GCN_LAUNCH_CHECK();
+    hipLaunchKernelGGL(k_fused_y, dim3((unsigned)((16 * C + 255) / 256)), dim3(256), 0, s, (int)C, 16 * NT, parts,
+                       (const float*)folded, Y);
+    GCN_LAUNCH_CHECK();
+    return loss_final_launch(blocks, a.lpart, 1.0 / (double)n_labelled, loss, s);
+}
+
+}  // namespace gcn

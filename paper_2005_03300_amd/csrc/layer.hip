@@ -139,6 +139,10 @@ static EpochLayout epoch_layout(int64_t n, int32_t L, const int32_t* dims, int o
         const size_t need = gemm_tn_scratch_bytes(dims[l], dims[l + 1], n);
         if (need > sc) sc = need;
     }
+    if (fused_last_supported(dims[L - 1], dims[L])) {
+        const size_t need = fused_last_scratch_bytes(n, dims[L]);
+        if (need > sc) sc = need;
+    }
     lay.scratch_bytes = sc;
     lay.scratch = take((sc + sizeof(float) - 1) / sizeof(float));
     lay.total = off;
@@ -230,20 +234,44 @@ static int epoch_impl(gcn_csr* a, int32_t L_w, const int32_t* dims, const float*
     auto layer_order = [&](int l) { return (l == 0 && P0) ? (int)GCN_ORDER_SPMM_FIRST : lay.order[l]; };
     auto layer_T = [&](int l) { return (l == 0 && P0) ? const_cast<float*>(P0) : at(lay.T[l]); };
 
+    // Last layer in SpMM-first order at hidden width 16: logits, loss, Equation 1, the weight gradient and
+    // the operand of Equation 2's sparse product come from one kernel per 16-row strip of T = A^T H^{L-1}.
+    const int last = L_w - 1;
+    const int fuse_mode = cfg_of(a).fused_last;
+    const bool fuse = fuse_mode != 0 && layer_order(last) == GCN_ORDER_SPMM_FIRST &&
+                      fused_last_supported(dims[last], dims[L_w]);
     const float* Hin = H0;
     for (int l = 0; l < L_w; ++l) {
-        const bool last = (l + 1 == L_w);
+        const bool is_last = (l == last);
+        if (is_last && fuse) {
+            if (!(l == 0 && P0))
+                GCN_TRY(norm_spmm(a, a->At, dims[l], Hin, dims[l], at(lay.XS), layer_T(l), dims[l], GCN_EPI_NONE, nullptr, 0, s));
+            break;
+        }
         GCN_TRY(layer_forward_impl(a, dims[l], dims[l + 1], Hin, dims[l], W[l], nullptr, at(lay.Z[l]),
-                                   last ? nullptr : at(lay.Z[l]), layer_T(l), layer_order(l),
-                                   last ? GCN_ACT_NONE : GCN_ACT_RELU, s, at(lay.XS), true, l == 0 && P0));
+                                   is_last ? nullptr : at(lay.Z[l]), layer_T(l), layer_order(l),
+                                   is_last ? GCN_ACT_NONE : GCN_ACT_RELU, s, at(lay.XS), true, l == 0 && P0));
         Hin = at(lay.H[l]);
     }
-    {
+    if (fuse) {
+        PhaseTimer pt(s, GCN_PHASE_GEMM);
+        const bool keep = fuse_mode == 2;
+        GCN_TRY(fused_last_launch(n, dims[L_w], layer_T(last), W[last], labels, n_labelled, loss, Y[last],
+                                  last > 0 ? at(lay.S) : nullptr, keep ? at(lay.Z[last]) : nullptr,
+                                  keep ? at(lay.G[last]) : nullptr, ws + lay.scratch, s));
+    } else {
         PhaseTimer pt(s, GCN_PHASE_OTHER);
         GCN_TRY(gcn_softmax_nll_masked(n, dims[L_w], at(lay.Z[L_w - 1]), dims[L_w], labels, n_labelled, loss,
                                        at(lay.G[L_w - 1]), dims[L_w], stream));
     }
     for (int l = L_w - 1; l >= 0; --l) {
+        if (l == last && fuse) {
+            // Y^L and S = G^L (W^L)^T are done; what is left of Equation 2 is the sparse product
+            if (l > 0)
+                GCN_TRY(norm_spmm(a, a->A, dims[l], at(lay.S), dims[l], at(lay.S), at(lay.G[l - 1]), dims[l], GCN_EPI_MASK,
+                                  at(lay.Z[l - 1]), dims[l], s));
+            continue;
+        }
         const float* Hl = l > 0 ? at(lay.H[l - 1]) : H0;
         GCN_TRY(layer_backward_impl(a, dims[l], dims[l + 1], Hl, dims[l], l > 0 ? at(lay.Z[l - 1]) : nullptr, W[l],
                                     at(lay.G[l]), layer_T(l), at(lay.S), Y[l], nullptr, l > 0 ? at(lay.G[l - 1]) : nullptr,

@@ -145,6 +145,12 @@ static void dispatch_rows(int lanes, int64_t n, int32_t C, const float* Z, int64
     }
 }
 
+int loss_final_launch(int64_t parts, const double* part, double inv_n, float* loss, hipStream_t s) {
+    hipLaunchKernelGGL(k_loss_final, dim3(1), dim3(256), 0, s, parts, part, inv_n, loss);
+    GCN_LAUNCH_CHECK();
+    return GCN_OK;
+}
+
 size_t loss_scratch_bytes() { return (size_t)LOSS_BLOCKS_MAX * sizeof(double); }
 
 }  // namespace gcn

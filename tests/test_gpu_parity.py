@@ -24,6 +24,16 @@ def G():
     return g
 
 
+@pytest.fixture(autouse=True)
+def _store_last_layer_logits():
+    """The parity tests read Z^L and G^L through gcn_epoch_view, so the fused last layer stores them here (mode 2);
+    the tests of the modes themselves and the full-size epochs set their own mode per matrix."""
+    g = G()
+    g.gcn_config(g.CFG_FUSED_LAST_LAYER, 2)
+    yield
+    g.gcn_config(g.CFG_FUSED_LAST_LAYER, 1)
+
+
 def flags_all():
     g = G()
     return g.SYMMETRISE | g.ADD_SELF_LOOPS | g.NORM_SYM | g.BUILD_TRANSPOSE
@@ -794,13 +804,17 @@ def oracle_epoch_same_signs(g, A, At, n, dims, order, ws, H0, y, Ws, lr=0.0):
     return ref, flips
 
 
-def assert_epoch_close(g, n, dims, order, ws, loss, Yd, ref, what=""):
-    """Loss, every weight gradient, the last layer's Z and every G^l of a GPU epoch against `ref`: 1e-4."""
+def assert_epoch_close(g, n, dims, order, ws, loss, Yd, ref, what="", last_stored=True):
+    """Loss, every weight gradient, the last layer's Z and every G^l of a GPU epoch against `ref`: 1e-4.
+    last_stored=False: the fused last layer did not write Z^L and G^L (they are covered through the loss, the
+    weight gradients and G^{L-1}, which all depend on them)."""
     e = abs(loss.item() - ref["loss"]) / abs(ref["loss"])
     assert e <= 1e-4, (what, "loss", e)
     for l in range(len(dims) - 1):
         e = rel_fro(host(Yd[l]), ref["Y"][l])
         assert e <= 1e-4, (what, "Y", l, e)
+        if l + 2 == len(dims) and not last_stored:
+            continue
         Zl, Gl = g.gcn_epoch_view(n, dims, order, ws, l + 1)      # hidden layers store H = ReLU(Z)
         e = rel_fro(host(Zl), ref["Z"][l] if l + 2 == len(dims) else ref["H"][l + 1])
         assert e <= 1e-4, (what, "Z/H", l, e)
@@ -842,6 +856,44 @@ def test_epoch_scaled_configs_parity(name, cfg, shrink):
     w = synth.scaled(cfg, shrink)
     g, a, A, dims, Wd, Yd, ws, loss, ref, _ = run_epoch(name, w, 0)
     assert_epoch_close(g, A.n, dims, 0, ws, loss, Yd, ref, name)
+    a.close()
+
+
+@pytest.mark.parametrize("mode", [0, 1, 2])
+@pytest.mark.parametrize("classes", [5, 16, 24, 41, 100, 256])
+def test_epoch_fused_last_layer_modes(mode, classes):
+    """The last layer in SpMM-first order at hidden width 16 (16 -> C): separate kernels (0), fused without
+    storing Z^L / G^L (1), fused and stored (2), for class counts around the 16-column tiles, with a training
+    split so that unlabelled rows are covered."""
+    import dataclasses
+    g = G()
+    w = dataclasses.replace(synth.scaled(4, 256), dims=(48, 16, 16, classes), n_classes=classes)
+    a = gpu_csr("c4s")
+    A = oracle_csr("c4s")
+    g.gcn_csr_config(a, g.CFG_FUSED_LAST_LAYER, mode)
+    H0, y, Ws = synth.make_model_inputs(dataclass_with_n(w, A.n))
+    y = y.copy()
+    y[synth.labels(A.n, 4, 77) == 0] = -1
+    m = int((y >= 0).sum())
+    dims = list(w.dims)
+    Wd = [dev(x) for x in Ws]
+    Yd = [torch.empty_like(x) for x in Wd]
+    ws = torch.full((g.gcn_epoch_workspace_bytes(A.n, dims, 0),), 0xff, dtype=torch.uint8, device="cuda")
+    loss = torch.zeros(1, device="cuda")
+    g.gcn_epoch_masked(a, dims, dev(H0), dev(y), m, Wd, Yd, 0.0, loss, ws, 0)
+    torch.cuda.synchronize()
+    ref, _ = oracle_epoch_same_signs(g, A, A, A.n, dims, 0, ws, H0, y, Ws)
+    assert_epoch_close(g, A.n, dims, 0, ws, loss, Yd, ref, f"fused mode {mode}, {classes} classes", last_stored=mode != 1)
+    a.close()
+
+
+def test_epoch_fused_last_layer_as_the_only_layer():
+    """One weight matrix (16 -> 40): the fused kernel is the whole dense part and no earlier layer needs G W^T."""
+    import dataclasses
+    g = G()
+    w = dataclasses.replace(synth.CONFIGS[1], dims=(16, 40), n_classes=40, features="normal")
+    _, a, A, dims, Wd, Yd, ws, loss, ref, _ = run_epoch("c1", w, 0)
+    assert_epoch_close(g, A.n, dims, 0, ws, loss, Yd, ref, "single layer")
     a.close()
 
 
@@ -1382,6 +1434,7 @@ def test_epoch_full_size_configs_4_and_5_against_the_oracle(cfg):
     w = synth.CONFIGS[cfg]
     n, src, dst = big_graph(cfg)
     a = g.gcn_csr_create(n, dev(src), dev(dst), flags_all())
+    g.gcn_csr_config(a, g.CFG_FUSED_LAST_LAYER, 1)             # as the benchmark runs it: Z^L and G^L are not stored
     rowptr, colidx, val, deg = [host(x) for x in a.views(False)]
     A = oracle.Csr(n=n, rowptr=rowptr, colidx=colidx, val=val, deg=deg)
     H0, y, Ws = synth.make_model_inputs(w)
@@ -1395,7 +1448,7 @@ def test_epoch_full_size_configs_4_and_5_against_the_oracle(cfg):
     assert g.gcn_last_spmm_schedule() == (g.SCHED_HUB if cfg == 4 else g.SCHED_SWEEP)
     ref, flips = oracle_epoch_same_signs(g, A, A, n, dims, 0, ws, H0, y, Ws)     # A == A^T (checked bit for bit elsewhere)
     assert flips <= 64, flips
-    assert_epoch_close(g, n, dims, 0, ws, loss, Yd, ref, f"config {cfg} at full size")
+    assert_epoch_close(g, n, dims, 0, ws, loss, Yd, ref, f"config {cfg} at full size", last_stored=False)
     a.close()
 
 
