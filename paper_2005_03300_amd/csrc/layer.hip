@@ -139,7 +139,8 @@ static EpochLayout epoch_layout(int64_t n, int32_t L, const int32_t* dims, int o
         const size_t need = gemm_tn_scratch_bytes(dims[l], dims[l + 1], n);
         if (need > sc) sc = need;
     }
-    if (fused_last_supported(dims[L - 1], dims[L])) {
+    // the fused last layer (SpMM-first order; a single layer can be put into that order by the pre-aggregated epoch)
+    if ((lay.order[L - 1] == GCN_ORDER_SPMM_FIRST || L == 1) && fused_last_supported(dims[L - 1], dims[L])) {
         const size_t need = fused_last_scratch_bytes(n, dims[L]);
         if (need > sc) sc = need;
     }
