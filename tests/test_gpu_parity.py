@@ -611,7 +611,9 @@ def test_spmm_pattern_directed_transpose_and_errors():
 # ------------------------------------------------------------------------------------------------
 
 @pytest.mark.parametrize("M,K,N", [(5000, 602, 16), (4097, 300, 16), (3000, 16, 41), (2049, 16, 256),
-                                   (1000, 64, 16), (777, 128, 16), (33, 7, 5), (1, 1, 1), (4096, 16, 16)])
+                                   (1000, 64, 16), (777, 128, 16), (33, 7, 5), (1, 1, 1), (4096, 16, 16),
+                                   # rows that are not whole 128-byte lines: strips staged through LDS
+                                   (70001, 300, 16), (4100, 100, 16), (4111, 204, 32), (5003, 76, 24), (4096, 304, 16)])
 def test_gemm_nn_parity(M, K, N):
     g = G()
     A = synth.normal_features(M, K, 21)
@@ -625,7 +627,8 @@ def test_gemm_nn_parity(M, K, N):
     assert_close(host(Cd), want, f"NN+bias+relu {M}x{K}x{N}")
 
 
-@pytest.mark.parametrize("M,K,N", [(5000, 16, 602), (3000, 41, 16), (2049, 16, 16), (1500, 256, 16), (33, 7, 5)])
+@pytest.mark.parametrize("M,K,N", [(5000, 16, 602), (3000, 41, 16), (2049, 16, 16), (1500, 256, 16), (33, 7, 5),
+                                   (4500, 300, 16), (4200, 76, 32)])
 def test_gemm_nt_mask_parity(M, K, N):
     """R = S W^T (Hadamard) sigma'(Zprev): op(B) = W^T with W stored N x K."""
     g = G()
