@@ -37,27 +37,26 @@ HBM_PEAK_GBPS = 8000.0
 # reports another schedule carries traffic = null instead of a stale figure.
 MEASURED_TRAFFIC = {
     ("rmat20_spmm_f128", 128): {
-        "bytes": int((4.56897e6 * 1.9999 + 555976 * 1.0) * 1024),
-        "kernels": "1 x k_spmm_split<8,4> over 4 panels of 32 columns (the fix-up kernel, 0.5 % of the bytes, not counted)",
+        "bytes": 10045335483,
+        "kernels": "k_spmm_split<8,4> over 4 panels of 32 columns + k_spmm_fixup",
         "schedule": "split(chunks=63376)",
         "profile": "profiles/spmm_split_rmat20_f128.txt"},
     ("chunglu_reddit_gcn_602_16_16_41", 16): {
-        "bytes": int((525976 * 1.9967 + 142071 * 1.0) * 1024),
-        "kernels": "1 x k_spmm_split<4,4> over the column-blocked copy",
-        "schedule": None,
+        "bytes": 1462660523,
+        "kernels": "k_spmm_split<4,4> over the column-blocked copy + k_spmm_fixup + k_block_reduce",
+        "schedule": "blocked(blocks=8,cols_per_block=29696,partial_rows=1863720,chunks=224269)",
         "profile": "profiles/spmm_blocked_chunglu_reddit_f16.txt"},
     ("rmat_amazon_gcn_300_16_16_24", 16): {
-        "bytes": int((8.49107e6 * 1.9999 + 1.6237e6 * 1.0) * 1024),
-        "kernels": "1 x k_spmm_split_pair<4,4> (paired launch of the hub schedule)",
-        "schedule": None,
+        "bytes": 20042035304,
+        "kernels": "k_pack_rows + k_spmm_split_pair<4,4> (paired launch of the hub schedule) + 2 x k_spmm_fixup + k_block_reduce",
+        "schedule": "hub(hot_cols=524288,cols_per_block=32768,long_row>=64,nnz_hot=148858651,nnz_rest=96949372,partial_rows=7701691)",
         "profile": "profiles/spmm_hub_rmat_amazon_f16.txt"},
     ("chunglu_protein_gcn_128_16_16_256", 16): {
-        "bytes": int(((15 * 2.26363e6 + 7.37308e6 + 159128 + 515303) * 1.9999
-                      + (15 * 36439.8 + 950387 + 45046.2 + 7828.04) * 1.0) * 1024),
+        "bytes": 87680817238,
         "kernels": "15 x k_spmm_sweep<4> + k_spmm_split<4,4> (column-blocked, long rows) + k_spmm_fixup + k_block_reduce",
         "schedule": "sweep(entries_per_step=16,rows_per_task=256,long_row>1024,tasks=34163,launches=15,stored=936862448)"
                     "+long_rows:blocked(blocks=101,cols_per_block=87040,partial_rows=12649811,chunks=745738)",
-        "profile": "profiles/spmm_sweep_chunglu_protein_f16.txt"},
+        "profile": "profiles/spmm_sweep_chunglu_protein_f16_default_command.txt"},
 }
 
 # kernels inside the library's event bracket of one product, by the schedule the library reports
