@@ -1290,6 +1290,7 @@ def test_epoch_full_size_config3_against_the_oracle():
     a = g.gcn_csr_create(n, dev(src), dev(dst), flags_all())
     del src, dst
     assert a.nnz == A.nnz
+    assert_traffic_figure_is_current(g, a, w, 16)
     rowptr, colidx, val, deg = a.arrays(True)                 # the transposed copy: the forward products read it
     assert torch.equal(rowptr.cpu(), torch.from_numpy(A.rowptr))
     assert torch.equal(colidx.cpu(), torch.from_numpy(A.colidx))
@@ -1308,6 +1309,16 @@ def test_epoch_full_size_config3_against_the_oracle():
     assert flips <= 16, flips            # of 7.5 M hidden pre-activations a handful are zero to rounding
     assert_epoch_close(g, n, dims, 0, ws, loss, Yd, ref, "config 3 at full size")
     a.close()
+
+
+def assert_traffic_figure_is_current(g, a, w, f):
+    """The benchmark reports a stored counter measurement as roofline.traffic; it names the schedule it was taken
+    on, and the library must still describe the same schedule for this workload (else: measure again)."""
+    import bench
+    meas = bench.MEASURED_TRAFFIC[(w.name, f)]
+    now = g.gcn_spmm_describe(a, 0, f)
+    assert meas["schedule"] == now, (meas["schedule"], now)
+    assert os.path.exists(os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), meas["profile"]))
 
 
 @functools.lru_cache(maxsize=2)
@@ -1354,6 +1365,7 @@ def test_full_size_config4_hub_schedule_properties():
     g = G()
     n, src, dst = big_graph(4)
     a = g.gcn_csr_create(n, dev(src), dev(dst), flags_all())
+    assert_traffic_figure_is_current(g, a, synth.CONFIGS[4], 16)
     X = torch.rand(n, 16, device="cuda") * 2 - 1
     Z = torch.full((n, 16), float("nan"), device="cuda")
     Z2 = torch.empty_like(Z)
@@ -1410,6 +1422,7 @@ def test_full_size_config5_column_sweep_against_the_oracle_rows():
     g = G()
     n, src, dst = big_graph(5)
     a = g.gcn_csr_create(n, dev(src), dev(dst), flags_all())
+    assert_traffic_figure_is_current(g, a, synth.CONFIGS[5], 16)
     X = torch.rand(n, 16, device="cuda") * 2 - 1
     Z = torch.full((n, 16), float("nan"), device="cuda")
     Z2 = torch.empty_like(Z)
