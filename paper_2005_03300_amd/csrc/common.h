@@ -260,14 +260,16 @@ int spmm_prepare(gcn_csr* a, Matrix& m, int32_t f, hipStream_t s);
 // grows one of the handle's buffers; the replaced buffer is retired, not freed
 int grow_retire(gcn_csr* a, float** buf, size_t* have, size_t need);
 
+// `row_scale` (optional): row i of C is multiplied by row_scale[i] after bias and epilogue
 int gemm_launch(int ta, int tb, int64_t M, int64_t N, int64_t K, const float* A, int64_t lda, const float* B,
                 int64_t ldb, float* C, int64_t ldc, const float* bias, int epilogue, const float* Zprev,
-                int64_t ldzprev, hipStream_t s);
+                int64_t ldzprev, hipStream_t s, const float* row_scale = nullptr);
 // the fused last layer of the epoch (f_in = 16, up to 256 classes)
 bool fused_last_supported(int32_t f_in, int32_t C);
 size_t fused_last_scratch_bytes(int64_t n, int32_t C);
 int fused_last_launch(int64_t n, int32_t C, const float* T, const float* W, const int32_t* labels, int64_t n_labelled,
-                      float* loss, float* Y, float* S, float* Zout, float* Gout, void* scratch, hipStream_t s);
+                      float* loss, float* Y, float* S, const float* s_scale, float* Zout, float* Gout, void* scratch,
+                      hipStream_t s);
 int colsum_launch(int64_t rows, int32_t cols, const float* G, int64_t ldg, float* out, hipStream_t s);
 int axpy_launch(int64_t count, float* W, const float* Y, float lr, hipStream_t s);
 int relu_launch(int64_t rows, int32_t cols, const float* Z, int64_t ldz, float* H, int64_t ldh, hipStream_t s);

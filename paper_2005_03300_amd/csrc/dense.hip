@@ -128,7 +128,7 @@ static inline unsigned nblocks(int64_t work) { return (unsigned)((work + 255) / 
 
 int gemm_mfma_launch(int ta, int tb, int64_t M, int64_t N, int64_t K, const float* A, int64_t lda, const float* B,
                      int64_t ldb, float* C, int64_t ldc, const float* bias, int epilogue, const float* Zprev,
-                     int64_t ldzprev, hipStream_t s, bool* handled);
+                     int64_t ldzprev, hipStream_t s, bool* handled, const float* row_scale, bool* scaled);
 
 // split of the long dimension of the plain (non-MFMA) A^T B kernel
 static void naive_tn_split(int64_t K, int64_t* parts_out, int64_t* kpb_out) {
@@ -169,10 +169,13 @@ size_t colsum_scratch_bytes(int64_t rows, int32_t cols) {
 
 int gemm_launch(int ta, int tb, int64_t M, int64_t N, int64_t K, const float* A, int64_t lda, const float* B,
                 int64_t ldb, float* C, int64_t ldc, const float* bias, int epilogue, const float* Zprev,
-                int64_t ldzprev, hipStream_t s) {
-    bool handled = false;
-    GCN_TRY(gemm_mfma_launch(ta, tb, M, N, K, A, lda, B, ldb, C, ldc, bias, epilogue, Zprev, ldzprev, s, &handled));
-    if (handled) return GCN_OK;
+                int64_t ldzprev, hipStream_t s, const float* row_scale) {
+    bool handled = false, scaled = false;
+    GCN_TRY(gemm_mfma_launch(ta, tb, M, N, K, A, lda, B, ldb, C, ldc, bias, epilogue, Zprev, ldzprev, s, &handled,
+                             row_scale, &scaled));
+    // kernels without a scaling store path leave the row factors to a pass of their own
+    auto finish = [&]() { return (row_scale && !scaled) ? scale_rows_launch(M, (int32_t)N, C, ldc, row_scale, C, ldc, s) : (int)GCN_OK; };
+    if (handled) return finish();
     if (!ta) {
         const int64_t work = M * N;
         if ((work + 255) / 256 >= (1ll << 31)) return fail(GCN_ERR_RANGE, "gcn_gemm: output too large");
@@ -182,7 +185,7 @@ int gemm_launch(int ta, int tb, int64_t M, int64_t N, int64_t K, const float* A,
             default: hipLaunchKernelGGL(k_gemm_naive<GCN_EPI_MASK>, dim3(nblocks(work)), dim3(256), 0, s, tb, M, N, K, A, lda, B, ldb, C, ldc, bias, Zprev, ldzprev); break;
         }
         GCN_LAUNCH_CHECK();
-        return GCN_OK;
+        return finish();
     }
     // ta: split K
     int64_t parts = 0, kpb = 0;
@@ -198,7 +201,7 @@ int gemm_launch(int ta, int tb, int64_t M, int64_t N, int64_t K, const float* A,
         default: hipLaunchKernelGGL(k_reduce_partials<GCN_EPI_MASK>, dim3(nblocks(count)), dim3(256), 0, s, count, N, (int)parts, (const float*)scratch, C, ldc, bias, Zprev, ldzprev); break;
     }
     GCN_LAUNCH_CHECK();
-    return GCN_OK;
+    return finish();
 }
 
 int colsum_launch(int64_t rows, int32_t cols, const float* G, int64_t ldg, float* out, hipStream_t s) {

@@ -36,6 +36,7 @@ struct FusedArgs {
     const int32_t* labels;    // n; negative: outside the training split
     float inv_m;              // 1 / labelled vertices
     float* S;                 // n x 16 = G W^T, or NULL when no earlier layer needs it
+    const float* s_scale;     // NULL, or one factor per row of S (the pre-scaling of the value-free sparse product)
     float* Zout;              // n x C (ld C) or NULL
     float* Gout;              // n x C (ld C) or NULL
     float* ypart;             // [gridDim.x][16][16*NT]
@@ -162,7 +163,10 @@ __global__ __launch_bounds__(256) void k_fused_last(FusedArgs a) {
                     sacc[v] = __builtin_amdgcn_mfma_f32_16x16x4f32(Wt[(16 * t + 4 * g + v) * ST + r], z[t][v], sacc[v], 0, 0, 0);
             }
             const floatx4 sum = (sacc[0] + sacc[1]) + (sacc[2] + sacc[3]);
-            if (valid) *reinterpret_cast<float4*>(a.S + row * 16 + 4 * g) = make_float4(sum[0], sum[1], sum[2], sum[3]);
+            if (valid) {
+                const float rs = a.s_scale ? a.s_scale[row] : 1.f;
+                *reinterpret_cast<float4*>(a.S + row * 16 + 4 * g) = make_float4(sum[0] * rs, sum[1] * rs, sum[2] * rs, sum[3] * rs);
+            }
         }
         // 3. Y += T^T G, tile by tile through a transposition in this wavefront's LDS (its LDS operations
         //    complete in program order; the barriers only keep the compiler from reordering them)
@@ -259,10 +263,11 @@ static void launch_fused(const FusedArgs& a, int64_t blocks, hipStream_t s) {
     hipLaunchKernelGGL((k_fused_last<NT, false>), dim3((unsigned)blocks), dim3(256), lds, s, a);
 }
 
-// T: n x 16 contiguous; W: 16 x C; Y: 16 x C; S: n x 16 or NULL; Zout / Gout: n x C or NULL; scratch: at
-// least fused_last_scratch_bytes(n, C).
+// T: n x 16 contiguous; W: 16 x C; Y: 16 x C; S: n x 16 or NULL, its rows multiplied by s_scale when that is given;
+// Zout / Gout: n x C or NULL; scratch: at least fused_last_scratch_bytes(n, C).
 int fused_last_launch(int64_t n, int32_t C, const float* T, const float* W, const int32_t* labels, int64_t n_labelled,
-                      float* loss, float* Y, float* S, float* Zout, float* Gout, void* scratch, hipStream_t s) {
+                      float* loss, float* Y, float* S, const float* s_scale, float* Zout, float* Gout, void* scratch,
+                      hipStream_t s) {
     const int NT = fused_nt(C);
     if (!NT) return fail(GCN_ERR_BADARG, "fused last layer: more than 256 classes");
     if (((uintptr_t)T & 15u) || (S && ((uintptr_t)S & 15u))) return fail(GCN_ERR_BADARG, "fused last layer: unaligned operand");
@@ -270,7 +275,7 @@ int fused_last_launch(int64_t n, int32_t C, const float* T, const float* W, cons
     const int count = 16 * 16 * NT;
     FusedArgs a;
     a.n = n; a.C = C; a.T = T; a.W = W; a.labels = labels; a.inv_m = 1.0f / (float)n_labelled;
-    a.S = S; a.Zout = Zout; a.Gout = Gout;
+    a.S = S; a.s_scale = s_scale; a.Zout = Zout; a.Gout = Gout;
     a.ypart = (float*)scratch;
     float* folded = a.ypart + (size_t)blocks * count;
     a.lpart = (double*)(folded + (size_t)FUSED_FOLD * count);

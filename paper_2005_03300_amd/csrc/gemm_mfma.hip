@@ -42,6 +42,7 @@ struct TallArgs {
     int32_t Kpad;      // K rounded up to 16
     int32_t S;         // LDS row stride in floats: 16*NT + 4 (bank-conflict-free B reads)
     int a_aligned;     // A rows are 16-byte aligned
+    const float* row_scale;   // NULL, or one factor per row of C, applied after bias and epilogue (wide store path only)
 };
 
 // TR: the two MFMA operands are swapped, so a lane ends up with four consecutive columns of one
@@ -142,6 +143,10 @@ __global__ __launch_bounds__(256) void k_gemm_tall(TallArgs a) {
                     const float4 m = *reinterpret_cast<const float4*>(a.Zprev + row * a.ldzprev + col);
                     o.x = m.x > 0.f ? o.x : 0.f; o.y = m.y > 0.f ? o.y : 0.f;
                     o.z = m.z > 0.f ? o.z : 0.f; o.w = m.w > 0.f ? o.w : 0.f;
+                }
+                if (a.row_scale) {
+                    const float rs = a.row_scale[row];
+                    o.x *= rs; o.y *= rs; o.z *= rs; o.w *= rs;
                 }
                 *reinterpret_cast<float4*>(a.C + row * a.ldc + col) = o;
             }
@@ -254,6 +259,10 @@ __global__ __launch_bounds__(512) void k_gemm_tall_flat(TallArgs a) {
                 const float4 m = *reinterpret_cast<const float4*>(a.Zprev + row * a.ldzprev + col);
                 o.x = m.x > 0.f ? o.x : 0.f; o.y = m.y > 0.f ? o.y : 0.f;
                 o.z = m.z > 0.f ? o.z : 0.f; o.w = m.w > 0.f ? o.w : 0.f;
+            }
+            if (a.row_scale) {
+                const float rs = a.row_scale[row];
+                o.x *= rs; o.y *= rs; o.z *= rs; o.w *= rs;
             }
             *reinterpret_cast<float4*>(a.C + row * a.ldc + col) = o;
         }
@@ -526,8 +535,9 @@ size_t gemm_mfma_tn_scratch_bytes(int64_t M, int64_t N, int64_t K) {
 
 int gemm_mfma_launch(int ta, int tb, int64_t M, int64_t N, int64_t K, const float* A, int64_t lda, const float* B,
                      int64_t ldb, float* C, int64_t ldc, const float* bias, int epilogue, const float* Zprev,
-                     int64_t ldzprev, hipStream_t s, bool* handled) {
+                     int64_t ldzprev, hipStream_t s, bool* handled, const float* row_scale, bool* scaled) {
     *handled = false;
+    *scaled = false;
     if (!ta) {
         if (K > 4096 || N > 4096 || M < 64) return GCN_OK;
         const int nt_total = (int)((N + 15) / 16);
@@ -544,8 +554,12 @@ int gemm_mfma_launch(int ta, int tb, int64_t M, int64_t N, int64_t K, const floa
         args.Kpad = (int32_t)((K + 15) & ~15ll);
         args.S = 16 * NT + 4;
         args.a_aligned = (lda % 4 == 0) && al16(A);
+        const bool wide_c = (N % 4 == 0) && (ldc % 4 == 0) && al16(C) &&
+                            (epilogue != GCN_EPI_MASK || ((ldzprev % 4 == 0) && al16(Zprev)));
+        args.row_scale = wide_c ? row_scale : nullptr;       // the 16-byte store path applies it; else the caller does
+        *scaled = args.row_scale != nullptr;
         const size_t lds = (size_t)args.Kpad * args.S * sizeof(float);
-        if (lds > 64 * 1024) return GCN_OK;
+        if (lds > 64 * 1024) { *scaled = false; return GCN_OK; }
         const int64_t ntiles = (M + 15) / 16;
         {   // rows that are not whole 128-byte lines: contiguous strips through LDS (see k_gemm_tall_flat)
             const bool wide = (N % 4 == 0) && (ldc % 4 == 0) && al16(C) &&

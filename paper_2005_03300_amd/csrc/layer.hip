@@ -25,23 +25,30 @@ static bool use_pattern(const gcn_csr* a) {
 
 // Z = epilogue(op(A) X) with the handle's normalised matrix.  `xs` (n x f, ld f) receives the
 // pre-scaled operand of the value-free form; it may be X itself when X is a temporary with ld f,
-// or NULL to force the valued product.
+// or NULL to force the valued product.  `prescaled`: the producer of X already applied the row factors
+// (only passed when pre_scale() said so for this operand).
 static int norm_spmm(gcn_csr* a, Matrix& m, int32_t f, const float* X, int64_t ldx, float* xs, float* Z, int64_t ldz,
-                     int epilogue, const float* Zprev, int64_t ldzprev, hipStream_t s) {
+                     int epilogue, const float* Zprev, int64_t ldzprev, hipStream_t s, bool prescaled = false) {
     PhaseTimer pt(s, GCN_PHASE_SPMM);
     if (!xs || !use_pattern(a)) return spmm_launch(a, m, f, X, ldx, Z, ldz, epilogue, Zprev, ldzprev, s);
-    GCN_TRY(scale_rows_launch(a->n, f, X, ldx, a->inv_sqrt_deg, xs, f, s));
+    if (!prescaled) GCN_TRY(scale_rows_launch(a->n, f, X, ldx, a->inv_sqrt_deg, xs, f, s));
     SpmmOpt o;
     o.pattern = true;
     o.row_scale = a->inv_sqrt_deg;
-    return spmm_launch(a, m, f, xs, f, Z, ldz, epilogue, Zprev, ldzprev, s, o);
+    return spmm_launch(a, m, f, prescaled ? X : xs, prescaled ? ldx : f, Z, ldz, epilogue, Zprev, ldzprev, s, o);
+}
+
+// The row factors that the kernel producing a temporary operand of norm_spmm should apply itself (the value-free
+// form pre-scales its operand; when the operand is a temporary the producer's store path does it for free), or NULL.
+static const float* pre_scale(const gcn_csr* a, bool operand_is_temporary) {
+    return (operand_is_temporary && use_pattern(a)) ? a->inv_sqrt_deg : nullptr;
 }
 
 static int timed_gemm(int ta, int tb, int64_t M, int64_t N, int64_t K, const float* A, int64_t lda, const float* B,
                       int64_t ldb, float* C, int64_t ldc, const float* bias, int epilogue, const float* Zprev,
-                      int64_t ldzprev, hipStream_t s) {
+                      int64_t ldzprev, hipStream_t s, const float* row_scale = nullptr) {
     PhaseTimer pt(s, GCN_PHASE_GEMM);
-    return gemm_launch(ta, tb, M, N, K, A, lda, B, ldb, C, ldc, bias, epilogue, Zprev, ldzprev, s);
+    return gemm_launch(ta, tb, M, N, K, A, lda, B, ldb, C, ldc, bias, epilogue, Zprev, ldzprev, s, row_scale);
 }
 
 // `xs`: scratch for the value-free product (n x the SpMM width) or NULL; `t_scratch` says that T is
@@ -55,9 +62,10 @@ static int layer_forward_impl(gcn_csr* a, int32_t f_in, int32_t f_out, const flo
     // the kernel that produces Z; otherwise Z is kept (backward needs it) and H is a second pass.
     const bool in_place = (act == GCN_ACT_RELU) && Hout == Z;
     if (order == GCN_ORDER_GEMM_FIRST) {
-        GCN_TRY(timed_gemm(0, 0, n, f_out, f_in, Hin, ldh, W, f_out, T, f_out, nullptr, GCN_EPI_NONE, nullptr, 0, s));
+        const float* ps = pre_scale(a, t_scratch);
+        GCN_TRY(timed_gemm(0, 0, n, f_out, f_in, Hin, ldh, W, f_out, T, f_out, nullptr, GCN_EPI_NONE, nullptr, 0, s, ps));
         GCN_TRY(norm_spmm(a, a->At, f_out, T, f_out, t_scratch ? T : xs, Z, f_out,
-                          (in_place && !bias) ? GCN_EPI_RELU : GCN_EPI_NONE, nullptr, 0, s));
+                          (in_place && !bias) ? GCN_EPI_RELU : GCN_EPI_NONE, nullptr, 0, s, ps != nullptr));
         if (bias) {
             PhaseTimer pt(s, GCN_PHASE_OTHER);
             GCN_TRY(bias_add_launch(n, f_out, Z, f_out, bias, in_place ? 1 : 0, s));
@@ -96,8 +104,10 @@ static int layer_backward_impl(gcn_csr* a, int32_t f_in, int32_t f_out, const fl
         // SpMM at width f_in.
         GCN_TRY(timed_gemm(1, 0, f_in, f_out, n, T, f_in, G, f_out, Y, f_out, nullptr, GCN_EPI_NONE, nullptr, 0, s));
         if (Gprev) {
-            GCN_TRY(timed_gemm(0, 1, n, f_in, f_out, G, f_out, W, f_out, S, f_in, nullptr, GCN_EPI_NONE, nullptr, 0, s));
-            GCN_TRY(norm_spmm(a, a->A, f_in, S, f_in, s_scratch ? S : xs, Gprev, f_in, GCN_EPI_MASK, Zprev, f_in, s));
+            const float* ps = pre_scale(a, s_scratch);
+            GCN_TRY(timed_gemm(0, 1, n, f_in, f_out, G, f_out, W, f_out, S, f_in, nullptr, GCN_EPI_NONE, nullptr, 0, s, ps));
+            GCN_TRY(norm_spmm(a, a->A, f_in, S, f_in, s_scratch ? S : xs, Gprev, f_in, GCN_EPI_MASK, Zprev, f_in, s,
+                              ps != nullptr));
         }
     }
     return GCN_OK;
@@ -258,7 +268,7 @@ static int epoch_impl(gcn_csr* a, int32_t L_w, const int32_t* dims, const float*
         PhaseTimer pt(s, GCN_PHASE_GEMM);
         const bool keep = fuse_mode == 2;
         GCN_TRY(fused_last_launch(n, dims[L_w], layer_T(last), W[last], labels, n_labelled, loss, Y[last],
-                                  last > 0 ? at(lay.S) : nullptr, keep ? at(lay.Z[last]) : nullptr,
+                                  last > 0 ? at(lay.S) : nullptr, pre_scale(a, true), keep ? at(lay.Z[last]) : nullptr,
                                   keep ? at(lay.G[last]) : nullptr, ws + lay.scratch, s));
     } else {
         PhaseTimer pt(s, GCN_PHASE_OTHER);
@@ -270,7 +280,7 @@ static int epoch_impl(gcn_csr* a, int32_t L_w, const int32_t* dims, const float*
             // Y^L and S = G^L (W^L)^T are done; what is left of Equation 2 is the sparse product
             if (l > 0)
                 GCN_TRY(norm_spmm(a, a->A, dims[l], at(lay.S), dims[l], at(lay.S), at(lay.G[l - 1]), dims[l], GCN_EPI_MASK,
-                                  at(lay.Z[l - 1]), dims[l], s));
+                                  at(lay.Z[l - 1]), dims[l], s, pre_scale(a, true) != nullptr));
             continue;
         }
         const float* Hl = l > 0 ? at(lay.H[l - 1]) : H0;
