@@ -18,8 +18,17 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 struct __attribute__((packed, aligned(4))) f4u { float x, y, z, w; };   // 16 bytes at 4-byte alignment
 
-__device__ __forceinline__ float4 load4(const float* p, bool aligned) {
-    if (aligned) return *reinterpret_cast<const float4*>(p);
+// 16-byte load of data that is read once: the non-temporal hint keeps the stream from displacing what other
+// wavefronts still need in the caches.  Measured on 14 M rows: +10 % on the A^T B kernel when every row of A is
+// whole 128-byte lines (256 floats: 2.67 -> 2.39 ms, 128 floats: 1.62 -> 1.42 ms), +2 % on the strip kernel; a loss
+// where neighbouring wavefronts share lines (A^T B at 300 floats per row: 4.13 -> 4.22 ms), so the callers decide.
+__device__ __forceinline__ float4 stream4(const float* p) {
+    const floatx4 v = __builtin_nontemporal_load(reinterpret_cast<const floatx4*>(p));
+    return make_float4(v[0], v[1], v[2], v[3]);
+}
+
+__device__ __forceinline__ float4 load4(const float* p, bool aligned, bool nt = false) {
+    if (aligned) return nt ? stream4(p) : *reinterpret_cast<const float4*>(p);
     f4u v = *reinterpret_cast<const f4u*>(p);
     return make_float4(v.x, v.y, v.z, v.w);
 }
@@ -202,7 +211,7 @@ __global__ __launch_bounds__(512) void k_gemm_tall_flat(TallArgs a) {
 #pragma unroll
         for (int q = 0; q < KV; ++q) {
             const int64_t off = base + (int64_t)(q * 64 + lane) * 4;
-            pre[q] = (q * 256 + lane * 4 < strip_floats && off + 4 <= total) ? *reinterpret_cast<const float4*>(a.A + off)
+            pre[q] = (q * 256 + lane * 4 < strip_floats && off + 4 <= total) ? stream4(a.A + off)
                                                                              : make_float4(0.f, 0.f, 0.f, 0.f);
         }
     };
@@ -285,6 +294,7 @@ struct TnArgs {
     float* part;
     int64_t k_per_block;
     int a_aligned;
+    int a_stream;      // rows of A are whole 128-byte lines: non-temporal loads
     int waves;         // wavefronts per workgroup (the column groups are dealt to them round-robin); 4 when NARROW
 };
 
@@ -335,7 +345,7 @@ __global__ __launch_bounds__(512) void k_gemm_tn(TnArgs a) {
                     av[s][g][0] = (kok && mvalid[g]) ? arow[mcol[g]] : 0.f;
                 } else {
                     if (kok && mvalid[g] == 4) {
-                        const float4 v = load4(arow + mcol[g], a.a_aligned);
+                        const float4 v = load4(arow + mcol[g], a.a_aligned, a.a_stream);
                         av[s][g][0] = v.x; av[s][g][1] = v.y; av[s][g][2] = v.z; av[s][g][3] = v.w;
                     } else {
 #pragma unroll
@@ -561,17 +571,19 @@ int gemm_mfma_launch(int ta, int tb, int64_t M, int64_t N, int64_t K, const floa
         const size_t lds = (size_t)args.Kpad * args.S * sizeof(float);
         if (lds > 64 * 1024) { *scaled = false; return GCN_OK; }
         const int64_t ntiles = (M + 15) / 16;
-        {   // rows that are not whole 128-byte lines: contiguous strips through LDS (see k_gemm_tall_flat)
+        {   // rows that are not whole 128-byte lines, and short rows (up to 208 floats, where the coalesced copy also beats
+            // the strided 64-byte pieces: 128 floats 1.02 -> 0.96 ms on 8.7 M rows; at 256 floats it loses, 3.14 -> 3.23 ms):
+            // contiguous strips through LDS (see k_gemm_tall_flat)
             const bool wide = (N % 4 == 0) && (ldc % 4 == 0) && al16(C) &&
                               (epilogue != GCN_EPI_MASK || ((ldzprev % 4 == 0) && al16(Zprev)));
             const int kv_need = (int)((K + 15) / 16);
             const int KV = kv_need <= 7 ? 7 : (kv_need <= 13 ? 13 : 19);     // the compiled per-lane load counts
-            // wavefronts per workgroup (one workgroup per compute unit): up to four, as the strips leave room beside
-            // op(B); measured on 14 M rows of 300 floats: 4 wavefronts 3.65 ms, 6 wavefronts 3.74 ms
+            // wavefronts per workgroup: up to four, as the strips leave room beside op(B); measured on 14 M rows of
+            // 300 floats: 2: 4.15, 3: 4.29, 4: 3.57, 5: 3.87, 6: 3.74 ms (the same ranking at 64, 128 and 192 floats)
             int fw = (int)((150 * 1024 - (int64_t)lds) / ((int64_t)KV * 256 * sizeof(float)));
             fw = fw > 4 ? 4 : fw;
             const size_t lds_flat = lds + (size_t)(fw > 0 ? fw : 1) * KV * 256 * sizeof(float);
-            if (fw >= 2 && wide && lda == K && (K % 4) == 0 && ((K * 4) % 128) != 0 && K >= 64 && kv_need <= 19 && NT <= 2 && al16(A) &&
+            if (fw >= 2 && wide && lda == K && (K % 4) == 0 && (((K * 4) % 128) != 0 || K <= 208) && K >= 64 && kv_need <= 19 && NT <= 2 && al16(A) &&
                 lds_flat <= 150 * 1024 && M >= 4096) {
                 int64_t fb = (ntiles + fw - 1) / fw;
                 const int per_cu = (int)((160 * 1024) / lds_flat);
@@ -618,6 +630,7 @@ int gemm_mfma_launch(int ta, int tb, int64_t M, int64_t N, int64_t K, const floa
     args.A = Aw; args.lda = ldaw; args.B = Bw; args.ldb = ldbw;
     args.part = (float*)scratch; args.k_per_block = kpb;
     args.a_aligned = (ldaw % 4 == 0) && al16(Aw);
+    args.a_stream = args.a_aligned && (ldaw % 32 == 0) && (((uintptr_t)Aw & 127u) == 0);
     args.waves = W;
 #define GCN_TN_CASE(mg, nt) if (!narrow && MG == mg && NTn == nt) launch_tn<mg, nt, false>(args, (int)blocks, s)
     GCN_TN_CASE(1, 1); GCN_TN_CASE(2, 1); GCN_TN_CASE(3, 1); GCN_TN_CASE(4, 1);

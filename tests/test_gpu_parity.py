@@ -612,8 +612,10 @@ def test_spmm_pattern_directed_transpose_and_errors():
 
 @pytest.mark.parametrize("M,K,N", [(5000, 602, 16), (4097, 300, 16), (3000, 16, 41), (2049, 16, 256),
                                    (1000, 64, 16), (777, 128, 16), (33, 7, 5), (1, 1, 1), (4096, 16, 16),
-                                   # rows that are not whole 128-byte lines: strips staged through LDS
-                                   (70001, 300, 16), (4100, 100, 16), (4111, 204, 32), (5003, 76, 24), (4096, 304, 16)])
+                                   # rows that are not whole 128-byte lines, and rows of up to 208 floats: strips staged
+                                   # through LDS; 256 floats: the strided kernel again
+                                   (70001, 300, 16), (4100, 100, 16), (4111, 204, 32), (5003, 76, 24), (4096, 304, 16),
+                                   (8203, 128, 16), (4500, 64, 8), (4300, 192, 16), (4101, 208, 32), (4100, 256, 16)])
 def test_gemm_nn_parity(M, K, N):
     g = G()
     A = synth.normal_features(M, K, 21)
@@ -644,7 +646,11 @@ def test_gemm_nt_mask_parity(M, K, N):
 
 
 @pytest.mark.parametrize("K,M,N", [(20000, 602, 16), (30001, 300, 16), (9999, 16, 41), (5000, 16, 256),
-                                   (100000, 16, 16), (50, 7, 5), (1, 3, 2)])
+                                   (100000, 16, 16), (50, 7, 5), (1, 3, 2),
+                                   # rows that are not whole 128-byte lines, ragged lengths, a narrow side below 16,
+                                   # the transposed product; rows that are whole lines (streamed with non-temporal loads)
+                                   (70003, 100, 16), (50021, 204, 12), (4100, 76, 16), (9000, 304, 8), (40000, 16, 300),
+                                   (5000, 300, 24), (4095, 300, 16), (8192, 256, 16), (8200, 128, 16)])
 def test_gemm_tn_parity(K, M, N):
     """Y = H^T S with the long dimension summed (Equation 3)."""
     g = G()
@@ -656,6 +662,18 @@ def test_gemm_tn_parity(K, M, N):
     assert_close(first, oracle.gemm(H, S, ta=True), f"TN {K}: {M}x{N}")
     g.gcn_gemm(1, 0, dev(H), dev(S), Yd)
     np.testing.assert_array_equal(first.view(np.uint32), host(Yd).view(np.uint32))
+
+
+def test_gemm_tn_with_a_leading_dimension():
+    """Rows of 300 floats inside a wider buffer (1248-byte pitch)."""
+    g = G()
+    K, M, N = 20000, 300, 16
+    H = synth.normal_features(K, M, 35)
+    S = synth.normal_features(K, N, 36)
+    Hd = dev(np.concatenate([H, np.full((K, 12), np.nan, np.float32)], 1))[:, :M]
+    Yd = torch.empty(M, N, device="cuda")
+    g.gcn_gemm(1, 0, Hd, dev(S), Yd)
+    assert_close(host(Yd), oracle.gemm(H, S, ta=True), "TN with ld")
 
 
 def test_gemm_leading_dimensions():
@@ -925,6 +943,23 @@ def test_epoch_value_free_spmm_on_and_off(mode, order):
         w = synth.CONFIGS[1]
         _, a, A, dims, Wd, Yd, ws, loss, ref, _ = run_epoch("c1", w, order)
         assert_epoch_close(g, A.n, dims, order, ws, loss, Yd, ref, f"value-free mode {mode}")
+        a.close()
+    finally:
+        g.gcn_config(g.CFG_PATTERN_SPMM, 2)
+
+
+@pytest.mark.parametrize("order", [0, 1, 2])
+def test_epoch_value_free_spmm_with_widths_that_are_not_multiples_of_four(order):
+    """With the value-free form the kernel that produces a temporary SpMM operand applies the d^-1/2 row factors in
+    its store path; widths of 6 and 5 take the dense kernels without that path, where the factors fall back to a pass
+    of their own.  Same oracle epoch."""
+    import dataclasses
+    g = G()
+    g.gcn_config(g.CFG_PATTERN_SPMM, 1)
+    try:
+        w = dataclasses.replace(synth.CONFIGS[1], dims=(64, 6, 5, 3), n_classes=3)
+        _, a, A, dims, Wd, Yd, ws, loss, ref, _ = run_epoch("c1", w, order)
+        assert_epoch_close(g, A.n, dims, order, ws, loss, Yd, ref, f"value-free, odd widths, order {order}")
         a.close()
     finally:
         g.gcn_config(g.CFG_PATTERN_SPMM, 2)
