@@ -74,7 +74,7 @@ extern "C" {
 #define GCN_CFG_SPMM_BLOCKS 3 /* column blocks of the SpMM: 0 = automatic, 1 = never block, k >= 2 = k blocks */
 #define GCN_CFG_SWEEP_HEAVY 4 /* rows longer than this bypass the column sweep (default 1024; >= 1) */
 #define GCN_CFG_SWEEP_WAVES 5 /* column sweep: tasks per compute unit in one launch (default 9: 9 x 16 KB of LDS accumulators per compute unit, the most that fit; 1..18) */
-#define GCN_CFG_PATTERN_SPMM 6 /* gcn_epoch on a matrix made by gcn_csr_create with GCN_NORM_SYM: use the value-free SpMM (operand rows pre-scaled by d^-1/2, output rows scaled by d^-1/2) instead of reading the stored values. 0 never, 1 always, 2 (default) when the mean row has at least 64 entries */
+#define GCN_CFG_PATTERN_SPMM 6 /* gcn_spmm and gcn_epoch* on a matrix made by gcn_csr_create with GCN_NORM_SYM: use the value-free SpMM (operand rows pre-scaled by d^-1/2, output rows scaled by d^-1/2) instead of reading the stored values. 0 never, 1 always, 2 (default) when the mean row has at least 64 entries */
 #define GCN_CFG_HUB_MB 7   /* hub schedule: size in MB of the packed buffer that holds the rows of X selected by the columns with the most entries (default 32) */
 #define GCN_CFG_HUB_DMIN 8 /* hub schedule: rows with at least this many entries are treated as long rows (default 64) */
 #define GCN_CFG_HUB_BLOCK_COLS 9 /* hub schedule: columns per block of the packed buffer (0, default: about 2 MB of the gathered panel; a multiple of 64) */
@@ -142,6 +142,11 @@ int gcn_csr_export(const gcn_csr* a, int transposed, int64_t* rowptr, int32_t* c
  * Sums are fp32 and run-to-run reproducible (no floating-point atomics).  The first call at a
  * given width may build and cache a column-blocked copy of the matrix inside `a` (it allocates
  * and synchronises once); later calls only queue kernels.
+ * For a matrix that gcn_csr_create normalised symmetrically the same product is D^-1/2 ((A+I) (D^-1/2 X)); when
+ * GCN_CFG_PATTERN_SPMM says so (by default: mean row of at least 64 entries) it is computed in that form, without
+ * reading the stored values: X is copied with its rows scaled into a buffer of the handle (n x f floats, allocated by
+ * gcn_spmm_prepare or by the first call at that width), the gathered rows are summed and the output rows scaled.  The
+ * result differs from the sum over val[k] by fp32 roundings only (a few 1e-7 of the result's rms).
  * ----------------------------------------------------------------------------------------- */
 int gcn_spmm(gcn_csr* a, int trans, int32_t f, const float* X, int64_t ldx, float* Z, int64_t ldz,
              int epilogue, const float* Zprev, int64_t ldzprev, void* stream);

@@ -331,6 +331,7 @@ int gcn_csr_destroy(gcn_csr* a) {
     device_free(a->inv_sqrt_deg);
     device_free(a->carry);
     device_free(a->partial);
+    device_free(a->xs);
     for (void* p : a->retired) device_free(p);
     delete a;
     return GCN_OK;

@@ -171,6 +171,8 @@ struct gcn_csr {
     size_t carry2_bytes = 0;
     float* partial = nullptr;    // P of the column-blocked SpMM
     size_t partial_bytes = 0;
+    float* xs = nullptr;         // operand of gcn_spmm with its rows pre-scaled (value-free form)
+    size_t xs_bytes = 0;
     std::vector<void*> retired;  // buffers replaced by larger ones: kept until destroy (queued or captured work may use them)
     bool own_cfg = false;        // set by gcn_csr_config: this matrix has settings of its own
     gcn::Config cfg;             // valid when own_cfg
@@ -251,6 +253,8 @@ struct SpmmOpt {
 };
 int scale_rows_launch(int64_t rows, int32_t cols, const float* X, int64_t ldx, const float* scale, float* Y, int64_t ldy,
                       hipStream_t s);
+// whether products with this matrix take the value-free form (GCN_CFG_PATTERN_SPMM and the matrix's own shape)
+bool use_value_free(const gcn_csr* a);
 int inv_sqrt_deg_launch(int64_t n, const int32_t* deg, float* out, hipStream_t s);
 int spmm_launch(gcn_csr* a, Matrix& m, int32_t f, const float* X, int64_t ldx, float* Z, int64_t ldz,
                 int epilogue, const float* Zprev, int64_t ldzprev, hipStream_t s, const SpmmOpt& o = SpmmOpt());

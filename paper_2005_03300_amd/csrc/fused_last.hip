@@ -75,9 +75,11 @@ __global__ __launch_bounds__(256) void k_fused_last(FusedArgs a) {
         const bool valid = row < a.n;
         float4 tv = make_float4(0.f, 0.f, 0.f, 0.f);
         int32_t y = -1;
+        float rs = 1.f;                                    // the factor of this row of S, fetched with the row
         if (valid) {
             tv = *reinterpret_cast<const float4*>(a.T + row * 16 + 4 * g);
             y = a.labels[row];
+            if (a.s_scale) rs = a.s_scale[row];
         }
         // (The operands from W do not depend on the strip: the compiler keeps them in registers across the
         // loop, 128 of them at 256 classes, which leaves one wavefront per SIMD; forcing two by re-reading them
@@ -163,10 +165,7 @@ __global__ __launch_bounds__(256) void k_fused_last(FusedArgs a) {
                     sacc[v] = __builtin_amdgcn_mfma_f32_16x16x4f32(Wt[(16 * t + 4 * g + v) * ST + r], z[t][v], sacc[v], 0, 0, 0);
             }
             const floatx4 sum = (sacc[0] + sacc[1]) + (sacc[2] + sacc[3]);
-            if (valid) {
-                const float rs = a.s_scale ? a.s_scale[row] : 1.f;
-                *reinterpret_cast<float4*>(a.S + row * 16 + 4 * g) = make_float4(sum[0] * rs, sum[1] * rs, sum[2] * rs, sum[3] * rs);
-            }
+            if (valid) *reinterpret_cast<float4*>(a.S + row * 16 + 4 * g) = make_float4(sum[0] * rs, sum[1] * rs, sum[2] * rs, sum[3] * rs);
         }
         // 3. Y += T^T G, tile by tile through a transposition in this wavefront's LDS (its LDS operations
         //    complete in program order; the barriers only keep the compiler from reordering them)

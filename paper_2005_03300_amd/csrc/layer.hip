@@ -14,15 +14,6 @@ static int resolve_order(int order, int32_t f_in, int32_t f_out) {
     return f_out <= f_in ? GCN_ORDER_GEMM_FIRST : GCN_ORDER_SPMM_FIRST;
 }
 
-// For a matrix this library normalised symmetrically, D^-1/2 (A+I) D^-1/2 X = D^-1/2 ((A+I) (D^-1/2 X))
-// (section "Graph Neural Networks"): the product can skip the stored values, which halves the
-// index/value stream.  It pays when rows are long (the pre-scaling pass over X is amortised).
-static bool use_pattern(const gcn_csr* a) {
-    const int mode = cfg_of(a).pattern_spmm;
-    if (!a->inv_sqrt_deg || mode == 0) return false;
-    return mode == 1 || a->nnz / (a->n > 0 ? a->n : 1) >= 64;
-}
-
 // Z = epilogue(op(A) X) with the handle's normalised matrix.  `xs` (n x f, ld f) receives the
 // pre-scaled operand of the value-free form; it may be X itself when X is a temporary with ld f,
 // or NULL to force the valued product.  `prescaled`: the producer of X already applied the row factors
@@ -30,7 +21,7 @@ static bool use_pattern(const gcn_csr* a) {
 static int norm_spmm(gcn_csr* a, Matrix& m, int32_t f, const float* X, int64_t ldx, float* xs, float* Z, int64_t ldz,
                      int epilogue, const float* Zprev, int64_t ldzprev, hipStream_t s, bool prescaled = false) {
     PhaseTimer pt(s, GCN_PHASE_SPMM);
-    if (!xs || !use_pattern(a)) return spmm_launch(a, m, f, X, ldx, Z, ldz, epilogue, Zprev, ldzprev, s);
+    if (!xs || !use_value_free(a)) return spmm_launch(a, m, f, X, ldx, Z, ldz, epilogue, Zprev, ldzprev, s);
     if (!prescaled) GCN_TRY(scale_rows_launch(a->n, f, X, ldx, a->inv_sqrt_deg, xs, f, s));
     SpmmOpt o;
     o.pattern = true;
@@ -41,7 +32,7 @@ static int norm_spmm(gcn_csr* a, Matrix& m, int32_t f, const float* X, int64_t l
 // The row factors that the kernel producing a temporary operand of norm_spmm should apply itself (the value-free
 // form pre-scales its operand; when the operand is a temporary the producer's store path does it for free), or NULL.
 static const float* pre_scale(const gcn_csr* a, bool operand_is_temporary) {
-    return (operand_is_temporary && use_pattern(a)) ? a->inv_sqrt_deg : nullptr;
+    return (operand_is_temporary && use_value_free(a)) ? a->inv_sqrt_deg : nullptr;
 }
 
 static int timed_gemm(int ta, int tb, int64_t M, int64_t N, int64_t K, const float* A, int64_t lda, const float* B,

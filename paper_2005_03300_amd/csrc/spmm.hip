@@ -1001,6 +1001,15 @@ int spmm_launch(gcn_csr* a, Matrix& m, int32_t f, const float* X, int64_t ldx, f
     return run_matrix(a, m, nullptr, nnz, nblocks, f, X, ldx, Z, ldz, epilogue, Zprev, ldzprev, o, s);
 }
 
+// For a matrix this library normalised symmetrically, D^-1/2 (A+I) D^-1/2 X = D^-1/2 ((A+I) (D^-1/2 X))
+// (section "Graph Neural Networks"): the product can skip the stored values, which halves the
+// index/value stream.  It pays when rows are long (the pre-scaling pass over X is amortised).
+bool use_value_free(const gcn_csr* a) {
+    const int mode = cfg_of(a).pattern_spmm;
+    if (!a->inv_sqrt_deg || mode == 0) return false;
+    return mode == 1 || a->nnz / (a->n > 0 ? a->n : 1) >= 64;
+}
+
 int spmm_prepare(gcn_csr* a, Matrix& m, int32_t f, hipStream_t s) {
     SpmmOpt o;
     o.dry = true;
@@ -1032,12 +1041,23 @@ extern "C" int gcn_spmm(gcn_csr* a, int trans, int32_t f, const float* X, int64_
                         int epilogue, const float* Zprev, int64_t ldzprev, void* stream) {
     GCN_TRY(check_spmm_args("gcn_spmm", a, trans, f, X, ldx, Z, ldz, epilogue, Zprev, ldzprev));
     PhaseTimer whole(s_of(stream), GCN_PHASE_SPMM);           // the whole product: every kernel it queues
+    if (use_value_free(a)) {
+        // value-free form: a pre-scaled copy of X in the handle (n x f), then sums of gathered rows, the output
+        // rows scaled in the kernels' store path; differs from the valued product by fp32 roundings only
+        GCN_TRY(grow_retire(a, &a->xs, &a->xs_bytes, (size_t)a->n * (size_t)f * sizeof(float)));
+        GCN_TRY(scale_rows_launch(a->n, f, X, ldx, a->inv_sqrt_deg, a->xs, f, s_of(stream)));
+        SpmmOpt o;
+        o.pattern = true;
+        o.row_scale = a->inv_sqrt_deg;
+        return spmm_launch(a, trans ? a->At : a->A, f, a->xs, f, Z, ldz, epilogue, Zprev, ldzprev, s_of(stream), o);
+    }
     return spmm_launch(a, trans ? a->At : a->A, f, X, ldx, Z, ldz, epilogue, Zprev, ldzprev, (hipStream_t)stream);
 }
 
 extern "C" int gcn_spmm_prepare(gcn_csr* a, int trans, int32_t f, void* stream) {
     if (!a || f <= 0) return fail(GCN_ERR_BADARG, "gcn_spmm_prepare: NULL matrix or f <= 0");
     if (trans && !a->has_t) return fail(GCN_ERR_NOTRANSPOSE, "gcn_spmm_prepare: trans=1 needs GCN_BUILD_TRANSPOSE");
+    if (use_value_free(a)) GCN_TRY(grow_retire(a, &a->xs, &a->xs_bytes, (size_t)a->n * (size_t)f * sizeof(float)));
     return spmm_prepare(a, trans ? a->At : a->A, f, (hipStream_t)stream);
 }
 
@@ -1048,7 +1068,9 @@ extern "C" int gcn_spmm_describe(gcn_csr* a, int trans, int32_t f, char* out, si
     SpmmOpt o;
     o.dry = true;
     o.describe = &text;
+    o.pattern = use_value_free(a);
     GCN_TRY(spmm_launch(a, trans ? a->At : a->A, f, nullptr, f, nullptr, f, GCN_EPI_NONE, nullptr, 0, (hipStream_t)stream, o));
+    if (o.pattern) text += "; value-free (operand rows pre-scaled by d^-1/2, output rows scaled)";
     snprintf(out, out_bytes, "%s", text.c_str());
     return GCN_OK;
 }

@@ -1226,6 +1226,58 @@ def test_first_epoch_after_prepare_is_captured_in_a_hip_graph():
     a.close()
 
 
+def test_stand_alone_product_takes_the_value_free_form_where_it_pays():
+    """gcn_spmm on a matrix that this library normalised symmetrically and whose mean row has at least 64 entries
+    pre-scales the operand into a buffer of the handle and sums gathered rows without reading the stored values
+    (section "Graph Neural Networks": D^-1/2 (A+I) D^-1/2).  Both forms against the oracle's valued product, against
+    each other to rounding, the description names the form, and after gcn_spmm_prepare the first product is captured
+    in a HIP graph (the handle's buffer exists) and replays bit for bit."""
+    g = G()
+    n, src, dst = synth.make_graph(synth.scaled(3, 32))
+    A = oracle.build_csr(n, src, dst)
+    a = g.gcn_csr_create(n, dev(src), dev(dst), flags_all())
+    assert a.nnz // n >= 64
+    X = synth.normal_features(n, 16, 61)
+    Xd = dev(X)
+    for trans in (0, 1):
+        g.gcn_spmm_prepare(a, trans, 16)
+        assert "value-free" in g.gcn_spmm_describe(a, trans, 16)
+        side = torch.cuda.Stream()
+        Zg = torch.full((n, 16), float("nan"), device="cuda")
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            g.gcn_spmm(a, trans, Xd, Zg)
+        got = []
+        for rep in range(2):
+            Zg.fill_(float("nan"))
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            got.append(Zg.clone())
+        Zf = torch.empty(n, 16, device="cuda")
+        g.gcn_spmm(a, trans, Xd, Zf)                                   # eager, value-free
+        assert torch.equal(got[0], Zf) and torch.equal(got[1], Zf)
+        g.gcn_config(g.CFG_PATTERN_SPMM, 0)
+        try:
+            assert "value-free" not in g.gcn_spmm_describe(a, trans, 16)
+            Zv = torch.empty(n, 16, device="cuda")
+            g.gcn_spmm(a, trans, Xd, Zv)                               # the stored values
+        finally:
+            g.gcn_config(g.CFG_PATTERN_SPMM, 2)
+        want = oracle.spmm(A, X)                                       # A is symmetric: the same for both
+        assert_close(host(Zf), want, f"value-free, trans={trans}")
+        assert_close(host(Zv), want, f"valued, trans={trans}")
+        rms = float(Zv.double().pow(2).mean().sqrt())
+        assert float((Zf - Zv).abs().max()) <= 2e-6 * rms
+    # a matrix with short rows keeps the stored values
+    n1, s1, d1 = synth.make_graph(synth.CONFIGS[1])
+    b = g.gcn_csr_create(n1, dev(s1), dev(d1), flags_all())
+    assert "value-free" not in g.gcn_spmm_describe(b, 0, 16)
+    a.close()
+    b.close()
+
+
 def test_two_matrices_with_settings_of_their_own():
     """gcn_csr_config: one matrix runs the per-element kernel, the other the nonzero-split kernel, in the same
     process and interleaved; each reports its own schedule; the description names what ran."""

@@ -37,12 +37,14 @@ def _pair(g, name_cfg, shrink, f, trans, seed, epilogue=0):
     # the existing entry point forced to the same schedule: bit for bit
     g.gcn_config(g.CFG_SPMM_ALGO, 2)
     g.gcn_config(g.CFG_SPMM_BLOCKS, 1)
+    g.gcn_config(g.CFG_PATTERN_SPMM, 0)           # the stored values, as the static entry point reads them
     try:
         Zf = torch.empty(n, f, device="cuda")
         g.gcn_spmm(a, trans, Xd, Zf, epilogue, Zprev)
     finally:
         g.gcn_config(g.CFG_SPMM_ALGO, 0)
         g.gcn_config(g.CFG_SPMM_BLOCKS, 0)
+        g.gcn_config(g.CFG_PATTERN_SPMM, 2)
     assert torch.equal(Zs, Zf), f"static differs from the same schedule of gcn_spmm, f={f}"
     if epilogue == 0:
         A = oracle.build_csr(n, src, dst)
