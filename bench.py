@@ -315,12 +315,17 @@ def main() -> int:
         if value_free:
             # the library took the form that skips the stored values (4 B per entry instead of 8, one pre-scaling pass
             # over X); `achieved` still prices the product at the CSR formula's bytes, this is the form's own count
-            extra["value_free_bytes_alg_per_spmm"] = 4 * nnz + 8 * (n + 1) + 4 * n + 8 * n * f + 8 * n * f
+            vf_bytes = 4 * nnz + 8 * (n + 1) + 4 * n + 8 * n * f + 8 * n * f
+            extra["value_free_bytes_alg_per_spmm"] = vf_bytes
+            extra["value_free_achieved_GBps"] = round(vf_bytes / (avg_product_ms * 1e-3) / 1e9, 2)
+            extra["value_free_frac_of_hbm_peak"] = round(vf_bytes / (avg_product_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)
         out["roofline"] = {"bound": "hbm", "kernel": ("k_scale_rows + " if value_free else "") + SCHEDULE_KERNELS.get(sched, "k_spmm_split"),
                            "achieved": round(achieved, 2),
                            "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
                            "avg_kernel_ms": round(avg_product_ms, 4),
                            "covers": "every kernel of one product (HIP events around the whole product on the launch stream)",
+                           "bytes_basis": "the task's CSR formula 8 nnz + 8 (n + 1) + 8 n f, whatever form the library takes"
+                                          + ("; this run took the value-free form, whose own minimum is extra.value_free_bytes_alg_per_spmm" if value_free else ""),
                            "traffic": traffic,
                            "traffic_is": "bytes across the L2 <-> fabric interface per product (rocprofv3 FETCH_SIZE / WRITE_SIZE, "
                                          "scaled by a plain copy); fills served by the Infinity Cache are included, so an "
