@@ -16,7 +16,7 @@
 //   2. S^T = W G^T:  A = W[feature r][c = 16t + 4g + v], B = the lane's own G[row r][16t + 4g + v]
 //      -> the lane holds S[row r][4g + v], stored with one 16-byte store.
 //   3. Y tiles += T^T G over the 16 rows of the strip: here the row index is the contraction index, which
-//      both operand layouts keep in l/16, so G goes through a 16 x 16 transposition in LDS, tile by tile.
+//      both operand layouts keep in l/16, so G goes through 16 x 16 transpositions in LDS, four tiles at a time.
 // Y accumulates in registers over all strips of a wavefront; the wavefronts of a workgroup are added in a fixed
 // order in LDS, the workgroups by two small kernels in a fixed order: bit-reproducible.
 #include "common.h"
@@ -49,10 +49,12 @@ __global__ __launch_bounds__(256) void k_fused_last(FusedArgs a) {
     constexpr int CP = 16 * NT;            // padded class count
     constexpr int SW = CP + 4;             // row stride of Ws
     constexpr int ST = 20;                 // row stride of Wt and of the per-wavefront tiles
+    constexpr int GT = NT < 4 ? NT : 4;    // tiles of G that go through LDS together (NT is 1, 2, 3, 4, 8 or 16; measured at
+                                           // 256 classes: 1 tile 3.03 ms, 4 tiles 2.82 ms, 8 tiles 2.95 ms, all 16 slower still)
     extern __shared__ float lds[];
     float* Ws = lds;                       // [16][SW]   W[feature][c]
     float* Wt = Ws + 16 * SW;              // [CP][ST]   W[feature][c] stored as [c][feature]
-    float* tiles = Wt + CP * ST;           // per wavefront: Ts[16][ST], Gs[16][ST]
+    float* tiles = Wt + CP * ST;           // per wavefront: Ts[16][ST], Gs[GT][16][ST]
     for (int idx = threadIdx.x; idx < 16 * CP; idx += 256) {
         const int k = idx / CP, c = idx % CP;
         const float v = c < a.C ? a.W[k * a.C + c] : 0.f;
@@ -63,24 +65,38 @@ __global__ __launch_bounds__(256) void k_fused_last(FusedArgs a) {
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int r = lane & 15, g = lane >> 4;
-    float* Ts = tiles + wave * (2 * 16 * ST);
+    float* Ts = tiles + wave * ((1 + GT) * 16 * ST);
     float* Gs = Ts + 16 * ST;
     floatx4 yacc[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t) yacc[t] = (floatx4){0.f, 0.f, 0.f, 0.f};
     double lmine = 0.0;
     const int64_t nstrips = (a.n + 15) / 16;
-    for (int64_t strip = (int64_t)blockIdx.x * 4 + wave; strip < nstrips; strip += (int64_t)gridDim.x * 4) {
+    // The strip's inputs (16 bytes of T per lane, the row's label and the factor of its row of S) are fetched one
+    // strip ahead: with one wavefront per SIMD nothing else hides the latency of these loads.
+    float4 tv_next = make_float4(0.f, 0.f, 0.f, 0.f);
+    int32_t y_next = -1;
+    float rs_next = 1.f;
+    auto fetch = [&](int64_t strip) {
+        const int64_t row = strip * 16 + r;
+        tv_next = make_float4(0.f, 0.f, 0.f, 0.f);
+        y_next = -1;
+        rs_next = 1.f;
+        if (row < a.n) {
+            tv_next = *reinterpret_cast<const float4*>(a.T + row * 16 + 4 * g);
+            y_next = a.labels[row];
+            if (a.s_scale) rs_next = a.s_scale[row];
+        }
+    };
+    const int64_t stride = (int64_t)gridDim.x * 4;
+    if ((int64_t)blockIdx.x * 4 + wave < nstrips) fetch((int64_t)blockIdx.x * 4 + wave);
+    for (int64_t strip = (int64_t)blockIdx.x * 4 + wave; strip < nstrips; strip += stride) {
         const int64_t row = strip * 16 + r;
         const bool valid = row < a.n;
-        float4 tv = make_float4(0.f, 0.f, 0.f, 0.f);
-        int32_t y = -1;
-        float rs = 1.f;                                    // the factor of this row of S, fetched with the row
-        if (valid) {
-            tv = *reinterpret_cast<const float4*>(a.T + row * 16 + 4 * g);
-            y = a.labels[row];
-            if (a.s_scale) rs = a.s_scale[row];
-        }
+        const float4 tv = tv_next;
+        const int32_t y = y_next;
+        const float rs = rs_next;
+        if (strip + stride < nstrips) fetch(strip + stride);
         // (The operands from W do not depend on the strip: the compiler keeps them in registers across the
         // loop, 128 of them at 256 classes, which leaves one wavefront per SIMD; forcing two by re-reading them
         // from LDS made the register allocator spill, so this is the faster form.)
@@ -167,17 +183,29 @@ __global__ __launch_bounds__(256) void k_fused_last(FusedArgs a) {
             const floatx4 sum = (sacc[0] + sacc[1]) + (sacc[2] + sacc[3]);
             if (valid) *reinterpret_cast<float4*>(a.S + row * 16 + 4 * g) = make_float4(sum[0] * rs, sum[1] * rs, sum[2] * rs, sum[3] * rs);
         }
-        // 3. Y += T^T G, tile by tile through a transposition in this wavefront's LDS (its LDS operations
-        //    complete in program order; the barriers only keep the compiler from reordering them)
+        // 3. Y += T^T G: the row index is the contraction index, so G goes through a transposition in this
+        //    wavefront's LDS, GT tiles at a time (one round trip through LDS per group instead of per tile, and the
+        //    tiles' accumulation chains are independent).  The wavefront's LDS operations complete in program order;
+        //    the barriers only keep the compiler from reordering them.
+        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        float tk[4];                               // T[row 4kk + g][feature r]: the same for every tile
 #pragma unroll
-        for (int t = 0; t < NT; ++t) {
-            *reinterpret_cast<float4*>(Gs + r * ST + 4 * g) = make_float4(z[t][0], z[t][1], z[t][2], z[t][3]);
+        for (int kk = 0; kk < 4; ++kk) tk[kk] = Ts[(4 * kk + g) * ST + r];
+#pragma unroll
+        for (int t0 = 0; t0 < NT; t0 += GT) {
+#pragma unroll
+            for (int u = 0; u < GT; ++u)
+                *reinterpret_cast<float4*>(Gs + u * (16 * ST) + r * ST + 4 * g) =
+                    make_float4(z[t0 + u][0], z[t0 + u][1], z[t0 + u][2], z[t0 + u][3]);
             __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
             __builtin_amdgcn_wave_barrier();
 #pragma unroll
             for (int kk = 0; kk < 4; ++kk) {
-                const int rs = 4 * kk + g;         // the strip's row this lane contributes to instruction kk
-                yacc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(Ts[rs * ST + r], Gs[rs * ST + r], yacc[t], 0, 0, 0);
+                const int rs4 = 4 * kk + g;        // the strip's row this lane contributes to instruction kk
+#pragma unroll
+                for (int u = 0; u < GT; ++u)
+                    yacc[t0 + u] = __builtin_amdgcn_mfma_f32_16x16x4f32(tk[kk], Gs[u * (16 * ST) + rs4 * ST + r], yacc[t0 + u], 0, 0, 0);
             }
             __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
             __builtin_amdgcn_wave_barrier();
@@ -257,7 +285,8 @@ size_t fused_last_scratch_bytes(int64_t n, int32_t C) {
 
 template <int NT>
 static void launch_fused(const FusedArgs& a, int64_t blocks, hipStream_t s) {
-    const size_t lds = (size_t)(16 * (16 * NT + 4) + 16 * NT * 20 + 4 * 2 * 16 * 20) * sizeof(float);
+    const int GT = NT < 4 ? NT : 4;
+    const size_t lds = (size_t)(16 * (16 * NT + 4) + 16 * NT * 20 + 4 * (1 + GT) * 16 * 20) * sizeof(float);
     // (a variant with the padding tests compiled out for C == 16 NT made the register allocator spill: not used)
     hipLaunchKernelGGL((k_fused_last<NT, false>), dim3((unsigned)blocks), dim3(256), lds, s, a);
 }
