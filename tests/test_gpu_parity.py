@@ -881,11 +881,12 @@ def test_epoch_scaled_configs_parity(name, cfg, shrink):
 
 
 @pytest.mark.parametrize("mode", [0, 1, 2])
-@pytest.mark.parametrize("classes", [5, 16, 24, 41, 100, 256])
+@pytest.mark.parametrize("classes", [5, 16, 24, 41, 64, 65, 100, 128, 129, 200, 256])
 def test_epoch_fused_last_layer_modes(mode, classes):
     """The last layer in SpMM-first order at hidden width 16 (16 -> C): separate kernels (0), fused without
-    storing Z^L / G^L (1), fused and stored (2), for class counts around the 16-column tiles, with a training
-    split so that unlabelled rows are covered."""
+    storing Z^L / G^L (1), fused and stored (2), for class counts around the 16-column tiles and on both sides of 64
+    and 128 (above 64 classes the wavefronts of a workgroup split the class tiles), with a training split so that
+    unlabelled rows are covered.  A second run must give the same bits (every sum runs in a fixed order)."""
     import dataclasses
     g = G()
     w = dataclasses.replace(synth.scaled(4, 256), dims=(48, 16, 16, classes), n_classes=classes)
@@ -905,6 +906,11 @@ def test_epoch_fused_last_layer_modes(mode, classes):
     torch.cuda.synchronize()
     ref, _ = oracle_epoch_same_signs(g, A, A, A.n, dims, 0, ws, H0, y, Ws)
     assert_epoch_close(g, A.n, dims, 0, ws, loss, Yd, ref, f"fused mode {mode}, {classes} classes", last_stored=mode != 1)
+    Y2 = [torch.empty_like(x) for x in Wd]
+    loss2 = torch.zeros(1, device="cuda")
+    g.gcn_epoch_masked(a, dims, dev(H0), dev(y), m, Wd, Y2, 0.0, loss2, ws, 0)
+    torch.cuda.synchronize()
+    assert torch.equal(loss, loss2) and all(torch.equal(p, q) for p, q in zip(Yd, Y2))
     a.close()
 
 
