@@ -518,7 +518,7 @@ static void launch_fused(const FusedArgs& a, int64_t blocks, hipStream_t s) {
 
 template <int TW>
 static void launch_fused_wide(const FusedArgs& a, int64_t blocks, hipStream_t s) {
-    const int NT = 4 * TW;
+    // per wavefront Ts and TW tiles of G, two sets of softmax slots, two sets of partial S tiles
     const size_t lds = (size_t)(4 * (1 + TW) * 16 * 20 + 2 * 128 + 2 * 4 * 64 * 4) * sizeof(float);
     hipLaunchKernelGGL((k_fused_last_wide<TW>), dim3((unsigned)blocks), dim3(256), lds, s, a);
 }
