@@ -71,6 +71,20 @@ GRAPH_WORDS = {1: "Erdos-Renyi, 4096 vertices", 2: "R-MAT scale 20, edge factor 
                3: "Reddit-shaped Chung-Lu", 4: "Amazon-shaped R-MAT scale 24", 5: "Protein-shaped Chung-Lu"}
 
 
+def host_cpu() -> dict:
+    """Model string and logical CPU count of the host the oracle is timed on."""
+    model = "unknown"
+    try:
+        with open("/proc/cpuinfo") as fh:
+            for line in fh:
+                if line.lower().startswith("model name"):
+                    model = line.split(":", 1)[1].strip()
+                    break
+    except OSError:
+        pass
+    return {"model": model, "logical_cpus": os.cpu_count()}
+
+
 def spmm_alg_bytes(n: int, nnz: int, f: int) -> int:
     return 8 * nnz + 8 * (n + 1) + 4 * n * f + 4 * n * f
 
@@ -353,7 +367,7 @@ def main() -> int:
             out["cpu_baseline"] = {"value": round(b_alg / t_o / 1e9, 3), "unit": "GB/s", "cores": oracle.threads(),
                                    "kind": "oracle",
                                    "sample": f"one full Z = A X on the same stored matrix ({zrows} x {n}, nnz={nnz}, f={f}), 1 rep",
-                                   "ms": round(t_o * 1e3, 1), "matrix_copy_to_host_s": round(t_ex, 2)}
+                                   "ms": round(t_o * 1e3, 1), "matrix_copy_to_host_s": round(t_ex, 2), "host": host_cpu()}
             # the same product on one core, on a bounded sample of the rows: random rows and the longest ones
             all_threads = oracle.threads()
             rs = np.random.default_rng(args.seed)
@@ -470,7 +484,7 @@ def main() -> int:
             progress("oracle: epoch done")
             out["cpu_baseline"] = {"value": round(t_o * 1e3, 1), "unit": "ms", "cores": oracle.threads(), "kind": "oracle",
                                    "sample": "one full oracle epoch (forward + loss + backward, every product) on the same "
-                                             "stored matrix and inputs, 1 rep"}
+                                             "stored matrix and inputs, 1 rep", "host": host_cpu()}
             extra["loss_rel_err_vs_oracle"] = abs(float(loss.item()) - ref["loss"]) / abs(ref["loss"])
     out["extra"] = extra
     print(json.dumps(out))
