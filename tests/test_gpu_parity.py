@@ -914,6 +914,19 @@ def test_epoch_fused_last_layer_modes(mode, classes):
     a.close()
 
 
+@pytest.mark.parametrize("name", ["tiny", "one", "ring"])
+@pytest.mark.parametrize("classes", [24, 130, 256])
+def test_epoch_fused_last_layer_on_very_small_graphs(name, classes):
+    """Three vertices, one vertex, a ring of 1000: fewer rows than one strip, a single workgroup, a ragged last strip
+    -- through both forms of the fused kernel."""
+    import dataclasses
+    g = G()
+    w = dataclasses.replace(synth.CONFIGS[1], dims=(8, 16, classes), n_classes=classes, features="normal")
+    _, a, A, dims, Wd, Yd, ws, loss, ref, _ = run_epoch(name, w, 0)
+    assert_epoch_close(g, A.n, dims, 0, ws, loss, Yd, ref, f"{name}, {classes} classes")
+    a.close()
+
+
 def test_epoch_fused_last_layer_as_the_only_layer():
     """One weight matrix (16 -> 40): the fused kernel is the whole dense part and no earlier layer needs G W^T."""
     import dataclasses
